@@ -1,0 +1,188 @@
+"""ctypes access to the CPU oracle (oracle/dbw_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the benchmark's
+CPU-baseline leg; never by the product package.  This wrapper marshals NumPy arrays and
+holds no arithmetic of its own.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_DIR = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_DIR, "dbw_oracle.c")
+_LIB = os.path.join(_DIR, "liboracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain C, OpenMP over workers)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = C.CDLL(_LIB)
+        _lib.orc_select.restype = C.c_int
+        _lib.orc_spanning_tree.restype = C.c_int
+    return _lib
+
+
+def _p(a, t):
+    return a.ctypes.data_as(C.POINTER(t))
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def select(rowptr, colidx, t, b):
+    """-> (mask[nnz] uint8, p[N] int32, wait[N] fp32); raises ValueError on b out of range."""
+    rowptr, colidx, t, b = _i32(rowptr), _i32(colidx), _f32(t), _i32(b)
+    n = rowptr.size - 1
+    mask = np.zeros(colidx.size, dtype=np.uint8)
+    p = np.zeros(n, dtype=np.int32)
+    wait = np.zeros(n, dtype=np.float32)
+    rc = lib().orc_select(n, _p(rowptr, C.c_int32), _p(colidx, C.c_int32), _p(t, C.c_float),
+                          _p(b, C.c_int32), _p(mask, C.c_uint8), _p(p, C.c_int32), _p(wait, C.c_float))
+    if rc != 0:
+        raise ValueError(f"orc_select: {rc}")
+    return mask, p, wait
+
+
+def weights(rowptr, colidx, mask, p):
+    rowptr, colidx, p = _i32(rowptr), _i32(colidx), _i32(p)
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    n = rowptr.size - 1
+    we = np.zeros(max(colidx.size, 1), dtype=np.float64)
+    ws = np.zeros(n, dtype=np.float64)
+    lib().orc_weights(n, _p(rowptr, C.c_int32), _p(colidx, C.c_int32), _p(mask, C.c_uint8),
+                      _p(p, C.c_int32), _p(we, C.c_double), _p(ws, C.c_double))
+    return we[:colidx.size], ws
+
+
+def dense_P(rowptr, colidx, mask, p):
+    rowptr, colidx, p = _i32(rowptr), _i32(colidx), _i32(p)
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    n = rowptr.size - 1
+    P = np.zeros((n, n), dtype=np.float64)
+    lib().orc_dense_P(n, _p(rowptr, C.c_int32), _p(colidx, C.c_int32), _p(mask, C.c_uint8),
+                      _p(p, C.c_int32), _p(P, C.c_double))
+    return P
+
+
+def round_(rowptr, colidx, mask, p, x, g, lr, order=0, d=None):
+    """x, g: [N, ld] fp32 (g may be None) -> out [N, ld] fp32 (columns >= d left zero)."""
+    rowptr, colidx, p = _i32(rowptr), _i32(colidx), _i32(p)
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    x = _f32(x)
+    n, ld = x.shape
+    d = ld if d is None else d
+    gp = None
+    if g is not None:
+        g = _f32(g)
+        assert g.shape == x.shape
+        gp = _p(g, C.c_float)
+    out = np.zeros_like(x)
+    lib().orc_round(n, C.c_int64(d), C.c_int64(ld), _p(rowptr, C.c_int32), _p(colidx, C.c_int32),
+                    _p(mask, C.c_uint8), _p(p, C.c_int32), _p(x, C.c_float), gp,
+                    C.c_float(lr), int(order), _p(out, C.c_float))
+    return out
+
+
+def spanning_tree(rowptr, colidx):
+    rowptr, colidx = _i32(rowptr), _i32(colidx)
+    n = rowptr.size - 1
+    edges = np.zeros((max(n - 1, 1), 2), dtype=np.int32)
+    rc = lib().orc_spanning_tree(n, _p(rowptr, C.c_int32), _p(colidx, C.c_int32), _p(edges, C.c_int32))
+    if rc < 0:
+        raise ValueError("graph not connected")
+    return edges[:rc]
+
+
+class Dtur:
+    """State of the d-iteration procedure: the link set, the visited set P', its size."""
+
+    def __init__(self, rowptr, colidx):
+        self.rowptr, self.colidx = _i32(rowptr), _i32(colidx)
+        self.n = self.rowptr.size - 1
+        self.edges = np.ascontiguousarray(spanning_tree(rowptr, colidx))
+        self.visited = np.zeros(max(len(self.edges), 1), dtype=np.uint8)
+        self.n_visited = C.c_int32(0)
+
+    def step(self, t):
+        t = _f32(t)
+        b = np.zeros(self.n, dtype=np.int32)
+        theta = C.c_float(0)
+        lib().orc_dtur(self.n, _p(self.rowptr, C.c_int32), _p(self.colidx, C.c_int32), len(self.edges),
+                       _p(self.edges, C.c_int32), _p(self.visited, C.c_uint8), C.byref(self.n_visited),
+                       _p(t, C.c_float), _p(b, C.c_int32), C.byref(theta))
+        return b, float(theta.value)
+
+
+def grad_mlp(dims, params, x, y):
+    """One worker: params [d], x [B, dims[0]], y [B] -> (grad [d] fp32, loss float)."""
+    dims = _i32(dims)
+    params, x, y = _f32(params), _f32(x), _i32(y)
+    grad = np.zeros_like(params)
+    loss = C.c_double(0)
+    lib().orc_grad_mlp(len(dims) - 1, _p(dims, C.c_int32), x.shape[0], _p(params, C.c_float),
+                       _p(x, C.c_float), _p(y, C.c_int32), _p(grad, C.c_float), C.byref(loss))
+    return grad, loss.value
+
+
+def grad_cnn(shape, params, x, y):
+    """One worker: shape = (C0, H, W, C1, C2, K, F, classes)."""
+    shape = _i32(shape)
+    params, x, y = _f32(params), _f32(x), _i32(y)
+    grad = np.zeros_like(params)
+    loss = C.c_double(0)
+    lib().orc_grad_cnn(_p(shape, C.c_int32), x.shape[0], _p(params, C.c_float), _p(x, C.c_float),
+                       _p(y, C.c_int32), _p(grad, C.c_float), C.byref(loss))
+    return grad, loss.value
+
+
+def grad_all(kind, desc, d, params, x, y):
+    """All workers: params [N, ld], x [N, B, in], y [N, B] -> (grad [N, ld], loss [N])."""
+    desc = _i32(desc)
+    params, x, y = _f32(params), _f32(x), _i32(y)
+    n, ld = params.shape
+    B = x.shape[1]
+    in_dim = int(np.prod(x.shape[2:]))
+    grad = np.zeros_like(params)
+    loss = np.zeros(n, dtype=np.float64)
+    lib().orc_grad_all(int(kind), _p(desc, C.c_int32), n, C.c_int64(d), C.c_int64(ld), B,
+                       C.c_int64(in_dim), _p(params, C.c_float), _p(x, C.c_float), _p(y, C.c_int32),
+                       _p(grad, C.c_float), _p(loss, C.c_double))
+    return grad, loss
+
+
+def model_desc(desc):
+    """(kind, int32 descriptor) for grad_all from a model description dict."""
+    if desc["kind"] == "mlp":
+        dims = desc["dims"]
+        return 0, np.array([len(dims) - 1] + list(dims), dtype=np.int32)
+    c, h, w = desc["in"]
+    return 1, np.array([c, h, w, desc["c1"], desc["c2"], desc["k"], desc["fc"], desc["classes"]], dtype=np.int32)
+
+
+def n_threads() -> int:
+    """Threads the OpenMP loops over workers will use."""
+    try:
+        omp = C.CDLL("libgomp.so.1")
+        return int(omp.omp_get_max_threads())
+    except OSError:
+        return 1

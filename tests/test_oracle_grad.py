@@ -1,0 +1,195 @@
+"""Pins for the oracle's mini-batch gradients (Section 2.1, stochastic gradient of the
+local loss; cross-entropy loss as in Section 5): central finite differences of an
+independently written float64 forward pass, PyTorch CPU autograd on the real shapes,
+and the closed form of softmax regression at zero parameters."""
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from paper_2102_06280_amd import inputs
+
+
+# ---- independent forward passes (loss only), float64 NumPy
+
+def xent(logits, y):
+    z = logits - logits.max(1, keepdims=True)
+    logp = z - np.log(np.exp(z).sum(1, keepdims=True))
+    return -logp[np.arange(len(y)), y].mean()
+
+
+def mlp_loss(dims, params, x, y):
+    a, off = x.astype(np.float64), 0
+    for l in range(len(dims) - 1):
+        i, o = dims[l], dims[l + 1]
+        W = params[off:off + o * i].reshape(o, i); off += o * i
+        b = params[off:off + o]; off += o
+        a = a @ W.T + b
+        if l + 2 < len(dims):
+            a = np.maximum(a, 0)
+    return xent(a, y)
+
+
+def conv_same(x, W, b):
+    B, C, H, Wd = x.shape
+    K = W.shape[-1]
+    pad = K // 2
+    xp = np.pad(x, ((0, 0), (0, 0), (pad, pad), (pad, pad)))
+    out = np.zeros((B, W.shape[0], H, Wd))
+    for kh in range(K):
+        for kw in range(K):
+            out += np.einsum("bchw,oc->bohw", xp[:, :, kh:kh + H, kw:kw + Wd], W[:, :, kh, kw])
+    return out + b[None, :, None, None]
+
+
+def pool2(x):
+    B, C, H, W = x.shape
+    return x.reshape(B, C, H // 2, 2, W // 2, 2).max(axis=(3, 5))
+
+
+def cnn_loss(shape, params, x, y):
+    C0, H, W, C1, C2, K, Fc, NC = shape
+    params = params.astype(np.float64)
+    off = 0
+    def take(*s):
+        nonlocal off
+        n = int(np.prod(s)); v = params[off:off + n].reshape(s); off += n
+        return v
+    W1, b1 = take(C1, C0, K, K), take(C1)
+    W2, b2 = take(C2, C1, K, K), take(C2)
+    flat = C2 * (H // 4) * (W // 4)
+    W3, b3 = take(Fc, flat), take(Fc)
+    W4, b4 = take(NC, Fc), take(NC)
+    a = pool2(np.maximum(conv_same(x.astype(np.float64), W1, b1), 0))
+    a = pool2(np.maximum(conv_same(a, W2, b2), 0))
+    a = np.maximum(a.reshape(len(y), -1) @ W3.T + b3, 0)
+    return xent(a @ W4.T + b4, y)
+
+
+def fd_check(loss_fn, params, grad, n_probe, g, eps=1e-5):
+    idx = g.choice(params.size, size=min(n_probe, params.size), replace=False)
+    for k in idx:
+        pp, pm = params.astype(np.float64).copy(), params.astype(np.float64).copy()
+        pp[k] += eps; pm[k] -= eps
+        fd = (loss_fn(pp) - loss_fn(pm)) / (2 * eps)
+        assert abs(fd - grad[k]) <= 1e-6 + 2e-5 * abs(fd), (k, fd, grad[k])
+
+
+@pytest.mark.parametrize("dims", [[12, 5], [9, 7, 4], [6, 8, 5, 3]])
+def test_mlp_finite_differences(orc, dims):
+    g = np.random.default_rng(71)
+    d = sum(dims[l + 1] * (dims[l] + 1) for l in range(len(dims) - 1))
+    params = (g.standard_normal(d) * 0.5).astype(np.float32)
+    x = g.standard_normal((6, dims[0])).astype(np.float32)
+    y = g.integers(0, dims[-1], 6).astype(np.int32)
+    grad, loss = orc.grad_mlp(dims, params, x, y)
+    assert abs(loss - mlp_loss(dims, params.astype(np.float64), x, y)) < 1e-12
+    fd_check(lambda p: mlp_loss(dims, p, x, y), params, grad, 200, g)
+
+
+def test_cnn_finite_differences(orc):
+    g = np.random.default_rng(73)
+    shape = (2, 8, 8, 3, 4, 3, 6, 5)
+    C0, H, W, C1, C2, K, Fc, NC = shape
+    d = C1 * C0 * K * K + C1 + C2 * C1 * K * K + C2 + Fc * C2 * (H // 4) * (W // 4) + Fc + NC * Fc + NC
+    params = (g.standard_normal(d) * 0.3).astype(np.float32)
+    x = g.standard_normal((4, C0, H, W)).astype(np.float32)
+    y = g.integers(0, NC, 4).astype(np.int32)
+    grad, loss = orc.grad_cnn(shape, params, x, y)
+    assert abs(loss - cnn_loss(shape, params, x, y)) < 1e-12
+    fd_check(lambda p: cnn_loss(shape, p, x, y), params, grad, 150, g)
+    # 5x5 kernels as in the full-size model
+    shape = (3, 8, 8, 2, 3, 5, 4, 3)
+    C0, H, W, C1, C2, K, Fc, NC = shape
+    d = C1 * C0 * K * K + C1 + C2 * C1 * K * K + C2 + Fc * C2 * (H // 4) * (W // 4) + Fc + NC * Fc + NC
+    params = (g.standard_normal(d) * 0.3).astype(np.float32)
+    x = g.standard_normal((3, C0, H, W)).astype(np.float32)
+    y = g.integers(0, NC, 3).astype(np.int32)
+    grad, loss = orc.grad_cnn(shape, params, x, y)
+    fd_check(lambda p: cnn_loss(shape, p, x, y), params, grad, 150, g)
+
+
+def test_softmax_zero_init_closed_form(orc):
+    """All-zero parameters: logits 0, probabilities 1/10, loss ln 10,
+    dW = (1/B) sum_l (1/10 - e_{y_l}) x_l^T, db = (1/B) sum_l (1/10 - e_{y_l})."""
+    cfg = inputs.CONFIGS[1]
+    x, y = inputs.batch(cfg, 0, workers=[3])
+    x, y = x[0], y[0]
+    grad, loss = orc.grad_mlp([784, 10], np.zeros(7850, np.float32), x, y)
+    assert abs(loss - np.log(10.0)) < 1e-12
+    E = np.full((len(y), 10), 0.1)
+    E[np.arange(len(y)), y] -= 1.0
+    dW = E.T @ x.astype(np.float64) / len(y)
+    assert np.allclose(grad[:7840].reshape(10, 784), dW, rtol=1e-6, atol=1e-9)
+    assert np.allclose(grad[7840:], E.mean(0), rtol=1e-6, atol=1e-9)
+
+
+def _torch_mlp_grad(dims, params, x, y):
+    p = torch.tensor(params, dtype=torch.float64, requires_grad=True)
+    a, off = torch.tensor(x, dtype=torch.float64), 0
+    for l in range(len(dims) - 1):
+        i, o = dims[l], dims[l + 1]
+        W = p[off:off + o * i].view(o, i); off += o * i
+        b = p[off:off + o]; off += o
+        a = F.linear(a, W, b)
+        if l + 2 < len(dims):
+            a = F.relu(a)
+    loss = F.cross_entropy(a, torch.tensor(y, dtype=torch.long))
+    loss.backward()
+    return p.grad.numpy(), float(loss.detach())
+
+
+@pytest.mark.parametrize("cid", [1, 2])
+def test_mlp_matches_autograd_full_shape(orc, cid):
+    cfg = inputs.CONFIGS[cid]
+    desc = inputs.model_dims(cfg.model)
+    params = inputs.init_params(desc, 2, cfg.d, inputs.rng(cid, inputs.P_PARAMS))[1]
+    x, y = inputs.batch(cfg, 0, workers=[1])
+    grad, loss = orc.grad_mlp(desc["dims"], params, x[0], y[0])
+    want, wl = _torch_mlp_grad(desc["dims"], params, x[0], y[0])
+    assert abs(loss - wl) < 1e-10
+    assert np.allclose(grad, want, rtol=1e-6, atol=1e-9)
+
+
+def test_cnn_matches_autograd_full_shape(orc):
+    cfg = inputs.CONFIGS[3]
+    desc = inputs.model_dims("cnn")
+    params = inputs.init_params(desc, 1, cfg.d, inputs.rng(3, inputs.P_PARAMS))[0]
+    x, y = inputs.batch(cfg, 0, workers=[0])
+    x, y = x[0][:4], y[0][:4]              # 4 samples keep the direct loops to a few seconds
+    shape = (3, 32, 32, 32, 64, 5, 512, 10)
+    grad, loss = orc.grad_cnn(shape, params, x, y)
+    p = torch.tensor(params, dtype=torch.float64, requires_grad=True)
+    off = 0
+    def take(*s):
+        nonlocal off
+        n = int(np.prod(s)); v = p[off:off + n].view(*s); off += n
+        return v
+    W1, b1, W2, b2 = take(32, 3, 5, 5), take(32), take(64, 32, 5, 5), take(64)
+    W3, b3, W4, b4 = take(512, 4096), take(512), take(10, 512), take(10)
+    a = torch.tensor(x, dtype=torch.float64).view(-1, 3, 32, 32)
+    a = F.max_pool2d(F.relu(F.conv2d(a, W1, b1, padding=2)), 2)
+    a = F.max_pool2d(F.relu(F.conv2d(a, W2, b2, padding=2)), 2)
+    a = F.relu(F.linear(a.flatten(1), W3, b3))
+    l = F.cross_entropy(F.linear(a, W4, b4), torch.tensor(y, dtype=torch.long))
+    l.backward()
+    assert abs(loss - float(l)) < 1e-10
+    assert np.allclose(grad, p.grad.numpy(), rtol=1e-6, atol=1e-9)
+
+
+def test_grad_all_rows_and_padding(orc):
+    """orc.grad_all = the single-worker routine applied row by row, padding zeroed."""
+    dims = [10, 6, 4]
+    d = 6 * 11 + 4 * 7
+    g = np.random.default_rng(79)
+    n, ld, B = 3, 96, 5
+    params = np.zeros((n, ld), np.float32)
+    params[:, :d] = g.standard_normal((n, d))
+    x = g.standard_normal((n, B, 10)).astype(np.float32)
+    y = g.integers(0, 4, (n, B)).astype(np.int32)
+    kind, desc = orc.model_desc({"kind": "mlp", "dims": dims})
+    grad, loss = orc.grad_all(kind, desc, d, params, x, y)
+    assert not grad[:, d:].any()
+    for i in range(n):
+        gi, li = orc.grad_mlp(dims, params[i, :d], x[i], y[i])
+        assert np.array_equal(grad[i, :d], gi) and loss[i] == li

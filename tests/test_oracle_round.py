@@ -1,0 +1,188 @@
+"""Pins for the oracle's mixing + correction pass (CPU only): reduction to full
+participation, closed forms, invariants of the worker mean, the unrolled recursion,
+the consensus limit, convexity."""
+import numpy as np
+import pytest
+
+from paper_2102_06280_amd import inputs
+
+
+def adjacency(rowptr, colidx):
+    n = rowptr.size - 1
+    A = np.zeros((n, n), bool)
+    for i in range(n):
+        A[i, colidx[rowptr[i]:rowptr[i + 1]]] = True
+    return A
+
+
+def mh_static(rowptr, colidx):
+    """Static Metropolis-Hastings matrix of the full graph, from degrees alone."""
+    A = adjacency(rowptr, colidx)
+    deg = A.sum(1)
+    W = np.where(A, 1.0 / (1.0 + np.maximum.outer(deg, deg)), 0.0)
+    W[np.diag_indices_from(W)] = 1.0 - W.sum(1)
+    return W
+
+
+def graphs():
+    g = np.random.default_rng(21)
+    return [inputs.graph_ring(8), inputs.graph_complete(6), inputs.graph_er(9, 0.4, g),
+            inputs.graph_regular(12, 4, g), inputs.graph_er(16, 0.3, g)]
+
+
+@pytest.mark.parametrize("order", [0, 1])
+def test_b0_is_full_participation(orc, order):
+    """Section 1: with b_j = 0 for all j the method is full-participation consensus SGD
+    (Section 2.1 update with static Metropolis-Hastings weights)."""
+    g = np.random.default_rng(23)
+    for rowptr, colidx in graphs():
+        n, d = rowptr.size - 1, 37
+        x = g.standard_normal((n, d)).astype(np.float32)
+        gr = g.standard_normal((n, d)).astype(np.float32)
+        t = g.standard_exponential(n).astype(np.float32)
+        lr = np.float32(0.05)
+        mask, p, _ = orc.select(rowptr, colidx, t, np.zeros(n, np.int32))
+        out = orc.round_(rowptr, colidx, mask, p, x, gr, lr, order)
+        W = mh_static(rowptr, colidx)
+        xd, gd = x.astype(np.float64), gr.astype(np.float64)
+        want = W @ xd - float(lr) * gd if order == 0 else W @ (xd - float(lr) * gd)
+        assert np.allclose(out, want, rtol=2e-7, atol=1e-7)
+
+
+def test_closed_forms_regular_and_complete(orc):
+    """k-regular, b = 0: mean over the closed neighbourhood minus lr g_i
+    (ring: (x_{i-1}+x_i+x_{i+1})/3); complete: global mean minus lr g_i."""
+    g = np.random.default_rng(29)
+    n, d, lr = 8, 19, np.float32(0.1)
+    x = g.standard_normal((n, d)).astype(np.float32)
+    gr = g.standard_normal((n, d)).astype(np.float32)
+    t = g.standard_exponential(n).astype(np.float32)
+    rowptr, colidx = inputs.graph_ring(n)
+    mask, p, _ = orc.select(rowptr, colidx, t, np.zeros(n, np.int32))
+    out = orc.round_(rowptr, colidx, mask, p, x, gr, lr, 0)
+    xd = x.astype(np.float64)
+    want = (np.roll(xd, 1, 0) + xd + np.roll(xd, -1, 0)) / 3 - float(lr) * gr
+    assert np.allclose(out, want, rtol=2e-7, atol=1e-7)
+    rowptr, colidx = inputs.graph_complete(n)
+    mask, p, _ = orc.select(rowptr, colidx, t, np.zeros(n, np.int32))
+    out = orc.round_(rowptr, colidx, mask, p, x, gr, lr, 0)
+    want = xd.mean(0, keepdims=True) - float(lr) * gr
+    assert np.allclose(out, want, rtol=2e-7, atol=1e-7)
+
+
+def test_ring_one_backup_closed_form(orc):
+    """Ring with b = 1: p = 1 everywhere, so every weight is 1/2 and
+    x_i' = (x_i + x_j*)/2 - lr g_i with j* the faster of i-1, i+1 (lower index on a tie)."""
+    g = np.random.default_rng(31)
+    n, d, lr = 8, 11, np.float32(0.05)
+    rowptr, colidx = inputs.graph_ring(n)
+    for quant in (None, 1.0):
+        x = g.standard_normal((n, d)).astype(np.float32)
+        gr = g.standard_normal((n, d)).astype(np.float32)
+        t = g.standard_exponential(n).astype(np.float32)
+        if quant:
+            t = np.round(t).astype(np.float32)
+        mask, p, _ = orc.select(rowptr, colidx, t, np.ones(n, np.int32))
+        out = orc.round_(rowptr, colidx, mask, p, x, gr, lr, 0)
+        for i in range(n):
+            a, c = (i - 1) % n, (i + 1) % n
+            js = min((t[a], a), (t[c], c))[1]
+            want = 0.5 * (x[i].astype(np.float64) + x[js]) - float(lr) * gr[i]
+            assert np.allclose(out[i], want, rtol=2e-7, atol=1e-7)
+
+
+@pytest.mark.parametrize("order", [0, 1])
+def test_mean_recursion_symmetric_mask(orc, order):
+    """Proof sketch of Theorem 1: under a doubly stochastic P the worker mean obeys
+    y(k+1) = y(k) - (lr/N) sum_j g_j.  Symmetric masks: b = 0 and threshold-rule sets."""
+    g = np.random.default_rng(37)
+    for rowptr, colidx in graphs():
+        n, d, lr = rowptr.size - 1, 23, np.float32(0.07)
+        x = g.standard_normal((n, d)).astype(np.float32)
+        gr = g.standard_normal((n, d)).astype(np.float32)
+        t = g.standard_exponential(n).astype(np.float32)
+        dt = orc.Dtur(rowptr, colidx)
+        for b in (np.zeros(n, np.int32), dt.step(t)[0]):
+            mask, p, _ = orc.select(rowptr, colidx, t, b)
+            out = orc.round_(rowptr, colidx, mask, p, x, gr, lr, order)
+            want = x.astype(np.float64).mean(0) - float(lr) * gr.astype(np.float64).mean(0)
+            assert np.allclose(out.astype(np.float64).mean(0), want, atol=2e-7)
+
+
+def test_unrolled_recursion(orc):
+    """Section 2.2, the unrolled recursion: K rounds of local-step-then-average equal
+    X(0) and the per-round gradients pushed through explicit products of the P(k)."""
+    g = np.random.default_rng(41)
+    rowptr, colidx = inputs.graph_er(6, 0.5, g)
+    n, d, K, lr = 6, 5, 4, np.float32(0.1)
+    deg = np.diff(rowptr)
+    x0 = g.standard_normal((n, d)).astype(np.float32)
+    Gs = [g.standard_normal((n, d)).astype(np.float32) for _ in range(K)]
+    Ps, x = [], x0
+    xd = x0.astype(np.float64)              # exact recursion carried alongside
+    for k in range(K):
+        t = g.standard_exponential(n).astype(np.float32)
+        b = g.integers(0, deg + 1).astype(np.int32)
+        mask, p, _ = orc.select(rowptr, colidx, t, b)
+        Ps.append(orc.dense_P(rowptr, colidx, mask, p))
+        x = orc.round_(rowptr, colidx, mask, p, x, Gs[k], lr, 1)
+    # rows are workers, so the paper's right-multiplication becomes left-multiplication
+    prod = lambda s: np.linalg.multi_dot([np.eye(n)] + [Ps[k] for k in range(K - 1, s - 1, -1)] + [np.eye(n)])
+    want = prod(0) @ xd
+    for s in range(K):
+        want -= float(lr) * prod(s) @ Gs[s].astype(np.float64)
+    assert np.allclose(x, want, rtol=1e-6, atol=1e-6)
+
+
+def test_consensus_limit(orc):
+    """Corollary 1 / Lemmas 1-2: gradient-free rounds under b = 0 on a connected graph drive
+    every worker to the (invariant) mean, geometrically."""
+    g = np.random.default_rng(43)
+    rowptr, colidx = inputs.graph_er(10, 0.3, g)
+    n, d = 10, 7
+    x = g.standard_normal((n, d)).astype(np.float32)
+    mean0 = x.astype(np.float64).mean(0)
+    mask, p, _ = orc.select(rowptr, colidx, np.zeros(n, np.float32), np.zeros(n, np.int32))
+    spread = []
+    for k in range(200):
+        x = orc.round_(rowptr, colidx, mask, p, x, None, 0.0, 0)
+        spread.append(np.abs(x - x.mean(0)).max())
+    assert spread[-1] < 1e-5 and spread[50] < spread[0] * 0.5
+    assert np.allclose(x.astype(np.float64).mean(0), mean0, atol=1e-5)
+    assert np.allclose(x, mean0, atol=2e-5)
+
+
+def test_convexity_and_constants(orc):
+    """lr = 0: each output component lies within [min, max] over S_i and i itself, and a
+    constant field is a fixed point (rows of P sum to one, also for asymmetric masks)."""
+    g = np.random.default_rng(47)
+    for rowptr, colidx in graphs():
+        n, d = rowptr.size - 1, 13
+        deg = np.diff(rowptr)
+        x = g.standard_normal((n, d)).astype(np.float32)
+        t = g.standard_exponential(n).astype(np.float32)
+        b = g.integers(0, deg + 1).astype(np.int32)
+        mask, p, _ = orc.select(rowptr, colidx, t, b)
+        for order in (0, 1):
+            out = orc.round_(rowptr, colidx, mask, p, x, np.ones_like(x), 0.0, order)
+            for i in range(n):
+                idx = [i] + [int(colidx[e]) for e in range(rowptr[i], rowptr[i + 1]) if mask[e]]
+                assert np.all(out[i] <= x[idx].max(0) + 1e-6) and np.all(out[i] >= x[idx].min(0) - 1e-6)
+            const = np.full((n, d), 3.25, np.float32)
+            assert np.allclose(orc.round_(rowptr, colidx, mask, p, const, None, 0.0, order), 3.25, atol=1e-6)
+
+
+def test_padding_and_column_slices(orc):
+    """Columns are independent: a column slice of the output equals the output of the
+    slice; columns at or beyond d are not written."""
+    g = np.random.default_rng(53)
+    rowptr, colidx = inputs.graph_regular(12, 4, g)
+    n, d, ld = 12, 50, 64
+    x = g.standard_normal((n, ld)).astype(np.float32)
+    gr = g.standard_normal((n, ld)).astype(np.float32)
+    mask, p, _ = orc.select(rowptr, colidx, g.standard_exponential(n).astype(np.float32),
+                            g.integers(0, 5, n).astype(np.int32))
+    full = orc.round_(rowptr, colidx, mask, p, x, gr, 0.05, 0, d=d)
+    assert not full[:, d:].any()
+    part = orc.round_(rowptr, colidx, mask, p, x[:, 10:30], gr[:, 10:30], 0.05, 0)
+    assert np.array_equal(full[:, 10:30], part)
