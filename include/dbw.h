@@ -1,0 +1,186 @@
+/*
+ * dbw - consensus-based distributed SGD with dynamic backup workers, one training round
+ * for all N simulated workers at once on one AMD MI355X (gfx950).
+ *
+ * C ABI.  Pointers are tagged "host" or "dev" (device memory, HIP).  `stream` is a
+ * hipStream_t passed as void* (NULL = the default stream).  Every function returns an
+ * int: DBW_OK or a negative DBW_ERR_* code; nothing throws across this boundary.  No
+ * function synchronises the stream unless its comment says so.  The library never frees
+ * or keeps caller memory except where stated; caller arrays must stay valid until the
+ * stream work that uses them has completed.
+ *
+ * Layout.  Worker i's parameter vector is row i of a row-major [N][ld] float array,
+ * d <= ld; columns [d, ld) are padding that the library never reads into results and
+ * never writes.  This is the transpose of the paper's d x N matrix W(k) (Section 2.2),
+ * so the paper's right-multiplication by the consensus matrix P(k) becomes a
+ * left-multiplication: X' = P X with row i of P holding worker i's weights.
+ * Inside a row the model parameters are stored layer by layer, weight [out][in]
+ * (convolutions [Cout][Cin][kh][kw]) followed by the bias [out].
+ *
+ * Graph.  The communication graph G = (N, E) of Section 2.1 is given in CSR form
+ * without self loops: the neighbours of worker i are colidx[rowptr[i] .. rowptr[i+1]),
+ * strictly ascending; the graph must be symmetric and connected.  deg_i is the row
+ * length; the paper's neighbourhood N_i is that row plus i itself.
+ */
+#ifndef DBW_H
+#define DBW_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dbw_ctx dbw_ctx; /* opaque, owned by the library */
+
+enum {
+    DBW_OK = 0,
+    DBW_ERR_NULL = -1,        /* a required pointer is NULL */
+    DBW_ERR_INVALID = -2,     /* bad N, d, ld, model description, or b_i outside [0, deg_i] */
+    DBW_ERR_GRAPH = -3,       /* CSR unsorted / asymmetric / self loop / out of range / disconnected */
+    DBW_ERR_ALIAS = -4,       /* params_in overlaps params_out */
+    DBW_ERR_STATE = -5,       /* dbw_round or dbw_get_selection before any dbw_select */
+    DBW_ERR_ALLOC = -6,       /* device or host allocation failed */
+    DBW_ERR_HIP = -7,         /* a HIP call failed */
+    DBW_ERR_UNSUPPORTED = -8  /* combination not implemented (e.g. dense mixing for N > 256) */
+};
+
+/* Order of averaging and local step inside one round. */
+enum {
+    /* x_i' = sum_j P_ij x_j - lr g(x_i): average the neighbours' estimates, then correct
+     * with the gradient taken at the pre-average point (Section 2.1, the
+     * full-participation update; the abstract describes the same order). */
+    DBW_ORDER_CTA = 0,
+    /* x~_j = x_j - lr g(x_j) for all j, then x_i' = sum_j P_ij x~_j (Section 2.2, the
+     * local update followed by the partial consensus update; Algorithm 1). */
+    DBW_ORDER_ATC = 1
+};
+
+/* How the masked consensus average is evaluated. */
+enum {
+    DBW_MIX_AUTO = 0,  /* dense when N <= 256 and the graph holds more than N*N/4 links */
+    DBW_MIX_CSR = 1,   /* gather over the selected neighbours only (HBM bound) */
+    DBW_MIX_DENSE = 2  /* materialise P(k) as N x N and multiply on the matrix cores */
+};
+
+enum {
+    DBW_MODEL_NONE = 0, /* gradients are supplied by the caller (ext_grads) */
+    DBW_MODEL_MLP = 1,  /* fully connected dims[0] -> ... -> dims[n_layers], ReLU between
+                           layers, softmax cross-entropy; n_layers = 1 is multinomial
+                           logistic regression (the LRM of Section 5) */
+    DBW_MODEL_CNN = 2   /* conv KxK (C0->C1, same padding) ReLU maxpool2, conv KxK (C1->C2)
+                           ReLU maxpool2, flatten, FC F ReLU, FC classes, cross-entropy;
+                           dims = {C0, H, W, C1, C2, K, F, classes} */
+};
+
+typedef struct {
+    int32_t kind;     /* DBW_MODEL_* */
+    int32_t batch;    /* samples per worker per round (|C_j(k)| of Section 2.1) */
+    int32_t n_layers; /* MLP only */
+    int32_t dims[9];
+} dbw_model;
+
+typedef struct {
+    int64_t ld;       /* row stride in floats, >= d; 0 means d */
+    int32_t order;    /* DBW_ORDER_* */
+    int32_t mix_path; /* DBW_MIX_* */
+    dbw_model model;
+} dbw_opts;
+
+/* Create a context for N workers with d parameters each on the current HIP device.
+ * rowptr [host, N+1] and colidx [host, rowptr[N]] are validated (DBW_ERR_GRAPH) and
+ * copied; the caller may free them afterwards.  opts may be NULL (ld = d, CTA order,
+ * automatic mixing path, no model).  With a model, d must equal the model's parameter
+ * count.  The link set for dbw_dtur_b (a breadth-first spanning tree from worker 0,
+ * neighbours in ascending index, N - 1 links; Section 4.1) is built here.  Allocates the
+ * context's device scratch; synchronous. */
+int dbw_create(dbw_ctx **out, int32_t N, int64_t d, const int32_t *rowptr, const int32_t *colidx,
+               const dbw_opts *opts);
+
+/* Fastest-neighbour selection for one round (Section 1 "Dynamic Backup Workers",
+ * Section 2.2): worker i waits for the p_i = deg_i - b_i neighbours with the smallest
+ * response times and treats the other b_i as backups.  Neighbours are ordered by
+ * (time, index) under IEEE comparison, NaN counting as +inf, so ties go to the lower
+ * index.  Also prepares the Metropolis weights of Assumption 1,
+ * P_ij = 1 / (1 + max(p_i, p_j)) for selected j, P_ii = 1 - sum_j P_ij, for the next
+ * dbw_round.  resp_times [dev, N] float, b [dev, N] int32.  A b_i outside [0, deg_i] is
+ * clamped for memory safety and recorded; dbw_get_selection / dbw_check report it as
+ * DBW_ERR_INVALID.  Asynchronous on `stream`. */
+int dbw_select(dbw_ctx *ctx, const float *resp_times, const int32_t *b, void *stream);
+
+/* Backup counts from the distributed threshold-based update rule (Section 4.1,
+ * Algorithm 2): theta = the earliest time max(t_u, t_v) at which a link (u, v) of the
+ * link set that was not yet visited in the current epoch is established (lowest link id
+ * on ties); that link is marked visited, and after all N - 1 links have been visited the
+ * set is emptied.  A worker with t_j <= theta waits for exactly its neighbours with
+ * t_i <= theta, any other worker for nobody: b_out[j] = deg_j - |S_j|.  Feed b_out to
+ * dbw_select.  The epoch state lives in the context (dbw_dtur_reset empties it).
+ * resp_times [dev, N], b_out [dev, N], theta_out [dev, 1] or NULL.  Asynchronous. */
+int dbw_dtur_b(dbw_ctx *ctx, const float *resp_times, int32_t *b_out, float *theta_out, void *stream);
+int dbw_dtur_reset(dbw_ctx *ctx, void *stream);
+
+/* Copy out the last selection: p [dev, N] int32 (number of neighbours waited for),
+ * mask [dev, nnz] uint8 aligned with colidx (1 = selected), wait_time [dev, N] float
+ * (T_i = max(t_i, max over selected t_j), Section 3.2.2); each may be NULL.
+ * Synchronises the stream and returns DBW_ERR_INVALID if the last dbw_select saw an
+ * out-of-range b_i. */
+int dbw_get_selection(dbw_ctx *ctx, int32_t *p, uint8_t *mask, float *wait_time, void *stream);
+
+/* Copy out the dense consensus matrix P(k) [dev, N*N] float, row i = worker i's weights,
+ * built from the last selection.  Synchronises the stream. */
+int dbw_get_weights(dbw_ctx *ctx, float *P, void *stream);
+
+/* One training round for all N workers (Algorithm 1, one pass of its loop body):
+ * mini-batch gradient of every worker at its own parameters (Section 2.1), masked
+ * consensus average with the weights of the last dbw_select (Assumption 1, Section 2.2)
+ * and the local SGD step, in the order chosen at create.
+ *   params_in  [dev, N*ld]  read only
+ *   params_out [dev, N*ld]  written in columns [0, d); must not overlap params_in
+ *   batch_x    [dev, N*batch*in] float, batch_y [dev, N*batch] int32 labels in
+ *              [0, classes): used iff the context has a model
+ *   ext_grads  [dev, N*ld]: used iff the context has no model; NULL there means a
+ *              gradient-free consensus round (the truncated model of Section 3.2.1)
+ *   loss_out   [dev, N] float mean loss per worker, or NULL
+ * Asynchronous on `stream`. */
+int dbw_round(dbw_ctx *ctx, const float *params_in, float *params_out, const float *batch_x,
+              const int32_t *batch_y, const float *ext_grads, float *loss_out, float lr, void *stream);
+
+/* Mini-batch gradients only (the first step of dbw_round), written to grads [dev, N*ld]
+ * in columns [0, d).  Needs a model.  Asynchronous. */
+int dbw_grad(dbw_ctx *ctx, const float *params, const float *batch_x, const int32_t *batch_y,
+             float *grads, float *loss_out, void *stream);
+
+/* Synchronise `stream` and return the deferred device-side status (DBW_OK or
+ * DBW_ERR_INVALID), clearing it. */
+int dbw_check(dbw_ctx *ctx, void *stream);
+
+/* Link set used by dbw_dtur_b: edges [host, 2*(N-1)] int32 as (u, v) pairs in link-id
+ * order.  Returns N - 1 (or a negative error). */
+int dbw_get_links(dbw_ctx *ctx, int32_t *edges);
+
+/* Which mixing path the context resolved to (DBW_MIX_CSR or DBW_MIX_DENSE). */
+int dbw_mix_path(const dbw_ctx *ctx);
+
+/* Release the context and its device memory.  NULL is a no-op returning DBW_OK.
+ * Synchronises the device. */
+int dbw_destroy(dbw_ctx *ctx);
+
+const char *dbw_strerror(int code);
+
+/* Names and average durations (milliseconds, measured with HIP events on the launch
+ * stream) of the kernels of the most recent dbw_round when timing was switched on with
+ * dbw_set_timing(ctx, 1); used to report achieved bandwidth / FLOP rate per kernel.
+ * dbw_get_timing synchronises, writes up to `cap` entries and returns the entry count. */
+typedef struct {
+    const char *name;
+    double ms_total;
+    int64_t launches;
+} dbw_kernel_time;
+int dbw_set_timing(dbw_ctx *ctx, int32_t on);
+int dbw_get_timing(dbw_ctx *ctx, dbw_kernel_time *out, int32_t cap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DBW_H */

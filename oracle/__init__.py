@@ -31,6 +31,7 @@ def lib():
     global _lib
     if _lib is None:
         build()
+        os.environ.setdefault("OMP_WAIT_POLICY", "passive")   # idle workers sleep instead of spinning
         _lib = C.CDLL(_LIB)
         _lib.orc_select.restype = C.c_int
         _lib.orc_spanning_tree.restype = C.c_int
@@ -179,10 +180,7 @@ def model_desc(desc):
     return 1, np.array([c, h, w, desc["c1"], desc["c2"], desc["k"], desc["fc"], desc["classes"]], dtype=np.int32)
 
 
-def n_threads() -> int:
-    """Threads the OpenMP loops over workers will use."""
-    try:
-        omp = C.CDLL("libgomp.so.1")
-        return int(omp.omp_get_max_threads())
-    except OSError:
-        return 1
+def set_threads(n: int) -> int:
+    """Threads for the loops over workers (default 1); returns the value in force."""
+    lib().orc_set_threads(int(n))
+    return int(lib().orc_get_threads())

@@ -38,6 +38,12 @@
 #include <stdlib.h>
 #include <string.h>
 
+/* Threads for the loops over workers (the only parallelism here); 1 unless a timing run
+ * asks for more. */
+static int orc_threads = 1;
+void orc_set_threads(int n) { orc_threads = n > 0 ? n : 1; }
+int orc_get_threads(void) { return orc_threads; }
+
 #define ORC_OK 0
 #define ORC_ERR_INVALID (-2)
 #define ORC_ERR_GRAPH (-3)
@@ -135,7 +141,7 @@ void orc_round(int N, int64_t d, int64_t ld, const int32_t *rowptr, const int32_
     double *ws = (double *)malloc(sizeof(double) * (size_t)N);
     orc_weights(N, rowptr, colidx, mask, p, we, ws);
     const double eta = (double)lr;
-#pragma omp parallel for schedule(static)
+#pragma omp parallel for schedule(static) num_threads(orc_threads)
     for (int i = 0; i < N; ++i) {
         const float *xi = x + (size_t)i * ld;
         const float *gi = g ? g + (size_t)i * ld : NULL;
@@ -482,7 +488,7 @@ void orc_grad_all(int kind, const int32_t *desc, int N, int64_t d, int64_t ld, i
                   int64_t in_dim, const float *params, const float *x, const int32_t *y,
                   float *grad, double *loss /* N, nullable */)
 {
-#pragma omp parallel for schedule(dynamic, 1)
+#pragma omp parallel for schedule(dynamic, 1) num_threads(orc_threads)
     for (int i = 0; i < N; ++i) {
         float *gi = grad + (size_t)i * ld;
         double li = 0.0;

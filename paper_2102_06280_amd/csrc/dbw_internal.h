@@ -1,0 +1,86 @@
+// Internal declarations shared by the library's translation units (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "dbw.h"
+
+#define DBW_HIP(call)                                   \
+    do {                                                \
+        hipError_t e_ = (call);                         \
+        if (e_ != hipSuccess) return DBW_ERR_HIP;       \
+    } while (0)
+
+constexpr int DBW_DENSE_MAX_N = 256;   // the dense mixing kernel keeps all of P(k) in registers
+constexpr int DBW_SELECT_LDS_KEYS = 2048;
+
+struct dbw_timing_slot {
+    const char *name;
+    hipEvent_t start, stop;
+};
+
+struct dbw_ctx {
+    int32_t N = 0;
+    int64_t d = 0, ld = 0;
+    int32_t nnz = 0, max_deg = 0;
+    int32_t order = DBW_ORDER_CTA;
+    int32_t mix = DBW_MIX_CSR;
+    int32_t Npad = 0;                 // N rounded up to 32 (dense path)
+    dbw_model model{};
+    int64_t in_dim = 0;               // floats per sample
+    bool selected = false;
+
+    std::vector<int32_t> h_rowptr, h_colidx, h_links;
+
+    // device: graph
+    int32_t *rowptr = nullptr, *colidx = nullptr;
+    // device: selection state of the current round
+    int32_t *p = nullptr;             // [N]
+    uint8_t *mask = nullptr;          // [nnz]
+    float *wait = nullptr;            // [N]
+    int32_t *sel_idx = nullptr;       // [nnz] row i: first p_i entries = selected neighbours, ascending
+    float *sel_w = nullptr;           // [nnz] their weights
+    float *self_w = nullptr;          // [N]
+    float *Wdense = nullptr;          // [Npad*Npad] row-major (dense path only)
+    int32_t *err = nullptr;           // [1] deferred status
+    // device: threshold rule
+    int32_t *links = nullptr;         // [2*(N-1)]
+    uint8_t *visited = nullptr;       // [N-1]
+    int32_t *n_visited = nullptr;     // [1]
+    // device: model scratch
+    float *grads = nullptr;           // [N*ld] when a model is attached
+    float *act = nullptr;             // activations / deltas
+    size_t act_floats = 0;
+
+    // timing
+    bool timing = false;
+    std::vector<dbw_timing_slot> slots;
+    std::vector<hipEvent_t> free_events;
+};
+
+struct dbw_timer {
+    dbw_ctx *c;
+    hipStream_t s;
+    hipEvent_t stop = nullptr;
+    dbw_timer(dbw_ctx *ctx, const char *name, hipStream_t st);
+    ~dbw_timer();
+};
+
+// select.hip
+int dbw_launch_select(dbw_ctx *c, const float *t, const int32_t *b, hipStream_t s);
+int dbw_launch_dtur(dbw_ctx *c, const float *t, int32_t *b_out, float *theta_out, hipStream_t s);
+// mix_csr.hip
+int dbw_launch_mix_csr(dbw_ctx *c, const float *x, const float *g, float *out, float lr, hipStream_t s);
+// mix_dense.hip
+int dbw_launch_mix_dense(dbw_ctx *c, const float *x, const float *g, float *out, float lr, hipStream_t s);
+// grad_mlp.hip / grad_cnn.hip
+size_t dbw_mlp_scratch_floats(const dbw_ctx *c);
+int dbw_launch_grad_mlp(dbw_ctx *c, const float *params, const float *bx, const int32_t *by, float *grads,
+                        float *loss, hipStream_t s);
+size_t dbw_cnn_scratch_floats(const dbw_ctx *c);
+int dbw_launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const int32_t *by, float *grads,
+                        float *loss, hipStream_t s);

@@ -1,0 +1,3 @@
+#include "dbw_internal.h"
+size_t dbw_cnn_scratch_floats(const dbw_ctx *) { return 1; }
+int dbw_launch_grad_cnn(dbw_ctx *, const float *, const float *, const int32_t *, float *, float *, hipStream_t) { return DBW_ERR_UNSUPPORTED; }

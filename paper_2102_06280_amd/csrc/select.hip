@@ -1,0 +1,200 @@
+// Fastest-neighbour selection, Metropolis weights and the threshold rule.
+//
+// Selection (Section 1 "Dynamic Backup Workers", Section 2.2): worker i waits for the
+// p_i = deg_i - b_i neighbours that answer first; the rest are backups.  One 64-lane
+// wavefront per worker ranks the row's neighbours by the 64-bit key (time, index): a
+// neighbour is selected iff fewer than p_i keys in the row are smaller than its own.
+// Keys are distinct (indices are), so the ranks form a permutation and the result does
+// not depend on any scheduling order.
+//
+// Weights (Assumption 1): P_ij = 1/(1 + max(p_i, p_j)) for selected j, P_ii = 1 - sum.
+#include "dbw_internal.h"
+
+namespace {
+
+// Monotone map from float to uint32 under IEEE ordering, with NaN -> +inf and -0 -> +0.
+__device__ __forceinline__ float canon_time(float t)
+{
+    return (t != t) ? __builtin_inff() : (t == 0.0f ? 0.0f : t);
+}
+
+__device__ __forceinline__ uint32_t sortable(float t)
+{
+    uint32_t u = __float_as_uint(canon_time(t));
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__device__ __forceinline__ uint64_t make_key(float t, int32_t j)
+{
+    return ((uint64_t)sortable(t) << 32) | (uint32_t)j;
+}
+
+__device__ __forceinline__ int clamp_b(int b, int deg) { return b < 0 ? 0 : (b > deg ? deg : b); }
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+__device__ __forceinline__ float wave_max(float v)
+{
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// grid = N blocks of one wavefront.
+__global__ __launch_bounds__(64) void select_kernel(
+    int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
+    const float *__restrict__ t, const int32_t *__restrict__ b, int32_t *__restrict__ p_out,
+    uint8_t *__restrict__ mask, float *__restrict__ wait, int32_t *__restrict__ sel_idx,
+    float *__restrict__ sel_w, float *__restrict__ self_w, float *__restrict__ Wdense, int Npad,
+    int32_t *__restrict__ err)
+{
+    __shared__ uint64_t keys[DBW_SELECT_LDS_KEYS];
+    __shared__ float wrow[DBW_DENSE_MAX_N];
+    const int i = blockIdx.x, lane = threadIdx.x;
+    const int beg = rowptr[i], deg = rowptr[i + 1] - beg;
+    const int bi_raw = b[i];
+    if ((bi_raw < 0 || bi_raw > deg) && lane == 0) *err = DBW_ERR_INVALID;
+    const int pi = deg - clamp_b(bi_raw, deg);
+    const bool in_lds = deg <= DBW_SELECT_LDS_KEYS;
+
+    if (in_lds)
+        for (int k = lane; k < deg; k += 64) {
+            int j = colidx[beg + k];
+            keys[k] = make_key(t[j], j);
+        }
+    if (Wdense)
+        for (int c = lane; c < Npad; c += 64) wrow[c] = 0.0f;
+    __syncthreads();
+
+    float wsum = 0.0f, tmax = canon_time(t[i]);
+    int base = 0;
+    for (int k0 = 0; k0 < deg; k0 += 64) {
+        const int k = k0 + lane;
+        bool sel = false;
+        int j = 0;
+        float w = 0.0f;
+        if (k < deg) {
+            j = colidx[beg + k];
+            const float tj = t[j];
+            const uint64_t mine = make_key(tj, j);
+            int rank = 0;
+            if (in_lds) {
+                for (int m = 0; m < deg; ++m) rank += keys[m] < mine ? 1 : 0;
+            } else {
+                for (int m = 0; m < deg; ++m) {
+                    int jm = colidx[beg + m];
+                    rank += make_key(t[jm], jm) < mine ? 1 : 0;
+                }
+            }
+            sel = rank < pi;
+            mask[beg + k] = sel ? 1 : 0;
+            if (sel) {
+                const int degj = rowptr[j + 1] - rowptr[j];
+                const int pj = degj - clamp_b(b[j], degj);
+                w = 1.0f / (1.0f + (float)(pi > pj ? pi : pj));
+                wsum += w;
+                tmax = fmaxf(tmax, canon_time(tj));
+            }
+        }
+        // compact the selected neighbours of this 64-wide slice, keeping ascending order
+        const uint64_t ballot = __ballot(sel);
+        if (sel) {
+            const int pos = base + __popcll(ballot & ((1ull << lane) - 1ull));
+            sel_idx[beg + pos] = j;
+            sel_w[beg + pos] = w;
+            if (Wdense) wrow[j] = w;
+        }
+        base += __popcll(ballot);
+    }
+    wsum = wave_sum(wsum);
+    tmax = wave_max(tmax);
+    const float ws = 1.0f - wsum;
+    if (lane == 0) {
+        p_out[i] = pi;
+        wait[i] = tmax;
+        self_w[i] = ws;
+    }
+    if (Wdense) {
+        __syncthreads();
+        if (lane == 0) wrow[i] = ws;
+        __syncthreads();
+        for (int c = lane; c < Npad; c += 64) Wdense[(size_t)i * Npad + c] = wrow[c];
+    }
+}
+
+// Rows [N, Npad) of the padded dense matrix stay zero: written once at create.
+
+// Threshold rule and the d-iteration procedure (Section 4.1, Algorithm 2); one block.
+// A link (u, v) is established at max(t_u, t_v).  theta = the smallest establishment
+// time over links not yet visited in this epoch, lowest link id on ties.
+__global__ __launch_bounds__(256) void dtur_kernel(
+    int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx, int n_links,
+    const int32_t *__restrict__ links, uint8_t *__restrict__ visited, int32_t *__restrict__ n_visited,
+    const float *__restrict__ t, int32_t *__restrict__ b_out, float *__restrict__ theta_out)
+{
+    __shared__ uint64_t red[256];
+    const int tid = threadIdx.x;
+    const bool fresh = *n_visited >= n_links;   // previous epoch complete: P' starts empty
+    uint64_t best = ~0ull;
+    for (int e = tid; e < n_links; e += 256) {
+        if (!fresh && visited[e]) continue;
+        const float est = fmaxf(canon_time(t[links[2 * e]]), canon_time(t[links[2 * e + 1]]));
+        const uint64_t key = make_key(est, e);
+        best = key < best ? key : best;
+    }
+    red[tid] = best;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if (tid < o) red[tid] = red[tid + o] < red[tid] ? red[tid + o] : red[tid];
+        __syncthreads();
+    }
+    best = red[0];
+    float theta = __builtin_inff();
+    int chosen = -1;
+    if (best != ~0ull) {
+        chosen = (int)(uint32_t)best;
+        theta = fmaxf(canon_time(t[links[2 * chosen]]), canon_time(t[links[2 * chosen + 1]]));
+    }
+    __syncthreads();    // every thread has read n_visited / visited before they change
+    if (fresh)
+        for (int e = tid; e < n_links; e += 256) visited[e] = 0;
+    __syncthreads();
+    if (tid == 0) {
+        if (chosen >= 0) visited[chosen] = 1;
+        *n_visited = (fresh ? 0 : *n_visited) + (chosen >= 0 ? 1 : 0);
+        if (theta_out) *theta_out = theta;
+    }
+    for (int j = tid; j < N; j += 256) {
+        const int beg = rowptr[j], end = rowptr[j + 1];
+        int bj = end - beg;
+        if (canon_time(t[j]) <= theta) {
+            int cnt = 0;
+            for (int e = beg; e < end; ++e) cnt += canon_time(t[colidx[e]]) <= theta ? 1 : 0;
+            bj -= cnt;
+        }
+        b_out[j] = bj;
+    }
+}
+
+}  // namespace
+
+int dbw_launch_select(dbw_ctx *c, const float *t, const int32_t *b, hipStream_t s)
+{
+    dbw_timer tm(c, "select_kernel", s);
+    hipLaunchKernelGGL(select_kernel, dim3(c->N), dim3(64), 0, s, c->N, c->rowptr, c->colidx, t, b, c->p,
+                       c->mask, c->wait, c->sel_idx, c->sel_w, c->self_w, c->Wdense, c->Npad, c->err);
+    DBW_HIP(hipGetLastError());
+    return DBW_OK;
+}
+
+int dbw_launch_dtur(dbw_ctx *c, const float *t, int32_t *b_out, float *theta_out, hipStream_t s)
+{
+    dbw_timer tm(c, "dtur_kernel", s);
+    hipLaunchKernelGGL(dtur_kernel, dim3(1), dim3(256), 0, s, c->N, c->rowptr, c->colidx, c->N - 1, c->links,
+                       c->visited, c->n_visited, t, b_out, theta_out);
+    DBW_HIP(hipGetLastError());
+    return DBW_OK;
+}

@@ -70,22 +70,32 @@ def graph_complete(n: int):
 
 
 def graph_regular(n: int, k: int, g: np.random.Generator):
-    """Random simple connected k-regular graph (pairing model, redrawn until valid)."""
+    """Random simple connected k-regular graph: a circulant k-regular graph randomised by
+    degree-preserving double edge swaps (a-b, c-d -> a-d, c-b), redone until connected."""
     assert (n * k) % 2 == 0 and k < n
     while True:
-        stubs = np.repeat(np.arange(n), k)
-        g.shuffle(stubs)
-        a, b = stubs[0::2], stubs[1::2]
-        if np.any(a == b):
-            continue
         adj = np.zeros((n, n), dtype=bool)
-        ok = True
-        for u, v in zip(a, b):
-            if adj[u, v]:
-                ok = False
-                break
-            adj[u, v] = adj[v, u] = True
-        if ok and _connected(adj):
+        for i in range(n):
+            for s in range(1, k // 2 + 1):
+                adj[i, (i + s) % n] = adj[(i + s) % n, i] = True
+            if k % 2:
+                adj[i, (i + n // 2) % n] = adj[(i + n // 2) % n, i] = True
+        edges = [(i, j) for i in range(n) for j in range(i + 1, n) if adj[i, j]]
+        m = len(edges)
+        picks = g.integers(0, m, size=(20 * m, 2))
+        flips = g.integers(0, 2, size=20 * m)
+        for (e1, e2), f in zip(picks, flips):
+            a, b = edges[e1]
+            c, d = edges[e2]
+            if f:
+                c, d = d, c
+            if len({a, b, c, d}) < 4 or adj[a, d] or adj[c, b]:
+                continue
+            adj[a, b] = adj[b, a] = adj[c, d] = adj[d, c] = False
+            adj[a, d] = adj[d, a] = adj[c, b] = adj[b, c] = True
+            edges[e1], edges[e2] = (a, d), (c, b)
+        assert np.all(adj.sum(1) == k)
+        if _connected(adj):
             return _csr_from_adj(adj)
 
 

@@ -1,0 +1,186 @@
+"""GPU parity: selection (bit-exact), Metropolis weights, sparse masked average + SGD step
+against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2102_06280_amd import inputs
+from gpu_util import assert_params_close, dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2102_06280_amd import binding
+    return binding
+
+
+def gpu_select(B, h, rowptr, colidx, t, b):
+    n, nnz = rowptr.size - 1, colidx.size
+    B.dbw_select(h, dev(t), dev(b))
+    p = torch.empty(n, dtype=torch.int32, device="cuda")
+    mask = torch.empty(max(nnz, 1), dtype=torch.uint8, device="cuda")
+    wait = torch.empty(n, dtype=torch.float32, device="cuda")
+    B.dbw_get_selection(h, p, mask, wait)
+    return mask.cpu().numpy()[:nnz], p.cpu().numpy(), wait.cpu().numpy()
+
+
+def graphs():
+    g = np.random.default_rng(101)
+    return [("ring8", inputs.graph_ring(8)), ("complete5", inputs.graph_complete(5)),
+            ("er40", inputs.graph_er(40, 0.2, g)), ("reg4x32", inputs.graph_regular(32, 4, g)),
+            ("complete100", inputs.graph_complete(100)), ("complete256", inputs.graph_complete(256)),
+            ("reg8x128", inputs.graph_regular(128, 8, g))]
+
+
+@pytest.mark.parametrize("name,graph", graphs(), ids=[n for n, _ in graphs()])
+def test_selection_bit_exact(B, orc, name, graph):
+    rowptr, colidx = graph
+    n = rowptr.size - 1
+    deg = np.diff(rowptr)
+    g = np.random.default_rng(103)
+    h = B.dbw_create(rowptr, colidx, n, 64, mix_path=B.MIX_CSR)
+    try:
+        for trial in range(6):
+            t = g.standard_exponential(n).astype(np.float32)
+            if trial % 3 == 1:
+                t = (np.round(t * 4) / 4).astype(np.float32)            # many ties
+            if trial % 3 == 2:
+                t[g.integers(0, n, max(1, n // 8))] = np.inf           # dead workers
+                t[g.integers(0, n)] = np.nan
+                t[g.integers(0, n)] = -0.0
+                t[g.integers(0, n)] = 0.0
+            b = g.integers(0, deg + 1).astype(np.int32)
+            if trial == 4:
+                b[:] = 0
+            if trial == 5:
+                b[:] = deg
+            mask, p, wait = gpu_select(B, h, rowptr, colidx, t, b)
+            omask, op, owait = orc.select(rowptr, colidx, t, b)
+            assert np.array_equal(mask, omask)
+            assert np.array_equal(p, op)
+            assert np.array_equal(wait, owait)
+            # weights: Assumption 1, against the oracle's double-precision matrix
+            P = torch.empty((n, n), dtype=torch.float32, device="cuda")
+            B.dbw_get_weights(h, P)
+            oP = orc.dense_P(rowptr, colidx, omask, op)
+            assert np.array_equal(P.cpu().numpy() != 0, oP != 0) or (oP.diagonal() == 0).any()
+            assert np.allclose(P.cpu().numpy(), oP, rtol=3e-7, atol=3e-7)
+    finally:
+        B.dbw_destroy(h)
+
+
+def test_select_reports_bad_backup_counts(B):
+    rowptr, colidx = inputs.graph_ring(8)
+    h = B.dbw_create(rowptr, colidx, 8, 16)
+    try:
+        t = dev(np.ones(8, np.float32))
+        for bad in (3, -1):
+            b = np.zeros(8, np.int32)
+            b[5] = bad
+            B.dbw_select(h, t, dev(b))
+            with pytest.raises(B.DbwError) as e:
+                B.dbw_check(h)
+            assert e.value.code == B.ERR_INVALID
+        B.dbw_select(h, t, dev(np.ones(8, np.int32)))
+        assert B.dbw_check(h) == 0
+    finally:
+        B.dbw_destroy(h)
+
+
+def test_round_argument_checks(B):
+    rowptr, colidx = inputs.graph_ring(8)
+    h = B.dbw_create(rowptr, colidx, 8, 64)
+    try:
+        x = torch.zeros(8, 64, device="cuda")
+        y = torch.zeros(8, 64, device="cuda")
+        with pytest.raises(B.DbwError) as e:
+            B.dbw_round(h, x, y, 0.1)
+        assert e.value.code == B.ERR_STATE
+        B.dbw_select(h, dev(np.ones(8, np.float32)), dev(np.zeros(8, np.int32)))
+        with pytest.raises(B.DbwError) as e:
+            B.dbw_round(h, x, x, 0.1)
+        assert e.value.code == B.ERR_ALIAS
+        with pytest.raises(B.DbwError) as e:
+            B.dbw_round(h, x, y, 0.1, ext_grads=y)
+        assert e.value.code == B.ERR_ALIAS
+        B.dbw_round(h, x, y, 0.1, ext_grads=None)
+        torch.cuda.synchronize()
+    finally:
+        B.dbw_destroy(h)
+
+
+CASES = [
+    # name, graph, d, ld
+    ("ring8-d7850", "ring8", 7850, 7850),          # rows not 16-byte aligned: scalar path
+    ("ring8-d7850-ld7872", "ring8", 7850, 7872),   # aligned rows + ragged tail of 2
+    ("reg4x32-d159010", "reg4x32", 159010, 159040),
+    ("er40-d5000", "er40", 5000, 5120),
+    ("reg8x128-d70001", "reg8x128", 70001, 70016),
+    ("complete100-d3000", "complete100", 3000, 3008),
+    ("ring8-d3", "ring8", 3, 4),
+    ("ring8-d1", "ring8", 1, 1),
+]
+
+
+@pytest.mark.parametrize("order", [0, 1], ids=["cta", "atc"])
+@pytest.mark.parametrize("name,gname,d,ld", CASES, ids=[c[0] for c in CASES])
+def test_sparse_round_matches_oracle(B, orc, name, gname, d, ld, order):
+    rowptr, colidx = dict(graphs())[gname]
+    n = rowptr.size - 1
+    deg = np.diff(rowptr)
+    g = np.random.default_rng(107)
+    h = B.dbw_create(rowptr, colidx, n, d, ld=ld, order=order, mix_path=B.MIX_CSR)
+    try:
+        x = g.standard_normal((n, ld)).astype(np.float32)
+        out_prev = None
+        for rnd in range(3):
+            gr = (g.standard_normal((n, ld)) * 0.01).astype(np.float32)
+            t = g.standard_exponential(n).astype(np.float32)
+            b = g.integers(0, deg + 1).astype(np.int32) if rnd else np.zeros(n, np.int32)
+            lr = np.float32(0.05)
+            dx, dg = dev(x), dev(gr)
+            dout = torch.full((n, ld), 7.0, dtype=torch.float32, device="cuda")
+            B.dbw_select(h, dev(t), dev(b))
+            B.dbw_round(h, dx, dout, lr, ext_grads=dg if rnd < 2 else None)
+            got = dout.cpu().numpy()
+            mask, p, _ = orc.select(rowptr, colidx, t, b)
+            want = orc.round_(rowptr, colidx, mask, p, x, gr if rnd < 2 else None, lr, order, d=d)
+            assert_params_close(got, want, d=d, what=f"{name} round {rnd}")
+            assert np.all(got[:, d:] == 7.0)                 # padding untouched
+            # determinism: same inputs again give the same bits
+            dout2 = torch.full((n, ld), 7.0, dtype=torch.float32, device="cuda")
+            B.dbw_round(h, dx, dout2, lr, ext_grads=dg if rnd < 2 else None)
+            assert torch.equal(dout, dout2)
+            x = want                                          # lock-step with the oracle
+            x[:, d:] = 0
+    finally:
+        B.dbw_destroy(h)
+
+
+def test_isolated_and_dead_workers(B, orc):
+    """b_i = deg_i keeps only the local step (P_ii = 1); a worker with t = +inf is never
+    waited for while enough live neighbours exist."""
+    rowptr, colidx = inputs.graph_complete(6)
+    n, d = 6, 128
+    g = np.random.default_rng(109)
+    x = g.standard_normal((n, d)).astype(np.float32)
+    gr = g.standard_normal((n, d)).astype(np.float32)
+    t = np.array([0.3, np.inf, 0.1, 0.2, 0.5, 0.4], np.float32)
+    b = np.array([5, 1, 1, 2, 3, 4], np.int32)
+    h = B.dbw_create(rowptr, colidx, n, d, mix_path=B.MIX_CSR)
+    try:
+        out = torch.empty(n, d, device="cuda")
+        B.dbw_select(h, dev(t), dev(b))
+        B.dbw_round(h, dev(x), out, 0.5, ext_grads=dev(gr))
+        got = out.cpu().numpy()
+        assert np.allclose(got[0], x[0] - 0.5 * gr[0], rtol=1e-6, atol=1e-6)
+        mask = torch.empty(30, dtype=torch.uint8, device="cuda")
+        B.dbw_get_selection(h, None, mask, None)
+        m = mask.cpu().numpy()
+        assert not m[colidx == 1].any()
+        om, op, _ = orc.select(rowptr, colidx, t, b)
+        assert_params_close(got, orc.round_(rowptr, colidx, om, op, x, gr, 0.5, 0))
+    finally:
+        B.dbw_destroy(h)
