@@ -1,0 +1,169 @@
+#!/usr/bin/env python3
+"""Benchmark of one training round (selection + masked consensus average + local SGD step,
+plus the per-worker gradients where the configuration has a model) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C]
+
+A step is one pass of the whole hot path over one round of synthetic input that is already
+resident in HBM.  Prints one JSON line.  The default workload is the consensus-only stress
+configuration (128 workers, 8-regular graph, d = 11.2 M), the one the averaging-bandwidth
+metric is quoted on.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix
+
+
+def cpu_baseline(cid: int, wl_rowptr, wl_colidx, budget_s: float = 15.0):
+    """The CPU oracle, as it stands, timed on this host on a bounded sample of the same
+    workload; reported as worker-rounds/s.  Not the target, a reference point."""
+    import numpy as np
+    import oracle
+    from paper_2102_06280_amd import inputs
+
+    cfg = inputs.CONFIGS[cid]
+    threads = oracle.set_threads(min(16, os.cpu_count() or 1))
+    n = cfg.n
+    if cfg.model == "none":
+        frac = 16 if cid == 4 else 4
+        cols = cfg.d // frac
+        x = inputs.flat_params(cfg, n, cols, inputs.P_PARAMS, 1.0)
+        g = inputs.flat_params(cfg, n, cols, inputs.P_GRADS, 0.01)
+        done, t0 = 0, time.perf_counter()
+        while True:
+            t = inputs.response_times(cfg, done)
+            b = inputs.backup_counts(cfg, done, wl_rowptr)
+            t1 = time.perf_counter()
+            mask, p, _ = oracle.select(wl_rowptr, wl_colidx, t, b)
+            x = oracle.round_(wl_rowptr, wl_colidx, mask, p, x, g, cfg.lr, 0)
+            dt = time.perf_counter() - t1
+            done += 1
+            if done == 1:
+                per_round = dt
+            else:
+                per_round = min(per_round, dt)
+            if time.perf_counter() - t0 > budget_s or done >= 4:
+                break
+        value = n / (per_round * frac)
+        sample = f"{done} rounds on the first d/{frac} = {cols} columns (columns are independent), time scaled x{frac}"
+    else:
+        desc = inputs.model_dims(cfg.model)
+        kind, od = oracle.model_desc(desc)
+        ld = inputs.pad_ld(cfg.d)
+        workers = list(range(min(n, threads if cid == 3 else n)))
+        x = inputs.init_params(desc, n, ld, inputs.rng(cid, inputs.P_PARAMS), zero=cfg.zero_init)
+        bx, by = inputs.batch(cfg, 0, workers=workers)
+        t1 = time.perf_counter()
+        grad, _ = oracle.grad_all(kind, od, cfg.d, x[workers], bx, by)
+        t_grad = (time.perf_counter() - t1) * n / len(workers)
+        t = inputs.response_times(cfg, 0)
+        b = np.zeros(n, np.int32)
+        g = np.zeros_like(x)
+        t1 = time.perf_counter()
+        mask, p, _ = oracle.select(wl_rowptr, wl_colidx, t, b)
+        oracle.round_(wl_rowptr, wl_colidx, mask, p, x, g, cfg.lr, 0, d=cfg.d)
+        t_mix = time.perf_counter() - t1
+        value = n / (t_grad + t_mix)
+        sample = (f"1 round: gradients of {len(workers)} of {n} workers (time scaled to {n}) "
+                  f"+ selection and averaging of all workers")
+    oracle.set_threads(1)
+    return {"value": value, "unit": "worker-rounds/s", "cores": threads, "kind": "oracle", "sample": sample}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--order", choices=["cta", "atc"], default="cta")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this implementation runs on exactly one GPU (all N workers are simulated on it); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2102_06280_amd import binding as B, inputs
+    from paper_2102_06280_amd.workload import Workload
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg = inputs.CONFIGS[args.config]
+    rounds = args.steps + args.warmup
+    wl = Workload(args.config, min(rounds, max(cfg.rounds, 8)), order=B.ORDER_ATC if args.order == "atc" else B.ORDER_CTA)
+
+    for _ in range(args.warmup):
+        wl.step()
+    B.dbw_check(wl.h)
+    B.dbw_set_timing(wl.h, True)          # HIP events around every kernel, on the launch stream
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        wl.step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    kern = B.dbw_get_timing(wl.h)
+    B.dbw_set_timing(wl.h, False)
+    B.dbw_check(wl.h)
+
+    ms_per_step = elapsed / args.steps * 1e3
+    value = cfg.n * args.steps / elapsed
+
+    mix_path = B.dbw_mix_path(wl.h)
+    dominant = max(kern, key=lambda k: kern[k][0])
+    dom_ms = kern[dominant][0] / kern[dominant][1]
+    if dominant.startswith("mix_csr"):
+        work = 3.0 * cfg.n * cfg.d * 4          # read X, read G, write X' once each
+        roofline = {"bound": "hbm", "achieved": work / (dom_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "traffic": None}
+    elif dominant.startswith("mix_dense"):
+        npad = 32
+        while npad < cfg.n:
+            npad *= 2
+        work = 2.0 * cfg.n * cfg.n * cfg.d      # dense P(k) X
+        roofline = {"bound": "mfma", "achieved": work / (dom_ms * 1e-3) / 1e12, "peak": MFMA_FP32_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "traffic": None}
+    else:
+        from paper_2102_06280_amd.flops import kernel_flops
+        work = kernel_flops(cfg, dominant)
+        roofline = {"bound": "mfma", "achieved": work / (dom_ms * 1e-3) / 1e12, "peak": MFMA_FP32_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "traffic": None}
+    roofline["frac"] = roofline["achieved"] / roofline["peak"]
+    roofline["kernel"] = dominant
+    roofline["kernel_ms"] = dom_ms
+    roofline["kernels_ms"] = {k: v[0] / v[1] for k, v in kern.items()}
+
+    out = {
+        "metric": "worker-rounds/sec", "value": value, "unit": "worker-rounds/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"config {cfg.cid}: {cfg.name}", "workers": cfg.n, "graph": cfg.graph, "d": cfg.d,
+                   "ld": wl.ld, "model": cfg.model, "batch": cfg.batch, "order": args.order,
+                   "mix_path": "dense" if mix_path == B.MIX_DENSE else "csr",
+                   "gradients": "one fixed supplied matrix, reused every round" if cfg.model == "none" else "computed"},
+        "roofline": roofline,
+    }
+    rowptr, colidx = wl.rowptr, wl.colidx
+    wl.close()
+    del wl
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.config, rowptr, colidx)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -182,7 +182,8 @@ int dbw_create(dbw_ctx **out, int32_t N, int64_t d, const int32_t *rowptr, const
         delete c;
         return DBW_ERR_UNSUPPORTED;
     }
-    c->Npad = (N + 31) / 32 * 32;
+    c->Npad = 32;                                   // dense path: padded to a power of two
+    while (c->Npad < N) c->Npad *= 2;
 
     rc = DBW_OK;
     auto A = [&](int r) { if (rc == DBW_OK) rc = r; };

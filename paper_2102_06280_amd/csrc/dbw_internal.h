@@ -29,7 +29,7 @@ struct dbw_ctx {
     int32_t nnz = 0, max_deg = 0;
     int32_t order = DBW_ORDER_CTA;
     int32_t mix = DBW_MIX_CSR;
-    int32_t Npad = 0;                 // N rounded up to 32 (dense path)
+    int32_t Npad = 0;                 // N rounded up to a power of two >= 32 (dense path)
     dbw_model model{};
     int64_t in_dim = 0;               // floats per sample
     bool selected = false;
@@ -45,7 +45,7 @@ struct dbw_ctx {
     int32_t *sel_idx = nullptr;       // [nnz] row i: first p_i entries = selected neighbours, ascending
     float *sel_w = nullptr;           // [nnz] their weights
     float *self_w = nullptr;          // [N]
-    float *Wdense = nullptr;          // [Npad*Npad] row-major (dense path only)
+    float *Wdense = nullptr;          // [Npad*Npad] in MFMA A-fragment order (dense path only)
     int32_t *err = nullptr;           // [1] deferred status
     // device: threshold rule
     int32_t *links = nullptr;         // [2*(N-1)]

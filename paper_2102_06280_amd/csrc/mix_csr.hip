@@ -111,6 +111,17 @@ __global__ __launch_bounds__(256) void mix_csr_scalar(
 }
 
 template <int ORDER, bool HAS_G>
+int launch_scalar(dbw_ctx *c, const float *x, const float *g, float *out, float lr, int64_t c_begin, hipStream_t s)
+{
+    const int64_t cols = c->d - c_begin;
+    dbw_timer tm(c, "mix_csr_scalar", s);
+    hipLaunchKernelGGL((mix_csr_scalar<ORDER, HAS_G>), dim3((unsigned)((cols + 255) / 256), c->N), dim3(256), 0, s,
+                       c->N, c_begin, c->d, c->ld, c->rowptr, c->p, c->sel_idx, c->sel_w, c->self_w, x, g, out, lr);
+    DBW_HIP(hipGetLastError());
+    return DBW_OK;
+}
+
+template <int ORDER, bool HAS_G>
 int launch(dbw_ctx *c, const float *x, const float *g, float *out, float lr, hipStream_t s)
 {
     constexpr int UNROLL = 2;
@@ -129,15 +140,7 @@ int launch(dbw_ctx *c, const float *x, const float *g, float *out, float lr, hip
                            c->self_w, (const float4 *)x, (const float4 *)g, (float4 *)out, lr);
         DBW_HIP(hipGetLastError());
     }
-    const int64_t c_begin = n_vec * 4;
-    if (c_begin < c->d) {
-        const int64_t cols = c->d - c_begin;
-        dbw_timer tm(c, "mix_csr_scalar", s);
-        hipLaunchKernelGGL((mix_csr_scalar<ORDER, HAS_G>), dim3((unsigned)((cols + 255) / 256), c->N), dim3(256), 0,
-                           s, c->N, c_begin, c->d, c->ld, c->rowptr, c->p, c->sel_idx, c->sel_w, c->self_w, x, g,
-                           out, lr);
-        DBW_HIP(hipGetLastError());
-    }
+    if (n_vec * 4 < c->d) return launch_scalar<ORDER, HAS_G>(c, x, g, out, lr, n_vec * 4, s);
     return DBW_OK;
 }
 
@@ -148,4 +151,13 @@ int dbw_launch_mix_csr(dbw_ctx *c, const float *x, const float *g, float *out, f
     if (g == nullptr) return launch<DBW_ORDER_CTA, false>(c, x, g, out, lr, s);
     if (c->order == DBW_ORDER_ATC) return launch<DBW_ORDER_ATC, true>(c, x, g, out, lr, s);
     return launch<DBW_ORDER_CTA, true>(c, x, g, out, lr, s);
+}
+
+// Scalar evaluation of columns [c_begin, d) only (the ragged tail left by a vector path).
+int dbw_launch_mix_csr_range(dbw_ctx *c, const float *x, const float *g, float *out, float lr, int64_t c_begin,
+                             hipStream_t s)
+{
+    if (g == nullptr) return launch_scalar<DBW_ORDER_CTA, false>(c, x, g, out, lr, c_begin, s);
+    if (c->order == DBW_ORDER_ATC) return launch_scalar<DBW_ORDER_ATC, true>(c, x, g, out, lr, c_begin, s);
+    return launch_scalar<DBW_ORDER_CTA, true>(c, x, g, out, lr, c_begin, s);
 }

@@ -1,3 +1,197 @@
-// placeholder, replaced below
+// Dense form of the consensus update for near-complete graphs: X' = P(k) X on the matrix
+// cores, fused with the local SGD step (Section 2.2, compact matrix form; rows are workers
+// here, so the paper's W(k) P(k) reads P X).
+//
+//   CTA: out = P X - lr G            ATC: out = P (X - lr G)
+//
+// P (N x N, zero-padded to NPAD = 32 * MB) is tiny and lives in registers: each of the 8
+// wavefronts of a workgroup keeps the A-operand fragments of one 32-row block of P for the
+// whole kernel.  The workgroup walks over column tiles of X; a tile (NPAD rows x TC
+// columns) is staged once through LDS, laid out so that the B-operand fragment of
+// v_mfma_f32_32x32x2_f32 for k-step kk is one conflict-free 64-lane row.  The next tile's
+// global loads are in flight while the current one is multiplied.  True fp32 MFMA: no
+// reduced-precision input format anywhere.
+//
+// Fragment layout of v_mfma_f32_32x32x2_f32 (M = N = 32, K = 2), lane l in [0, 64):
+//   A: a = A[m = l % 32][k = l / 32]        B: b = B[k = l / 32][n = l % 32]
+//   D: 16 floats, d[v] = D[m = 8 * (v / 4) + 4 * (l / 32) + v % 4][n = l % 32]
+#include <algorithm>
+
 #include "dbw_internal.h"
-int dbw_launch_mix_dense(dbw_ctx *, const float *, const float *, float *, float, hipStream_t) { return DBW_ERR_UNSUPPORTED; }
+
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int DENSE_THREADS = 512;
+
+template <int MB>
+struct dense_cfg {
+    static constexpr int NPAD = 32 * MB;              // padded number of workers
+    static constexpr int KB = NPAD / 2;               // k-steps of the 32x32x2 instruction
+    static constexpr int CG = 8 / MB;                 // column groups among the 8 waves
+    static constexpr int NSUB = CG > 2 ? CG : 2;      // 32-column sub-tiles per tile
+    static constexpr int SPW = NSUB / CG;             // sub-tiles per wave
+    static constexpr int TC = 32 * NSUB;              // tile columns
+    static constexpr int TILE = NPAD * TC;            // floats per LDS buffer
+    static constexpr int PASSES = TILE / 4 / DENSE_THREADS;
+};
+
+template <int MB, int ORDER, bool HAS_G>
+__global__ __launch_bounds__(DENSE_THREADS) void mix_dense_kernel(
+    int N, int64_t n_vec /* float4 columns covered */, int64_t ld4, const float *__restrict__ Wsw,
+    const float4 *__restrict__ x, const float4 *__restrict__ g, float *__restrict__ out,
+    const float *__restrict__ gs, float lr, int n_tiles)
+{
+    using C = dense_cfg<MB>;
+    __shared__ __attribute__((aligned(16))) float lds[2 * C::TILE];
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int rb = w % MB, cg = w / MB;
+    const int64_t ld = ld4 * 4, dcols = n_vec * 4;
+
+    float wreg[C::KB];
+#pragma unroll
+    for (int kk = 0; kk < C::KB; ++kk) wreg[kk] = Wsw[((size_t)(rb * C::KB + kk)) * 64 + lane];
+
+    // global -> registers for one tile
+    float4 stage[C::PASSES];
+    auto fetch = [&](int64_t tile) {
+#pragma unroll
+        for (int ps = 0; ps < C::PASSES; ++ps) {
+            const int f = ps * DENSE_THREADS + tid;
+            const int k = f / (C::TC / 4), c4 = f % (C::TC / 4);
+            const int64_t col4 = tile * (C::TC / 4) + c4;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (k < N && col4 < n_vec) {
+                v = x[(int64_t)k * ld4 + col4];
+                if (ORDER == DBW_ORDER_ATC && HAS_G) {
+                    const float4 gv = g[(int64_t)k * ld4 + col4];
+                    v.x = fmaf(-lr, gv.x, v.x);
+                    v.y = fmaf(-lr, gv.y, v.y);
+                    v.z = fmaf(-lr, gv.z, v.z);
+                    v.w = fmaf(-lr, gv.w, v.w);
+                }
+            }
+            stage[ps] = v;
+        }
+    };
+    // registers -> LDS buffer `buf`, in B-fragment order: [sub-tile][k-step][lane]
+    auto commit = [&](int buf) {
+#pragma unroll
+        for (int ps = 0; ps < C::PASSES; ++ps) {
+            const int f = ps * DENSE_THREADS + tid;
+            const int k = f / (C::TC / 4), c4 = f % (C::TC / 4);
+            const int s = c4 / 8, l = (k & 1) * 32 + (c4 & 7) * 4;
+            *(float4 *)&lds[buf * C::TILE + ((s * C::KB + (k >> 1)) * 64 + l)] = stage[ps];
+        }
+    };
+
+    int64_t tile = blockIdx.x;
+    if (tile >= n_tiles) return;
+    fetch(tile);
+    commit(0);
+    __syncthreads();
+
+    int buf = 0;
+    for (; tile < n_tiles; tile += gridDim.x) {
+        const int64_t next = tile + gridDim.x;
+        if (next < n_tiles) fetch(next);
+
+        f32x16 acc[C::SPW];
+#pragma unroll
+        for (int sp = 0; sp < C::SPW; ++sp)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[sp][v] = 0.f;
+
+        const float *bbase = &lds[buf * C::TILE + lane];
+#pragma unroll
+        for (int kk = 0; kk < C::KB; ++kk) {
+#pragma unroll
+            for (int sp = 0; sp < C::SPW; ++sp) {
+                const int s = cg * C::SPW + sp;
+                const float b = bbase[(s * C::KB + kk) * 64];
+                acc[sp] = __builtin_amdgcn_mfma_f32_32x32x2f32(wreg[kk], b, acc[sp], 0, 0, 0);
+            }
+        }
+
+        // epilogue: local SGD correction and store, 32 consecutive columns per row
+#pragma unroll
+        for (int sp = 0; sp < C::SPW; ++sp) {
+            const int s = cg * C::SPW + sp;
+            const int64_t col = tile * C::TC + 32 * s + (lane & 31);
+            if (col < dcols) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = 32 * rb + 8 * (v / 4) + 4 * (lane >> 5) + (v & 3);
+                    if (row < N) {
+                        float r = acc[sp][v];
+                        if (ORDER == DBW_ORDER_CTA && HAS_G) r = fmaf(-lr, gs[(int64_t)row * ld + col], r);
+                        out[(int64_t)row * ld + col] = r;
+                    }
+                }
+            }
+        }
+
+        if (next < n_tiles) commit(buf ^ 1);
+        __syncthreads();
+        buf ^= 1;
+    }
+}
+
+template <int MB, int ORDER, bool HAS_G>
+int launch_mb(dbw_ctx *c, const float *x, const float *g, float *out, float lr, int64_t n_vec, hipStream_t s)
+{
+    using C = dense_cfg<MB>;
+    const int64_t n_tiles = (n_vec * 4 + C::TC - 1) / C::TC;
+    if (n_tiles > INT32_MAX) return DBW_ERR_UNSUPPORTED;
+    int cus = 256;
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+        cus = prop.multiProcessorCount;
+    const int blocks_per_cu = (int)((160 * 1024) / (sizeof(float) * 2 * C::TILE));
+    const int64_t grid = std::min<int64_t>(n_tiles, (int64_t)cus * std::max(1, std::min(blocks_per_cu, 4)));
+    dbw_timer tm(c, "mix_dense_kernel", s);
+    hipLaunchKernelGGL((mix_dense_kernel<MB, ORDER, HAS_G>), dim3((unsigned)grid), dim3(DENSE_THREADS), 0, s, c->N,
+                       n_vec, c->ld / 4, c->Wdense, (const float4 *)x, (const float4 *)g, out, g, lr, (int)n_tiles);
+    DBW_HIP(hipGetLastError());
+    return DBW_OK;
+}
+
+template <int ORDER, bool HAS_G>
+int launch(dbw_ctx *c, const float *x, const float *g, float *out, float lr, int64_t n_vec, hipStream_t s)
+{
+    switch (c->Npad) {
+    case 32: return launch_mb<1, ORDER, HAS_G>(c, x, g, out, lr, n_vec, s);
+    case 64: return launch_mb<2, ORDER, HAS_G>(c, x, g, out, lr, n_vec, s);
+    case 128: return launch_mb<4, ORDER, HAS_G>(c, x, g, out, lr, n_vec, s);
+    case 256: return launch_mb<8, ORDER, HAS_G>(c, x, g, out, lr, n_vec, s);
+    default: return DBW_ERR_UNSUPPORTED;
+    }
+}
+
+}  // namespace
+
+int dbw_launch_mix_csr_range(dbw_ctx *c, const float *x, const float *g, float *out, float lr, int64_t c_begin,
+                             hipStream_t s);
+
+int dbw_launch_mix_dense(dbw_ctx *c, const float *x, const float *g, float *out, float lr, hipStream_t s)
+{
+    const bool aligned = (c->ld % 4 == 0) && ((uintptr_t)x % 16 == 0) && ((uintptr_t)out % 16 == 0) &&
+                         (!g || (uintptr_t)g % 16 == 0);
+    const int64_t n_vec = aligned ? c->d / 4 : 0;
+    int rc = DBW_OK;
+    if (n_vec > 0) {
+        if (!g)
+            rc = launch<DBW_ORDER_CTA, false>(c, x, g, out, lr, n_vec, s);
+        else if (c->order == DBW_ORDER_ATC)
+            rc = launch<DBW_ORDER_ATC, true>(c, x, g, out, lr, n_vec, s);
+        else
+            rc = launch<DBW_ORDER_CTA, true>(c, x, g, out, lr, n_vec, s);
+        if (rc != DBW_OK) return rc;
+    }
+    // ragged tail (d % 4 columns), or everything when rows are not 16-byte aligned
+    if (n_vec * 4 < c->d) rc = dbw_launch_mix_csr_range(c, x, g, out, lr, n_vec * 4, s);
+    return rc;
+}

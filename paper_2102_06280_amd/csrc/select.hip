@@ -121,11 +121,15 @@ __global__ __launch_bounds__(64) void select_kernel(
         __syncthreads();
         if (lane == 0) wrow[i] = ws;
         __syncthreads();
-        for (int c = lane; c < Npad; c += 64) Wdense[(size_t)i * Npad + c] = wrow[c];
+        // A-operand fragment order of the dense kernel: [row block][k-step][lane], with
+        // lane = (k % 2) * 32 + row % 32 holding P[row][k]
+        const int KB = Npad / 2;
+        for (int c = lane; c < Npad; c += 64)
+            Wdense[((size_t)(i >> 5) * KB + (c >> 1)) * 64 + (c & 1) * 32 + (i & 31)] = wrow[c];
     }
 }
 
-// Rows [N, Npad) of the padded dense matrix stay zero: written once at create.
+// Rows [N, Npad) of the padded dense matrix stay zero: cleared once at create.
 
 // Threshold rule and the d-iteration procedure (Section 4.1, Algorithm 2); one block.
 // A link (u, v) is established at max(t_u, t_v).  theta = the smallest establishment

@@ -1,0 +1,44 @@
+"""Parity at the full benchmark sizes, in the launch configuration bench.py times: the
+consensus-only stress (N = 128, d = 11.2 M, sparse path) and the dense-mixing stress
+(N = 256, d = 1 M, matrix-core path).  The averaging is column-separable, so the oracle
+is evaluated on sampled column blocks (first, last, and random ones) of the device data."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import assert_params_close
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("cid,order", [(4, 0), (4, 1), (5, 0), (5, 1)], ids=["c4-cta", "c4-atc", "c5-cta", "c5-atc"])
+def test_full_size_sampled_columns(orc, cid, order):
+    from paper_2102_06280_amd import binding as B
+    from paper_2102_06280_amd.workload import Workload
+    wl = Workload(cid, rounds=2, order=order)
+    try:
+        cfg = wl.cfg
+        blk = 4096
+        g = np.random.default_rng(311 + cid)
+        starts = [0, wl.d - blk] + [int(s) for s in g.integers(0, wl.d - blk, 6)]
+        starts.append(int(g.integers(0, wl.d - blk)) | 1)       # an odd, unaligned start
+        for rnd in range(2):
+            src = wl.params()
+            before = [src[:, s:s + blk].cpu().numpy() for s in starts]
+            grads = [wl.g[:, s:s + blk].cpu().numpy() for s in starts]
+            wl.step()
+            assert B.dbw_check(wl.h) == 0
+            dst = wl.params()
+            mask_d = torch.empty(wl.colidx.size, dtype=torch.uint8, device="cuda")
+            p_d = torch.empty(wl.n, dtype=torch.int32, device="cuda")
+            B.dbw_get_selection(wl.h, p_d, mask_d, None)
+            mask, p, _ = orc.select(wl.rowptr, wl.colidx, wl.t_host[rnd], wl.b_host[rnd])
+            assert np.array_equal(mask_d.cpu().numpy(), mask) and np.array_equal(p_d.cpu().numpy(), p)
+            for s, xb, gb in zip(starts, before, grads):
+                want = orc.round_(wl.rowptr, wl.colidx, mask, p, xb, gb, cfg.lr, order)
+                got = dst[:, s:s + blk].cpu().numpy()
+                assert_params_close(got, want, what=f"config {cid} round {rnd} columns {s}..{s + blk}")
+            # padding columns (if any) and the source buffer are untouched
+            assert torch.equal(src[:, :blk], torch.from_numpy(before[0]).cuda())
+    finally:
+        wl.close()
