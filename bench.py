@@ -125,7 +125,7 @@ def main():
     mix_path = B.dbw_mix_path(wl.h)
     dominant = max(kern, key=lambda k: kern[k][0])
     dom_ms = kern[dominant][0] / kern[dominant][1]
-    if dominant.startswith("mix_csr"):
+    if dominant.startswith(("mix_csr", "mix_lds")):
         work = 3.0 * cfg.n * cfg.d * 4          # read X, read G, write X' once each
         roofline = {"bound": "hbm", "achieved": work / (dom_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "traffic": None}

@@ -1,3 +1,137 @@
+// Mini-batch gradients of fully connected models for all workers at once (Section 2.1,
+// stochastic gradient of the local loss; cross-entropy as in Section 5).  Worker w uses
+// row w of the parameter matrix and its own batch: every GEMM below is batched over
+// workers with per-worker operands.
+//
+// Parameter row layout: per layer l, W_l [out][in] then b_l [out].
+// Scratch per worker: activations a_1..a_L ([B][dims[l]], a_L = logits) followed by the
+// deltas dz_1..dz_L of the same shapes.
+#include "bgemm.h"
 #include "dbw_internal.h"
-size_t dbw_mlp_scratch_floats(const dbw_ctx *) { return 1; }
-int dbw_launch_grad_mlp(dbw_ctx *, const float *, const float *, const int32_t *, float *, float *, hipStream_t) { return DBW_ERR_UNSUPPORTED; }
+
+namespace {
+
+using bgemm::Dense;
+using bgemm::Epilogue;
+
+// One workgroup per worker: softmax, mean cross-entropy loss and its gradient with respect
+// to the logits, dz = (softmax(z) - onehot(y)) / B.
+__global__ __launch_bounds__(256) void softmax_xent_kernel(
+    int B, int C, const float *__restrict__ logits, int64_t stride_logits, const int32_t *__restrict__ y,
+    float *__restrict__ dz, int64_t stride_dz, float *__restrict__ loss)
+{
+    __shared__ float red[256];
+    const int w = blockIdx.x, tid = threadIdx.x;
+    const float *z = logits + w * stride_logits;
+    float *d = dz + w * stride_dz;
+    const float inv_b = 1.0f / (float)B;
+    float part = 0.f;
+    for (int s = tid; s < B; s += 256) {
+        const float *zs = z + (int64_t)s * C;
+        float m = zs[0];
+        for (int c = 1; c < C; ++c) m = fmaxf(m, zs[c]);
+        float sum = 0.f;
+        for (int c = 0; c < C; ++c) sum += expf(zs[c] - m);
+        const int label = y[(int64_t)w * B + s];
+        const float inv = 1.0f / sum;
+        for (int c = 0; c < C; ++c) d[(int64_t)s * C + c] = (expf(zs[c] - m) * inv - (c == label ? 1.f : 0.f)) * inv_b;
+        part += logf(sum) + m - zs[label];
+    }
+    red[tid] = part;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if (tid < o) red[tid] += red[tid + o];
+        __syncthreads();
+    }
+    if (tid == 0 && loss) loss[w] = red[0] * inv_b;
+}
+
+// Bias gradient: db[o] = sum over the batch of dz[s][o].  grid = (ceil(C / 256), workers).
+__global__ __launch_bounds__(256) void colsum_kernel(int B, int C, const float *__restrict__ dz, int64_t stride_dz,
+                                                     float *__restrict__ db, int64_t stride_db)
+{
+    const int w = blockIdx.y, o = blockIdx.x * 256 + threadIdx.x;
+    if (o >= C) return;
+    const float *d = dz + w * stride_dz;
+    float s = 0.f;
+    for (int b = 0; b < B; ++b) s += d[(int64_t)b * C + o];
+    db[w * stride_db + o] = s;
+}
+
+int64_t acts_per_worker(const dbw_model &m)
+{
+    int64_t n = 0;
+    for (int l = 1; l <= m.n_layers; ++l) n += (int64_t)m.batch * m.dims[l];
+    return n;
+}
+
+}  // namespace
+
+size_t dbw_mlp_scratch_floats(const dbw_ctx *c) { return (size_t)(2 * acts_per_worker(c->model)) * c->N; }
+
+int dbw_launch_grad_mlp(dbw_ctx *c, const float *params, const float *bx, const int32_t *by, float *grads,
+                        float *loss, hipStream_t s)
+{
+    const dbw_model &m = c->model;
+    const int L = m.n_layers, B = m.batch, N = c->N;
+    const int64_t per = acts_per_worker(m), wstride = 2 * per;
+    // offsets inside a worker's scratch block and parameter row
+    int64_t a_off[9], dz_off[9], w_off[9], b_off[9];
+    int64_t ao = 0, po = 0;
+    for (int l = 1; l <= L; ++l) {
+        a_off[l] = ao;
+        dz_off[l] = per + ao;
+        ao += (int64_t)B * m.dims[l];
+        w_off[l] = po;
+        b_off[l] = po + (int64_t)m.dims[l] * m.dims[l - 1];
+        po = b_off[l] + m.dims[l];
+    }
+    float *act = c->act;
+
+    // forward: a_l = relu(a_{l-1} W_l^T + b_l), no ReLU on the logits
+    for (int l = 1; l <= L; ++l) {
+        Dense<true> A, Bm;
+        if (l == 1)
+            A = {bx, m.dims[0], (int64_t)B * m.dims[0]};
+        else
+            A = {act + a_off[l - 1], m.dims[l - 1], wstride};
+        Bm = {params + w_off[l], m.dims[l - 1], c->ld};
+        Epilogue E{act + a_off[l], m.dims[l], wstride, params + b_off[l], c->ld, nullptr, 0, 0, l < L ? 1 : 0};
+        dbw_timer tm(c, "mlp_forward_gemm", s);
+        DBW_HIP(bgemm::launch(A, Bm, E, B, m.dims[l], m.dims[l - 1], N, s));
+    }
+    {
+        dbw_timer tm(c, "softmax_xent_kernel", s);
+        hipLaunchKernelGGL(softmax_xent_kernel, dim3(N), dim3(256), 0, s, B, m.dims[L], act + a_off[L], wstride, by,
+                           act + dz_off[L], wstride, loss);
+        DBW_HIP(hipGetLastError());
+    }
+    // backward
+    for (int l = L; l >= 1; --l) {
+        {   // dW_l = dz_l^T a_{l-1}
+            Dense<false> A{act + dz_off[l], m.dims[l], wstride}, Bm;
+            if (l == 1)
+                Bm = {bx, m.dims[0], (int64_t)B * m.dims[0]};
+            else
+                Bm = {act + a_off[l - 1], m.dims[l - 1], wstride};
+            Epilogue E{grads + w_off[l], m.dims[l - 1], c->ld, nullptr, 0, nullptr, 0, 0, 0};
+            dbw_timer tm(c, "mlp_wgrad_gemm", s);
+            DBW_HIP(bgemm::launch(A, Bm, E, m.dims[l], m.dims[l - 1], B, N, s));
+        }
+        {
+            dbw_timer tm(c, "colsum_kernel", s);
+            hipLaunchKernelGGL(colsum_kernel, dim3((m.dims[l] + 255) / 256, N), dim3(256), 0, s, B, m.dims[l],
+                               act + dz_off[l], wstride, grads + b_off[l], c->ld);
+            DBW_HIP(hipGetLastError());
+        }
+        if (l > 1) {   // dz_{l-1} = (dz_l W_l) masked by a_{l-1} > 0
+            Dense<true> A{act + dz_off[l], m.dims[l], wstride};
+            Dense<false> Bm{params + w_off[l], m.dims[l - 1], c->ld};
+            Epilogue E{act + dz_off[l - 1], m.dims[l - 1], wstride, nullptr, 0, act + a_off[l - 1], m.dims[l - 1],
+                       wstride, 0};
+            dbw_timer tm(c, "mlp_dgrad_gemm", s);
+            DBW_HIP(bgemm::launch(A, Bm, E, B, m.dims[l - 1], m.dims[l], N, s));
+        }
+    }
+    return DBW_OK;
+}

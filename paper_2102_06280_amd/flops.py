@@ -1,0 +1,37 @@
+"""Algorithmic FLOP counts of the gradient kernels, per launch, for the roofline line of
+the benchmark.  A GEMM of shape M x N x K counts 2 M N K; one workload launch covers all
+N workers.  Kernel names are the ones the library reports through dbw_get_timing."""
+from __future__ import annotations
+
+from . import inputs
+
+
+def _mlp(cfg, dims):
+    B, n = cfg.batch, cfg.n
+    fwd = [2 * B * dims[l] * dims[l + 1] for l in range(len(dims) - 1)]
+    wgrad = list(fwd)
+    dgrad = [2 * B * dims[l] * dims[l + 1] for l in range(1, len(dims) - 1)]
+    return {"mlp_forward_gemm": n * sum(fwd) / len(fwd), "mlp_wgrad_gemm": n * sum(wgrad) / len(wgrad),
+            "mlp_dgrad_gemm": n * sum(dgrad) / max(len(dgrad), 1)}
+
+
+def _cnn(cfg, desc):
+    B, n = cfg.batch, cfg.n
+    c0, h, w = desc["in"]
+    c1, c2, k, f, nc = desc["c1"], desc["c2"], desc["k"], desc["fc"], desc["classes"]
+    conv1 = 2 * B * h * w * c1 * c0 * k * k
+    conv2 = 2 * B * (h // 2) * (w // 2) * c2 * c1 * k * k
+    flat = c2 * (h // 4) * (w // 4)
+    fc = [2 * B * flat * f, 2 * B * f * nc]
+    return {"conv1_forward": n * conv1, "conv1_wgrad": n * conv1,
+            "conv2_forward": n * conv2, "conv2_wgrad": n * conv2, "conv2_dgrad": n * conv2,
+            "mlp_forward_gemm": n * sum(fc) / 2, "mlp_wgrad_gemm": n * sum(fc) / 2, "mlp_dgrad_gemm": n * sum(fc) / 2}
+
+
+def kernel_flops(cfg, kernel_name: str) -> float:
+    desc = inputs.model_dims(cfg.model)
+    table = _mlp(cfg, desc["dims"]) if desc["kind"] == "mlp" else _cnn(cfg, desc)
+    for key, val in table.items():
+        if kernel_name.startswith(key):
+            return float(val)
+    return 0.0

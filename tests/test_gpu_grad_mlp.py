@@ -1,0 +1,124 @@
+"""GPU parity of the batched per-worker gradients of fully connected models, and of whole
+rounds (gradient + selection + masked average + SGD step) in lock-step with the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2102_06280_amd import inputs
+from gpu_util import assert_params_close, dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2102_06280_amd import binding
+    return binding
+
+
+def rel_l2(a, b):
+    return np.linalg.norm(a.astype(np.float64) - b) / max(np.linalg.norm(b), 1e-30)
+
+
+SHAPES = [
+    # dims, batch, workers
+    ([784, 10], 32, 8),            # config 1 model
+    ([784, 200, 10], 64, 32),      # config 2 model
+    ([256, 256, 256, 10], 128, 6), # the paper's 2NN (Appendix B, Table 1), smaller batch
+    ([37, 19, 5], 7, 3),           # ragged everything
+    ([100, 70, 33, 65, 3], 50, 4),
+    ([5, 2], 1, 2),
+]
+
+
+@pytest.mark.parametrize("dims,batch,n", SHAPES, ids=[f"{'-'.join(map(str, s[0]))}-B{s[1]}-N{s[2]}" for s in SHAPES])
+def test_mlp_gradients_match_oracle(B, orc, dims, batch, n):
+    g = np.random.default_rng(401)
+    desc = {"kind": "mlp", "dims": dims}
+    d = inputs.param_count(desc)
+    ld = inputs.pad_ld(d)
+    rowptr, colidx = inputs.graph_ring(max(n, 3)) if n >= 3 else (np.array([0, 1, 2], np.int32), np.array([1, 0], np.int32))
+    n = rowptr.size - 1
+    params = inputs.init_params(desc, n, ld, g)
+    params[:, :d] += (g.standard_normal((n, d)) * 0.05).astype(np.float32)      # non-zero biases too
+    x = g.standard_normal((n, batch, dims[0])).astype(np.float32)
+    y = g.integers(0, dims[-1], (n, batch)).astype(np.int32)
+    h = B.dbw_create(rowptr, colidx, n, d, ld=ld, model=B.make_model(B.MODEL_MLP, batch, dims))
+    try:
+        grads = torch.full((n, ld), 7.0, dtype=torch.float32, device="cuda")
+        loss = torch.zeros(n, dtype=torch.float32, device="cuda")
+        B.dbw_grad(h, dev(params), dev(x), dev(y), grads, loss)
+        got, gl = grads.cpu().numpy(), loss.cpu().numpy()
+        kind, od = orc.model_desc(desc)
+        want, wl = orc.grad_all(kind, od, d, params, x, y)
+        assert np.allclose(gl, wl, rtol=2e-6, atol=1e-6)
+        assert np.all(got[:, d:] == 7.0)
+        off = 0
+        for fan_in, nw, nb in inputs.layer_shapes(desc):
+            for lo, hi, what in ((off, off + nw, "W"), (off + nw, off + nw + nb, "b")):
+                for i in range(n):
+                    r = rel_l2(got[i, lo:hi], want[i, lo:hi])
+                    assert r <= 2e-5, f"worker {i} {what}[{lo}:{hi}] rel L2 {r:.2e}"
+            off += nw + nb
+    finally:
+        B.dbw_destroy(h)
+
+
+def test_softmax_zero_init_round_one(B, orc):
+    """Config 1, round 1: all parameters zero, so every worker's loss is ln 10."""
+    cfg = inputs.CONFIGS[1]
+    rowptr, colidx = inputs.make_graph(cfg)
+    ld = inputs.pad_ld(cfg.d)
+    x, y = inputs.batch(cfg, 0)
+    h = B.dbw_create(rowptr, colidx, cfg.n, cfg.d, ld=ld, model=B.make_model(B.MODEL_MLP, cfg.batch, [784, 10]))
+    try:
+        grads = torch.zeros((cfg.n, ld), device="cuda")
+        loss = torch.zeros(cfg.n, device="cuda")
+        B.dbw_grad(h, torch.zeros((cfg.n, ld), device="cuda"), dev(x), dev(y), grads, loss)
+        assert np.allclose(loss.cpu().numpy(), np.log(10.0), rtol=1e-6)
+    finally:
+        B.dbw_destroy(h)
+
+
+@pytest.mark.parametrize("cid,rounds,order", [(1, 10, 0), (1, 10, 1), (2, 6, 0), (2, 3, 1)],
+                         ids=["config1-cta", "config1-atc", "config2-cta", "config2-atc"])
+def test_rounds_lock_step(B, orc, cid, rounds, order):
+    """Whole rounds of configurations 1 and 2.  Each round both sides start from the
+    oracle's previous output; the free-running GPU trajectory is carried along and must
+    stay close as well (reported, loosely bounded)."""
+    cfg = inputs.CONFIGS[cid]
+    desc = inputs.model_dims(cfg.model)
+    rowptr, colidx = inputs.make_graph(cfg)
+    ld = inputs.pad_ld(cfg.d)
+    kind, od = orc.model_desc(desc)
+    h = B.dbw_create(rowptr, colidx, cfg.n, cfg.d, ld=ld, order=order,
+                     model=B.make_model(B.MODEL_MLP, cfg.batch, desc["dims"]))
+    try:
+        x = inputs.init_params(desc, cfg.n, ld, inputs.rng(cid, inputs.P_PARAMS), zero=cfg.zero_init)
+        free = dev(x)
+        for rnd in range(rounds):
+            t = inputs.response_times(cfg, rnd)
+            b = inputs.backup_counts(cfg, rnd, rowptr) if rnd else np.zeros(cfg.n, np.int32)
+            bx, by = inputs.batch(cfg, rnd)
+            dt, db, dbx, dby = dev(t), dev(b), dev(bx), dev(by)
+            out = torch.zeros((cfg.n, ld), device="cuda")
+            loss = torch.zeros(cfg.n, device="cuda")
+            B.dbw_select(h, dt, db)
+            B.dbw_round(h, dev(x), out, cfg.lr, batch_x=dbx, batch_y=dby, loss_out=loss)
+            free_out = torch.zeros((cfg.n, ld), device="cuda")
+            B.dbw_round(h, free, free_out, cfg.lr, batch_x=dbx, batch_y=dby)
+            free = free_out
+            mask, p, _ = orc.select(rowptr, colidx, t, b)
+            grad, oloss = orc.grad_all(kind, od, cfg.d, x, bx, by)
+            want = orc.round_(rowptr, colidx, mask, p, x, grad, cfg.lr, order, d=cfg.d)
+            mask_d = torch.empty(colidx.size, dtype=torch.uint8, device="cuda")
+            B.dbw_get_selection(h, None, mask_d, None)
+            assert np.array_equal(mask_d.cpu().numpy(), mask)
+            assert_params_close(out.cpu().numpy(), want, d=cfg.d, what=f"config {cid} round {rnd}")
+            assert np.allclose(loss.cpu().numpy(), oloss, rtol=1e-5, atol=1e-6)
+            x = want
+        drift = rel_l2(free.cpu().numpy()[:, :cfg.d], x[:, :cfg.d])
+        print(f"config {cid}: free-running drift after {rounds} rounds: {drift:.2e}")
+        assert drift < 1e-3
+    finally:
+        B.dbw_destroy(h)
