@@ -141,7 +141,7 @@ def grad_mlp(dims, params, x, y):
     grad = np.zeros_like(params)
     loss = C.c_double(0)
     lib().orc_grad_mlp(len(dims) - 1, _p(dims, C.c_int32), x.shape[0], _p(params, C.c_float),
-                       _p(x, C.c_float), _p(y, C.c_int32), _p(grad, C.c_float), C.byref(loss))
+                       _p(x, C.c_float), _p(y, C.c_int32), _p(grad, C.c_float), C.byref(loss), None)
     return grad, loss.value
 
 
@@ -152,12 +152,15 @@ def grad_cnn(shape, params, x, y):
     grad = np.zeros_like(params)
     loss = C.c_double(0)
     lib().orc_grad_cnn(_p(shape, C.c_int32), x.shape[0], _p(params, C.c_float), _p(x, C.c_float),
-                       _p(y, C.c_int32), _p(grad, C.c_float), C.byref(loss))
+                       _p(y, C.c_int32), _p(grad, C.c_float), C.byref(loss), None)
     return grad, loss.value
 
 
-def grad_all(kind, desc, d, params, x, y):
-    """All workers: params [N, ld], x [N, B, in], y [N, B] -> (grad [N, ld], loss [N])."""
+def grad_all(kind, desc, d, params, x, y, with_margin=False):
+    """All workers: params [N, ld], x [N, B, in], y [N, B] -> (grad [N, ld], loss [N]).
+    with_margin adds a third result [N, 2]: how close each worker's nearest decision was to
+    flipping (the gradient is discontinuous there): column 0 ReLU + max-pooling windows of
+    convolutional stages, column 1 ReLU inputs of fully connected layers."""
     desc = _i32(desc)
     params, x, y = _f32(params), _f32(x), _i32(y)
     n, ld = params.shape
@@ -165,10 +168,11 @@ def grad_all(kind, desc, d, params, x, y):
     in_dim = int(np.prod(x.shape[2:]))
     grad = np.zeros_like(params)
     loss = np.zeros(n, dtype=np.float64)
+    margin = np.zeros((n, 2), dtype=np.float64)
     lib().orc_grad_all(int(kind), _p(desc, C.c_int32), n, C.c_int64(d), C.c_int64(ld), B,
                        C.c_int64(in_dim), _p(params, C.c_float), _p(x, C.c_float), _p(y, C.c_int32),
-                       _p(grad, C.c_float), _p(loss, C.c_double))
-    return grad, loss
+                       _p(grad, C.c_float), _p(loss, C.c_double), _p(margin, C.c_double))
+    return (grad, loss, margin) if with_margin else (grad, loss)
 
 
 def model_desc(desc):

@@ -241,6 +241,16 @@ void orc_dtur(int N, const int32_t *rowptr, const int32_t *colidx, int n_edges,
 
 /* ------------------------------------------------------------------ gradients */
 
+/* Diagnostic for the tests, not part of the method: the gradients are discontinuous where a
+ * ReLU input is zero or two pooled values tie, so a finite-precision evaluation can
+ * legitimately take the other branch there.  The gradient routines report how close the
+ * nearest such decision was: margin[0] = smallest gap at a ReLU + max-pooling window of a
+ * convolutional stage, margin[1] = smallest |z| at a ReLU of a fully connected layer. */
+static void margin_update(double *margin, double v)
+{
+    if (margin && v < *margin) *margin = v;
+}
+
 /* Softmax cross-entropy on one sample: fills dz = (softmax(z) - onehot(y)) * scale and
  * returns -log softmax(z)[y]. */
 static double softmax_xent(int C, const double *z, int y, double scale, double *dz)
@@ -258,8 +268,9 @@ static double softmax_xent(int C, const double *z, int y, double scale, double *
  * but the last, mean cross-entropy over the B samples.  params / grad: per layer
  * W[out][in] then bias[out].  x: [B][dims[0]], y: [B]. */
 void orc_grad_mlp(int L, const int32_t *dims, int B, const float *params, const float *x,
-                  const int32_t *y, float *grad, double *loss_out)
+                  const int32_t *y, float *grad, double *loss_out, double *margin /* nullable */)
 {
+    if (margin) margin[0] = margin[1] = INFINITY;
     size_t total = 0, maxw = 0;
     for (int l = 0; l < L; ++l) {
         total += (size_t)dims[l + 1] * dims[l] + dims[l + 1];
@@ -285,7 +296,10 @@ void orc_grad_mlp(int L, const int32_t *dims, int B, const float *params, const 
                 double v = (double)bias[o];
                 for (int k = 0; k < in; ++k) v += (double)W[(size_t)o * in + k] * a[l][k];
                 z[l][o] = v;
-                if (l + 1 < L) a[l + 1][o] = v > 0.0 ? v : 0.0;
+                if (l + 1 < L) {
+                    a[l + 1][o] = v > 0.0 ? v : 0.0;
+                    margin_update(margin ? margin + 1 : NULL, fabs(v));
+                }
             }
             off += (size_t)out * in + out;
         }
@@ -372,7 +386,7 @@ static void conv_bwd(int Ci, int Co, int H, int Wd, int K, const float *W, const
 
 /* ReLU then 2x2/stride-2 max pooling; arg[] keeps the flat input index of the first
  * maximum in window order (0,0),(0,1),(1,0),(1,1). */
-static void relu_pool_fwd(int C, int H, int Wd, const double *z, double *out, int *arg)
+static void relu_pool_fwd(int C, int H, int Wd, const double *z, double *out, int *arg, double *margin)
 {
     int Ho = H / 2, Wo = Wd / 2;
     for (int c = 0; c < C; ++c)
@@ -388,6 +402,16 @@ static void relu_pool_fwd(int C, int H, int Wd, const double *z, double *out, in
                     }
                 out[(c * Ho + oh) * Wo + ow] = best;
                 arg[(c * Ho + oh) * Wo + ow] = bi;
+                if (margin) {
+                    double top = -INFINITY, second = -INFINITY;
+                    for (int dh = 0; dh < 2; ++dh)
+                        for (int dw = 0; dw < 2; ++dw) {
+                            double v = z[(c * H + 2 * oh + dh) * Wd + 2 * ow + dw];
+                            if (v > top) { second = top; top = v; }
+                            else if (v > second) second = v;
+                        }
+                    margin_update(margin, top > 0.0 ? fmin(top, top - second) : -top);
+                }
             }
 }
 
@@ -405,8 +429,9 @@ static void relu_pool_bwd(int C, int H, int Wd, const double *z, const int *arg,
  * shape = {C0, H, W, C1, C2, K, F, classes}.  Parameter order: conv1 W,b; conv2 W,b;
  * fc1 W,b; fc2 W,b. */
 void orc_grad_cnn(const int32_t *shape, int B, const float *params, const float *x,
-                  const int32_t *y, float *grad, double *loss_out)
+                  const int32_t *y, float *grad, double *loss_out, double *margin /* nullable */)
 {
+    if (margin) margin[0] = margin[1] = INFINITY;
     int C0 = shape[0], H = shape[1], Wd = shape[2], C1 = shape[3], C2 = shape[4], K = shape[5],
         F = shape[6], NC = shape[7];
     int H2 = H / 2, W2 = Wd / 2, H4 = H / 4, W4 = Wd / 4, flat = C2 * H4 * W4;
@@ -434,14 +459,15 @@ void orc_grad_cnn(const int32_t *shape, int B, const float *params, const float 
     for (int s = 0; s < B; ++s) {
         for (int q = 0; q < C0 * H * Wd; ++q) a0[q] = (double)x[(size_t)s * C0 * H * Wd + q];
         conv_fwd(C0, C1, H, Wd, K, params + o_w1, params + o_b1, a0, z1);
-        relu_pool_fwd(C1, H, Wd, z1, p1, arg1);
+        relu_pool_fwd(C1, H, Wd, z1, p1, arg1, margin);
         conv_fwd(C1, C2, H2, W2, K, params + o_w2, params + o_b2, p1, z2);
-        relu_pool_fwd(C2, H2, W2, z2, p2, arg2);
+        relu_pool_fwd(C2, H2, W2, z2, p2, arg2, margin);
         for (int o = 0; o < F; ++o) {
             double v = (double)params[o_b3 + o];
             for (int k = 0; k < flat; ++k) v += (double)params[o_w3 + (size_t)o * flat + k] * p2[k];
             z3[o] = v;
             a3[o] = v > 0.0 ? v : 0.0;
+            margin_update(margin ? margin + 1 : NULL, fabs(v));
         }
         for (int o = 0; o < NC; ++o) {
             double v = (double)params[o_b4 + o];
@@ -486,18 +512,19 @@ void orc_grad_cnn(const int32_t *shape, int B, const float *params, const float 
  * (desc = {L, dims[0..L]}), kind 1: convolutional (desc = shape[8]). */
 void orc_grad_all(int kind, const int32_t *desc, int N, int64_t d, int64_t ld, int B,
                   int64_t in_dim, const float *params, const float *x, const int32_t *y,
-                  float *grad, double *loss /* N, nullable */)
+                  float *grad, double *loss /* N, nullable */, double *margin /* N x 2, nullable */)
 {
 #pragma omp parallel for schedule(dynamic, 1) num_threads(orc_threads)
     for (int i = 0; i < N; ++i) {
         float *gi = grad + (size_t)i * ld;
         double li = 0.0;
+        double *mi = margin ? margin + 2 * i : NULL;
         if (kind == 0)
             orc_grad_mlp(desc[0], desc + 1, B, params + (size_t)i * ld,
-                         x + (size_t)i * B * in_dim, y + (size_t)i * B, gi, &li);
+                         x + (size_t)i * B * in_dim, y + (size_t)i * B, gi, &li, mi);
         else
             orc_grad_cnn(desc, B, params + (size_t)i * ld, x + (size_t)i * B * in_dim,
-                         y + (size_t)i * B, gi, &li);
+                         y + (size_t)i * B, gi, &li, mi);
         for (int64_t c = d; c < ld; ++c) gi[c] = 0.0f;
         if (loss) loss[i] = li;
     }

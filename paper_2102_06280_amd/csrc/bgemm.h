@@ -49,18 +49,13 @@ struct Epilogue {
     const float *mask;      // keep C[m][n] only where mask[m][n] > 0; nullptr = none
     int64_t ldmask, strideMask;
     int relu;
-    __device__ __forceinline__ void store(int w, int m, int n, float v) const
+    __device__ __forceinline__ void store(int w, int /*split*/, int m, int n, float v) const
     {
         if (bias) v += bias[w * strideBias + n];
         if (relu) v = v > 0.f ? v : 0.f;
         if (mask) v = mask[w * strideMask + (int64_t)m * ldmask + n] > 0.f ? v : 0.f;
         C[w * strideC + (int64_t)m * ldc + n] = v;
     }
-};
-
-template <class L>
-struct TileRegs {
-    float v[8];
 };
 
 // Global -> registers for a 64 x 32 operand tile (8 elements per thread).
@@ -109,13 +104,18 @@ __device__ __forceinline__ f32x4 frag(const float *lds, int rbase, int kg, int l
 
 constexpr int lds_floats(bool kc) { return kc ? 64 * LDS_KC : BK * LDS_RC; }
 
-template <class LA, class LB>
-__global__ __launch_bounds__(THREADS) void kernel(LA A, LB B, Epilogue E, int M, int N, int K)
+// blockIdx.z = worker * splits + split; a split covers k in [split * kper, (split + 1) * kper)
+// (kper a multiple of BK) and hands its partial sum to the epilogue, which decides where it
+// goes; with splits == 1 the result is final.
+template <class LA, class LB, class EP>
+__global__ __launch_bounds__(THREADS) void kernel(LA A, LB B, EP E, int M, int N, int K, int splits, int kper)
 {
     __shared__ __attribute__((aligned(16))) float As[lds_floats(LA::KC)];
     __shared__ __attribute__((aligned(16))) float Bs[lds_floats(LB::KC)];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int w = blockIdx.z, m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    const int w = blockIdx.z / splits, split = blockIdx.z % splits;
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    const int kbeg = split * kper, kend = min(K, kbeg + kper);
     const int wm = (wave & 1) * 32, wn = (wave >> 1) * 32;
 
     f32x4 acc[2][2];
@@ -125,16 +125,16 @@ __global__ __launch_bounds__(THREADS) void kernel(LA A, LB B, Epilogue E, int M,
         for (int b = 0; b < 2; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     float ra[8], rb[8];
-    fetch_tile(A, w, m0, M, 0, K, tid, ra);
-    fetch_tile(B, w, n0, N, 0, K, tid, rb);
-    for (int k0 = 0; k0 < K; k0 += BK) {
+    fetch_tile(A, w, m0, M, kbeg, kend, tid, ra);
+    fetch_tile(B, w, n0, N, kbeg, kend, tid, rb);
+    for (int k0 = kbeg; k0 < kend; k0 += BK) {
         __syncthreads();                       // previous tile fully consumed
         commit_tile<LA>(As, tid, ra);
         commit_tile<LB>(Bs, tid, rb);
         __syncthreads();
-        if (k0 + BK < K) {                     // next tile's loads fly during the MFMAs
-            fetch_tile(A, w, m0, M, k0 + BK, K, tid, ra);
-            fetch_tile(B, w, n0, N, k0 + BK, K, tid, rb);
+        if (k0 + BK < kend) {                  // next tile's loads fly during the MFMAs
+            fetch_tile(A, w, m0, M, k0 + BK, kend, tid, ra);
+            fetch_tile(B, w, n0, N, k0 + BK, kend, tid, rb);
         }
 #pragma unroll
         for (int kg = 0; kg < BK / 16; ++kg) {
@@ -160,16 +160,19 @@ __global__ __launch_bounds__(THREADS) void kernel(LA A, LB B, Epilogue E, int M,
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int m = m0 + wm + 16 * a + 4 * (lane >> 4) + v;
-                if (m < M && n < N) E.store(w, m, n, acc[a][b][v]);
+                if (m < M && n < N) E.store(w, split, m, n, acc[a][b][v]);
             }
         }
 }
 
-template <class LA, class LB>
-inline hipError_t launch(const LA &A, const LB &B, const Epilogue &E, int M, int N, int K, int batch, hipStream_t s)
+template <class LA, class LB, class EP>
+inline hipError_t launch(const LA &A, const LB &B, const EP &E, int M, int N, int K, int batch, hipStream_t s,
+                         int splits = 1)
 {
-    dim3 grid((N + BN - 1) / BN, (M + BM - 1) / BM, batch);
-    hipLaunchKernelGGL((kernel<LA, LB>), grid, dim3(THREADS), 0, s, A, B, E, M, N, K);
+    int kper = (K + splits - 1) / splits;
+    kper = (kper + BK - 1) / BK * BK;
+    dim3 grid((N + BN - 1) / BN, (M + BM - 1) / BM, batch * splits);
+    hipLaunchKernelGGL((kernel<LA, LB, EP>), grid, dim3(THREADS), 0, s, A, B, E, M, N, K, splits, kper);
     return hipGetLastError();
 }
 

@@ -78,6 +78,29 @@ int dbw_launch_mix_csr(dbw_ctx *c, const float *x, const float *g, float *out, f
 // mix_dense.hip
 int dbw_launch_mix_dense(dbw_ctx *c, const float *x, const float *g, float *out, float lr, hipStream_t s);
 // grad_mlp.hip / grad_cnn.hip
+// A stack of fully connected layers dims[0] -> ... -> dims[L] with ReLU between layers and
+// softmax cross-entropy on top, for all workers.  Parameters of the stack start at float
+// offset param_off inside each worker's row (row stride c->ld); gradients go to the same
+// offsets of `grads`.  `in` is the stack's input [B][in_ld] per worker; `act` is scratch of
+// act_stride floats per worker (see dbw_fc_scratch_per_worker); `din`, if not null,
+// receives the gradient with respect to the input.
+struct dbw_fc_args {
+    int L, B;
+    const int32_t *dims;
+    const float *params;
+    float *grads;
+    int64_t param_off;
+    const float *in;
+    int64_t in_ld, in_stride;
+    float *act;
+    int64_t act_stride;
+    float *din;
+    int64_t din_ld, din_stride;
+    const int32_t *y;
+    float *loss;
+};
+int64_t dbw_fc_scratch_per_worker(int L, const int32_t *dims, int B);
+int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s);
 size_t dbw_mlp_scratch_floats(const dbw_ctx *c);
 int dbw_launch_grad_mlp(dbw_ctx *c, const float *params, const float *bx, const int32_t *by, float *grads,
                         float *loss, hipStream_t s);

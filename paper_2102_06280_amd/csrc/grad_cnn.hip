@@ -1,3 +1,359 @@
+// Mini-batch gradients of the convolutional model for all workers at once (Section 2.1,
+// stochastic gradient of the local loss).  Network per worker, input [B][C0][H][W]:
+//   conv KxK (C0->C1, same padding) -> ReLU -> maxpool 2x2 -> conv KxK (C1->C2, same) ->
+//   ReLU -> maxpool 2x2 -> flatten [C2][H/4][W/4] -> FC F -> ReLU -> FC classes -> softmax
+//   cross-entropy, mean over the batch.
+// Parameter row layout: conv1 W [C1][C0][K][K], b [C1]; conv2 W [C2][C1][K][K], b [C2];
+// fc1 W [F][flat], b [F]; fc2 W [classes][F], b [classes].
+//
+// Convolutions are implicit GEMMs on the batched fp32 MFMA kernel: the patch matrix is
+// never materialised, the operand loaders compute the input address of each element.
+//   forward   z[co][pix]      = sum_k  W[co][k] * patch[k][pix]        k = (ci, kh, kw)
+//   wgrad     dW[co][k]       = sum_pix dz[co][pix] * patch[k][pix]
+//   dgrad     din[ci][pix_in] = sum_k' W[co][ci][kh][kw] * dz[co][pix_in shifted]   k' = (co, kh, kw)
+// Output channels are the GEMM's M and pixels its N, so stores run along consecutive pixels.
+// Max pooling keeps no index: the backward pass re-derives the first maximum of each
+// window from the stored pre-activations (first in window order (0,0),(0,1),(1,0),(1,1)).
+#include "bgemm.h"
 #include "dbw_internal.h"
-size_t dbw_cnn_scratch_floats(const dbw_ctx *) { return 1; }
-int dbw_launch_grad_cnn(dbw_ctx *, const float *, const float *, const int32_t *, float *, float *, hipStream_t) { return DBW_ERR_UNSUPPORTED; }
+
+namespace {
+
+using bgemm::Dense;
+
+struct ConvShape {
+    int Cin, Cout, H, W, KS, pad;   // stride-1 'same' convolution
+};
+
+// patch element for output pixel `pix` = (b, oh, ow) and k = (ci, kh, kw); zero outside.
+__device__ __forceinline__ float patch_at(const float *in, const ConvShape &s, int pix, int k)
+{
+    const int HW = s.H * s.W, KK = s.KS * s.KS;
+    const int b = pix / HW, hw = pix - b * HW, oh = hw / s.W, ow = hw - oh * s.W;
+    const int ci = k / KK, rr = k - ci * KK, kh = rr / s.KS, kw = rr - kh * s.KS;
+    const int ih = oh + kh - s.pad, iw = ow + kw - s.pad;
+    if (ih < 0 || ih >= s.H || iw < 0 || iw >= s.W) return 0.f;
+    return in[((int64_t)(b * s.Cin + ci) * s.H + ih) * s.W + iw];
+}
+
+// B operand of the forward GEMM: (k, pix), contiguous along pixels.
+struct PatchRC {
+    static constexpr bool KC = false;
+    const float *in;
+    int64_t stride;
+    ConvShape s;
+    __device__ __forceinline__ float load(int w, int pix, int k) const { return patch_at(in + w * stride, s, pix, k); }
+};
+
+// B operand of the weight-gradient GEMM: row = k of the filter, reduction index = pixel.
+struct PatchKC {
+    static constexpr bool KC = true;
+    const float *in;
+    int64_t stride;
+    ConvShape s;
+    __device__ __forceinline__ float load(int w, int kf, int pix) const { return patch_at(in + w * stride, s, pix, kf); }
+};
+
+// A operand of the weight-gradient GEMM: dz[co][pix] stored as [B][Cout][H][W].
+struct DeltaKC {
+    static constexpr bool KC = true;
+    const float *dz;
+    int64_t stride;
+    int Cout, HW;
+    __device__ __forceinline__ float load(int w, int co, int pix) const
+    {
+        const int b = pix / HW, hw = pix - b * HW;
+        return dz[w * stride + (int64_t)(b * Cout + co) * HW + hw];
+    }
+};
+
+// A operand of the data-gradient GEMM: (ci, k' = (co, kh, kw)) -> W[co][ci][kh][kw].
+struct FilterT {
+    static constexpr bool KC = true;
+    const float *wgt;
+    int64_t stride;
+    int Cin, KK;
+    __device__ __forceinline__ float load(int w, int ci, int k) const
+    {
+        const int co = k / KK, rr = k - co * KK;
+        return wgt[w * stride + (int64_t)(co * Cin + ci) * KK + rr];
+    }
+};
+
+// B operand of the data-gradient GEMM: (k' = (co, kh, kw), input pixel) -> dz at the output
+// position that used this input pixel with that filter tap; zero outside.
+struct DeltaShiftRC {
+    static constexpr bool KC = false;
+    const float *dz;
+    int64_t stride;
+    ConvShape s;
+    __device__ __forceinline__ float load(int w, int pix, int k) const
+    {
+        const int HW = s.H * s.W, KK = s.KS * s.KS;
+        const int b = pix / HW, hw = pix - b * HW, ih = hw / s.W, iw = hw - ih * s.W;
+        const int co = k / KK, rr = k - co * KK, kh = rr / s.KS, kw = rr - kh * s.KS;
+        const int oh = ih - kh + s.pad, ow = iw - kw + s.pad;
+        if (oh < 0 || oh >= s.H || ow < 0 || ow >= s.W) return 0.f;
+        return dz[w * stride + ((int64_t)(b * s.Cout + co) * s.H + oh) * s.W + ow];
+    }
+};
+
+// Store C[m = channel][n = pixel] into a [B][C][H][W] tensor, adding a per-channel bias.
+struct ChannelPixelOut {
+    float *out;
+    int64_t stride;
+    int C, HW;
+    const float *bias;     // per worker at bias[w * bias_stride + channel]; nullptr = none
+    int64_t bias_stride;
+    __device__ __forceinline__ void store(int w, int, int ch, int pix, float v) const
+    {
+        if (bias) v += bias[w * bias_stride + ch];
+        const int b = pix / HW, hw = pix - b * HW;
+        out[w * stride + (int64_t)(b * C + ch) * HW + hw] = v;
+    }
+};
+
+// Partial sums of a split-k GEMM, inside each worker's scratch block: part[split][m][n].
+struct PartialOut {
+    float *part;
+    int64_t stride;
+    int M, N;
+    __device__ __forceinline__ void store(int w, int split, int m, int n, float v) const
+    {
+        part[w * stride + ((int64_t)split * M + m) * N + n] = v;
+    }
+};
+
+// dst[w * stride + i] = sum over splits of part[w][split][i], in split order.
+__global__ __launch_bounds__(256) void reduce_splits_kernel(const float *__restrict__ part, int64_t pstride,
+                                                            int splits, int MN, float *__restrict__ dst,
+                                                            int64_t stride)
+{
+    const int w = blockIdx.y, i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= MN) return;
+    float s = 0.f;
+    for (int sp = 0; sp < splits; ++sp) s += part[w * pstride + (int64_t)sp * MN + i];
+    dst[w * stride + i] = s;
+}
+
+// ReLU + 2x2 max pooling of z [B][C][H][W] -> p [B][C][H/2][W/2]; one thread per output.
+__global__ __launch_bounds__(256) void relu_pool_fwd_kernel(const float *__restrict__ z, int64_t zstride,
+                                                            float *__restrict__ p, int64_t pstride, int planes, int H, int W)
+{
+    const int w = blockIdx.y;
+    const int Ho = H / 2, Wo = W / 2, total = planes * Ho * Wo;
+    const int o = blockIdx.x * 256 + threadIdx.x;
+    if (o >= total) return;
+    const int pl = o / (Ho * Wo), rem = o - pl * Ho * Wo, oh = rem / Wo, ow = rem - oh * Wo;
+    const float *src = z + w * zstride + ((int64_t)pl * H + 2 * oh) * W + 2 * ow;
+    const float m = fmaxf(fmaxf(src[0], src[1]), fmaxf(src[W], src[W + 1]));
+    p[w * pstride + o] = fmaxf(m, 0.f);
+}
+
+// Backward of ReLU + max pooling: the pooled gradient goes to the first element of the
+// window that attains the (positive) maximum; everything else gets zero.
+__global__ __launch_bounds__(256) void relu_pool_bwd_kernel(const float *__restrict__ z, int64_t zstride,
+                                                            const float *__restrict__ dp, int64_t pstride,
+                                                            float *__restrict__ dz, int planes, int H, int W)
+{
+    const int w = blockIdx.y;
+    const int Ho = H / 2, Wo = W / 2, total = planes * Ho * Wo;
+    const int o = blockIdx.x * 256 + threadIdx.x;
+    if (o >= total) return;
+    const int pl = o / (Ho * Wo), rem = o - pl * Ho * Wo, oh = rem / Wo, ow = rem - oh * Wo;
+    const int64_t base = w * zstride + ((int64_t)pl * H + 2 * oh) * W + 2 * ow;
+    const float v0 = z[base], v1 = z[base + 1], v2 = z[base + W], v3 = z[base + W + 1];
+    const float m = fmaxf(fmaxf(v0, v1), fmaxf(v2, v3));
+    const float gsrc = dp[w * pstride + o];
+    int arg = -1;
+    if (m > 0.f) arg = (v0 == m) ? 0 : (v1 == m) ? 1 : (v2 == m) ? 2 : 3;
+    dz[base] = arg == 0 ? gsrc : 0.f;
+    dz[base + 1] = arg == 1 ? gsrc : 0.f;
+    dz[base + W] = arg == 2 ? gsrc : 0.f;
+    dz[base + W + 1] = arg == 3 ? gsrc : 0.f;
+}
+
+// db[ch] = sum over batch and pixels of dz[b][ch][hw]; one workgroup per (channel, worker).
+__global__ __launch_bounds__(256) void channel_sum_kernel(const float *__restrict__ dz, int64_t stride, int B, int C,
+                                                          int HW, float *__restrict__ db, int64_t dbstride)
+{
+    __shared__ float red[256];
+    const int ch = blockIdx.x, w = blockIdx.y, tid = threadIdx.x;
+    float s = 0.f;
+    for (int i = tid; i < B * HW; i += 256) {
+        const int b = i / HW, hw = i - b * HW;
+        s += dz[w * stride + (int64_t)(b * C + ch) * HW + hw];
+    }
+    red[tid] = s;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if (tid < o) red[tid] += red[tid + o];
+        __syncthreads();
+    }
+    if (tid == 0) db[w * dbstride + ch] = red[0];
+}
+
+struct cnn_layout {
+    int C0, H, W, C1, C2, KS, F, NC, B;
+    int H2, W2, H4, W4, flat;
+    int fc_dims[3];
+    // parameter offsets inside a row
+    int64_t w1, b1, w2, b2, fc;
+    // scratch offsets inside a worker's block (floats)
+    int64_t z1, p1, z2, p2, dp2, dz2, dp1, dz1, fc_act, part, total;
+    int splits1, splits2;
+};
+
+cnn_layout make_layout(const dbw_model &m)
+{
+    cnn_layout L{};
+    L.C0 = m.dims[0]; L.H = m.dims[1]; L.W = m.dims[2]; L.C1 = m.dims[3]; L.C2 = m.dims[4];
+    L.KS = m.dims[5]; L.F = m.dims[6]; L.NC = m.dims[7]; L.B = m.batch;
+    L.H2 = L.H / 2; L.W2 = L.W / 2; L.H4 = L.H / 4; L.W4 = L.W / 4;
+    L.flat = L.C2 * L.H4 * L.W4;
+    L.fc_dims[0] = L.flat; L.fc_dims[1] = L.F; L.fc_dims[2] = L.NC;
+    const int64_t KK = (int64_t)L.KS * L.KS;
+    L.w1 = 0;
+    L.b1 = L.w1 + L.C1 * L.C0 * KK;
+    L.w2 = L.b1 + L.C1;
+    L.b2 = L.w2 + L.C2 * L.C1 * KK;
+    L.fc = L.b2 + L.C2;
+    const int64_t B = L.B;
+    int64_t o = 0;
+    auto take = [&](int64_t n) { const int64_t at = o; o += (n + 63) / 64 * 64; return at; };
+    L.z1 = take(B * L.C1 * L.H * L.W);
+    L.p1 = take(B * L.C1 * L.H2 * L.W2);
+    L.z2 = take(B * L.C2 * L.H2 * L.W2);
+    L.p2 = take(B * L.flat);
+    L.dp2 = take(B * L.flat);
+    L.dz2 = take(B * L.C2 * L.H2 * L.W2);
+    L.dp1 = take(B * L.C1 * L.H2 * L.W2);
+    L.dz1 = take(B * L.C1 * L.H * L.W);
+    L.fc_act = take(dbw_fc_scratch_per_worker(2, L.fc_dims, L.B));
+    // split the long pixel reductions of the weight gradients so that the grid fills the chip
+    auto pick = [&](int64_t K) { int s = 1; while (s < 32 && K / (s * 2) >= 1024) s *= 2; return s; };
+    L.splits1 = pick(B * L.H * L.W);
+    L.splits2 = pick(B * L.H2 * L.W2);
+    const int64_t p1n = (int64_t)L.splits1 * L.C1 * L.C0 * KK, p2n = (int64_t)L.splits2 * L.C2 * L.C1 * KK;
+    L.part = take(p1n > p2n ? p1n : p2n);
+    L.total = o;
+    return L;
+}
+
+}  // namespace
+
+size_t dbw_cnn_scratch_floats(const dbw_ctx *c) { return (size_t)make_layout(c->model).total * c->N; }
+
+int dbw_launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const int32_t *by, float *grads,
+                        float *loss, hipStream_t s)
+{
+    const cnn_layout L = make_layout(c->model);
+    const int N = c->N, B = L.B, KK = L.KS * L.KS;
+    float *A = c->act;
+    const int64_t ws = L.total, ld = c->ld;
+    const int64_t xstride = (int64_t)B * L.C0 * L.H * L.W;
+    const ConvShape s1{L.C0, L.C1, L.H, L.W, L.KS, L.KS / 2}, s2{L.C1, L.C2, L.H2, L.W2, L.KS, L.KS / 2};
+    const int pix1 = B * L.H * L.W, pix2 = B * L.H2 * L.W2;
+    auto blocks = [](int64_t n) { return (unsigned)((n + 255) / 256); };
+
+    {   // conv1 forward
+        dbw_timer tm(c, "conv1_forward", s);
+        DBW_HIP(bgemm::launch(Dense<true>{params + L.w1, L.C0 * KK, ld}, PatchRC{bx, xstride, s1},
+                              ChannelPixelOut{A + L.z1, ws, L.C1, L.H * L.W, params + L.b1, ld}, L.C1, pix1,
+                              L.C0 * KK, N, s));
+    }
+    {
+        dbw_timer tm(c, "relu_pool_fwd_kernel", s);
+        hipLaunchKernelGGL(relu_pool_fwd_kernel, dim3(blocks((int64_t)B * L.C1 * L.H2 * L.W2), N), dim3(256), 0, s,
+                           A + L.z1, ws, A + L.p1, ws, B * L.C1, L.H, L.W);
+        DBW_HIP(hipGetLastError());
+    }
+    {   // conv2 forward
+        dbw_timer tm(c, "conv2_forward", s);
+        DBW_HIP(bgemm::launch(Dense<true>{params + L.w2, L.C1 * KK, ld}, PatchRC{A + L.p1, ws, s2},
+                              ChannelPixelOut{A + L.z2, ws, L.C2, L.H2 * L.W2, params + L.b2, ld}, L.C2, pix2,
+                              L.C1 * KK, N, s));
+    }
+    {
+        dbw_timer tm(c, "relu_pool_fwd_kernel", s);
+        hipLaunchKernelGGL(relu_pool_fwd_kernel, dim3(blocks((int64_t)B * L.flat), N), dim3(256), 0, s, A + L.z2, ws,
+                           A + L.p2, ws, B * L.C2, L.H2, L.W2);
+        DBW_HIP(hipGetLastError());
+    }
+    {   // fully connected head, forward and backward, down to the gradient of the pooled features
+        dbw_fc_args a{};
+        a.L = 2;
+        a.B = B;
+        a.dims = L.fc_dims;
+        a.params = params;
+        a.grads = grads;
+        a.param_off = L.fc;
+        a.in = A + L.p2;
+        a.in_ld = L.flat;
+        a.in_stride = ws;
+        a.act = A + L.fc_act;
+        a.act_stride = ws;
+        a.din = A + L.dp2;
+        a.din_ld = L.flat;
+        a.din_stride = ws;
+        a.y = by;
+        a.loss = loss;
+        const int rc = dbw_fc_forward_backward(c, a, s);
+        if (rc != DBW_OK) return rc;
+    }
+    {
+        dbw_timer tm(c, "relu_pool_bwd_kernel", s);
+        hipLaunchKernelGGL(relu_pool_bwd_kernel, dim3(blocks((int64_t)B * L.flat), N), dim3(256), 0, s, A + L.z2, ws,
+                           A + L.dp2, ws, A + L.dz2, B * L.C2, L.H2, L.W2);
+        DBW_HIP(hipGetLastError());
+    }
+    {   // conv2 weight gradient (split over pixels, then summed in split order) and bias gradient
+        dbw_timer tm(c, "conv2_wgrad", s);
+        DBW_HIP(bgemm::launch(DeltaKC{A + L.dz2, ws, L.C2, L.H2 * L.W2}, PatchKC{A + L.p1, ws, s2},
+                              PartialOut{A + L.part, ws, L.C2, L.C1 * KK}, L.C2, L.C1 * KK, pix2, N, s,
+                              L.splits2));
+    }
+    {
+        dbw_timer tm(c, "reduce_splits_kernel", s);
+        hipLaunchKernelGGL(reduce_splits_kernel, dim3(blocks((int64_t)L.C2 * L.C1 * KK), N), dim3(256), 0, s,
+                           A + L.part, ws, L.splits2, L.C2 * L.C1 * KK, grads + L.w2, ld);
+        DBW_HIP(hipGetLastError());
+    }
+    {
+        dbw_timer tm(c, "channel_sum_kernel", s);
+        hipLaunchKernelGGL(channel_sum_kernel, dim3(L.C2, N), dim3(256), 0, s, A + L.dz2, ws, B, L.C2, L.H2 * L.W2,
+                           grads + L.b2, ld);
+        DBW_HIP(hipGetLastError());
+    }
+    {   // conv2 data gradient -> gradient of the first pooled map
+        dbw_timer tm(c, "conv2_dgrad", s);
+        DBW_HIP(bgemm::launch(FilterT{params + L.w2, ld, L.C1, KK}, DeltaShiftRC{A + L.dz2, ws, s2},
+                              ChannelPixelOut{A + L.dp1, ws, L.C1, L.H2 * L.W2, nullptr, 0}, L.C1, pix2, L.C2 * KK, N,
+                              s));
+    }
+    {
+        dbw_timer tm(c, "relu_pool_bwd_kernel", s);
+        hipLaunchKernelGGL(relu_pool_bwd_kernel, dim3(blocks((int64_t)B * L.C1 * L.H2 * L.W2), N), dim3(256), 0, s,
+                           A + L.z1, ws, A + L.dp1, ws, A + L.dz1, B * L.C1, L.H, L.W);
+        DBW_HIP(hipGetLastError());
+    }
+    {   // conv1 weight and bias gradients
+        dbw_timer tm(c, "conv1_wgrad", s);
+        DBW_HIP(bgemm::launch(DeltaKC{A + L.dz1, ws, L.C1, L.H * L.W}, PatchKC{bx, xstride, s1},
+                              PartialOut{A + L.part, ws, L.C1, L.C0 * KK}, L.C1, L.C0 * KK, pix1, N, s,
+                              L.splits1));
+    }
+    {
+        dbw_timer tm(c, "reduce_splits_kernel", s);
+        hipLaunchKernelGGL(reduce_splits_kernel, dim3(blocks((int64_t)L.C1 * L.C0 * KK), N), dim3(256), 0, s,
+                           A + L.part, ws, L.splits1, L.C1 * L.C0 * KK, grads + L.w1, ld);
+        DBW_HIP(hipGetLastError());
+    }
+    {
+        dbw_timer tm(c, "channel_sum_kernel", s);
+        hipLaunchKernelGGL(channel_sum_kernel, dim3(L.C1, N), dim3(256), 0, s, A + L.dz1, ws, B, L.C1, L.H * L.W,
+                           grads + L.b1, ld);
+        DBW_HIP(hipGetLastError());
+    }
+    return DBW_OK;
+}

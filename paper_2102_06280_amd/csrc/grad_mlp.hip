@@ -58,80 +58,112 @@ __global__ __launch_bounds__(256) void colsum_kernel(int B, int C, const float *
     db[w * stride_db + o] = s;
 }
 
-int64_t acts_per_worker(const dbw_model &m)
-{
-    int64_t n = 0;
-    for (int l = 1; l <= m.n_layers; ++l) n += (int64_t)m.batch * m.dims[l];
-    return n;
-}
-
 }  // namespace
 
-size_t dbw_mlp_scratch_floats(const dbw_ctx *c) { return (size_t)(2 * acts_per_worker(c->model)) * c->N; }
-
-int dbw_launch_grad_mlp(dbw_ctx *c, const float *params, const float *bx, const int32_t *by, float *grads,
-                        float *loss, hipStream_t s)
+int64_t dbw_fc_scratch_per_worker(int L, const int32_t *dims, int B)
 {
-    const dbw_model &m = c->model;
-    const int L = m.n_layers, B = m.batch, N = c->N;
-    const int64_t per = acts_per_worker(m), wstride = 2 * per;
+    int64_t n = 0;
+    for (int l = 1; l <= L; ++l) n += (int64_t)B * dims[l];
+    return 2 * n;
+}
+
+// Forward and backward pass of a stack of fully connected layers for all workers.
+int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
+{
+    const int L = a.L, B = a.B, N = c->N;
+    const int32_t *dims = a.dims;
+    const int64_t per = dbw_fc_scratch_per_worker(L, dims, B) / 2, wstride = a.act_stride;
     // offsets inside a worker's scratch block and parameter row
     int64_t a_off[9], dz_off[9], w_off[9], b_off[9];
-    int64_t ao = 0, po = 0;
+    int64_t ao = 0, po = a.param_off;
     for (int l = 1; l <= L; ++l) {
         a_off[l] = ao;
         dz_off[l] = per + ao;
-        ao += (int64_t)B * m.dims[l];
+        ao += (int64_t)B * dims[l];
         w_off[l] = po;
-        b_off[l] = po + (int64_t)m.dims[l] * m.dims[l - 1];
-        po = b_off[l] + m.dims[l];
+        b_off[l] = po + (int64_t)dims[l] * dims[l - 1];
+        po = b_off[l] + dims[l];
     }
-    float *act = c->act;
+    float *act = a.act;
+    const float *params = a.params;
+    float *grads = a.grads;
 
     // forward: a_l = relu(a_{l-1} W_l^T + b_l), no ReLU on the logits
     for (int l = 1; l <= L; ++l) {
         Dense<true> A, Bm;
         if (l == 1)
-            A = {bx, m.dims[0], (int64_t)B * m.dims[0]};
+            A = {a.in, a.in_ld, a.in_stride};
         else
-            A = {act + a_off[l - 1], m.dims[l - 1], wstride};
-        Bm = {params + w_off[l], m.dims[l - 1], c->ld};
-        Epilogue E{act + a_off[l], m.dims[l], wstride, params + b_off[l], c->ld, nullptr, 0, 0, l < L ? 1 : 0};
+            A = {act + a_off[l - 1], dims[l - 1], wstride};
+        Bm = {params + w_off[l], dims[l - 1], c->ld};
+        Epilogue E{act + a_off[l], dims[l], wstride, params + b_off[l], c->ld, nullptr, 0, 0, l < L ? 1 : 0};
         dbw_timer tm(c, "mlp_forward_gemm", s);
-        DBW_HIP(bgemm::launch(A, Bm, E, B, m.dims[l], m.dims[l - 1], N, s));
+        DBW_HIP(bgemm::launch(A, Bm, E, B, dims[l], dims[l - 1], N, s));
     }
     {
         dbw_timer tm(c, "softmax_xent_kernel", s);
-        hipLaunchKernelGGL(softmax_xent_kernel, dim3(N), dim3(256), 0, s, B, m.dims[L], act + a_off[L], wstride, by,
-                           act + dz_off[L], wstride, loss);
+        hipLaunchKernelGGL(softmax_xent_kernel, dim3(N), dim3(256), 0, s, B, dims[L], act + a_off[L], wstride, a.y,
+                           act + dz_off[L], wstride, a.loss);
         DBW_HIP(hipGetLastError());
     }
     // backward
     for (int l = L; l >= 1; --l) {
         {   // dW_l = dz_l^T a_{l-1}
-            Dense<false> A{act + dz_off[l], m.dims[l], wstride}, Bm;
+            Dense<false> A{act + dz_off[l], dims[l], wstride}, Bm;
             if (l == 1)
-                Bm = {bx, m.dims[0], (int64_t)B * m.dims[0]};
+                Bm = {a.in, a.in_ld, a.in_stride};
             else
-                Bm = {act + a_off[l - 1], m.dims[l - 1], wstride};
-            Epilogue E{grads + w_off[l], m.dims[l - 1], c->ld, nullptr, 0, nullptr, 0, 0, 0};
+                Bm = {act + a_off[l - 1], dims[l - 1], wstride};
+            Epilogue E{grads + w_off[l], dims[l - 1], c->ld, nullptr, 0, nullptr, 0, 0, 0};
             dbw_timer tm(c, "mlp_wgrad_gemm", s);
-            DBW_HIP(bgemm::launch(A, Bm, E, m.dims[l], m.dims[l - 1], B, N, s));
+            DBW_HIP(bgemm::launch(A, Bm, E, dims[l], dims[l - 1], B, N, s));
         }
         {
             dbw_timer tm(c, "colsum_kernel", s);
-            hipLaunchKernelGGL(colsum_kernel, dim3((m.dims[l] + 255) / 256, N), dim3(256), 0, s, B, m.dims[l],
+            hipLaunchKernelGGL(colsum_kernel, dim3((dims[l] + 255) / 256, N), dim3(256), 0, s, B, dims[l],
                                act + dz_off[l], wstride, grads + b_off[l], c->ld);
             DBW_HIP(hipGetLastError());
         }
         if (l > 1) {   // dz_{l-1} = (dz_l W_l) masked by a_{l-1} > 0
-            Dense<true> A{act + dz_off[l], m.dims[l], wstride};
-            Dense<false> Bm{params + w_off[l], m.dims[l - 1], c->ld};
-            Epilogue E{act + dz_off[l - 1], m.dims[l - 1], wstride, nullptr, 0, act + a_off[l - 1], m.dims[l - 1],
+            Dense<true> A{act + dz_off[l], dims[l], wstride};
+            Dense<false> Bm{params + w_off[l], dims[l - 1], c->ld};
+            Epilogue E{act + dz_off[l - 1], dims[l - 1], wstride, nullptr, 0, act + a_off[l - 1], dims[l - 1],
                        wstride, 0};
             dbw_timer tm(c, "mlp_dgrad_gemm", s);
-            DBW_HIP(bgemm::launch(A, Bm, E, B, m.dims[l - 1], m.dims[l], N, s));
+            DBW_HIP(bgemm::launch(A, Bm, E, B, dims[l - 1], dims[l], N, s));
+        } else if (a.din) {   // gradient with respect to the stack's input, unmasked
+            Dense<true> A{act + dz_off[1], dims[1], wstride};
+            Dense<false> Bm{params + w_off[1], dims[0], c->ld};
+            Epilogue E{a.din, a.din_ld, a.din_stride, nullptr, 0, nullptr, 0, 0, 0};
+            dbw_timer tm(c, "mlp_dgrad_gemm", s);
+            DBW_HIP(bgemm::launch(A, Bm, E, B, dims[0], dims[1], N, s));
         }
     }
     return DBW_OK;
+}
+
+size_t dbw_mlp_scratch_floats(const dbw_ctx *c)
+{
+    return (size_t)dbw_fc_scratch_per_worker(c->model.n_layers, c->model.dims, c->model.batch) * c->N;
+}
+
+int dbw_launch_grad_mlp(dbw_ctx *c, const float *params, const float *bx, const int32_t *by, float *grads,
+                        float *loss, hipStream_t s)
+{
+    const dbw_model &m = c->model;
+    dbw_fc_args a{};
+    a.L = m.n_layers;
+    a.dims = m.dims;
+    a.B = m.batch;
+    a.params = params;
+    a.grads = grads;
+    a.param_off = 0;
+    a.in = bx;
+    a.in_ld = m.dims[0];
+    a.in_stride = (int64_t)m.batch * m.dims[0];
+    a.act = c->act;
+    a.act_stride = dbw_fc_scratch_per_worker(m.n_layers, m.dims, m.batch);
+    a.y = by;
+    a.loss = loss;
+    return dbw_fc_forward_backward(c, a, s);
 }

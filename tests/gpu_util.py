@@ -7,10 +7,40 @@ def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
+# The gradients are discontinuous where a ReLU input is zero or two pooled values tie.  fp32
+# accumulation leaves pre-activations of unit scale uncertain by about 1e-6, so a decision
+# whose margin (reported by the oracle) is below these bounds may legitimately fall on the
+# other side on the GPU; observed flips all had margins below 1.5e-6.  Such a worker is
+# compared loosely, every other worker to the full tolerance, and at least three quarters
+# of all workers must meet the full tolerance whatever their margins.
+AMBIGUOUS_CONV, AMBIGUOUS_FC = 2e-6, 1e-5
+AMBIGUOUS_TOL = 1e-3
+
+
+def ambiguous(margin):
+    margin = np.asarray(margin)
+    return (margin[:, 0] < AMBIGUOUS_CONV) | (margin[:, 1] < AMBIGUOUS_FC)
+
+
+def row_tolerances(margin, tol=1e-5):
+    """Per-worker tolerance: `tol` where every ReLU / max-pooling decision of the worker's
+    gradient is clear, AMBIGUOUS_TOL where the oracle reports a near-tie."""
+    return np.where(ambiguous(margin), AMBIGUOUS_TOL, tol)
+
+
+def assert_mostly_tight(got, want, d, tol=1e-5, frac=0.75, what=""):
+    g, w = got[:, :d].astype(np.float64), want[:, :d].astype(np.float64)
+    rel = np.linalg.norm(g - w, axis=1) / np.maximum(np.linalg.norm(w, axis=1), 1e-300)
+    ok = (rel <= tol).mean()
+    assert ok >= frac, f"{what}: only {ok:.0%} of the workers within {tol:g}"
+    return rel
+
+
 def assert_params_close(got: np.ndarray, want: np.ndarray, d=None, tol=1e-5, what=""):
     """Per worker row: ||got - want||_2 <= tol * ||want||_2 (absolute tol when the row is
-    zero) and max |got - want| <= tol * max(1, ||want||_inf)."""
+    zero) and max |got - want| <= tol * max(1, ||want||_inf).  tol may be per row."""
     d = got.shape[1] if d is None else d
+    tol = np.broadcast_to(np.asarray(tol, dtype=np.float64), (got.shape[0],))
     g, w = got[:, :d].astype(np.float64), want[:, :d].astype(np.float64)
     diff = g - w
     l2 = np.linalg.norm(diff, axis=1)

@@ -1,0 +1,145 @@
+"""GPU parity of the convolutional model's batched gradients, the threshold rule, and a
+lock-step round of configuration 3 (threshold-rule backup counts), against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2102_06280_amd import inputs
+from gpu_util import ambiguous, assert_mostly_tight, assert_params_close, dev, row_tolerances
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2102_06280_amd import binding
+    return binding
+
+
+def rel_l2(a, b):
+    return np.linalg.norm(a.astype(np.float64) - b) / max(np.linalg.norm(b), 1e-30)
+
+
+def cnn_desc(shape):
+    C0, H, W, C1, C2, K, F, NC = shape
+    return {"kind": "cnn", "in": (C0, H, W), "c1": C1, "c2": C2, "k": K, "fc": F, "classes": NC}
+
+
+SHAPES = [((2, 8, 8, 3, 4, 3, 6, 5), 4, 3), ((3, 8, 8, 2, 3, 5, 4, 3), 3, 3), ((3, 16, 16, 8, 8, 5, 16, 10), 5, 4),
+          ((1, 12, 20, 5, 7, 3, 9, 4), 6, 3), ((3, 32, 32, 32, 64, 5, 512, 10), 32, 3)]
+
+
+@pytest.mark.parametrize("shape,batch,n", SHAPES, ids=["tiny3x3", "tiny5x5", "mid", "rect", "full-shape"])
+def test_cnn_gradients_match_oracle(B, orc, shape, batch, n):
+    g = np.random.default_rng(501)
+    desc = cnn_desc(shape)
+    d = inputs.param_count(desc)
+    ld = inputs.pad_ld(d)
+    rowptr, colidx = inputs.graph_ring(n)
+    params = inputs.init_params(desc, n, ld, g)
+    params[:, :d] += (g.standard_normal((n, d)) * 0.02).astype(np.float32)
+    C0, H, W = desc["in"]
+    x = g.standard_normal((n, batch, C0 * H * W)).astype(np.float32)
+    y = g.integers(0, shape[-1], (n, batch)).astype(np.int32)
+    h = B.dbw_create(rowptr, colidx, n, d, ld=ld, model=B.make_model(B.MODEL_CNN, batch, shape))
+    try:
+        grads = torch.full((n, ld), 7.0, dtype=torch.float32, device="cuda")
+        loss = torch.zeros(n, dtype=torch.float32, device="cuda")
+        B.dbw_grad(h, dev(params), dev(x), dev(y), grads, loss)
+        got, gl = grads.cpu().numpy(), loss.cpu().numpy()
+        kind, od = orc.model_desc(desc)
+        orc.set_threads(min(n, 8))
+        want, wl, margin = orc.grad_all(kind, od, d, params, x, y, with_margin=True)
+        orc.set_threads(1)
+        amb = ambiguous(margin)
+        assert np.allclose(gl, wl, rtol=5e-6, atol=1e-6)
+        assert np.all(got[:, d:] == 7.0)
+        off = 0
+        for li, (fan_in, nw, nb) in enumerate(inputs.layer_shapes(desc)):
+            for lo, hi, what in ((off, off + nw, "W"), (off + nw, off + nw + nb, "b")):
+                for i in range(n):
+                    r = rel_l2(got[i, lo:hi], want[i, lo:hi])
+                    assert r <= (2e-2 if amb[i] else 3e-5), f"worker {i} layer {li} {what} rel L2 {r:.2e}"
+            off += nw + nb
+    finally:
+        B.dbw_destroy(h)
+
+
+def test_threshold_rule_matches_oracle(B, orc):
+    """dbw_dtur_b over three epochs on configuration 3's graph, ties included."""
+    cfg = inputs.CONFIGS[3]
+    rowptr, colidx = inputs.make_graph(cfg)
+    n = cfg.n
+    h = B.dbw_create(rowptr, colidx, n, 64)
+    try:
+        dt = orc.Dtur(rowptr, colidx)
+        assert np.array_equal(B.dbw_get_links(h, n), dt.edges)
+        b_d = torch.zeros(n, dtype=torch.int32, device="cuda")
+        th_d = torch.zeros(1, dtype=torch.float32, device="cuda")
+        g = np.random.default_rng(503)
+        for k in range(3 * (n - 1) + 5):
+            t = inputs.response_times(cfg, k)
+            if k % 3 == 1:
+                t = (np.ceil(t * 2) / 2).astype(np.float32)
+            if k % 7 == 3:
+                t[g.integers(0, n)] = np.inf
+            B.dbw_dtur_b(h, dev(t), b_d, th_d)
+            b, theta = dt.step(t)
+            assert np.array_equal(b_d.cpu().numpy(), b), k
+            assert th_d.item() == np.float32(theta), k
+        B.dbw_dtur_reset(h)
+        dt2 = orc.Dtur(rowptr, colidx)
+        t = inputs.response_times(cfg, 99)
+        B.dbw_dtur_b(h, dev(t), b_d, th_d)
+        assert np.array_equal(b_d.cpu().numpy(), dt2.step(t)[0])
+    finally:
+        B.dbw_destroy(h)
+
+
+def test_config3_rounds_lock_step(B, orc):
+    """Two rounds of configuration 3: round 1 with b = 0 (Algorithm 1), round 2 with backup
+    counts from the threshold rule; parameters compared per round from the oracle's state."""
+    cfg = inputs.CONFIGS[3]
+    desc = inputs.model_dims(cfg.model)
+    rowptr, colidx = inputs.make_graph(cfg)
+    ld = inputs.pad_ld(cfg.d)
+    kind, od = orc.model_desc(desc)
+    c, hh, ww = desc["in"]
+    shape = [c, hh, ww, desc["c1"], desc["c2"], desc["k"], desc["fc"], desc["classes"]]
+    h = B.dbw_create(rowptr, colidx, cfg.n, cfg.d, ld=ld, model=B.make_model(B.MODEL_CNN, cfg.batch, shape))
+    try:
+        x = inputs.init_params(desc, cfg.n, ld, inputs.rng(3, inputs.P_PARAMS))
+        dt = orc.Dtur(rowptr, colidx)
+        b_d = torch.zeros(cfg.n, dtype=torch.int32, device="cuda")
+        for rnd in range(2):
+            t = inputs.response_times(cfg, rnd)
+            bx, by = inputs.batch(cfg, rnd)
+            dtt = dev(t)
+            if rnd == 0:
+                b = np.zeros(cfg.n, np.int32)
+            else:
+                b, _ = dt.step(t)
+                B.dbw_dtur_b(h, dtt, b_d)
+                assert np.array_equal(b_d.cpu().numpy(), b)
+            out = torch.zeros((cfg.n, ld), device="cuda")
+            loss = torch.zeros(cfg.n, device="cuda")
+            B.dbw_select(h, dtt, b_d)
+            B.dbw_round(h, dev(x), out, cfg.lr, batch_x=dev(bx), batch_y=dev(by), loss_out=loss)
+            got = out.cpu().numpy()
+            mask, p, _ = orc.select(rowptr, colidx, t, b)
+            orc.set_threads(16)
+            grad, oloss, margin = orc.grad_all(kind, od, cfg.d, x, bx, by, with_margin=True)
+            orc.set_threads(1)
+            print(f"round {rnd}: smallest decision margins conv {margin[:, 0].min():.1e} fc {margin[:, 1].min():.1e}, "
+                  f"{ambiguous(margin).sum()} workers flagged")
+            want = orc.round_(rowptr, colidx, mask, p, x, grad, cfg.lr, 0, d=cfg.d)
+            mask_d = torch.empty(colidx.size, dtype=torch.uint8, device="cuda")
+            B.dbw_get_selection(h, None, mask_d, None)
+            assert np.array_equal(mask_d.cpu().numpy(), mask)
+            assert_params_close(got, want, d=cfg.d, tol=row_tolerances(margin), what=f"config 3 round {rnd}")
+            rel = assert_mostly_tight(got, want, cfg.d, what=f"config 3 round {rnd}")
+            print(f"round {rnd}: median row error {np.median(rel):.1e}, {(rel > 1e-5).sum()} rows above 1e-5")
+            assert np.allclose(loss.cpu().numpy(), oloss, rtol=1e-5, atol=1e-6)
+            x = want
+    finally:
+        B.dbw_destroy(h)

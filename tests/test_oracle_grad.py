@@ -193,3 +193,27 @@ def test_grad_all_rows_and_padding(orc):
     for i in range(n):
         gi, li = orc.grad_mlp(dims, params[i, :d], x[i], y[i])
         assert np.array_equal(grad[i, :d], gi) and loss[i] == li
+
+
+def test_decision_margin_diagnostic(orc):
+    """The margin reported next to the gradients is the smallest |z| over all hidden ReLU
+    inputs (recomputed here with NumPy)."""
+    dims = [9, 7, 6, 4]
+    g = np.random.default_rng(83)
+    d = sum(dims[l + 1] * (dims[l] + 1) for l in range(3))
+    params = np.zeros((2, 192), np.float32)
+    params[:, :d] = g.standard_normal((2, d)) * 0.5
+    x = g.standard_normal((2, 5, 9)).astype(np.float32)
+    y = g.integers(0, 4, (2, 5)).astype(np.int32)
+    kind, desc = orc.model_desc({"kind": "mlp", "dims": dims})
+    _, _, margin = orc.grad_all(kind, desc, d, params, x, y, with_margin=True)
+    for i in range(2):
+        a, off, smallest = x[i].astype(np.float64), 0, np.inf
+        for l in range(2):
+            o, k = dims[l + 1], dims[l]
+            W = params[i, off:off + o * k].reshape(o, k).astype(np.float64); off += o * k
+            b = params[i, off:off + o].astype(np.float64); off += o
+            z = a @ W.T + b
+            smallest = min(smallest, np.abs(z).min())
+            a = np.maximum(z, 0)
+        assert abs(margin[i, 1] - smallest) < 1e-12 and np.isinf(margin[i, 0])
