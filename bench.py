@@ -24,6 +24,11 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix
 
+# HBM bytes per launch from hardware counters (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors
+# from a plain copy of known size; profiles/ holds the runs).  Keyed by (kernel, config);
+# an entry is removed when its kernel changes.
+MEASURED_TRAFFIC = {("mix_lds_tiles", 4): 17.203e9}
+
 
 def cpu_baseline(cid: int, wl_rowptr, wl_colidx, budget_s: float = 15.0):
     """The CPU oracle, as it stands, timed on this host on a bounded sample of the same
@@ -89,6 +94,9 @@ def main():
     ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--order", choices=["cta", "atc"], default="cta")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="after the timed region, run three plain device copies of one N x ld parameter matrix "
+                         "(known size) so that hardware byte counters can be scaled against them")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this implementation runs on exactly one GPU (all N workers are simulated on it); "
@@ -119,6 +127,11 @@ def main():
     B.dbw_set_timing(wl.h, False)
     B.dbw_check(wl.h)
 
+    if args.copy_calibration:
+        for _ in range(3):
+            wl.x[wl.cur ^ 1].copy_(wl.x[wl.cur])
+        torch.cuda.synchronize()
+
     ms_per_step = elapsed / args.steps * 1e3
     value = cfg.n * args.steps / elapsed
 
@@ -141,6 +154,7 @@ def main():
         work = kernel_flops(cfg, dominant)
         roofline = {"bound": "mfma", "achieved": work / (dom_ms * 1e-3) / 1e12, "peak": MFMA_FP32_PEAK_TFLOPS,
                     "unit": "TFLOP/s", "traffic": None}
+    roofline["traffic"] = MEASURED_TRAFFIC.get((dominant, cfg.cid))
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
     roofline["kernel"] = dominant
     roofline["kernel_ms"] = dom_ms
