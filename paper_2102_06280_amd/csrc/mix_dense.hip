@@ -8,9 +8,12 @@
 // wavefronts of a workgroup keeps the A-operand fragments of one 32-row block of P for the
 // whole kernel.  The workgroup walks over column tiles of X; a tile (NPAD rows x TC
 // columns) is staged once through LDS, laid out so that the B-operand fragment of
-// v_mfma_f32_32x32x2_f32 for k-step kk is one conflict-free 64-lane row.  The next tile's
-// global loads are in flight while the current one is multiplied.  True fp32 MFMA: no
-// reduced-precision input format anywhere.
+// v_mfma_f32_32x32x2_f32 for k-step kk is one conflict-free 64-lane row.  The next tile is
+// on its way while the current one is multiplied: when no element needs a guard or a
+// prologue (FULL tiles, CTA order) it goes from global memory straight into LDS
+// (global_load_lds, 16 bytes per lane), otherwise through registers.  The gradient values
+// of the epilogue are requested before the multiply loop so that they have arrived when it
+// ends.  True fp32 MFMA: no reduced-precision input format anywhere.
 //
 // Fragment layout of v_mfma_f32_32x32x2_f32 (M = N = 32, K = 2), lane l in [0, 64):
 //   A: a = A[m = l % 32][k = l / 32]        B: b = B[k = l / 32][n = l % 32]
@@ -22,6 +25,8 @@
 namespace {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(1))) const void *global_cptr;
+typedef __attribute__((address_space(3))) void *lds_ptr;
 
 constexpr int DENSE_THREADS = 512;
 
@@ -35,18 +40,22 @@ struct dense_cfg {
     static constexpr int TC = 32 * NSUB;              // tile columns
     static constexpr int TILE = NPAD * TC;            // floats per LDS buffer
     static constexpr int PASSES = TILE / 4 / DENSE_THREADS;
+    static constexpr int DMA_PER_WAVE = TILE / 256 / 8;   // 1 KB blocks per wave and tile
 };
 
-template <int MB, int ORDER, bool HAS_G>
+// FULL: N == NPAD and every tile has all TC columns, so no access needs a guard.
+template <int MB, int ORDER, bool HAS_G, bool FULL>
 __global__ __launch_bounds__(DENSE_THREADS) void mix_dense_kernel(
     int N, int64_t n_vec /* float4 columns covered */, int64_t ld4, const float *__restrict__ Wsw,
     const float4 *__restrict__ x, const float4 *__restrict__ g, float *__restrict__ out,
     const float *__restrict__ gs, float lr, int n_tiles)
 {
     using C = dense_cfg<MB>;
+    constexpr bool DMA = FULL && !(ORDER == DBW_ORDER_ATC && HAS_G);
     __shared__ __attribute__((aligned(16))) float lds[2 * C::TILE];
 
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave index, kept scalar
     const int rb = w % MB, cg = w / MB;
     const int64_t ld = ld4 * 4, dcols = n_vec * 4;
 
@@ -54,19 +63,21 @@ __global__ __launch_bounds__(DENSE_THREADS) void mix_dense_kernel(
 #pragma unroll
     for (int kk = 0; kk < C::KB; ++kk) wreg[kk] = Wsw[((size_t)(rb * C::KB + kk)) * 64 + lane];
 
-    // global -> registers for one tile
-    float4 stage[C::PASSES];
+    // ---- next-tile staging through registers (guards / ATC prologue)
+    float4 stage[DMA ? 1 : C::PASSES];
+    const uint32_t fetch_lane_off = (uint32_t)((tid / (C::TC / 4)) * ld4 + tid % (C::TC / 4));
     auto fetch = [&](int64_t tile) {
 #pragma unroll
-        for (int ps = 0; ps < C::PASSES; ++ps) {
-            const int f = ps * DENSE_THREADS + tid;
-            const int k = f / (C::TC / 4), c4 = f % (C::TC / 4);
-            const int64_t col4 = tile * (C::TC / 4) + c4;
+        for (int ps = 0; ps < (DMA ? 0 : C::PASSES); ++ps) {
+            const int k0 = ps * (DENSE_THREADS / (C::TC / 4));                   // uniform first row of the pass
+            const int k = k0 + tid / (C::TC / 4);
+            const int64_t col4 = tile * (C::TC / 4) + tid % (C::TC / 4);
+            const float4 *xb = x + (int64_t)k0 * ld4 + tile * (C::TC / 4);        // uniform base
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (k < N && col4 < n_vec) {
-                v = x[(int64_t)k * ld4 + col4];
+            if (FULL || (k < N && col4 < n_vec)) {
+                v = xb[fetch_lane_off];
                 if (ORDER == DBW_ORDER_ATC && HAS_G) {
-                    const float4 gv = g[(int64_t)k * ld4 + col4];
+                    const float4 gv = (g + (int64_t)k0 * ld4 + tile * (C::TC / 4))[fetch_lane_off];
                     v.x = fmaf(-lr, gv.x, v.x);
                     v.y = fmaf(-lr, gv.y, v.y);
                     v.z = fmaf(-lr, gv.z, v.z);
@@ -79,24 +90,68 @@ __global__ __launch_bounds__(DENSE_THREADS) void mix_dense_kernel(
     // registers -> LDS buffer `buf`, in B-fragment order: [sub-tile][k-step][lane]
     auto commit = [&](int buf) {
 #pragma unroll
-        for (int ps = 0; ps < C::PASSES; ++ps) {
+        for (int ps = 0; ps < (DMA ? 0 : C::PASSES); ++ps) {
             const int f = ps * DENSE_THREADS + tid;
             const int k = f / (C::TC / 4), c4 = f % (C::TC / 4);
             const int s = c4 / 8, l = (k & 1) * 32 + (c4 & 7) * 4;
             *(float4 *)&lds[buf * C::TILE + ((s * C::KB + (k >> 1)) * 64 + l)] = stage[ps];
         }
     };
+    // ---- next-tile staging straight into LDS.  One instruction fills 1 KB = the 64-lane
+    // rows of four consecutive k-steps of one sub-tile; lane -> (row, 4 columns) follows.
+    const uint32_t dma_lane_off = (uint32_t)((2 * (lane >> 4) + ((lane >> 3) & 1)) * ld4 + (lane & 7));
+    auto dma = [&](int64_t tile, int buf) {
+#pragma unroll
+        for (int i = 0; i < (DMA ? C::DMA_PER_WAVE : 0); ++i) {
+            const int q = w + 8 * i;                                             // uniform block id
+            const int s = q / (C::KB / 4), kq = q % (C::KB / 4);
+            const float4 *src = x + (int64_t)(8 * kq) * ld4 + tile * (C::TC / 4) + s * 8;   // uniform base
+            __builtin_amdgcn_global_load_lds((global_cptr)(src + dma_lane_off),
+                                             (lds_ptr)&lds[buf * C::TILE + q * 256], 16, 0, 0);
+        }
+    };
 
     int64_t tile = blockIdx.x;
     if (tile >= n_tiles) return;
-    fetch(tile);
-    commit(0);
+    if (DMA) {
+        dma(tile, 0);
+        __builtin_amdgcn_s_waitcnt(0);
+    } else {
+        fetch(tile);
+        commit(0);
+    }
     __syncthreads();
+
+    // epilogue addressing: uniform base per (tile, row block, sub-tile, v) + one lane offset
+    const uint32_t epi_lane_off = (uint32_t)(4 * (lane >> 5) * ld + (lane & 31));
 
     int buf = 0;
     for (; tile < n_tiles; tile += gridDim.x) {
         const int64_t next = tile + gridDim.x;
-        if (next < n_tiles) fetch(next);
+        if (next < n_tiles) {
+            if (DMA) dma(next, buf ^ 1); else fetch(next);
+        }
+
+        // gradient values of the epilogue, requested now, used after the multiply loop
+        float gv[C::SPW][16];
+        if (ORDER == DBW_ORDER_CTA && HAS_G) {
+#pragma unroll
+            for (int sp = 0; sp < C::SPW; ++sp) {
+                const int s = cg * C::SPW + sp;
+                const int64_t col0 = tile * C::TC + 32 * s;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row0 = 32 * rb + 8 * (v / 4) + (v & 3);             // uniform
+                    const float *gb = gs + (int64_t)row0 * ld + col0;
+                    if (FULL) {
+                        gv[sp][v] = gb[epi_lane_off];
+                    } else {
+                        const bool ok = row0 + 4 * (lane >> 5) < N && col0 + (lane & 31) < dcols;
+                        gv[sp][v] = ok ? gb[epi_lane_off] : 0.f;
+                    }
+                }
+            }
+        }
 
         f32x16 acc[C::SPW];
 #pragma unroll
@@ -115,27 +170,27 @@ __global__ __launch_bounds__(DENSE_THREADS) void mix_dense_kernel(
             }
         }
 
+        // the next tile is complete in LDS before anybody starts on it; the barrier sits
+        // before this tile's stores so that they drain while the next tile is multiplied
+        if (next < n_tiles && !DMA) commit(buf ^ 1);
+        if (DMA) __builtin_amdgcn_s_waitcnt(0);      // the tile written by global_load_lds has landed
+        __syncthreads();
+        buf ^= 1;
+
         // epilogue: local SGD correction and store, 32 consecutive columns per row
 #pragma unroll
         for (int sp = 0; sp < C::SPW; ++sp) {
             const int s = cg * C::SPW + sp;
-            const int64_t col = tile * C::TC + 32 * s + (lane & 31);
-            if (col < dcols) {
+            const int64_t col0 = tile * C::TC + 32 * s;
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int row = 32 * rb + 8 * (v / 4) + 4 * (lane >> 5) + (v & 3);
-                    if (row < N) {
-                        float r = acc[sp][v];
-                        if (ORDER == DBW_ORDER_CTA && HAS_G) r = fmaf(-lr, gs[(int64_t)row * ld + col], r);
-                        out[(int64_t)row * ld + col] = r;
-                    }
-                }
+            for (int v = 0; v < 16; ++v) {
+                const int row0 = 32 * rb + 8 * (v / 4) + (v & 3);
+                float r = acc[sp][v];
+                if (ORDER == DBW_ORDER_CTA && HAS_G) r = fmaf(-lr, gv[sp][v], r);
+                float *ob = out + (int64_t)row0 * ld + col0;
+                if (FULL || (row0 + 4 * (lane >> 5) < N && col0 + (lane & 31) < dcols)) ob[epi_lane_off] = r;
             }
         }
-
-        if (next < n_tiles) commit(buf ^ 1);
-        __syncthreads();
-        buf ^= 1;
     }
 }
 
@@ -145,6 +200,8 @@ int launch_mb(dbw_ctx *c, const float *x, const float *g, float *out, float lr, 
     using C = dense_cfg<MB>;
     const int64_t n_tiles = (n_vec * 4 + C::TC - 1) / C::TC;
     if (n_tiles > INT32_MAX) return DBW_ERR_UNSUPPORTED;
+    // 32-bit lane offsets inside the kernel cover up to 32 rows
+    if ((int64_t)40 * c->ld * 4 > (int64_t)UINT32_MAX) return DBW_ERR_UNSUPPORTED;
     int cus = 256;
     int dev = 0;
     hipDeviceProp_t prop;
@@ -152,9 +209,16 @@ int launch_mb(dbw_ctx *c, const float *x, const float *g, float *out, float lr, 
         cus = prop.multiProcessorCount;
     const int blocks_per_cu = (int)((160 * 1024) / (sizeof(float) * 2 * C::TILE));
     const int64_t grid = std::min<int64_t>(n_tiles, (int64_t)cus * std::max(1, std::min(blocks_per_cu, 4)));
+    const bool full = c->N == C::NPAD && (n_vec * 4) % C::TC == 0;
     dbw_timer tm(c, "mix_dense_kernel", s);
-    hipLaunchKernelGGL((mix_dense_kernel<MB, ORDER, HAS_G>), dim3((unsigned)grid), dim3(DENSE_THREADS), 0, s, c->N,
-                       n_vec, c->ld / 4, c->Wdense, (const float4 *)x, (const float4 *)g, out, g, lr, (int)n_tiles);
+    if (full)
+        hipLaunchKernelGGL((mix_dense_kernel<MB, ORDER, HAS_G, true>), dim3((unsigned)grid), dim3(DENSE_THREADS), 0, s,
+                           c->N, n_vec, c->ld / 4, c->Wdense, (const float4 *)x, (const float4 *)g, out, g, lr,
+                           (int)n_tiles);
+    else
+        hipLaunchKernelGGL((mix_dense_kernel<MB, ORDER, HAS_G, false>), dim3((unsigned)grid), dim3(DENSE_THREADS), 0,
+                           s, c->N, n_vec, c->ld / 4, c->Wdense, (const float4 *)x, (const float4 *)g, out, g, lr,
+                           (int)n_tiles);
     DBW_HIP(hipGetLastError());
     return DBW_OK;
 }
