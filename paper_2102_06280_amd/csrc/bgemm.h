@@ -1,14 +1,19 @@
 // Batched fp32 GEMM on the matrix cores, one independent problem per worker:
-//   C_w[m][n] = epilogue( sum_k A_w(m, k) * B_w(k, n) ),   w = blockIdx.z
+//   C_w[m][n] = epilogue( sum_k A_w(m, k) * B_w(k, n) ),   w = blockIdx.z / splits
 // Every worker has its own operands (its own parameters, its own mini-batch), which is
 // what the per-worker gradient of Section 2.1 needs.
 //
-// Operands are described by small loader structs.  A loader states whether its elements
-// are contiguous along k (KC) or along the row index, so that the 64 lanes of a wavefront
-// always read consecutive addresses, and the tile keeps that natural layout in LDS.
+// Operands are described by small loader structs with a `load(w, row, k)` method.  A
+// loader states whether its elements are contiguous along k (KC) or along the row index.
+// The global -> LDS copy assigns work so that one of the two indices is the same for a
+// whole wavefront and the other runs with the lane: for a KC operand a wavefront reads 64
+// consecutive k of one row, otherwise 64 consecutive rows of one k.  Loads are therefore
+// coalesced, and everything a loader derives from the wave-uniform index (for a
+// convolution: channel and filter tap) is computed once per wavefront on the scalar unit.
+// The tile keeps the operand's natural layout in LDS.
 //
-// Workgroup: 256 threads = 4 wavefronts, tile 64 x 64, k-step 32.  Each wavefront owns a
-// 32 x 32 quarter as 2 x 2 fragments of v_mfma_f32_16x16x4_f32 (true fp32):
+// Workgroup: 256 threads = 4 wavefronts, tile BM x BN (64 x 64 or 32 x 128), k-step 64.
+// Each wavefront owns a 32 x 32 part as 2 x 2 fragments of v_mfma_f32_16x16x4_f32 (true fp32):
 //   A fragment: lane l holds A[m = l % 16][slot l / 16], B fragment: B[slot l / 16][n = l % 16]
 //   D: 4 floats, d[v] = D[m = 4 * (l / 16) + v][n = l % 16]
 // The four k-slots of instruction j (0..3) of a 16-wide k group are k = 4 * slot + j for
@@ -23,9 +28,10 @@ namespace bgemm {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int BM = 64, BN = 64, BK = 32, THREADS = 256;
-constexpr int LDS_KC = BK + 4;    // row stride of a k-contiguous tile  [64][36]
-constexpr int LDS_RC = 64 + 4;    // row stride of a row-contiguous tile [32][68]
+constexpr int BK = 64, THREADS = 256;
+constexpr int LDS_KC = BK + 4;                       // row stride of a k-contiguous tile [rows][68]
+constexpr int lds_rc(int rows) { return rows + 4; }  // row stride of a row-contiguous tile [64][rows + 4]
+constexpr int lds_floats(bool kc, int rows) { return kc ? rows * LDS_KC : BK * lds_rc(rows); }
 
 // Dense operand.  KC: element (r, k) at p[w * stride + r * ld + k]; otherwise at
 // p[w * stride + k * ld + r].
@@ -58,38 +64,42 @@ struct Epilogue {
     }
 };
 
-// Global -> registers for a 64 x 32 operand tile (8 elements per thread).
-template <class L>
-__device__ __forceinline__ void fetch_tile(const L &op, int w, int r0, int R, int k0, int K, int tid, float (&v)[8])
+// Global -> registers for a ROWS x 64 operand tile (ROWS / 4 elements per thread).
+//   KC: element j of the thread is (row = wave + 4 j, k = lane)
+//   RC: ROWS >= 64; element j is (row = lane + 64 (j % (ROWS / 64)), k = wave + 4 (j / (ROWS / 64)))
+template <class L, int ROWS>
+__device__ __forceinline__ void fetch_tile(const L &op, int w, int r0, int R, int k0, int K, int wave, int lane,
+                                           float (&v)[ROWS / 4])
 {
+    static_assert(L::KC || ROWS >= 64, "a row-contiguous operand needs at least 64 tile rows");
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
+    for (int j = 0; j < ROWS / 4; ++j) {
         int r, k;
         if (L::KC) {
-            k = tid % BK;
-            r = tid / BK + 8 * j;
+            r = wave + 4 * j;
+            k = lane;
         } else {
-            r = tid % 64;
-            k = tid / 64 + 4 * j;
+            r = lane + 64 * (j % (ROWS / 64));
+            k = wave + 4 * (j / (ROWS / 64));
         }
         v[j] = (r0 + r < R && k0 + k < K) ? op.load(w, r0 + r, k0 + k) : 0.f;
     }
 }
 
-template <class L>
-__device__ __forceinline__ void commit_tile(float *lds, int tid, const float (&v)[8])
+template <class L, int ROWS>
+__device__ __forceinline__ void commit_tile(float *lds, int wave, int lane, const float (&v)[ROWS / 4])
 {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
+    for (int j = 0; j < ROWS / 4; ++j) {
         if (L::KC)
-            lds[(tid / BK + 8 * j) * LDS_KC + tid % BK] = v[j];
+            lds[(wave + 4 * j) * LDS_KC + lane] = v[j];
         else
-            lds[(tid / 64 + 4 * j) * LDS_RC + tid % 64] = v[j];
+            lds[(wave + 4 * (j / (ROWS / 64))) * lds_rc(ROWS) + lane + 64 * (j % (ROWS / 64))] = v[j];
     }
 }
 
 // Values of the four instructions of k group `kg` for the 16-row fragment at row `rbase`.
-template <class L>
+template <class L, int ROWS>
 __device__ __forceinline__ f32x4 frag(const float *lds, int rbase, int kg, int lane)
 {
     f32x4 f;
@@ -97,26 +107,28 @@ __device__ __forceinline__ f32x4 frag(const float *lds, int rbase, int kg, int l
         f = *(const f32x4 *)&lds[(rbase + (lane & 15)) * LDS_KC + kg * 16 + 4 * (lane >> 4)];
     } else {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) f[j] = lds[(kg * 16 + 4 * (lane >> 4) + j) * LDS_RC + rbase + (lane & 15)];
+        for (int j = 0; j < 4; ++j) f[j] = lds[(kg * 16 + 4 * (lane >> 4) + j) * lds_rc(ROWS) + rbase + (lane & 15)];
     }
     return f;
 }
 
-constexpr int lds_floats(bool kc) { return kc ? 64 * LDS_KC : BK * LDS_RC; }
-
 // blockIdx.z = worker * splits + split; a split covers k in [split * kper, (split + 1) * kper)
 // (kper a multiple of BK) and hands its partial sum to the epilogue, which decides where it
 // goes; with splits == 1 the result is final.
-template <class LA, class LB, class EP>
+template <class LA, class LB, class EP, int BM, int BN>
 __global__ __launch_bounds__(THREADS) void kernel(LA A, LB B, EP E, int M, int N, int K, int splits, int kper)
 {
-    __shared__ __attribute__((aligned(16))) float As[lds_floats(LA::KC)];
-    __shared__ __attribute__((aligned(16))) float Bs[lds_floats(LB::KC)];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    static_assert((BM == 64 && BN == 64) || (BM == 32 && BN == 128), "supported tiles: 64 x 64, 32 x 128");
+    static_assert(BM == 64 || LA::KC, "the 32-row tile needs a k-contiguous A operand");
+    __shared__ __attribute__((aligned(16))) float As[lds_floats(LA::KC, BM)];
+    __shared__ __attribute__((aligned(16))) float Bs[lds_floats(LB::KC, BN)];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int w = blockIdx.z / splits, split = blockIdx.z % splits;
     const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
     const int kbeg = split * kper, kend = min(K, kbeg + kper);
-    const int wm = (wave & 1) * 32, wn = (wave >> 1) * 32;
+    constexpr int WM = BM / 32;                          // waves along m
+    const int wm = (wave % WM) * 32, wn = (wave / WM) * 32;
 
     f32x4 acc[2][2];
 #pragma unroll
@@ -124,25 +136,25 @@ __global__ __launch_bounds__(THREADS) void kernel(LA A, LB B, EP E, int M, int N
 #pragma unroll
         for (int b = 0; b < 2; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    float ra[8], rb[8];
-    fetch_tile(A, w, m0, M, kbeg, kend, tid, ra);
-    fetch_tile(B, w, n0, N, kbeg, kend, tid, rb);
+    float ra[BM / 4], rb[BN / 4];
+    fetch_tile<LA, BM>(A, w, m0, M, kbeg, kend, wave, lane, ra);
+    fetch_tile<LB, BN>(B, w, n0, N, kbeg, kend, wave, lane, rb);
     for (int k0 = kbeg; k0 < kend; k0 += BK) {
         __syncthreads();                       // previous tile fully consumed
-        commit_tile<LA>(As, tid, ra);
-        commit_tile<LB>(Bs, tid, rb);
+        commit_tile<LA, BM>(As, wave, lane, ra);
+        commit_tile<LB, BN>(Bs, wave, lane, rb);
         __syncthreads();
         if (k0 + BK < kend) {                  // next tile's loads fly during the MFMAs
-            fetch_tile(A, w, m0, M, k0 + BK, kend, tid, ra);
-            fetch_tile(B, w, n0, N, k0 + BK, kend, tid, rb);
+            fetch_tile<LA, BM>(A, w, m0, M, k0 + BK, kend, wave, lane, ra);
+            fetch_tile<LB, BN>(B, w, n0, N, k0 + BK, kend, wave, lane, rb);
         }
 #pragma unroll
         for (int kg = 0; kg < BK / 16; ++kg) {
             f32x4 fa[2], fb[2];
 #pragma unroll
-            for (int a = 0; a < 2; ++a) fa[a] = frag<LA>(As, wm + 16 * a, kg, lane);
+            for (int a = 0; a < 2; ++a) fa[a] = frag<LA, BM>(As, wm + 16 * a, kg, lane);
 #pragma unroll
-            for (int b = 0; b < 2; ++b) fb[b] = frag<LB>(Bs, wn + 16 * b, kg, lane);
+            for (int b = 0; b < 2; ++b) fb[b] = frag<LB, BN>(Bs, wn + 16 * b, kg, lane);
 #pragma unroll
             for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -165,14 +177,16 @@ __global__ __launch_bounds__(THREADS) void kernel(LA A, LB B, EP E, int M, int N
         }
 }
 
-template <class LA, class LB, class EP>
+// BM = 32 uses 32 x 128 tiles (for problems with at most 32 rows), otherwise 64 x 64.
+template <int BM, class LA, class LB, class EP>
 inline hipError_t launch(const LA &A, const LB &B, const EP &E, int M, int N, int K, int batch, hipStream_t s,
                          int splits = 1)
 {
+    constexpr int BN = BM == 32 ? 128 : 64;
     int kper = (K + splits - 1) / splits;
     kper = (kper + BK - 1) / BK * BK;
     dim3 grid((N + BN - 1) / BN, (M + BM - 1) / BM, batch * splits);
-    hipLaunchKernelGGL((kernel<LA, LB, EP>), grid, dim3(THREADS), 0, s, A, B, E, M, N, K, splits, kper);
+    hipLaunchKernelGGL((kernel<LA, LB, EP, BM, BN>), grid, dim3(THREADS), 0, s, A, B, E, M, N, K, splits, kper);
     return hipGetLastError();
 }
 

@@ -25,33 +25,50 @@ struct ConvShape {
     int Cin, Cout, H, W, KS, pad;   // stride-1 'same' convolution
 };
 
+// Filter size as a compile-time constant where it is a common one (KS_ = 0: run time), so
+// that splitting k into (channel, tap) needs no division.  In every loader one of the two
+// indices is wave-uniform (see bgemm.h) and its decomposition runs on the scalar unit; the
+// per-lane decomposition of the other is loop invariant or shared by a whole k-step.
+template <int KS_>
+__device__ __forceinline__ int filter_size(const ConvShape &s) { return KS_ > 0 ? KS_ : s.KS; }
+
 // patch element for output pixel `pix` = (b, oh, ow) and k = (ci, kh, kw); zero outside.
+template <int KS_>
 __device__ __forceinline__ float patch_at(const float *in, const ConvShape &s, int pix, int k)
 {
-    const int HW = s.H * s.W, KK = s.KS * s.KS;
+    const int KS = filter_size<KS_>(s);
+    const int HW = s.H * s.W, KK = KS * KS;
     const int b = pix / HW, hw = pix - b * HW, oh = hw / s.W, ow = hw - oh * s.W;
-    const int ci = k / KK, rr = k - ci * KK, kh = rr / s.KS, kw = rr - kh * s.KS;
+    const int ci = k / KK, rr = k - ci * KK, kh = rr / KS, kw = rr - kh * KS;
     const int ih = oh + kh - s.pad, iw = ow + kw - s.pad;
     if (ih < 0 || ih >= s.H || iw < 0 || iw >= s.W) return 0.f;
     return in[((int64_t)(b * s.Cin + ci) * s.H + ih) * s.W + iw];
 }
 
 // B operand of the forward GEMM: (k, pix), contiguous along pixels.
+template <int KS_>
 struct PatchRC {
     static constexpr bool KC = false;
     const float *in;
     int64_t stride;
     ConvShape s;
-    __device__ __forceinline__ float load(int w, int pix, int k) const { return patch_at(in + w * stride, s, pix, k); }
+    __device__ __forceinline__ float load(int w, int pix, int k) const
+    {
+        return patch_at<KS_>(in + w * stride, s, pix, k);
+    }
 };
 
 // B operand of the weight-gradient GEMM: row = k of the filter, reduction index = pixel.
+template <int KS_>
 struct PatchKC {
     static constexpr bool KC = true;
     const float *in;
     int64_t stride;
     ConvShape s;
-    __device__ __forceinline__ float load(int w, int kf, int pix) const { return patch_at(in + w * stride, s, pix, kf); }
+    __device__ __forceinline__ float load(int w, int kf, int pix) const
+    {
+        return patch_at<KS_>(in + w * stride, s, pix, kf);
+    }
 };
 
 // A operand of the weight-gradient GEMM: dz[co][pix] stored as [B][Cout][H][W].
@@ -68,13 +85,15 @@ struct DeltaKC {
 };
 
 // A operand of the data-gradient GEMM: (ci, k' = (co, kh, kw)) -> W[co][ci][kh][kw].
+template <int KS_>
 struct FilterT {
     static constexpr bool KC = true;
     const float *wgt;
     int64_t stride;
-    int Cin, KK;
+    int Cin, KKrt;
     __device__ __forceinline__ float load(int w, int ci, int k) const
     {
+        const int KK = KS_ > 0 ? KS_ * KS_ : KKrt;
         const int co = k / KK, rr = k - co * KK;
         return wgt[w * stride + (int64_t)(co * Cin + ci) * KK + rr];
     }
@@ -82,6 +101,7 @@ struct FilterT {
 
 // B operand of the data-gradient GEMM: (k' = (co, kh, kw), input pixel) -> dz at the output
 // position that used this input pixel with that filter tap; zero outside.
+template <int KS_>
 struct DeltaShiftRC {
     static constexpr bool KC = false;
     const float *dz;
@@ -89,9 +109,10 @@ struct DeltaShiftRC {
     ConvShape s;
     __device__ __forceinline__ float load(int w, int pix, int k) const
     {
-        const int HW = s.H * s.W, KK = s.KS * s.KS;
+        const int KS = filter_size<KS_>(s);
+        const int HW = s.H * s.W, KK = KS * KS;
         const int b = pix / HW, hw = pix - b * HW, ih = hw / s.W, iw = hw - ih * s.W;
-        const int co = k / KK, rr = k - co * KK, kh = rr / s.KS, kw = rr - kh * s.KS;
+        const int co = k / KK, rr = k - co * KK, kh = rr / KS, kw = rr - kh * KS;
         const int oh = ih - kh + s.pad, ow = iw - kw + s.pad;
         if (oh < 0 || oh >= s.H || ow < 0 || ow >= s.W) return 0.f;
         return dz[w * stride + ((int64_t)(b * s.Cout + co) * s.H + oh) * s.W + ow];
@@ -240,12 +261,18 @@ cnn_layout make_layout(const dbw_model &m)
     return L;
 }
 
-}  // namespace
+// 32 x 128 tiles when the GEMM has at most 32 rows (output channels), else 64 x 64
+template <class LA, class LB, class EP>
+hipError_t conv_gemm(const LA &A, const LB &B, const EP &E, int M, int N, int K, int batch, hipStream_t s,
+                     int splits = 1)
+{
+    if (M <= 32) return bgemm::launch<32>(A, B, E, M, N, K, batch, s, splits);
+    return bgemm::launch<64>(A, B, E, M, N, K, batch, s, splits);
+}
 
-size_t dbw_cnn_scratch_floats(const dbw_ctx *c) { return (size_t)make_layout(c->model).total * c->N; }
-
-int dbw_launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const int32_t *by, float *grads,
-                        float *loss, hipStream_t s)
+template <int KS_>
+int launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const int32_t *by, float *grads,
+                    float *loss, hipStream_t s)
 {
     const cnn_layout L = make_layout(c->model);
     const int N = c->N, B = L.B, KK = L.KS * L.KS;
@@ -258,7 +285,7 @@ int dbw_launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const 
 
     {   // conv1 forward
         dbw_timer tm(c, "conv1_forward", s);
-        DBW_HIP(bgemm::launch(Dense<true>{params + L.w1, L.C0 * KK, ld}, PatchRC{bx, xstride, s1},
+        DBW_HIP(conv_gemm(Dense<true>{params + L.w1, L.C0 * KK, ld}, PatchRC<KS_>{bx, xstride, s1},
                               ChannelPixelOut{A + L.z1, ws, L.C1, L.H * L.W, params + L.b1, ld}, L.C1, pix1,
                               L.C0 * KK, N, s));
     }
@@ -270,7 +297,7 @@ int dbw_launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const 
     }
     {   // conv2 forward
         dbw_timer tm(c, "conv2_forward", s);
-        DBW_HIP(bgemm::launch(Dense<true>{params + L.w2, L.C1 * KK, ld}, PatchRC{A + L.p1, ws, s2},
+        DBW_HIP(conv_gemm(Dense<true>{params + L.w2, L.C1 * KK, ld}, PatchRC<KS_>{A + L.p1, ws, s2},
                               ChannelPixelOut{A + L.z2, ws, L.C2, L.H2 * L.W2, params + L.b2, ld}, L.C2, pix2,
                               L.C1 * KK, N, s));
     }
@@ -309,7 +336,7 @@ int dbw_launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const 
     }
     {   // conv2 weight gradient (split over pixels, then summed in split order) and bias gradient
         dbw_timer tm(c, "conv2_wgrad", s);
-        DBW_HIP(bgemm::launch(DeltaKC{A + L.dz2, ws, L.C2, L.H2 * L.W2}, PatchKC{A + L.p1, ws, s2},
+        DBW_HIP(conv_gemm(DeltaKC{A + L.dz2, ws, L.C2, L.H2 * L.W2}, PatchKC<KS_>{A + L.p1, ws, s2},
                               PartialOut{A + L.part, ws, L.C2, L.C1 * KK}, L.C2, L.C1 * KK, pix2, N, s,
                               L.splits2));
     }
@@ -327,7 +354,7 @@ int dbw_launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const 
     }
     {   // conv2 data gradient -> gradient of the first pooled map
         dbw_timer tm(c, "conv2_dgrad", s);
-        DBW_HIP(bgemm::launch(FilterT{params + L.w2, ld, L.C1, KK}, DeltaShiftRC{A + L.dz2, ws, s2},
+        DBW_HIP(conv_gemm(FilterT<KS_>{params + L.w2, ld, L.C1, KK}, DeltaShiftRC<KS_>{A + L.dz2, ws, s2},
                               ChannelPixelOut{A + L.dp1, ws, L.C1, L.H2 * L.W2, nullptr, 0}, L.C1, pix2, L.C2 * KK, N,
                               s));
     }
@@ -339,7 +366,7 @@ int dbw_launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const 
     }
     {   // conv1 weight and bias gradients
         dbw_timer tm(c, "conv1_wgrad", s);
-        DBW_HIP(bgemm::launch(DeltaKC{A + L.dz1, ws, L.C1, L.H * L.W}, PatchKC{bx, xstride, s1},
+        DBW_HIP(conv_gemm(DeltaKC{A + L.dz1, ws, L.C1, L.H * L.W}, PatchKC<KS_>{bx, xstride, s1},
                               PartialOut{A + L.part, ws, L.C1, L.C0 * KK}, L.C1, L.C0 * KK, pix1, N, s,
                               L.splits1));
     }
@@ -356,4 +383,18 @@ int dbw_launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const 
         DBW_HIP(hipGetLastError());
     }
     return DBW_OK;
+}
+
+}  // namespace
+
+size_t dbw_cnn_scratch_floats(const dbw_ctx *c) { return (size_t)make_layout(c->model).total * c->N; }
+
+int dbw_launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const int32_t *by, float *grads,
+                        float *loss, hipStream_t s)
+{
+    switch (c->model.dims[5]) {
+    case 3: return launch_grad_cnn<3>(c, params, bx, by, grads, loss, s);
+    case 5: return launch_grad_cnn<5>(c, params, bx, by, grads, loss, s);
+    default: return launch_grad_cnn<0>(c, params, bx, by, grads, loss, s);
+    }
 }

@@ -98,7 +98,7 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
         Bm = {params + w_off[l], dims[l - 1], c->ld};
         Epilogue E{act + a_off[l], dims[l], wstride, params + b_off[l], c->ld, nullptr, 0, 0, l < L ? 1 : 0};
         dbw_timer tm(c, "mlp_forward_gemm", s);
-        DBW_HIP(bgemm::launch(A, Bm, E, B, dims[l], dims[l - 1], N, s));
+        DBW_HIP(bgemm::launch<64>(A, Bm, E, B, dims[l], dims[l - 1], N, s));
     }
     {
         dbw_timer tm(c, "softmax_xent_kernel", s);
@@ -116,7 +116,7 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
                 Bm = {act + a_off[l - 1], dims[l - 1], wstride};
             Epilogue E{grads + w_off[l], dims[l - 1], c->ld, nullptr, 0, nullptr, 0, 0, 0};
             dbw_timer tm(c, "mlp_wgrad_gemm", s);
-            DBW_HIP(bgemm::launch(A, Bm, E, dims[l], dims[l - 1], B, N, s));
+            DBW_HIP(bgemm::launch<64>(A, Bm, E, dims[l], dims[l - 1], B, N, s));
         }
         {
             dbw_timer tm(c, "colsum_kernel", s);
@@ -130,13 +130,13 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
             Epilogue E{act + dz_off[l - 1], dims[l - 1], wstride, nullptr, 0, act + a_off[l - 1], dims[l - 1],
                        wstride, 0};
             dbw_timer tm(c, "mlp_dgrad_gemm", s);
-            DBW_HIP(bgemm::launch(A, Bm, E, B, dims[l - 1], dims[l], N, s));
+            DBW_HIP(bgemm::launch<64>(A, Bm, E, B, dims[l - 1], dims[l], N, s));
         } else if (a.din) {   // gradient with respect to the stack's input, unmasked
             Dense<true> A{act + dz_off[1], dims[1], wstride};
             Dense<false> Bm{params + w_off[1], dims[0], c->ld};
             Epilogue E{a.din, a.din_ld, a.din_stride, nullptr, 0, nullptr, 0, 0, 0};
             dbw_timer tm(c, "mlp_dgrad_gemm", s);
-            DBW_HIP(bgemm::launch(A, Bm, E, B, dims[0], dims[1], N, s));
+            DBW_HIP(bgemm::launch<64>(A, Bm, E, B, dims[0], dims[1], N, s));
         }
     }
     return DBW_OK;
