@@ -3,13 +3,16 @@
 // Every worker has its own operands (its own parameters, its own mini-batch), which is
 // what the per-worker gradient of Section 2.1 needs.
 //
-// Operands are described by small loader structs with a `load(w, row, k)` method.  A
-// loader states whether its elements are contiguous along k (KC) or along the row index.
+// Operands are described by small loader structs.  A loader splits the address of element
+// (row, k) into a part that depends on the row only (`row_ctx`), a part that depends on k
+// only (`k_ctx`) and a cheap combination (`load`), all in 32-bit arithmetic relative to
+// the worker's base pointer, and states whether its elements are contiguous along k (KC)
+// or along the row index.
 // The global -> LDS copy assigns work so that one of the two indices is the same for a
 // whole wavefront and the other runs with the lane: for a KC operand a wavefront reads 64
 // consecutive k of one row, otherwise 64 consecutive rows of one k.  Loads are therefore
-// coalesced, and everything a loader derives from the wave-uniform index (for a
-// convolution: channel and filter tap) is computed once per wavefront on the scalar unit.
+// coalesced; the context of the wave-uniform index is computed on the scalar unit, the
+// per-lane context once per k-step (KC) or once per kernel (otherwise).
 // The tile keeps the operand's natural layout in LDS.
 //
 // Workgroup: 256 threads = 4 wavefronts, tile BM x BN (64 x 64 or 32 x 128), k-step 64.
@@ -34,15 +37,21 @@ constexpr int lds_rc(int rows) { return rows + 4; }  // row stride of a row-cont
 constexpr int lds_floats(bool kc, int rows) { return kc ? rows * LDS_KC : BK * lds_rc(rows); }
 
 // Dense operand.  KC: element (r, k) at p[w * stride + r * ld + k]; otherwise at
-// p[w * stride + k * ld + r].
+// p[w * stride + k * ld + r].  Offsets inside one worker's block fit 32 bits.
 template <bool KC_>
 struct Dense {
     static constexpr bool KC = KC_;
     const float *p;
     int64_t ld, stride;
-    __device__ __forceinline__ float load(int w, int r, int k) const
+    struct RowCtx { int off; bool ok; };
+    struct KCtx { int off; bool ok; };
+    __device__ __forceinline__ RowCtx row_ctx(int r, bool ok) const { return {KC ? r * (int)ld : r, ok}; }
+    __device__ __forceinline__ KCtx k_ctx(int k, bool ok) const { return {KC ? k : k * (int)ld, ok}; }
+    __device__ __forceinline__ float load(int w, const RowCtx &r, const KCtx &k) const
     {
-        return KC ? p[w * stride + (int64_t)r * ld + k] : p[w * stride + (int64_t)k * ld + r];
+        const bool ok = r.ok && k.ok;
+        const float v = (p + w * stride)[ok ? r.off + k.off : 0];
+        return ok ? v : 0.f;
     }
 };
 
@@ -67,22 +76,44 @@ struct Epilogue {
 // Global -> registers for a ROWS x 64 operand tile (ROWS / 4 elements per thread).
 //   KC: element j of the thread is (row = wave + 4 j, k = lane)
 //   RC: ROWS >= 64; element j is (row = lane + 64 (j % (ROWS / 64)), k = wave + 4 (j / (ROWS / 64)))
+// `rows` holds the per-lane row contexts of an RC operand (computed once per kernel).
+template <class L, int ROWS>
+struct RowCache {
+    typename L::RowCtx c[L::KC ? 1 : ROWS / 64];
+};
+
+template <class L, int ROWS>
+__device__ __forceinline__ void make_rows(const L &op, int r0, int R, int lane, RowCache<L, ROWS> &rows)
+{
+    if (!L::KC) {
+#pragma unroll
+        for (int g = 0; g < ROWS / 64; ++g) {
+            const int r = r0 + lane + 64 * g;
+            rows.c[g] = op.row_ctx(r < R ? r : 0, r < R);
+        }
+    }
+}
+
 template <class L, int ROWS>
 __device__ __forceinline__ void fetch_tile(const L &op, int w, int r0, int R, int k0, int K, int wave, int lane,
-                                           float (&v)[ROWS / 4])
+                                           const RowCache<L, ROWS> &rows, float (&v)[ROWS / 4])
 {
     static_assert(L::KC || ROWS >= 64, "a row-contiguous operand needs at least 64 tile rows");
+    if (L::KC) {
+        const int k = k0 + lane;
+        const typename L::KCtx kc = op.k_ctx(k < K ? k : 0, k < K);      // per lane, shared by all rows
 #pragma unroll
-    for (int j = 0; j < ROWS / 4; ++j) {
-        int r, k;
-        if (L::KC) {
-            r = wave + 4 * j;
-            k = lane;
-        } else {
-            r = lane + 64 * (j % (ROWS / 64));
-            k = wave + 4 * (j / (ROWS / 64));
+        for (int j = 0; j < ROWS / 4; ++j) {
+            const int r = r0 + wave + 4 * j;                                 // wave-uniform
+            v[j] = op.load(w, op.row_ctx(r < R ? r : 0, r < R), kc);
         }
-        v[j] = (r0 + r < R && k0 + k < K) ? op.load(w, r0 + r, k0 + k) : 0.f;
+    } else {
+        constexpr int RG = ROWS / 64;
+#pragma unroll
+        for (int j = 0; j < ROWS / 4; ++j) {
+            const int k = k0 + wave + 4 * (j / RG);                          // wave-uniform
+            v[j] = op.load(w, rows.c[j % RG], op.k_ctx(k < K ? k : 0, k < K));
+        }
     }
 }
 
@@ -136,17 +167,21 @@ __global__ __launch_bounds__(THREADS) void kernel(LA A, LB B, EP E, int M, int N
 #pragma unroll
         for (int b = 0; b < 2; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+    RowCache<LA, BM> arows;
+    RowCache<LB, BN> brows;
+    make_rows<LA, BM>(A, m0, M, lane, arows);
+    make_rows<LB, BN>(B, n0, N, lane, brows);
     float ra[BM / 4], rb[BN / 4];
-    fetch_tile<LA, BM>(A, w, m0, M, kbeg, kend, wave, lane, ra);
-    fetch_tile<LB, BN>(B, w, n0, N, kbeg, kend, wave, lane, rb);
+    fetch_tile<LA, BM>(A, w, m0, M, kbeg, kend, wave, lane, arows, ra);
+    fetch_tile<LB, BN>(B, w, n0, N, kbeg, kend, wave, lane, brows, rb);
     for (int k0 = kbeg; k0 < kend; k0 += BK) {
         __syncthreads();                       // previous tile fully consumed
         commit_tile<LA, BM>(As, wave, lane, ra);
         commit_tile<LB, BN>(Bs, wave, lane, rb);
         __syncthreads();
         if (k0 + BK < kend) {                  // next tile's loads fly during the MFMAs
-            fetch_tile<LA, BM>(A, w, m0, M, k0 + BK, kend, wave, lane, ra);
-            fetch_tile<LB, BN>(B, w, n0, N, k0 + BK, kend, wave, lane, rb);
+            fetch_tile<LA, BM>(A, w, m0, M, k0 + BK, kend, wave, lane, arows, ra);
+            fetch_tile<LB, BN>(B, w, n0, N, k0 + BK, kend, wave, lane, brows, rb);
         }
 #pragma unroll
         for (int kg = 0; kg < BK / 16; ++kg) {

@@ -26,48 +26,73 @@ struct ConvShape {
 };
 
 // Filter size as a compile-time constant where it is a common one (KS_ = 0: run time), so
-// that splitting k into (channel, tap) needs no division.  In every loader one of the two
-// indices is wave-uniform (see bgemm.h) and its decomposition runs on the scalar unit; the
-// per-lane decomposition of the other is loop invariant or shared by a whole k-step.
+// that splitting k into (channel, tap) needs no division.
 template <int KS_>
 __device__ __forceinline__ int filter_size(const ConvShape &s) { return KS_ > 0 ? KS_ : s.KS; }
 
-// patch element for output pixel `pix` = (b, oh, ow) and k = (ci, kh, kw); zero outside.
-template <int KS_>
-__device__ __forceinline__ float patch_at(const float *in, const ConvShape &s, int pix, int k)
+// Contexts shared by the convolution loaders.  A pixel context addresses tensor element
+// (b, channel 0, y, x) of a [B][C][H][W] tensor; a tap context adds the channel plane and
+// the (dy, dx) shift of one filter tap.  Element = base + off, valid iff the shifted
+// position is inside the image.
+struct PixelCtx { int base, y, x; bool ok; };
+struct TapCtx { int off, dy, dx; bool ok; };
+
+__device__ __forceinline__ PixelCtx pixel_ctx(const ConvShape &s, int C, int pix, bool ok)
 {
-    const int KS = filter_size<KS_>(s);
-    const int HW = s.H * s.W, KK = KS * KS;
-    const int b = pix / HW, hw = pix - b * HW, oh = hw / s.W, ow = hw - oh * s.W;
-    const int ci = k / KK, rr = k - ci * KK, kh = rr / KS, kw = rr - kh * KS;
-    const int ih = oh + kh - s.pad, iw = ow + kw - s.pad;
-    if (ih < 0 || ih >= s.H || iw < 0 || iw >= s.W) return 0.f;
-    return in[((int64_t)(b * s.Cin + ci) * s.H + ih) * s.W + iw];
+    const int HW = s.H * s.W;
+    const int b = pix / HW, hw = pix - b * HW, y = hw / s.W, x = hw - y * s.W;
+    return {b * C * HW + hw, y, x, ok};
 }
 
-// B operand of the forward GEMM: (k, pix), contiguous along pixels.
+// k = (channel, kh, kw); sign = +1 reads the input of a forward tap (y + kh - pad),
+// sign = -1 the output position that used this input with that tap (y - kh + pad).
+template <int KS_>
+__device__ __forceinline__ TapCtx tap_ctx(const ConvShape &s, int k, int sign, bool ok)
+{
+    const int KS = filter_size<KS_>(s), KK = KS * KS;
+    const int ch = k / KK, rr = k - ch * KK, kh = rr / KS, kw = rr - kh * KS;
+    const int dy = sign * (kh - s.pad), dx = sign * (kw - s.pad);
+    return {ch * s.H * s.W + dy * s.W + dx, dy, dx, ok};
+}
+
+__device__ __forceinline__ float conv_load(const float *t, const ConvShape &s, const PixelCtx &p, const TapCtx &k)
+{
+    const bool ok = p.ok && k.ok && (unsigned)(p.y + k.dy) < (unsigned)s.H && (unsigned)(p.x + k.dx) < (unsigned)s.W;
+    const float v = t[ok ? p.base + k.off : 0];
+    return ok ? v : 0.f;
+}
+
+// B operand of the forward GEMM: (k = tap, row = output pixel), contiguous along pixels.
 template <int KS_>
 struct PatchRC {
     static constexpr bool KC = false;
     const float *in;
     int64_t stride;
     ConvShape s;
-    __device__ __forceinline__ float load(int w, int pix, int k) const
+    typedef PixelCtx RowCtx;
+    typedef TapCtx KCtx;
+    __device__ __forceinline__ RowCtx row_ctx(int pix, bool ok) const { return pixel_ctx(s, s.Cin, pix, ok); }
+    __device__ __forceinline__ KCtx k_ctx(int k, bool ok) const { return tap_ctx<KS_>(s, k, 1, ok); }
+    __device__ __forceinline__ float load(int w, const RowCtx &r, const KCtx &k) const
     {
-        return patch_at<KS_>(in + w * stride, s, pix, k);
+        return conv_load(in + w * stride, s, r, k);
     }
 };
 
-// B operand of the weight-gradient GEMM: row = k of the filter, reduction index = pixel.
+// B operand of the weight-gradient GEMM: row = filter tap, reduction index = output pixel.
 template <int KS_>
 struct PatchKC {
     static constexpr bool KC = true;
     const float *in;
     int64_t stride;
     ConvShape s;
-    __device__ __forceinline__ float load(int w, int kf, int pix) const
+    typedef TapCtx RowCtx;
+    typedef PixelCtx KCtx;
+    __device__ __forceinline__ RowCtx row_ctx(int kf, bool ok) const { return tap_ctx<KS_>(s, kf, 1, ok); }
+    __device__ __forceinline__ KCtx k_ctx(int pix, bool ok) const { return pixel_ctx(s, s.Cin, pix, ok); }
+    __device__ __forceinline__ float load(int w, const RowCtx &r, const KCtx &k) const
     {
-        return patch_at<KS_>(in + w * stride, s, pix, kf);
+        return conv_load(in + w * stride, s, k, r);
     }
 };
 
@@ -77,45 +102,61 @@ struct DeltaKC {
     const float *dz;
     int64_t stride;
     int Cout, HW;
-    __device__ __forceinline__ float load(int w, int co, int pix) const
+    struct RowCtx { int off; bool ok; };
+    struct KCtx { int base; bool ok; };
+    __device__ __forceinline__ RowCtx row_ctx(int co, bool ok) const { return {co * HW, ok}; }
+    __device__ __forceinline__ KCtx k_ctx(int pix, bool ok) const
     {
         const int b = pix / HW, hw = pix - b * HW;
-        return dz[w * stride + (int64_t)(b * Cout + co) * HW + hw];
+        return {b * Cout * HW + hw, ok};
+    }
+    __device__ __forceinline__ float load(int w, const RowCtx &r, const KCtx &k) const
+    {
+        const bool ok = r.ok && k.ok;
+        const float v = (dz + w * stride)[ok ? r.off + k.base : 0];
+        return ok ? v : 0.f;
     }
 };
 
-// A operand of the data-gradient GEMM: (ci, k' = (co, kh, kw)) -> W[co][ci][kh][kw].
+// A operand of the data-gradient GEMM: (row = ci, k' = (co, kh, kw)) -> W[co][ci][kh][kw].
 template <int KS_>
 struct FilterT {
     static constexpr bool KC = true;
     const float *wgt;
     int64_t stride;
     int Cin, KKrt;
-    __device__ __forceinline__ float load(int w, int ci, int k) const
+    struct RowCtx { int off; bool ok; };
+    struct KCtx { int base; bool ok; };
+    __device__ __forceinline__ RowCtx row_ctx(int ci, bool ok) const { return {ci * (KS_ > 0 ? KS_ * KS_ : KKrt), ok}; }
+    __device__ __forceinline__ KCtx k_ctx(int k, bool ok) const
     {
         const int KK = KS_ > 0 ? KS_ * KS_ : KKrt;
         const int co = k / KK, rr = k - co * KK;
-        return wgt[w * stride + (int64_t)(co * Cin + ci) * KK + rr];
+        return {co * Cin * KK + rr, ok};
+    }
+    __device__ __forceinline__ float load(int w, const RowCtx &r, const KCtx &k) const
+    {
+        const bool ok = r.ok && k.ok;
+        const float v = (wgt + w * stride)[ok ? r.off + k.base : 0];
+        return ok ? v : 0.f;
     }
 };
 
-// B operand of the data-gradient GEMM: (k' = (co, kh, kw), input pixel) -> dz at the output
-// position that used this input pixel with that filter tap; zero outside.
+// B operand of the data-gradient GEMM: (k' = (co, kh, kw), row = input pixel) -> dz at the
+// output position that used this input pixel with that filter tap; zero outside.
 template <int KS_>
 struct DeltaShiftRC {
     static constexpr bool KC = false;
     const float *dz;
     int64_t stride;
     ConvShape s;
-    __device__ __forceinline__ float load(int w, int pix, int k) const
+    typedef PixelCtx RowCtx;
+    typedef TapCtx KCtx;
+    __device__ __forceinline__ RowCtx row_ctx(int pix, bool ok) const { return pixel_ctx(s, s.Cout, pix, ok); }
+    __device__ __forceinline__ KCtx k_ctx(int k, bool ok) const { return tap_ctx<KS_>(s, k, -1, ok); }
+    __device__ __forceinline__ float load(int w, const RowCtx &r, const KCtx &k) const
     {
-        const int KS = filter_size<KS_>(s);
-        const int HW = s.H * s.W, KK = KS * KS;
-        const int b = pix / HW, hw = pix - b * HW, ih = hw / s.W, iw = hw - ih * s.W;
-        const int co = k / KK, rr = k - co * KK, kh = rr / KS, kw = rr - kh * KS;
-        const int oh = ih - kh + s.pad, ow = iw - kw + s.pad;
-        if (oh < 0 || oh >= s.H || ow < 0 || ow >= s.W) return 0.f;
-        return dz[w * stride + ((int64_t)(b * s.Cout + co) * s.H + oh) * s.W + ow];
+        return conv_load(dz + w * stride, s, r, k);
     }
 };
 
