@@ -1,0 +1,174 @@
+// Stride-1 'same' convolution on the matrix cores with the input image resident in LDS.
+//
+// One workgroup computes all output channels of one sample of one worker:
+//   out[co][y][x] = bias[co] + sum_{c, kh, kw} Wt[co][c][kh][kw] * in[c][y + kh - pad][x + kw - pad]
+// as the GEMM  out[co][pix] = sum_k Wt[co][k] * patch[k][pix],  k = (c, kh, kw).
+// The patch matrix repeats every input value KS * KS times, so it is never built and never
+// fetched: a group of CG input channels is copied once into LDS with a zero halo
+// ([CG][H + 2 pad][W + 2 pad]; 160 KB of LDS per CU make a whole 32-channel 16 x 16 image
+// fit), and the B fragment of v_mfma_f32_16x16x4_f32 is read straight from it at
+// address  pixel_offset(lane) + tap_offset(k)  with no bounds checks.  Tap offsets come
+// from a small LDS table, the weights stream through LDS in 64-wide k chunks (double
+// buffered).  Accumulators stay in registers across channel groups.
+//
+// The data gradient of a convolution is the same operation applied to the output deltas
+// with the filters transposed and rotated by 180 degrees (see flip_filters_kernel).
+//
+// Fragment layout of v_mfma_f32_16x16x4_f32, lane l: A[m = l % 16][slot l / 16],
+// B[slot l / 16][n = l % 16], D: d[v] = D[m = 4 (l / 16) + v][n = l % 16]; instruction j of a
+// 16-wide k group uses k = 4 slot + j.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace convlds {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+// CG: input channels per LDS fill; MT: 16-row output-channel fragments (all held by every
+// wave); NT: 16-pixel fragments per wave; WAVES * NT * 16 = H * W pixels per sample.
+template <int CG, int MT, int NT, int H, int W, int KS, int WAVES>
+struct Cfg {
+    static constexpr int PAD = KS / 2, HP = H + 2 * PAD, WP = W + 2 * PAD;
+    static constexpr int COUT = 16 * MT, PIX = H * W, KK = KS * KS;
+    static constexpr int TAPS = CG * KK;                 // k extent of one channel group
+    static constexpr int KGS = (TAPS + 15) / 16;         // 16-wide k groups per channel group
+    static constexpr int CHUNKS = (KGS + 3) / 4;         // 64-wide weight chunks per channel group
+    static constexpr int IMG = CG * HP * WP;
+    static constexpr int LDA = 68;                       // row stride of a weight chunk [COUT][64]
+    static constexpr int THREADS = 64 * WAVES;
+    static constexpr int AROWS = COUT / WAVES;           // weight rows fetched per thread and chunk
+    static_assert(PIX == 16 * NT * WAVES, "waves x fragments must cover the image");
+    static_assert(W % 4 == 0 && COUT % WAVES == 0, "shape not supported");
+    static constexpr size_t lds_bytes = sizeof(float) * (IMG + 2 * COUT * LDA) + sizeof(int) * KGS * 16;
+};
+
+// in  [worker][B][Cin][H][W]   (worker stride in_stride)
+// wgt [worker][COUT][ldw]      (row co holds its Cin * KK filter taps, worker stride w_stride)
+// out [worker][B][COUT][H][W]  (worker stride out_stride);  grid = (B, workers)
+template <int CG, int MT, int NT, int H, int W, int KS, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void conv_forward_kernel(
+    const float *__restrict__ in, int64_t in_stride, const float *__restrict__ wgt, int64_t w_stride, int ldw,
+    const float *__restrict__ bias, int64_t bias_stride, float *__restrict__ out, int64_t out_stride, int Cin)
+{
+    using C = Cfg<CG, MT, NT, H, W, KS, WAVES>;
+    __shared__ __attribute__((aligned(16))) float img[C::IMG];
+    __shared__ __attribute__((aligned(16))) float As[2][C::COUT * C::LDA];
+    __shared__ __attribute__((aligned(16))) int taptab[C::KGS * 16];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int b = blockIdx.x, w = blockIdx.y;
+
+    for (int k = tid; k < C::KGS * 16; k += C::THREADS) {
+        const int c = k / C::KK, rr = k % C::KK, kh = rr / KS, kw = rr % KS;
+        taptab[k] = k < C::TAPS ? c * C::HP * C::WP + kh * C::WP + kw : 0;
+    }
+    for (int e = tid; e < C::IMG; e += C::THREADS) img[e] = 0.f;     // the halo stays zero
+
+    int pixoff[NT];
+#pragma unroll
+    for (int nf = 0; nf < NT; ++nf) {
+        const int p = (wave * NT + nf) * 16 + (lane & 15);
+        pixoff[nf] = (p / W) * C::WP + (p % W);
+    }
+    f32x4 acc[MT][NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nf = 0; nf < NT; ++nf) acc[mt][nf] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const float *inb = in + w * in_stride + (int64_t)b * Cin * C::PIX;
+    const float *ww = wgt + w * w_stride;
+    const int groups = (Cin + CG - 1) / CG;
+
+    float areg[C::AROWS];
+    auto fetch_a = [&](int g, int chunk) {
+        const int kloc = chunk * 64 + lane;
+        const bool ok = kloc < C::TAPS && g * CG + kloc / C::KK < Cin;
+        const int kglob = ok ? g * C::TAPS + kloc : 0;
+#pragma unroll
+        for (int j = 0; j < C::AROWS; ++j) {
+            const float v = ww[(wave + WAVES * j) * ldw + kglob];
+            areg[j] = ok ? v : 0.f;
+        }
+    };
+    auto commit_a = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < C::AROWS; ++j) As[buf][(wave + WAVES * j) * C::LDA + lane] = areg[j];
+    };
+
+    int buf = 0;
+    for (int g = 0; g < groups; ++g) {
+        __syncthreads();                       // image and weight buffers of the previous group are free
+        for (int e = tid; e < CG * H * (W / 4); e += C::THREADS) {
+            const int c = e / (H * (W / 4)), rem = e % (H * (W / 4)), y = rem / (W / 4), x4 = rem % (W / 4);
+            const int ch = g * CG + c;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (ch < Cin) v = *(const float4 *)&inb[(ch * H + y) * W + 4 * x4];
+            float *dst = &img[c * C::HP * C::WP + (y + C::PAD) * C::WP + C::PAD + 4 * x4];
+            dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+        }
+        fetch_a(g, 0);
+        commit_a(buf);
+        __syncthreads();
+        for (int chunk = 0; chunk < C::CHUNKS; ++chunk) {
+            if (chunk + 1 < C::CHUNKS) fetch_a(g, chunk + 1);
+#pragma unroll
+            for (int kgl = 0; kgl < 4; ++kgl) {
+                const int kg = chunk * 4 + kgl;
+                if (kg < C::KGS) {
+                    const i32x4 tap = *(const i32x4 *)&taptab[kg * 16 + 4 * (lane >> 4)];
+                    f32x4 fa[MT], fb[NT];
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+                        fa[mt] = *(const f32x4 *)&As[buf][(16 * mt + (lane & 15)) * C::LDA + kgl * 16 + 4 * (lane >> 4)];
+#pragma unroll
+                    for (int nf = 0; nf < NT; ++nf)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) fb[nf][j] = img[pixoff[nf] + tap[j]];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                            for (int nf = 0; nf < NT; ++nf)
+                                acc[mt][nf] = __builtin_amdgcn_mfma_f32_16x16x4f32(fa[mt][j], fb[nf][j], acc[mt][nf], 0, 0, 0);
+                }
+            }
+            if (chunk + 1 < C::CHUNKS) commit_a(buf ^ 1);
+            __syncthreads();
+            buf ^= 1;
+        }
+    }
+
+    float *ob = out + w * out_stride + (int64_t)b * C::COUT * C::PIX;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int co = 16 * mt + 4 * (lane >> 4) + v;
+            const float bv = bias ? bias[w * bias_stride + co] : 0.f;
+#pragma unroll
+            for (int nf = 0; nf < NT; ++nf) {
+                const int p = (wave * NT + nf) * 16 + (lane & 15);
+                ob[co * C::PIX + p] = acc[mt][nf][v] + bv;
+            }
+        }
+}
+
+// dst[ci][(co, kh, kw)] = src[co][ci][KS - 1 - kh][KS - 1 - kw] per worker: the filters of the
+// data-gradient convolution.  grid = (ceil(Cin * Cout * KK / 256), workers).
+__global__ __launch_bounds__(256) void flip_filters_kernel(const float *__restrict__ src, int64_t src_stride,
+                                                           float *__restrict__ dst, int64_t dst_stride, int Cin,
+                                                           int Cout, int KK)
+{
+    const int w = blockIdx.y, idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= Cin * Cout * KK) return;
+    const int ci = idx / (Cout * KK), rem = idx - ci * Cout * KK, co = rem / KK, rr = rem - co * KK;
+    dst[w * dst_stride + idx] = src[w * src_stride + (co * Cin + ci) * KK + (KK - 1 - rr)];
+}
+
+}  // namespace convlds

@@ -15,6 +15,7 @@
 // Max pooling keeps no index: the backward pass re-derives the first maximum of each
 // window from the stored pre-activations (first in window order (0,0),(0,1),(1,0),(1,1)).
 #include "bgemm.h"
+#include "conv_lds.h"
 #include "dbw_internal.h"
 
 namespace {
@@ -262,7 +263,7 @@ struct cnn_layout {
     // parameter offsets inside a row
     int64_t w1, b1, w2, b2, fc;
     // scratch offsets inside a worker's block (floats)
-    int64_t z1, p1, z2, p2, dp2, dz2, dp1, dz1, fc_act, part, total;
+    int64_t z1, p1, z2, p2, dp2, dz2, dp1, dz1, fc_act, part, wflip, total;
     int splits1, splits2;
 };
 
@@ -298,6 +299,7 @@ cnn_layout make_layout(const dbw_model &m)
     L.splits2 = pick(B * L.H2 * L.W2);
     const int64_t p1n = (int64_t)L.splits1 * L.C1 * L.C0 * KK, p2n = (int64_t)L.splits2 * L.C2 * L.C1 * KK;
     L.part = take(p1n > p2n ? p1n : p2n);
+    L.wflip = take((int64_t)L.C1 * L.C2 * KK);
     L.total = o;
     return L;
 }
@@ -323,8 +325,17 @@ int launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const int3
     const ConvShape s1{L.C0, L.C1, L.H, L.W, L.KS, L.KS / 2}, s2{L.C1, L.C2, L.H2, L.W2, L.KS, L.KS / 2};
     const int pix1 = B * L.H * L.W, pix2 = B * L.H2 * L.W2;
     auto blocks = [](int64_t n) { return (unsigned)((n + 255) / 256); };
+    // The LDS-resident convolution kernels are instantiated for the 5x5 / 3-32-64 channel
+    // network on 32 x 32 inputs; every other shape takes the implicit-GEMM path.
+    const bool fast1 = KS_ == 5 && L.C0 == 3 && L.H == 32 && L.W == 32 && L.C1 == 32 && (uintptr_t)bx % 16 == 0;
+    const bool fast2 = KS_ == 5 && L.C1 == 32 && L.H2 == 16 && L.W2 == 16 && L.C2 == 64;
 
-    {   // conv1 forward
+    if (fast1) {
+        dbw_timer tm(c, "conv1_forward", s);
+        hipLaunchKernelGGL((convlds::conv_forward_kernel<3, 2, 8, 32, 32, 5, 8>), dim3(B, N), dim3(512), 0, s, bx,
+                           xstride, params + L.w1, ld, L.C0 * KK, params + L.b1, ld, A + L.z1, ws, L.C0);
+        DBW_HIP(hipGetLastError());
+    } else {   // conv1 forward
         dbw_timer tm(c, "conv1_forward", s);
         DBW_HIP(conv_gemm(Dense<true>{params + L.w1, L.C0 * KK, ld}, PatchRC<KS_>{bx, xstride, s1},
                               ChannelPixelOut{A + L.z1, ws, L.C1, L.H * L.W, params + L.b1, ld}, L.C1, pix1,
@@ -336,7 +347,12 @@ int launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const int3
                            A + L.z1, ws, A + L.p1, ws, B * L.C1, L.H, L.W);
         DBW_HIP(hipGetLastError());
     }
-    {   // conv2 forward
+    if (fast2) {
+        dbw_timer tm(c, "conv2_forward", s);
+        hipLaunchKernelGGL((convlds::conv_forward_kernel<32, 4, 2, 16, 16, 5, 8>), dim3(B, N), dim3(512), 0, s,
+                           A + L.p1, ws, params + L.w2, ld, L.C1 * KK, params + L.b2, ld, A + L.z2, ws, L.C1);
+        DBW_HIP(hipGetLastError());
+    } else {   // conv2 forward
         dbw_timer tm(c, "conv2_forward", s);
         DBW_HIP(conv_gemm(Dense<true>{params + L.w2, L.C1 * KK, ld}, PatchRC<KS_>{A + L.p1, ws, s2},
                               ChannelPixelOut{A + L.z2, ws, L.C2, L.H2 * L.W2, params + L.b2, ld}, L.C2, pix2,
@@ -393,7 +409,19 @@ int launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const int3
                            grads + L.b2, ld);
         DBW_HIP(hipGetLastError());
     }
-    {   // conv2 data gradient -> gradient of the first pooled map
+    if (fast2) {   // conv2 data gradient = forward convolution of the deltas with flipped filters
+        {
+            dbw_timer tm(c, "flip_filters_kernel", s);
+            hipLaunchKernelGGL(convlds::flip_filters_kernel, dim3(blocks((int64_t)L.C1 * L.C2 * KK), N), dim3(256), 0, s,
+                               params + L.w2, ld, A + L.wflip, ws, L.C1, L.C2, KK);
+            DBW_HIP(hipGetLastError());
+        }
+        dbw_timer tm(c, "conv2_dgrad", s);
+        hipLaunchKernelGGL((convlds::conv_forward_kernel<32, 2, 2, 16, 16, 5, 8>), dim3(B, N), dim3(512), 0, s,
+                           A + L.dz2, ws, A + L.wflip, ws, L.C2 * KK, (const float *)nullptr, (int64_t)0, A + L.dp1,
+                           ws, L.C2);
+        DBW_HIP(hipGetLastError());
+    } else {   // conv2 data gradient -> gradient of the first pooled map
         dbw_timer tm(c, "conv2_dgrad", s);
         DBW_HIP(conv_gemm(FilterT<KS_>{params + L.w2, ld, L.C1, KK}, DeltaShiftRC<KS_>{A + L.dz2, ws, s2},
                               ChannelPixelOut{A + L.dp1, ws, L.C1, L.H2 * L.W2, nullptr, 0}, L.C1, pix2, L.C2 * KK, N,
