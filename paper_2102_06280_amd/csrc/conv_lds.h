@@ -171,4 +171,114 @@ __global__ __launch_bounds__(256) void flip_filters_kernel(const float *__restri
     dst[w * dst_stride + idx] = src[w * src_stride + (co * Cin + ci) * KK + (KK - 1 - rr)];
 }
 
+// Weight gradient of the same convolution: dW[co][t] = sum over samples b and pixels p of
+// dz[b][co][p] * in[b][tap t shifted by p], as the GEMM with M = output channels, N = filter
+// taps t = (c, kh, kw), K = pixels.  The sample's input (all CIN channels, zero halo) and a
+// chunk of PC pixels of its deltas sit in LDS.  The A fragment (deltas, k = pixel) is a
+// 128-bit LDS read; the B fragment is img[tap_offset(lane's tap) + pixel_offset(k)], where
+// the pixel offset of k = 16 kg + 4 slot + j is a per-lane constant plus a compile-time
+// immediate, so the reads need no address arithmetic at all.
+// Waves are arranged WM (channels) x WN (taps) x WK (pixels); every (workgroup, wk) pair
+// writes its own partial result  part[worker][split = blockIdx.x * WK + wk][co][t], which a
+// separate pass sums in split order (deterministic).  grid = (ceil(B / SB), workers).
+template <int CIN, int MT, int NT, int WM, int WN, int WK, int H, int W, int KS, int PC>
+struct WCfg {
+    static constexpr int PAD = KS / 2, HP = H + 2 * PAD, WP = W + 2 * PAD;
+    static constexpr int COUT = 16 * MT * WM, PIX = H * W, KK = KS * KS, TAPS = CIN * KK;
+    static constexpr int WAVES = WM * WN * WK, THREADS = 64 * WAVES;
+    static constexpr int IMG = CIN * HP * WP;
+    static constexpr int LDD = PC + 4;                   // row stride of the delta tile [COUT][PC]
+    static constexpr int KG_CHUNK = PC / 16, KG_WAVE = KG_CHUNK / WK;
+    static_assert(16 * NT * WN >= TAPS, "tap fragments must cover all taps");
+    static_assert(PIX % PC == 0 && KG_CHUNK % WK == 0 && W % 16 == 0, "shape not supported");
+    static constexpr size_t lds_bytes = sizeof(float) * (IMG + COUT * LDD);
+};
+
+template <int CIN, int MT, int NT, int WM, int WN, int WK, int H, int W, int KS, int PC>
+__global__ __launch_bounds__(64 * WM * WN * WK) void conv_wgrad_kernel(
+    const float *__restrict__ in, int64_t in_stride, const float *__restrict__ dz, int64_t dz_stride,
+    float *__restrict__ part, int64_t part_stride, int B, int SB)
+{
+    using C = WCfg<CIN, MT, NT, WM, WN, WK, H, W, KS, PC>;
+    __shared__ __attribute__((aligned(16))) float img[C::IMG];
+    __shared__ __attribute__((aligned(16))) float dzs[C::COUT * C::LDD];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % WM, wn = (wave / WM) % WN, wk = wave / (WM * WN);
+    const int w = blockIdx.y, b0 = blockIdx.x * SB, b1 = min(B, b0 + SB);
+
+    for (int e = tid; e < C::IMG; e += C::THREADS) img[e] = 0.f;     // the halo stays zero
+
+    // per-lane LDS element index of this lane's tap (plus its k-slot) for each tap fragment
+    int bbase[NT];
+#pragma unroll
+    for (int nf = 0; nf < NT; ++nf) {
+        const int t = 16 * (wn * NT + nf) + (lane & 15);
+        const int c = t / C::KK, rr = t % C::KK, kh = rr / KS, kw = rr % KS;
+        bbase[nf] = (t < C::TAPS ? c * C::HP * C::WP + kh * C::WP + kw : 0) + 4 * (lane >> 4);
+    }
+    f32x4 acc[MT][NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nf = 0; nf < NT; ++nf) acc[mt][nf] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    for (int b = b0; b < b1; ++b) {
+        const float *inb = in + w * in_stride + (int64_t)b * CIN * C::PIX;
+        const float *dzb = dz + w * dz_stride + (int64_t)b * C::COUT * C::PIX;
+        for (int chunk = 0; chunk < C::PIX / PC; ++chunk) {
+            __syncthreads();                   // previous tile fully consumed
+            if (chunk == 0) {
+                for (int e = tid; e < CIN * H * (W / 4); e += C::THREADS) {
+                    const int c = e / (H * (W / 4)), rem = e % (H * (W / 4)), y = rem / (W / 4), x4 = rem % (W / 4);
+                    const float4 v = *(const float4 *)&inb[(c * H + y) * W + 4 * x4];
+                    float *dst = &img[c * C::HP * C::WP + (y + C::PAD) * C::WP + C::PAD + 4 * x4];
+                    dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+                }
+            }
+            for (int e = tid; e < C::COUT * (PC / 4); e += C::THREADS) {
+                const int co = e / (PC / 4), p4 = e % (PC / 4);
+                *(float4 *)&dzs[co * C::LDD + 4 * p4] = *(const float4 *)&dzb[co * C::PIX + chunk * PC + 4 * p4];
+            }
+            __syncthreads();
+            const int chunk_row = chunk * (PC / W);                  // first image row of the chunk
+#pragma unroll
+            for (int i = 0; i < C::KG_WAVE; ++i) {
+                const int kgl = wk * C::KG_WAVE + i;                 // k group inside the chunk (wave-uniform)
+                // pixel offset of the group's first pixel; W % 16 == 0 keeps a group inside one row
+                const int poff = (chunk_row + (16 * kgl) / W) * C::WP + (16 * kgl) % W;
+                f32x4 fa[MT];
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+                    fa[mt] = *(const f32x4 *)&dzs[(16 * (wm * MT + mt) + (lane & 15)) * C::LDD + 16 * kgl + 4 * (lane >> 4)];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    float fb[NT];
+#pragma unroll
+                    for (int nf = 0; nf < NT; ++nf) fb[nf] = img[bbase[nf] + poff + j];
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                        for (int nf = 0; nf < NT; ++nf)
+                            acc[mt][nf] = __builtin_amdgcn_mfma_f32_16x16x4f32(fa[mt][j], fb[nf], acc[mt][nf], 0, 0, 0);
+                }
+            }
+        }
+    }
+
+    float *pb = part + w * part_stride + (int64_t)(blockIdx.x * WK + wk) * C::COUT * C::TAPS;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nf = 0; nf < NT; ++nf) {
+            const int t = 16 * (wn * NT + nf) + (lane & 15);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int co = 16 * (wm * MT + mt) + 4 * (lane >> 4) + v;
+                if (t < C::TAPS) pb[co * C::TAPS + t] = acc[mt][nf][v];
+            }
+        }
+}
+
 }  // namespace convlds

@@ -14,6 +14,8 @@
 // Output channels are the GEMM's M and pixels its N, so stores run along consecutive pixels.
 // Max pooling keeps no index: the backward pass re-derives the first maximum of each
 // window from the stored pre-activations (first in window order (0,0),(0,1),(1,0),(1,1)).
+#include <algorithm>
+
 #include "bgemm.h"
 #include "conv_lds.h"
 #include "dbw_internal.h"
@@ -256,6 +258,8 @@ __global__ __launch_bounds__(256) void channel_sum_kernel(const float *__restric
     if (tid == 0) db[w * dbstride + ch] = red[0];
 }
 
+constexpr int WGRAD_SB = 4;     // samples per workgroup in the LDS-resident weight-gradient kernels
+
 struct cnn_layout {
     int C0, H, W, C1, C2, KS, F, NC, B;
     int H2, W2, H4, W4, flat;
@@ -297,7 +301,10 @@ cnn_layout make_layout(const dbw_model &m)
     auto pick = [&](int64_t K) { int s = 1; while (s < 32 && K / (s * 2) >= 1024) s *= 2; return s; };
     L.splits1 = pick(B * L.H * L.W);
     L.splits2 = pick(B * L.H2 * L.W2);
-    const int64_t p1n = (int64_t)L.splits1 * L.C1 * L.C0 * KK, p2n = (int64_t)L.splits2 * L.C2 * L.C1 * KK;
+    // the LDS-resident weight-gradient kernels write one partial per 4 samples (conv1: x 8 waves)
+    const int64_t nb = (B + WGRAD_SB - 1) / WGRAD_SB;
+    const int64_t s1 = std::max<int64_t>(L.splits1, nb * 8), s2 = std::max<int64_t>(L.splits2, nb);
+    const int64_t p1n = s1 * L.C1 * L.C0 * KK, p2n = s2 * L.C2 * L.C1 * KK;
     L.part = take(p1n > p2n ? p1n : p2n);
     L.wflip = take((int64_t)L.C1 * L.C2 * KK);
     L.total = o;
@@ -391,7 +398,14 @@ int launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const int3
                            A + L.dp2, ws, A + L.dz2, B * L.C2, L.H2, L.W2);
         DBW_HIP(hipGetLastError());
     }
-    {   // conv2 weight gradient (split over pixels, then summed in split order) and bias gradient
+    int splits2 = L.splits2, splits1 = L.splits1;
+    if (fast2) {
+        splits2 = (B + WGRAD_SB - 1) / WGRAD_SB;
+        dbw_timer tm(c, "conv2_wgrad", s);
+        hipLaunchKernelGGL((convlds::conv_wgrad_kernel<32, 2, 13, 2, 4, 1, 16, 16, 5, 256>), dim3(splits2, N), dim3(512),
+                           0, s, A + L.p1, ws, A + L.dz2, ws, A + L.part, ws, B, WGRAD_SB);
+        DBW_HIP(hipGetLastError());
+    } else {   // conv2 weight gradient (split over pixels, then summed in split order) and bias gradient
         dbw_timer tm(c, "conv2_wgrad", s);
         DBW_HIP(conv_gemm(DeltaKC{A + L.dz2, ws, L.C2, L.H2 * L.W2}, PatchKC<KS_>{A + L.p1, ws, s2},
                               PartialOut{A + L.part, ws, L.C2, L.C1 * KK}, L.C2, L.C1 * KK, pix2, N, s,
@@ -400,7 +414,7 @@ int launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const int3
     {
         dbw_timer tm(c, "reduce_splits_kernel", s);
         hipLaunchKernelGGL(reduce_splits_kernel, dim3(blocks((int64_t)L.C2 * L.C1 * KK), N), dim3(256), 0, s,
-                           A + L.part, ws, L.splits2, L.C2 * L.C1 * KK, grads + L.w2, ld);
+                           A + L.part, ws, splits2, L.C2 * L.C1 * KK, grads + L.w2, ld);
         DBW_HIP(hipGetLastError());
     }
     {
@@ -433,7 +447,14 @@ int launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const int3
                            A + L.z1, ws, A + L.dp1, ws, A + L.dz1, B * L.C1, L.H, L.W);
         DBW_HIP(hipGetLastError());
     }
-    {   // conv1 weight and bias gradients
+    if (fast1) {
+        const int nb = (B + WGRAD_SB - 1) / WGRAD_SB;
+        splits1 = nb * 8;
+        dbw_timer tm(c, "conv1_wgrad", s);
+        hipLaunchKernelGGL((convlds::conv_wgrad_kernel<3, 2, 5, 1, 1, 8, 32, 32, 5, 512>), dim3(nb, N), dim3(512), 0, s,
+                           bx, xstride, A + L.dz1, ws, A + L.part, ws, B, WGRAD_SB);
+        DBW_HIP(hipGetLastError());
+    } else {   // conv1 weight and bias gradients
         dbw_timer tm(c, "conv1_wgrad", s);
         DBW_HIP(conv_gemm(DeltaKC{A + L.dz1, ws, L.C1, L.H * L.W}, PatchKC<KS_>{bx, xstride, s1},
                               PartialOut{A + L.part, ws, L.C1, L.C0 * KK}, L.C1, L.C0 * KK, pix1, N, s,
@@ -442,7 +463,7 @@ int launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const int3
     {
         dbw_timer tm(c, "reduce_splits_kernel", s);
         hipLaunchKernelGGL(reduce_splits_kernel, dim3(blocks((int64_t)L.C1 * L.C0 * KK), N), dim3(256), 0, s,
-                           A + L.part, ws, L.splits1, L.C1 * L.C0 * KK, grads + L.w1, ld);
+                           A + L.part, ws, splits1, L.C1 * L.C0 * KK, grads + L.w1, ld);
         DBW_HIP(hipGetLastError());
     }
     {
