@@ -6,6 +6,8 @@
 // Parameter row layout: per layer l, W_l [out][in] then b_l [out].
 // Scratch per worker: activations a_1..a_L ([B][dims[l]], a_L = logits) followed by the
 // deltas dz_1..dz_L of the same shapes.
+#include <algorithm>
+
 #include "bgemm.h"
 #include "dbw_internal.h"
 
@@ -58,13 +60,54 @@ __global__ __launch_bounds__(256) void colsum_kernel(int B, int C, const float *
     db[w * stride_db + o] = s;
 }
 
+// Partial sums of a split-k forward GEMM: part[worker][split][m][n].
+struct SplitOut {
+    float *part;
+    int64_t stride;
+    int M, N;
+    __device__ __forceinline__ void store(int w, int split, int m, int n, float v) const
+    {
+        part[w * stride + ((int64_t)split * M + m) * N + n] = v;
+    }
+};
+
+// C[m][n] = act(sum over splits of part[split][m][n] + bias[n]); grid = (ceil(M N / 256), workers).
+__global__ __launch_bounds__(256) void fc_reduce_kernel(const float *__restrict__ part, int64_t pstride, int splits,
+                                                        int M, int N, const float *__restrict__ bias,
+                                                        int64_t bias_stride, int relu, float *__restrict__ C,
+                                                        int64_t ldc, int64_t cstride)
+{
+    const int w = blockIdx.y, i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= M * N) return;
+    const int m = i / N, n = i - m * N;
+    float s = 0.f;
+    for (int sp = 0; sp < splits; ++sp) s += part[w * pstride + (int64_t)sp * M * N + i];
+    s += bias[w * bias_stride + n];
+    if (relu) s = s > 0.f ? s : 0.f;
+    C[w * cstride + (int64_t)m * ldc + n] = s;
+}
+
+// A long reduction with few output tiles (e.g. batch 32 x 512 outputs over k = 4096) leaves
+// most of the chip idle and each workgroup waiting on its own loads; split k then.
+int forward_splits(int K) { return K >= 2048 ? 8 : (K >= 1024 ? 4 : 1); }
+
+int64_t act_floats(int L, const int32_t *dims, int B)
+{
+    int64_t n = 0;
+    for (int l = 1; l <= L; ++l) n += (int64_t)B * dims[l];
+    return n;
+}
+
 }  // namespace
 
 int64_t dbw_fc_scratch_per_worker(int L, const int32_t *dims, int B)
 {
-    int64_t n = 0;
-    for (int l = 1; l <= L; ++l) n += (int64_t)B * dims[l];
-    return 2 * n;
+    int64_t part = 0;
+    for (int l = 1; l <= L; ++l) {
+        const int sp = forward_splits(dims[l - 1]);
+        if (sp > 1) part = std::max<int64_t>(part, (int64_t)sp * B * dims[l]);
+    }
+    return 2 * act_floats(L, dims, B) + part;
 }
 
 // Forward and backward pass of a stack of fully connected layers for all workers.
@@ -72,7 +115,7 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
 {
     const int L = a.L, B = a.B, N = c->N;
     const int32_t *dims = a.dims;
-    const int64_t per = dbw_fc_scratch_per_worker(L, dims, B) / 2, wstride = a.act_stride;
+    const int64_t per = act_floats(L, dims, B), wstride = a.act_stride;
     // offsets inside a worker's scratch block and parameter row
     int64_t a_off[9], dz_off[9], w_off[9], b_off[9];
     int64_t ao = 0, po = a.param_off;
@@ -96,6 +139,21 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
         else
             A = {act + a_off[l - 1], dims[l - 1], wstride};
         Bm = {params + w_off[l], dims[l - 1], c->ld};
+        const int splits = forward_splits(dims[l - 1]);
+        if (splits > 1) {
+            float *part = act + 2 * per;
+            {
+                dbw_timer tm(c, "mlp_forward_gemm", s);
+                DBW_HIP(bgemm::launch<64>(A, Bm, SplitOut{part, wstride, B, dims[l]}, B, dims[l], dims[l - 1], N, s,
+                                          splits));
+            }
+            dbw_timer tm(c, "fc_reduce_kernel", s);
+            hipLaunchKernelGGL(fc_reduce_kernel, dim3((B * dims[l] + 255) / 256, N), dim3(256), 0, s, part, wstride,
+                               splits, B, dims[l], params + b_off[l], c->ld, l < L ? 1 : 0, act + a_off[l],
+                               (int64_t)dims[l], wstride);
+            DBW_HIP(hipGetLastError());
+            continue;
+        }
         Epilogue E{act + a_off[l], dims[l], wstride, params + b_off[l], c->ld, nullptr, 0, 0, l < L ? 1 : 0};
         dbw_timer tm(c, "mlp_forward_gemm", s);
         DBW_HIP(bgemm::launch<64>(A, Bm, E, B, dims[l], dims[l - 1], N, s));
