@@ -132,6 +132,17 @@ def main():
             wl.x[wl.cur ^ 1].copy_(wl.x[wl.cur])
         torch.cuda.synchronize()
 
+    # simulated duration of a round (Section 3.2.2) with the workload's backup counts and with
+    # full participation (b = 0) on the same response times; outside the timed region
+    T = torch.zeros(2, device="cuda")
+    zero_b = torch.zeros(cfg.n, dtype=torch.int32, device="cuda")
+    dur = {"dybw": 0.0, "full": 0.0}
+    for r in range(wl.rounds):
+        for key, b in (("dybw", wl.b[r]), ("full", zero_b)):
+            B.dbw_select(wl.h, wl.t[r], b)
+            B.dbw_round_time(wl.h, T)
+            dur[key] += float(T[1].item()) / wl.rounds      # T(k) over the workers somebody waits for
+
     ms_per_step = elapsed / args.steps * 1e3
     value = cfg.n * args.steps / elapsed
 
@@ -169,6 +180,8 @@ def main():
                    "mix_path": "dense" if mix_path == B.MIX_DENSE else "csr",
                    "gradients": "one fixed supplied matrix, reused every round" if cfg.model == "none" else "computed"},
         "roofline": roofline,
+        "simulated_round_duration": {"dybw": dur["dybw"], "full_participation": dur["full"],
+                                     "shorter_by": 1.0 - dur["dybw"] / dur["full"], "rounds": wl.rounds},
     }
     rowptr, colidx = wl.rowptr, wl.colidx
     wl.close()

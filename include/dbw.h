@@ -127,6 +127,14 @@ int dbw_dtur_reset(dbw_ctx *ctx, void *stream);
  * out-of-range b_i. */
 int dbw_get_selection(dbw_ctx *ctx, int32_t *p, uint8_t *mask, float *wait_time, void *stream);
 
+/* Duration of the round implied by the last selection (Section 3.2.2, T(k)):
+ * T_out [dev, 2] float; T_out[0] = max over all workers i of T_i, T_out[1] = max of T_j over
+ * the workers j that some worker waits for (the paper's set V'; 0 if nobody is waited
+ * for).  With b = 0 this is the duration of a full-participation round, so calling
+ * dbw_select twice on the same response times compares the two (Corollary 4).
+ * Asynchronous on `stream`. */
+int dbw_round_time(dbw_ctx *ctx, float *T_out, void *stream);
+
 /* Copy out the dense consensus matrix P(k) [dev, N*N] float, row i = worker i's weights,
  * built from the last selection.  Synchronises the stream. */
 int dbw_get_weights(dbw_ctx *ctx, float *P, void *stream);

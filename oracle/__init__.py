@@ -64,6 +64,16 @@ def select(rowptr, colidx, t, b):
     return mask, p, wait
 
 
+def round_time(rowptr, colidx, mask, wait):
+    """-> (max wait over all workers, max wait over workers somebody waits for)."""
+    rowptr, colidx, wait = _i32(rowptr), _i32(colidx), _f32(wait)
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    out = np.zeros(2, dtype=np.float32)
+    lib().orc_round_time(rowptr.size - 1, _p(rowptr, C.c_int32), _p(colidx, C.c_int32), _p(mask, C.c_uint8),
+                         _p(wait, C.c_float), _p(out, C.c_float))
+    return float(out[0]), float(out[1])
+
+
 def weights(rowptr, colidx, mask, p):
     rowptr, colidx, p = _i32(rowptr), _i32(colidx), _i32(p)
     mask = np.ascontiguousarray(mask, dtype=np.uint8)

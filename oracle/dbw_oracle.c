@@ -10,6 +10,7 @@
  *   orc_select         Section 1 ("Dynamic Backup Workers": wait for the fastest p_j
  *                      neighbours, the other b_j = n_j - p_j are backups), Section 2.2
  *                      (sets S_j(k), B_j(k)), Section 3.2.2 (wait time T_j(k)).
+ *   orc_round_time     Section 3.2.2 (duration T(k) of a round).
  *   orc_weights        Assumption 1 (Metropolis weights on the time-varying graph).
  *   orc_dense_P        the same weights laid out as the N x N consensus matrix P(k).
  *   orc_round          Section 2.1, the full-participation update (average, then correct
@@ -89,6 +90,25 @@ int orc_select(int N, const int32_t *rowptr, const int32_t *colidx, const float 
         free(order);
     }
     return ORC_OK;
+}
+
+/* Duration of the round (Section 3.2.2): out[0] = max over all workers of their wait time
+ * T_i; out[1] = the paper's literal T(k), the max of T_j over the workers j that appear in
+ * some worker's selected set (0 when nobody is waited for). */
+void orc_round_time(int N, const int32_t *rowptr, const int32_t *colidx, const uint8_t *mask,
+                    const float *wait, float *out)
+{
+    uint8_t *listed = (uint8_t *)calloc((size_t)N, 1);
+    for (int e = 0; e < rowptr[N]; ++e)
+        if (mask[e]) listed[colidx[e]] = 1;
+    float all = 0.0f, sel = 0.0f;
+    for (int i = 0; i < N; ++i) {
+        if (wait[i] > all) all = wait[i];
+        if (listed[i] && wait[i] > sel) sel = wait[i];
+    }
+    out[0] = all;
+    out[1] = sel;
+    free(listed);
 }
 
 /* Assumption 1: P_ij = 1 / (1 + max(p_i, p_j)) for j in S_i, P_ii = 1 - sum_j P_ij. */

@@ -21,7 +21,7 @@ MIX_AUTO, MIX_CSR, MIX_DENSE = 0, 1, 2
 MODEL_NONE, MODEL_MLP, MODEL_CNN = 0, 1, 2
 
 EXPORTS = ["dbw_create", "dbw_select", "dbw_dtur_b", "dbw_dtur_reset", "dbw_get_selection",
-           "dbw_get_weights", "dbw_round", "dbw_grad", "dbw_check", "dbw_get_links", "dbw_mix_path",
+           "dbw_get_weights", "dbw_round_time", "dbw_round", "dbw_grad", "dbw_check", "dbw_get_links", "dbw_mix_path",
            "dbw_destroy", "dbw_strerror", "dbw_set_timing", "dbw_get_timing"]
 
 
@@ -50,6 +50,7 @@ _lib.dbw_dtur_b.argtypes = [_vp, _vp, _vp, _vp, _vp]
 _lib.dbw_dtur_reset.argtypes = [_vp, _vp]
 _lib.dbw_get_selection.argtypes = [_vp, _vp, _vp, _vp, _vp]
 _lib.dbw_get_weights.argtypes = [_vp, _vp, _vp]
+_lib.dbw_round_time.argtypes = [_vp, _vp, _vp]
 _lib.dbw_round.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _f, _vp]
 _lib.dbw_grad.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.dbw_check.argtypes = [_vp, _vp]
@@ -128,6 +129,10 @@ def dbw_dtur_reset(h):
 
 def dbw_get_selection(h, p=None, mask=None, wait_time=None):
     return _chk(_lib.dbw_get_selection(h, _ptr(p), _ptr(mask), _ptr(wait_time), _stream()), "dbw_get_selection")
+
+
+def dbw_round_time(h, T_out):
+    return _chk(_lib.dbw_round_time(h, _ptr(T_out), _stream()), "dbw_round_time")
 
 
 def dbw_get_weights(h, P):

@@ -89,7 +89,7 @@ int dev_alloc(T **p, size_t n)
 void free_ctx(dbw_ctx *c)
 {
     if (!c) return;
-    void *ptrs[] = {c->rowptr, c->colidx, c->p, c->mask, c->wait, c->sel_idx, c->sel_w, c->self_w, c->Wdense,
+    void *ptrs[] = {c->rowptr, c->colidx, c->p, c->mask, c->wait, c->listed, c->sel_idx, c->sel_w, c->self_w, c->Wdense,
                     c->err, c->links, c->visited, c->n_visited, c->grads, c->act};
     for (void *q : ptrs)
         if (q) (void)hipFree(q);
@@ -192,6 +192,7 @@ int dbw_create(dbw_ctx **out, int32_t N, int64_t d, const int32_t *rowptr, const
     A(dev_alloc(&c->p, (size_t)N));
     A(dev_alloc(&c->mask, (size_t)c->nnz));
     A(dev_alloc(&c->wait, (size_t)N));
+    A(dev_alloc(&c->listed, (size_t)N));
     A(dev_alloc(&c->sel_idx, (size_t)c->nnz));
     A(dev_alloc(&c->sel_w, (size_t)c->nnz));
     A(dev_alloc(&c->self_w, (size_t)N));
@@ -274,6 +275,13 @@ int dbw_get_selection(dbw_ctx *c, int32_t *p, uint8_t *mask, float *wait_time, v
     if (mask && c->nnz) DBW_HIP(hipMemcpyAsync(mask, c->mask, (size_t)c->nnz, hipMemcpyDeviceToDevice, s));
     if (wait_time) DBW_HIP(hipMemcpyAsync(wait_time, c->wait, sizeof(float) * (size_t)c->N, hipMemcpyDeviceToDevice, s));
     return dbw_check(c, stream);
+}
+
+int dbw_round_time(dbw_ctx *c, float *T_out, void *stream)
+{
+    if (!c || !T_out) return DBW_ERR_NULL;
+    if (!c->selected) return DBW_ERR_STATE;
+    return dbw_launch_round_time(c, T_out, (hipStream_t)stream);
 }
 
 int dbw_get_weights(dbw_ctx *c, float *P, void *stream)

@@ -42,6 +42,7 @@ struct dbw_ctx {
     int32_t *p = nullptr;             // [N]
     uint8_t *mask = nullptr;          // [nnz]
     float *wait = nullptr;            // [N]
+    uint8_t *listed = nullptr;        // [N] scratch of the round-time kernel
     int32_t *sel_idx = nullptr;       // [nnz] row i: first p_i entries = selected neighbours, ascending
     float *sel_w = nullptr;           // [nnz] their weights
     float *self_w = nullptr;          // [N]
@@ -72,6 +73,7 @@ struct dbw_timer {
 
 // select.hip
 int dbw_launch_select(dbw_ctx *c, const float *t, const int32_t *b, hipStream_t s);
+int dbw_launch_round_time(dbw_ctx *c, float *out, hipStream_t s);
 int dbw_launch_dtur(dbw_ctx *c, const float *t, int32_t *b_out, float *theta_out, hipStream_t s);
 // mix_csr.hip
 int dbw_launch_mix_csr(dbw_ctx *c, const float *x, const float *g, float *out, float lr, hipStream_t s);

@@ -87,9 +87,17 @@ __global__ __launch_bounds__(256) void fc_reduce_kernel(const float *__restrict_
     C[w * cstride + (int64_t)m * ldc + n] = s;
 }
 
-// A long reduction with few output tiles (e.g. batch 32 x 512 outputs over k = 4096) leaves
-// most of the chip idle and each workgroup waiting on its own loads; split k then.
-int forward_splits(int K) { return K >= 2048 ? 8 : (K >= 1024 ? 4 : 1); }
+// A long reduction with few output tiles (e.g. batch 32 x 512 outputs over k = 4096, or any
+// small model) leaves most of the chip idle and each workgroup waiting on its own chain of
+// loads; split k then, up to MAX_SPLITS ways, keeping at least two k-steps per split.
+constexpr int MAX_SPLITS = 8;
+int forward_splits(int M, int N, int K, int workers)
+{
+    const int64_t tiles = (int64_t)((M + 63) / 64) * ((N + 63) / 64) * workers;
+    int splits = 1;
+    while (splits < MAX_SPLITS && tiles * splits < 2048 && K / (splits * 2) >= 2 * bgemm::BK) splits *= 2;
+    return splits;
+}
 
 int64_t act_floats(int L, const int32_t *dims, int B)
 {
@@ -103,10 +111,7 @@ int64_t act_floats(int L, const int32_t *dims, int B)
 int64_t dbw_fc_scratch_per_worker(int L, const int32_t *dims, int B)
 {
     int64_t part = 0;
-    for (int l = 1; l <= L; ++l) {
-        const int sp = forward_splits(dims[l - 1]);
-        if (sp > 1) part = std::max<int64_t>(part, (int64_t)sp * B * dims[l]);
-    }
+    for (int l = 1; l <= L; ++l) part = std::max<int64_t>(part, (int64_t)MAX_SPLITS * B * dims[l]);
     return 2 * act_floats(L, dims, B) + part;
 }
 
@@ -139,7 +144,7 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
         else
             A = {act + a_off[l - 1], dims[l - 1], wstride};
         Bm = {params + w_off[l], dims[l - 1], c->ld};
-        const int splits = forward_splits(dims[l - 1]);
+        const int splits = forward_splits(B, dims[l], dims[l - 1], N);
         if (splits > 1) {
             float *part = act + 2 * per;
             {

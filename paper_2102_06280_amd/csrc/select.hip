@@ -183,7 +183,52 @@ __global__ __launch_bounds__(256) void dtur_kernel(
     }
 }
 
+// Round duration (Section 3.2.2): max of the wait times over all workers and over the
+// workers that appear in some selected set.  One block; `listed` is context scratch [N].
+__global__ __launch_bounds__(256) void round_time_kernel(int N, int nnz, const int32_t *__restrict__ colidx,
+                                                         const uint8_t *__restrict__ mask,
+                                                         const float *__restrict__ wait, uint8_t *__restrict__ listed,
+                                                         float *__restrict__ out)
+{
+    __shared__ float red[2][256];
+    const int tid = threadIdx.x;
+    for (int i = tid; i < N; i += 256) listed[i] = 0;
+    __syncthreads();
+    for (int e = tid; e < nnz; e += 256)
+        if (mask[e]) listed[colidx[e]] = 1;       // benign race: every writer stores the same value
+    __syncthreads();
+    float all = 0.f, sel = 0.f;
+    for (int i = tid; i < N; i += 256) {
+        const float t = wait[i];
+        all = fmaxf(all, t);
+        if (listed[i]) sel = fmaxf(sel, t);
+    }
+    red[0][tid] = all;
+    red[1][tid] = sel;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if (tid < o) {
+            red[0][tid] = fmaxf(red[0][tid], red[0][tid + o]);
+            red[1][tid] = fmaxf(red[1][tid], red[1][tid + o]);
+        }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        out[0] = red[0][0];
+        out[1] = red[1][0];
+    }
+}
+
 }  // namespace
+
+int dbw_launch_round_time(dbw_ctx *c, float *out, hipStream_t s)
+{
+    dbw_timer tm(c, "round_time_kernel", s);
+    hipLaunchKernelGGL(round_time_kernel, dim3(1), dim3(256), 0, s, c->N, c->nnz, c->colidx, c->mask, c->wait,
+                       c->listed, out);
+    DBW_HIP(hipGetLastError());
+    return DBW_OK;
+}
 
 int dbw_launch_select(dbw_ctx *c, const float *t, const int32_t *b, hipStream_t s)
 {

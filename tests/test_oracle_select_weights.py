@@ -212,3 +212,24 @@ def test_worked_example(orc):
         out = orc.round_(rowptr, colidx, mask, p, x, g, lr, order)
         want = np.stack([fr(f"{tag}{i}") for i in range(4)])
         assert np.allclose(out, want, rtol=3e-7, atol=0), (tag, out, want)
+
+
+def test_round_time(orc):
+    """Section 3.2.2: T(k) is the max of the per-worker wait times; over all workers, and
+    over the set V' of workers that somebody waits for.  Recomputed here from the mask."""
+    g = np.random.default_rng(19)
+    for rowptr, colidx in small_graphs():
+        n = rowptr.size - 1
+        deg = np.diff(rowptr)
+        for _ in range(5):
+            t = g.standard_exponential(n).astype(np.float32)
+            b = g.integers(0, deg + 1).astype(np.int32)
+            mask, p, wait = orc.select(rowptr, colidx, t, b)
+            t_all, t_sel = orc.round_time(rowptr, colidx, mask, wait)
+            listed = sorted({int(colidx[e]) for e in range(colidx.size) if mask[e]})
+            assert t_all == wait.max()
+            assert t_sel == (wait[listed].max() if listed else 0.0)
+            # never longer than the full-participation round on the same response times
+            m0, _, w0 = orc.select(rowptr, colidx, t, np.zeros(n, np.int32))
+            f_all, f_sel = orc.round_time(rowptr, colidx, m0, w0)
+            assert t_all <= f_all and f_all == t.max() == f_sel
