@@ -132,6 +132,19 @@ def main():
             wl.x[wl.cur ^ 1].copy_(wl.x[wl.cur])
         torch.cuda.synchronize()
 
+    # the same rounds replayed as HIP graphs (one per round): what a launch-bound
+    # configuration gains from a single submission per round; reported next to the eager figure
+    graph_ms = None
+    if cfg.model != "none" and cfg.cid != 3:
+        graphs = wl.capture_steps(args.steps)
+        wl.replay(graphs[:2])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        wl.replay(graphs)
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) / args.steps * 1e3
+        del graphs
+
     # simulated duration of a round (Section 3.2.2) with the workload's backup counts and with
     # full participation (b = 0) on the same response times; outside the timed region
     T = torch.zeros(2, device="cuda")
@@ -180,6 +193,7 @@ def main():
                    "mix_path": "dense" if mix_path == B.MIX_DENSE else "csr",
                    "gradients": "one fixed supplied matrix, reused every round" if cfg.model == "none" else "computed"},
         "roofline": roofline,
+        "hip_graph_ms_per_step": graph_ms,
         "simulated_round_duration": {"dybw": dur["dybw"], "full_participation": dur["full"],
                                      "shorter_by": 1.0 - dur["dybw"] / dur["full"], "rounds": wl.rounds},
     }

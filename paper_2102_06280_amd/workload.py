@@ -80,6 +80,31 @@ class Workload:
         self.cur ^= 1
         self.k += 1
 
+    def capture_steps(self, n_steps: int):
+        """Capture the next `n_steps` rounds, one HIP graph per round (every round has its own
+        response times, backup counts, batch and ping-pong direction), so that a launch-bound
+        round replays as one submission.  A round calls no allocation, memset or
+        synchronisation, so it can be captured as it is.  Returns the list of graphs; replaying
+        them in order is equivalent to calling step() n_steps times from the current state."""
+        torch.cuda.synchronize()
+        graphs = []
+        k0, cur0 = self.k, self.cur
+        stream = torch.cuda.Stream()
+        for _ in range(n_steps):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                self.step()
+            graphs.append(g)
+        torch.cuda.synchronize()
+        self.k, self.cur = k0, cur0          # capturing ran nothing: restore the bookkeeping
+        return graphs
+
+    def replay(self, graphs):
+        for g in graphs:
+            g.replay()
+            self.cur ^= 1
+            self.k += 1
+
     def params(self):
         return self.x[self.cur]
 

@@ -122,3 +122,31 @@ def test_rounds_lock_step(B, orc, cid, rounds, order):
         assert drift < 1e-3
     finally:
         B.dbw_destroy(h)
+
+
+def test_graph_replay_matches_eager(B):
+    """Rounds captured as HIP graphs (one per round) give the same bits as eager rounds, on
+    every replay, with eager work and synchronisations between replays."""
+    from paper_2102_06280_amd.workload import Workload
+    eager = Workload(2, rounds=6)
+    graphed = Workload(2, rounds=6)
+    try:
+        for _ in range(6):
+            eager.step()
+        torch.cuda.synchronize()
+        want = eager.params().clone()
+        start = graphed.x[0].clone()
+        graphs = graphed.capture_steps(6)
+        for rep in range(3):
+            graphed.x[0].copy_(start)
+            graphed.cur, graphed.k = 0, 0
+            torch.cuda.synchronize()
+            graphed.replay(graphs[:3])
+            torch.cuda.synchronize()
+            scratch = torch.randn(1000, device="cuda").sum().item()     # unrelated eager work in between
+            graphed.replay(graphs[3:])
+            torch.cuda.synchronize()
+            assert torch.equal(graphed.params(), want), f"replay {rep}"
+    finally:
+        eager.close()
+        graphed.close()
