@@ -10,6 +10,7 @@ import ctypes as C
 import os
 
 import numpy as np
+import torch  # noqa: F401  (first: the library must bind to the HIP runtime that torch has already loaded)
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdbw.so")
@@ -87,7 +88,6 @@ def _ptr(t):
 
 
 def _stream():
-    import torch
     return torch.cuda.current_stream().cuda_stream
 
 
