@@ -144,14 +144,16 @@ class Dtur:
         return b, float(theta.value)
 
 
-def grad_mlp(dims, params, x, y):
-    """One worker: params [d], x [B, dims[0]], y [B] -> (grad [d] fp32, loss float)."""
+def grad_mlp(dims, params, x, y, loss_kind="xent"):
+    """One worker: params [d], x [B, dims[0]], y [B] -> (grad [d] fp32, loss float).
+    loss_kind: "xent" (softmax cross-entropy) or "mse" (squared error of the softmax outputs)."""
     dims = _i32(dims)
     params, x, y = _f32(params), _f32(x), _i32(y)
     grad = np.zeros_like(params)
     loss = C.c_double(0)
-    lib().orc_grad_mlp(len(dims) - 1, _p(dims, C.c_int32), x.shape[0], _p(params, C.c_float),
-                       _p(x, C.c_float), _p(y, C.c_int32), _p(grad, C.c_float), C.byref(loss), None)
+    lib().orc_grad_mlp_loss(len(dims) - 1, _p(dims, C.c_int32), x.shape[0], _p(params, C.c_float),
+                            _p(x, C.c_float), _p(y, C.c_int32), 1 if loss_kind == "mse" else 0,
+                            _p(grad, C.c_float), C.byref(loss), None)
     return grad, loss.value
 
 
@@ -189,7 +191,7 @@ def model_desc(desc):
     """(kind, int32 descriptor) for grad_all from a model description dict."""
     if desc["kind"] == "mlp":
         dims = desc["dims"]
-        return 0, np.array([len(dims) - 1] + list(dims), dtype=np.int32)
+        return (2 if desc.get("loss") == "mse" else 0), np.array([len(dims) - 1] + list(dims), dtype=np.int32)
     c, h, w = desc["in"]
     return 1, np.array([c, h, w, desc["c1"], desc["c2"], desc["k"], desc["fc"], desc["classes"]], dtype=np.int32)
 

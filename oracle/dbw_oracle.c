@@ -284,11 +284,45 @@ static double softmax_xent(int C, const double *z, int y, double scale, double *
     return -(z[y] - m - log(s));
 }
 
+/* Squared error of the softmax outputs on one sample (the loss of the 2NN experiment of
+ * Appendix B: a softmax output layer trained with the MSE loss):
+ *   f = sum_c (p_c - onehot_c)^2,   df/dz_k = 2 p_k ((p_k - o_k) - sum_c p_c (p_c - o_c)).
+ * Fills dz = df/dz * scale and returns f. */
+static double softmax_mse(int C, const double *z, int y, double scale, double *dz)
+{
+    double m = z[0];
+    for (int c = 1; c < C; ++c)
+        if (z[c] > m) m = z[c];
+    double s = 0.0;
+    for (int c = 0; c < C; ++c) s += exp(z[c] - m);
+    double f = 0.0, inner = 0.0;
+    for (int c = 0; c < C; ++c) {
+        double p = exp(z[c] - m) / s, e = p - (c == y ? 1.0 : 0.0);
+        f += e * e;
+        inner += p * e;
+    }
+    for (int c = 0; c < C; ++c) {
+        double p = exp(z[c] - m) / s, e = p - (c == y ? 1.0 : 0.0);
+        dz[c] = 2.0 * p * (e - inner) * scale;
+    }
+    return f;
+}
+
 /* Fully connected network dims[0] -> dims[1] -> ... -> dims[L], ReLU after every layer
  * but the last, mean cross-entropy over the B samples.  params / grad: per layer
  * W[out][in] then bias[out].  x: [B][dims[0]], y: [B]. */
+void orc_grad_mlp_loss(int L, const int32_t *dims, int B, const float *params, const float *x,
+                       const int32_t *y, int loss_kind /* 0 cross-entropy, 1 MSE on softmax outputs */,
+                       float *grad, double *loss_out, double *margin /* nullable */);
+
 void orc_grad_mlp(int L, const int32_t *dims, int B, const float *params, const float *x,
                   const int32_t *y, float *grad, double *loss_out, double *margin /* nullable */)
+{
+    orc_grad_mlp_loss(L, dims, B, params, x, y, 0, grad, loss_out, margin);
+}
+
+void orc_grad_mlp_loss(int L, const int32_t *dims, int B, const float *params, const float *x,
+                       const int32_t *y, int loss_kind, float *grad, double *loss_out, double *margin)
 {
     if (margin) margin[0] = margin[1] = INFINITY;
     size_t total = 0, maxw = 0;
@@ -323,7 +357,8 @@ void orc_grad_mlp(int L, const int32_t *dims, int B, const float *params, const 
             }
             off += (size_t)out * in + out;
         }
-        loss += softmax_xent(dims[L], z[L - 1], y[s], 1.0 / (double)B, dz);
+        loss += loss_kind == 1 ? softmax_mse(dims[L], z[L - 1], y[s], 1.0 / (double)B, dz)
+                               : softmax_xent(dims[L], z[L - 1], y[s], 1.0 / (double)B, dz);
         for (int l = L - 1; l >= 0; --l) {
             int in = dims[l], out = dims[l + 1];
             off -= (size_t)out * in + out;
@@ -529,7 +564,8 @@ void orc_grad_cnn(const int32_t *shape, int B, const float *params, const float 
 
 /* Gradients of all workers: worker i uses row i of params [N][ld], its own batch, and
  * writes row i of grad [N][ld] (padding columns zeroed).  kind 0: fully connected
- * (desc = {L, dims[0..L]}), kind 1: convolutional (desc = shape[8]). */
+ * (desc = {L, dims[0..L]}), kind 1: convolutional (desc = shape[8]), kind 2: fully connected
+ * with the MSE-on-softmax loss. */
 void orc_grad_all(int kind, const int32_t *desc, int N, int64_t d, int64_t ld, int B,
                   int64_t in_dim, const float *params, const float *x, const int32_t *y,
                   float *grad, double *loss /* N, nullable */, double *margin /* N x 2, nullable */)
@@ -539,9 +575,9 @@ void orc_grad_all(int kind, const int32_t *desc, int N, int64_t d, int64_t ld, i
         float *gi = grad + (size_t)i * ld;
         double li = 0.0;
         double *mi = margin ? margin + 2 * i : NULL;
-        if (kind == 0)
-            orc_grad_mlp(desc[0], desc + 1, B, params + (size_t)i * ld,
-                         x + (size_t)i * B * in_dim, y + (size_t)i * B, gi, &li, mi);
+        if (kind == 0 || kind == 2)
+            orc_grad_mlp_loss(desc[0], desc + 1, B, params + (size_t)i * ld,
+                              x + (size_t)i * B * in_dim, y + (size_t)i * B, kind == 2, gi, &li, mi);
         else
             orc_grad_cnn(desc, B, params + (size_t)i * ld, x + (size_t)i * B * in_dim,
                          y + (size_t)i * B, gi, &li, mi);

@@ -217,3 +217,57 @@ def test_decision_margin_diagnostic(orc):
             smallest = min(smallest, np.abs(z).min())
             a = np.maximum(z, 0)
         assert abs(margin[i, 1] - smallest) < 1e-12 and np.isinf(margin[i, 0])
+
+
+def mlp_mse_loss(dims, params, x, y):
+    a, off = x.astype(np.float64), 0
+    for l in range(len(dims) - 1):
+        i, o = dims[l], dims[l + 1]
+        W = params[off:off + o * i].reshape(o, i); off += o * i
+        b = params[off:off + o]; off += o
+        a = a @ W.T + b
+        if l + 2 < len(dims):
+            a = np.maximum(a, 0)
+    z = a - a.max(1, keepdims=True)
+    p = np.exp(z) / np.exp(z).sum(1, keepdims=True)
+    p[np.arange(len(y)), y] -= 1.0
+    return (p ** 2).sum(1).mean()
+
+
+@pytest.mark.parametrize("dims", [[12, 5], [9, 7, 4], [6, 8, 5, 3]])
+def test_mlp_mse_finite_differences(orc, dims):
+    """MSE on the softmax outputs (Appendix B, 2NN): loss value against an independent NumPy
+    forward pass, gradient against central differences of it."""
+    g = np.random.default_rng(89)
+    d = sum(dims[l + 1] * (dims[l] + 1) for l in range(len(dims) - 1))
+    params = (g.standard_normal(d) * 0.5).astype(np.float32)
+    x = g.standard_normal((6, dims[0])).astype(np.float32)
+    y = g.integers(0, dims[-1], 6).astype(np.int32)
+    grad, loss = orc.grad_mlp(dims, params, x, y, loss_kind="mse")
+    assert abs(loss - mlp_mse_loss(dims, params.astype(np.float64), x, y)) < 1e-12
+    fd_check(lambda p: mlp_mse_loss(dims, p, x, y), params, grad, 200, g)
+
+
+def test_2nn_mse_matches_autograd(orc):
+    """The paper's 2NN (Appendix B, Table 1: 256-256-256-10, softmax outputs, MSE loss)."""
+    dims = [256, 256, 256, 10]
+    g = np.random.default_rng(97)
+    desc = {"kind": "mlp", "dims": dims}
+    params = inputs.init_params(desc, 1, inputs.param_count(desc), g)[0]
+    x = g.standard_normal((64, 256)).astype(np.float32)
+    y = g.integers(0, 10, 64).astype(np.int32)
+    grad, loss = orc.grad_mlp(dims, params, x, y, loss_kind="mse")
+    p = torch.tensor(params, dtype=torch.float64, requires_grad=True)
+    a, off = torch.tensor(x, dtype=torch.float64), 0
+    for l in range(3):
+        i, o = dims[l], dims[l + 1]
+        W = p[off:off + o * i].view(o, i); off += o * i
+        b = p[off:off + o]; off += o
+        a = F.linear(a, W, b)
+        if l < 2:
+            a = F.relu(a)
+    target = F.one_hot(torch.tensor(y, dtype=torch.long), 10).to(torch.float64)
+    l = F.mse_loss(F.softmax(a, 1), target, reduction="sum") / len(y)
+    l.backward()
+    assert abs(loss - float(l.detach())) < 1e-12
+    assert np.allclose(grad, p.grad.numpy(), rtol=1e-6, atol=1e-10)
