@@ -74,10 +74,18 @@ enum {
                            dims = {C0, H, W, C1, C2, K, F, classes} */
 };
 
+/* Loss on top of the model's outputs. */
+enum {
+    DBW_LOSS_XENT = 0, /* softmax cross-entropy (Section 5) */
+    DBW_LOSS_MSE = 1   /* squared error of the softmax outputs against the one-hot label, summed
+                          over classes (the 2NN of Appendix B); DBW_MODEL_MLP only */
+};
+
 typedef struct {
     int32_t kind;     /* DBW_MODEL_* */
     int32_t batch;    /* samples per worker per round (|C_j(k)| of Section 2.1) */
     int32_t n_layers; /* MLP only */
+    int32_t loss;     /* DBW_LOSS_*; the mean over the batch is taken */
     int32_t dims[9];
 } dbw_model;
 

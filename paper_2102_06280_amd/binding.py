@@ -20,6 +20,7 @@ OK, ERR_NULL, ERR_INVALID, ERR_GRAPH, ERR_ALIAS, ERR_STATE, ERR_ALLOC, ERR_HIP, 
 ORDER_CTA, ORDER_ATC = 0, 1
 MIX_AUTO, MIX_CSR, MIX_DENSE = 0, 1, 2
 MODEL_NONE, MODEL_MLP, MODEL_CNN = 0, 1, 2
+LOSS_XENT, LOSS_MSE = 0, 1
 
 EXPORTS = ["dbw_create", "dbw_select", "dbw_dtur_b", "dbw_dtur_reset", "dbw_get_selection",
            "dbw_get_weights", "dbw_round_time", "dbw_round", "dbw_grad", "dbw_check", "dbw_get_links", "dbw_mix_path",
@@ -27,7 +28,8 @@ EXPORTS = ["dbw_create", "dbw_select", "dbw_dtur_b", "dbw_dtur_reset", "dbw_get_
 
 
 class dbw_model(C.Structure):
-    _fields_ = [("kind", C.c_int32), ("batch", C.c_int32), ("n_layers", C.c_int32), ("dims", C.c_int32 * 9)]
+    _fields_ = [("kind", C.c_int32), ("batch", C.c_int32), ("n_layers", C.c_int32), ("loss", C.c_int32),
+                ("dims", C.c_int32 * 9)]
 
 
 class dbw_opts(C.Structure):
@@ -91,9 +93,9 @@ def _stream():
     return torch.cuda.current_stream().cuda_stream
 
 
-def make_model(kind: int = MODEL_NONE, batch: int = 0, dims=()) -> dbw_model:
+def make_model(kind: int = MODEL_NONE, batch: int = 0, dims=(), loss: int = LOSS_XENT) -> dbw_model:
     m = dbw_model()
-    m.kind, m.batch = kind, batch
+    m.kind, m.batch, m.loss = kind, batch, loss
     dims = list(dims)
     m.n_layers = len(dims) - 1 if kind == MODEL_MLP else 0
     for k, v in enumerate(dims):

@@ -164,7 +164,9 @@ int dbw_create(dbw_ctx **out, int32_t N, int64_t d, const int32_t *rowptr, const
     }
     if (c->model.kind != DBW_MODEL_NONE) {
         const int64_t want = model_param_count(c->model, &c->in_dim);
-        if (want != d || c->model.batch < 1) {
+        const bool loss_ok = c->model.loss == DBW_LOSS_XENT ||
+                             (c->model.loss == DBW_LOSS_MSE && c->model.kind == DBW_MODEL_MLP);
+        if (want != d || c->model.batch < 1 || !loss_ok) {
             delete c;
             return DBW_ERR_INVALID;
         }

@@ -87,7 +87,7 @@ int dbw_launch_mix_dense(dbw_ctx *c, const float *x, const float *g, float *out,
 // act_stride floats per worker (see dbw_fc_scratch_per_worker); `din`, if not null,
 // receives the gradient with respect to the input.
 struct dbw_fc_args {
-    int L, B;
+    int L, B, loss_kind;
     const int32_t *dims;
     const float *params;
     float *grads;

@@ -16,9 +16,11 @@ namespace {
 using bgemm::Dense;
 using bgemm::Epilogue;
 
-// One workgroup per worker: softmax, mean cross-entropy loss and its gradient with respect
-// to the logits, dz = (softmax(z) - onehot(y)) / B.
-__global__ __launch_bounds__(256) void softmax_xent_kernel(
+// One workgroup per worker: softmax, mean loss over the batch and its gradient with respect
+// to the logits.  Cross-entropy: dz = (p - onehot(y)) / B.  MSE on the softmax outputs
+// (Appendix B, 2NN): f = sum_c (p_c - o_c)^2, dz_k = 2 p_k ((p_k - o_k) - sum_c p_c (p_c - o_c)) / B.
+template <int LOSS>
+__global__ __launch_bounds__(256) void softmax_loss_kernel(
     int B, int C, const float *__restrict__ logits, int64_t stride_logits, const int32_t *__restrict__ y,
     float *__restrict__ dz, int64_t stride_dz, float *__restrict__ loss)
 {
@@ -36,8 +38,23 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(
         for (int c = 0; c < C; ++c) sum += expf(zs[c] - m);
         const int label = y[(int64_t)w * B + s];
         const float inv = 1.0f / sum;
-        for (int c = 0; c < C; ++c) d[(int64_t)s * C + c] = (expf(zs[c] - m) * inv - (c == label ? 1.f : 0.f)) * inv_b;
-        part += logf(sum) + m - zs[label];
+        if (LOSS == DBW_LOSS_XENT) {
+            for (int c = 0; c < C; ++c)
+                d[(int64_t)s * C + c] = (expf(zs[c] - m) * inv - (c == label ? 1.f : 0.f)) * inv_b;
+            part += logf(sum) + m - zs[label];
+        } else {
+            float f = 0.f, inner = 0.f;
+            for (int c = 0; c < C; ++c) {
+                const float p = expf(zs[c] - m) * inv, e = p - (c == label ? 1.f : 0.f);
+                f += e * e;
+                inner += p * e;
+            }
+            for (int c = 0; c < C; ++c) {
+                const float p = expf(zs[c] - m) * inv, e = p - (c == label ? 1.f : 0.f);
+                d[(int64_t)s * C + c] = 2.f * p * (e - inner) * inv_b;
+            }
+            part += f;
+        }
     }
     red[tid] = part;
     __syncthreads();
@@ -164,9 +181,13 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
         DBW_HIP(bgemm::launch<64>(A, Bm, E, B, dims[l], dims[l - 1], N, s));
     }
     {
-        dbw_timer tm(c, "softmax_xent_kernel", s);
-        hipLaunchKernelGGL(softmax_xent_kernel, dim3(N), dim3(256), 0, s, B, dims[L], act + a_off[L], wstride, a.y,
-                           act + dz_off[L], wstride, a.loss);
+        dbw_timer tm(c, "softmax_loss_kernel", s);
+        if (a.loss_kind == DBW_LOSS_MSE)
+            hipLaunchKernelGGL(softmax_loss_kernel<DBW_LOSS_MSE>, dim3(N), dim3(256), 0, s, B, dims[L], act + a_off[L],
+                               wstride, a.y, act + dz_off[L], wstride, a.loss);
+        else
+            hipLaunchKernelGGL(softmax_loss_kernel<DBW_LOSS_XENT>, dim3(N), dim3(256), 0, s, B, dims[L], act + a_off[L],
+                               wstride, a.y, act + dz_off[L], wstride, a.loss);
         DBW_HIP(hipGetLastError());
     }
     // backward
@@ -218,6 +239,7 @@ int dbw_launch_grad_mlp(dbw_ctx *c, const float *params, const float *bx, const 
     a.L = m.n_layers;
     a.dims = m.dims;
     a.B = m.batch;
+    a.loss_kind = m.loss;
     a.params = params;
     a.grads = grads;
     a.param_off = 0;

@@ -121,8 +121,10 @@ def model_dims(model: str):
         return {"kind": "mlp", "dims": [784, 10]}
     if model == "mlp":
         return {"kind": "mlp", "dims": [784, 200, 10]}
-    if model == "2nn":  # Appendix B, Table 1 (inputs already reduced to 256 dims)
-        return {"kind": "mlp", "dims": [256, 256, 256, 10]}
+    if model == "2nn":  # Appendix B, Table 1 (inputs already reduced to 256 dims), MSE loss
+        return {"kind": "mlp", "dims": [256, 256, 256, 10], "loss": "mse"}
+    if model == "lrm":  # Section 5: logistic regression on 256 reduced dimensions, cross-entropy
+        return {"kind": "mlp", "dims": [256, 10]}
     if model == "cnn":
         return {"kind": "cnn", "in": (3, 32, 32), "c1": 32, "c2": 64, "k": 5, "fc": 512, "classes": 10}
     raise ValueError(model)
@@ -188,6 +190,7 @@ class Config:
     backup_arg: int
     x_dist: str = "normal"   # batch input distribution: uniform | normal
     zero_init: bool = False
+    lr_decay: float = 1.0    # lr(k) = lr * lr_decay ** k (Section 5: 0.95)
 
 
 CONFIGS = {
@@ -197,6 +200,9 @@ CONFIGS = {
     3: Config(3, "er64-cnn", 64, "er", 0.1, "cnn", 2156490, 32, 0.01, 50, "lognormal_slow", "dtur", 0),
     4: Config(4, "reg8x128-consensus", 128, "regular", 8, "none", 11_200_000, 0, 0.05, 20, "exp", "uniform", 4),
     5: Config(5, "complete256-dense", 256, "complete", 0, "none", 1_000_000, 0, 0.05, 20, "exp", "uniform", 128),
+    # the paper's own experiment shapes (Section 5 / Appendix B) on synthetic 256-dimensional inputs
+    6: Config(6, "paper-lrm", 6, "er", 0.5, "lrm", 2570, 1024, 0.2, 20, "lognormal_slow", "dtur", 0, lr_decay=0.95),
+    7: Config(7, "paper-2nn", 10, "er", 0.4, "2nn", 134154, 1024, 1.0, 20, "lognormal_slow", "dtur", 0, lr_decay=0.95),
 }
 
 
@@ -216,7 +222,7 @@ def make_graph(cfg: Config):
 def slow_workers(cfg: Config) -> np.ndarray:
     """Fixed set of slowed-down workers (10 % of N, rounded down), chosen once."""
     g = rng(cfg.cid, P_SLOW)
-    k = int(0.1 * cfg.n)
+    k = max(1, int(0.1 * cfg.n))       # Appendix B: at least one straggler in each iteration
     return np.sort(g.choice(cfg.n, size=k, replace=False)).astype(np.int32)
 
 
@@ -244,6 +250,10 @@ def backup_counts(cfg: Config, rnd: int, rowptr: np.ndarray) -> np.ndarray:
     else:
         raise ValueError("backup counts of this config come from the threshold rule")
     return np.minimum(b, deg).astype(np.int32)
+
+
+def learning_rate(cfg: Config, rnd: int) -> float:
+    return cfg.lr * cfg.lr_decay ** rnd
 
 
 def batch(cfg: Config, rnd: int, workers=None):

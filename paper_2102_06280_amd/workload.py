@@ -27,7 +27,8 @@ class Workload:
         model = None
         if self.desc is not None:
             if self.desc["kind"] == "mlp":
-                model = B.make_model(B.MODEL_MLP, cfg.batch, self.desc["dims"])
+                model = B.make_model(B.MODEL_MLP, cfg.batch, self.desc["dims"],
+                                     B.LOSS_MSE if self.desc.get("loss") == "mse" else B.LOSS_XENT)
             else:
                 c, h, w = self.desc["in"]
                 model = B.make_model(B.MODEL_CNN, cfg.batch, [c, h, w, self.desc["c1"], self.desc["c2"],
@@ -76,7 +77,8 @@ class Workload:
         if self.desc is None:
             B.dbw_round(self.h, src, dst, self.cfg.lr, ext_grads=self.g)
         else:
-            B.dbw_round(self.h, src, dst, self.cfg.lr, batch_x=self.bx[r], batch_y=self.by[r], loss_out=self.loss)
+            B.dbw_round(self.h, src, dst, inputs.learning_rate(self.cfg, r), batch_x=self.bx[r], batch_y=self.by[r],
+                        loss_out=self.loss)
         self.cur ^= 1
         self.k += 1
 
