@@ -91,7 +91,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4, 5, 6, 7])
     ap.add_argument("--order", choices=["cta", "atc"], default="cta")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -201,6 +201,13 @@ def main():
     wl.close()
     del wl
     torch.cuda.empty_cache()
+    # what plain kernels reach on this device, next to the nominal peak: a streaming triad
+    # over three 1 GiB arrays, or register-resident fp32 matrix instructions
+    if roofline["bound"] == "hbm":
+        roofline["achievable"] = B.dbw_calibrate(B.CAL_HBM_TRIAD, 1 << 30, 10)
+    else:
+        roofline["achievable"] = B.dbw_calibrate(B.CAL_MFMA_FP32, 4096, 5)
+    roofline["frac_of_achievable"] = roofline["achieved"] / roofline["achievable"]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config, rowptr, colidx)
     print(json.dumps(out))

@@ -114,6 +114,21 @@ def round_(rowptr, colidx, mask, p, x, g, lr, order=0, d=None):
     return out
 
 
+def round_eta(rowptr, colidx, mask, p, x, g, eta, order=0, d=None):
+    """round_ with a learning rate per worker: eta [N] fp32."""
+    rowptr, colidx, p = _i32(rowptr), _i32(colidx), _i32(p)
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    x, g, eta = _f32(x), _f32(g), _f32(eta)
+    n, ld = x.shape
+    assert g.shape == x.shape and eta.shape == (n,)
+    d = ld if d is None else d
+    out = np.zeros_like(x)
+    lib().orc_round_eta(n, C.c_int64(d), C.c_int64(ld), _p(rowptr, C.c_int32), _p(colidx, C.c_int32),
+                        _p(mask, C.c_uint8), _p(p, C.c_int32), _p(x, C.c_float), _p(g, C.c_float),
+                        _p(eta, C.c_float), int(order), _p(out, C.c_float))
+    return out
+
+
 def spanning_tree(rowptr, colidx):
     rowptr, colidx = _i32(rowptr), _i32(colidx)
     n = rowptr.size - 1

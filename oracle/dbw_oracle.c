@@ -17,6 +17,7 @@
  *                      with the gradient taken at the pre-average point) and Section 2.2,
  *                      the local update followed by the partial consensus update (local
  *                      step first, then average the stepped parameters).
+ *   orc_round_eta      the same with a learning rate per worker (eta_j(k), Sections 2.1, 2.2).
  *   orc_spanning_tree  Section 4.1: the link set P that connects all nodes, length d.
  *   orc_dtur           Section 4.1: threshold rule and the d-iteration procedure (Alg. 2).
  *   orc_grad_mlp       Section 2.1, the mini-batch stochastic gradient, for fully connected models
@@ -182,6 +183,43 @@ void orc_round(int N, int64_t d, int64_t ld, const int32_t *rowptr, const int32_
                     }
             }
             oi[c] = (float)acc;
+        }
+    }
+    free(we);
+    free(ws);
+}
+
+/* The same round with a learning rate of its own for every worker, eta_j(k) of Section 2.1
+ * and of the diagonal matrix eta(k) of Section 2.2.  Order 0: worker i corrects its average
+ * with eta_i g_i.  Order 1: worker j steps with eta_j g_j before anybody averages. */
+void orc_round_eta(int N, int64_t d, int64_t ld, const int32_t *rowptr, const int32_t *colidx,
+                   const uint8_t *mask, const int32_t *p, const float *x, const float *g,
+                   const float *eta, int order, float *out)
+{
+    int nnz = rowptr[N];
+    double *we = (double *)malloc(sizeof(double) * (size_t)(nnz > 0 ? nnz : 1));
+    double *ws = (double *)malloc(sizeof(double) * (size_t)N);
+    orc_weights(N, rowptr, colidx, mask, p, we, ws);
+#pragma omp parallel for schedule(static) num_threads(orc_threads)
+    for (int i = 0; i < N; ++i) {
+        for (int64_t c = 0; c < d; ++c) {
+            size_t own = (size_t)i * ld + c;
+            double acc;
+            if (order == 0) {
+                acc = ws[i] * (double)x[own];
+                for (int e = rowptr[i]; e < rowptr[i + 1]; ++e)
+                    if (mask[e]) acc += we[e] * (double)x[(size_t)colidx[e] * ld + c];
+                acc -= (double)eta[i] * (double)g[own];
+            } else {
+                acc = ws[i] * ((double)x[own] - (double)eta[i] * (double)g[own]);
+                for (int e = rowptr[i]; e < rowptr[i + 1]; ++e)
+                    if (mask[e]) {
+                        int j = colidx[e];
+                        size_t o = (size_t)j * ld + c;
+                        acc += we[e] * ((double)x[o] - (double)eta[j] * (double)g[o]);
+                    }
+            }
+            out[own] = (float)acc;
         }
     }
     free(we);

@@ -21,10 +21,11 @@ ORDER_CTA, ORDER_ATC = 0, 1
 MIX_AUTO, MIX_CSR, MIX_DENSE = 0, 1, 2
 MODEL_NONE, MODEL_MLP, MODEL_CNN = 0, 1, 2
 LOSS_XENT, LOSS_MSE = 0, 1
+CAL_HBM_TRIAD, CAL_MFMA_FP32 = 0, 1
 
 EXPORTS = ["dbw_create", "dbw_select", "dbw_dtur_b", "dbw_dtur_reset", "dbw_get_selection",
            "dbw_get_weights", "dbw_round_time", "dbw_round", "dbw_grad", "dbw_check", "dbw_get_links", "dbw_mix_path",
-           "dbw_destroy", "dbw_strerror", "dbw_set_timing", "dbw_get_timing"]
+           "dbw_destroy", "dbw_strerror", "dbw_set_timing", "dbw_get_timing", "dbw_calibrate"]
 
 
 class dbw_model(C.Structure):
@@ -62,6 +63,7 @@ _lib.dbw_mix_path.argtypes = [_vp]
 _lib.dbw_destroy.argtypes = [_vp]
 _lib.dbw_set_timing.argtypes = [_vp, _i32]
 _lib.dbw_get_timing.argtypes = [_vp, C.POINTER(dbw_kernel_time), _i32]
+_lib.dbw_calibrate.argtypes = [_i32, _i64, _i32, C.POINTER(C.c_double), _vp]
 
 
 class DbwError(RuntimeError):
@@ -178,3 +180,11 @@ def dbw_get_timing(h):
     buf = (dbw_kernel_time * 32)()
     n = _chk(_lib.dbw_get_timing(h, buf, 32), "dbw_get_timing")
     return {buf[k].name.decode(): (buf[k].ms_total, buf[k].launches) for k in range(n)}
+
+
+def dbw_calibrate(what: int, size: int, repeats: int = 10) -> float:
+    """Measured ceiling: GB/s (CAL_HBM_TRIAD, size = bytes per array) or TFLOP/s (CAL_MFMA_FP32,
+    size = loop iterations)."""
+    res = C.c_double(0.0)
+    _chk(_lib.dbw_calibrate(what, size, repeats, C.byref(res), _stream()), "dbw_calibrate")
+    return res.value

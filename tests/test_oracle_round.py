@@ -186,3 +186,68 @@ def test_padding_and_column_slices(orc):
     assert not full[:, d:].any()
     part = orc.round_(rowptr, colidx, mask, p, x[:, 10:30], gr[:, 10:30], 0.05, 0)
     assert np.array_equal(full[:, 10:30], part)
+
+
+# ---- a learning rate per worker (eta_j(k) of Sections 2.1 and 2.2)
+
+@pytest.mark.parametrize("order", [0, 1])
+def test_eta_vector_of_equal_entries_is_the_scalar_round(orc, order):
+    g = np.random.default_rng(61)
+    for rowptr, colidx in graphs():
+        n = rowptr.size - 1
+        x = g.standard_normal((n, 7)).astype(np.float32)
+        gr = g.standard_normal((n, 7)).astype(np.float32)
+        t = g.standard_exponential(n).astype(np.float32)
+        b = g.integers(0, np.diff(rowptr) + 1).astype(np.int32)
+        mask, p, _ = orc.select(rowptr, colidx, t, b)
+        a = orc.round_(rowptr, colidx, mask, p, x, gr, np.float32(0.3), order)
+        e = orc.round_eta(rowptr, colidx, mask, p, x, gr, np.full(n, 0.3, np.float32), order)
+        assert np.array_equal(a, e)
+
+
+def test_eta_single_worker_moves_the_right_rows(orc):
+    """With eta zero everywhere but at worker s, the result differs from a gradient-free
+    round by -eta_s g_s in row s alone (average first), or by -P_is eta_s g_s in every row i
+    (local step first): the index that eta carries in either order."""
+    g = np.random.default_rng(62)
+    for rowptr, colidx in graphs():
+        n = rowptr.size - 1
+        x = g.standard_normal((n, 5)).astype(np.float32)
+        gr = g.standard_normal((n, 5)).astype(np.float32)
+        t = g.standard_exponential(n).astype(np.float32)
+        b = g.integers(0, np.diff(rowptr) + 1).astype(np.int32)
+        mask, p, _ = orc.select(rowptr, colidx, t, b)
+        P = orc.dense_P(rowptr, colidx, mask, p)
+        base = orc.round_(rowptr, colidx, mask, p, x, None, 0.0, 0).astype(np.float64)
+        for s in (0, n // 2, n - 1):
+            eta = np.zeros(n, np.float32)
+            eta[s] = 0.7
+            cta = orc.round_eta(rowptr, colidx, mask, p, x, gr, eta, 0)
+            want = base.copy()
+            want[s] -= float(eta[s]) * gr[s].astype(np.float64)
+            assert np.allclose(cta, want, rtol=1e-6, atol=1e-6)
+            atc = orc.round_eta(rowptr, colidx, mask, p, x, gr, eta, 1)
+            want = base - float(eta[s]) * np.outer(P[:, s], gr[s].astype(np.float64))
+            assert np.allclose(atc, want, rtol=1e-6, atol=1e-6)
+
+
+def test_eta_unrolled_recursion_with_diagonal_rates(orc):
+    """Section 2.2: with eta(k) = diag(eta_1(k) .. eta_N(k)) the K-round result is X(0) pushed
+    through the P(k) minus every round's eta(k)-scaled gradients pushed through the later
+    P(k), written with explicit dense products."""
+    g = np.random.default_rng(63)
+    rowptr, colidx = inputs.graph_er(7, 0.5, g)
+    n, d, K = 7, 4, 5
+    deg = np.diff(rowptr)
+    x0 = g.standard_normal((n, d)).astype(np.float32)
+    x = x0
+    want = x0.astype(np.float64)
+    for k in range(K):
+        t = g.standard_exponential(n).astype(np.float32)
+        b = g.integers(0, deg + 1).astype(np.int32)
+        G = g.standard_normal((n, d)).astype(np.float32)
+        eta = g.uniform(0.01, 0.5, n).astype(np.float32)
+        mask, p, _ = orc.select(rowptr, colidx, t, b)
+        x = orc.round_eta(rowptr, colidx, mask, p, x, G, eta, 1)
+        want = orc.dense_P(rowptr, colidx, mask, p) @ (want - np.diag(eta.astype(np.float64)) @ G.astype(np.float64))
+    assert np.allclose(x, want, rtol=1e-6, atol=1e-6)
