@@ -162,6 +162,15 @@ int dbw_get_weights(dbw_ctx *ctx, float *P, void *stream);
 int dbw_round(dbw_ctx *ctx, const float *params_in, float *params_out, const float *batch_x,
               const int32_t *batch_y, const float *ext_grads, float *loss_out, float lr, void *stream);
 
+/* dbw_round with a learning rate of its own for every worker, eta [dev, N] float: eta_j(k) of
+ * Section 2.1 and the diagonal matrix eta(k) of Section 2.2.  Average-then-correct order:
+ * worker i subtracts eta_i g_i from its average; local-step-first order: worker j steps
+ * with eta_j g_j before the averaging.  eta must stay valid until the stream work is done.
+ * Everything else as dbw_round. */
+int dbw_round_eta(dbw_ctx *ctx, const float *params_in, float *params_out, const float *batch_x,
+                  const int32_t *batch_y, const float *ext_grads, float *loss_out, const float *eta,
+                  void *stream);
+
 /* Mini-batch gradients only (the first step of dbw_round), written to grads [dev, N*ld]
  * in columns [0, d).  Needs a model.  Asynchronous. */
 int dbw_grad(dbw_ctx *ctx, const float *params, const float *batch_x, const int32_t *batch_y,

@@ -320,8 +320,9 @@ int dbw_grad(dbw_ctx *c, const float *params, const float *batch_x, const int32_
     return DBW_ERR_STATE;
 }
 
-int dbw_round(dbw_ctx *c, const float *params_in, float *params_out, const float *batch_x,
-              const int32_t *batch_y, const float *ext_grads, float *loss_out, float lr, void *stream)
+static int round_impl(dbw_ctx *c, const float *params_in, float *params_out, const float *batch_x,
+                      const int32_t *batch_y, const float *ext_grads, float *loss_out, float lr, const float *lr_vec,
+                      void *stream)
 {
     if (!c || !params_in || !params_out) return DBW_ERR_NULL;
     if (!c->selected) return DBW_ERR_STATE;
@@ -336,8 +337,21 @@ int dbw_round(dbw_ctx *c, const float *params_in, float *params_out, const float
     } else if (g && overlaps(g, bytes, params_out, bytes)) {
         return DBW_ERR_ALIAS;
     }
-    if (c->mix == DBW_MIX_DENSE) return dbw_launch_mix_dense(c, params_in, g, params_out, lr, s);
-    return dbw_launch_mix_csr(c, params_in, g, params_out, lr, s);
+    if (c->mix == DBW_MIX_DENSE) return dbw_launch_mix_dense(c, params_in, g, params_out, lr, lr_vec, s);
+    return dbw_launch_mix_csr(c, params_in, g, params_out, lr, lr_vec, s);
+}
+
+int dbw_round(dbw_ctx *c, const float *params_in, float *params_out, const float *batch_x,
+              const int32_t *batch_y, const float *ext_grads, float *loss_out, float lr, void *stream)
+{
+    return round_impl(c, params_in, params_out, batch_x, batch_y, ext_grads, loss_out, lr, nullptr, stream);
+}
+
+int dbw_round_eta(dbw_ctx *c, const float *params_in, float *params_out, const float *batch_x,
+                  const int32_t *batch_y, const float *ext_grads, float *loss_out, const float *eta, void *stream)
+{
+    if (!eta) return DBW_ERR_NULL;
+    return round_impl(c, params_in, params_out, batch_x, batch_y, ext_grads, loss_out, 0.f, eta, stream);
 }
 
 int dbw_get_links(dbw_ctx *c, int32_t *edges)

@@ -76,9 +76,23 @@ int dbw_launch_select(dbw_ctx *c, const float *t, const int32_t *b, hipStream_t 
 int dbw_launch_round_time(dbw_ctx *c, float *out, hipStream_t s);
 int dbw_launch_dtur(dbw_ctx *c, const float *t, int32_t *b_out, float *theta_out, hipStream_t s);
 // mix_csr.hip
-int dbw_launch_mix_csr(dbw_ctx *c, const float *x, const float *g, float *out, float lr, hipStream_t s);
+// Learning rate of a round as the mixing kernels see it: one value for all workers, or
+// eta_j per worker read from device memory (Section 2.1).
+struct dbw_lr_scalar {
+    float v;
+    __device__ __forceinline__ float at(int) const { return v; }
+};
+struct dbw_lr_vector {
+    const float *v;
+    __device__ __forceinline__ float at(int j) const { return v[j]; }
+};
+
+// lr_vec (device, N) overrides lr when it is not null.
+int dbw_launch_mix_csr(dbw_ctx *c, const float *x, const float *g, float *out, float lr, const float *lr_vec,
+                       hipStream_t s);
 // mix_dense.hip
-int dbw_launch_mix_dense(dbw_ctx *c, const float *x, const float *g, float *out, float lr, hipStream_t s);
+int dbw_launch_mix_dense(dbw_ctx *c, const float *x, const float *g, float *out, float lr, const float *lr_vec,
+                         hipStream_t s);
 // grad_mlp.hip / grad_cnn.hip
 // A stack of fully connected layers dims[0] -> ... -> dims[L] with ReLU between layers and
 // softmax cross-entropy on top, for all workers.  Parameters of the stack start at float

@@ -16,21 +16,21 @@ namespace {
 using bgemm::Dense;
 using bgemm::Epilogue;
 
-// One workgroup per worker: softmax, mean loss over the batch and its gradient with respect
+// One workgroup (256 or 1024 threads) per worker: softmax, mean loss over the batch and its gradient with respect
 // to the logits.  Cross-entropy: dz = (p - onehot(y)) / B.  MSE on the softmax outputs
 // (Appendix B, 2NN): f = sum_c (p_c - o_c)^2, dz_k = 2 p_k ((p_k - o_k) - sum_c p_c (p_c - o_c)) / B.
 template <int LOSS>
-__global__ __launch_bounds__(256) void softmax_loss_kernel(
+__global__ __launch_bounds__(1024) void softmax_loss_kernel(
     int B, int C, const float *__restrict__ logits, int64_t stride_logits, const int32_t *__restrict__ y,
     float *__restrict__ dz, int64_t stride_dz, float *__restrict__ loss)
 {
-    __shared__ float red[256];
-    const int w = blockIdx.x, tid = threadIdx.x;
+    __shared__ float red[1024];
+    const int w = blockIdx.x, tid = threadIdx.x, nt = blockDim.x;
     const float *z = logits + w * stride_logits;
     float *d = dz + w * stride_dz;
     const float inv_b = 1.0f / (float)B;
     float part = 0.f;
-    for (int s = tid; s < B; s += 256) {
+    for (int s = tid; s < B; s += nt) {
         const float *zs = z + (int64_t)s * C;
         float m = zs[0];
         for (int c = 1; c < C; ++c) m = fmaxf(m, zs[c]);
@@ -58,23 +58,41 @@ __global__ __launch_bounds__(256) void softmax_loss_kernel(
     }
     red[tid] = part;
     __syncthreads();
-    for (int o = 128; o > 0; o >>= 1) {
+    for (int o = nt / 2; o > 0; o >>= 1) {
         if (tid < o) red[tid] += red[tid + o];
         __syncthreads();
     }
     if (tid == 0 && loss) loss[w] = red[0] * inv_b;
 }
 
-// Bias gradient: db[o] = sum over the batch of dz[s][o].  grid = (ceil(C / 256), workers).
+// Bias gradient: db[o] = sum over the batch of dz[s][o].  grid = (ceil(C / 32), workers); a
+// workgroup covers 32 columns with 8 groups of threads that stride over the batch, four
+// independent partial sums each, combined in a fixed order.
 __global__ __launch_bounds__(256) void colsum_kernel(int B, int C, const float *__restrict__ dz, int64_t stride_dz,
                                                      float *__restrict__ db, int64_t stride_db)
 {
-    const int w = blockIdx.y, o = blockIdx.x * 256 + threadIdx.x;
-    if (o >= C) return;
+    __shared__ float part[8][32];
+    const int w = blockIdx.y, cl = threadIdx.x & 31, rg = threadIdx.x >> 5;
+    const int o = blockIdx.x * 32 + cl;
     const float *d = dz + w * stride_dz;
-    float s = 0.f;
-    for (int b = 0; b < B; ++b) s += d[(int64_t)b * C + o];
-    db[w * stride_db + o] = s;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    if (o < C) {
+        int b = rg;
+        for (; b + 24 < B; b += 32) {
+            s0 += d[(int64_t)b * C + o];
+            s1 += d[(int64_t)(b + 8) * C + o];
+            s2 += d[(int64_t)(b + 16) * C + o];
+            s3 += d[(int64_t)(b + 24) * C + o];
+        }
+        for (; b < B; b += 8) s0 += d[(int64_t)b * C + o];
+    }
+    part[rg][cl] = (s0 + s1) + (s2 + s3);
+    __syncthreads();
+    if (rg == 0 && o < C) {
+        float s = part[0][cl];
+        for (int r = 1; r < 8; ++r) s += part[r][cl];
+        db[w * stride_db + o] = s;
+    }
 }
 
 // Partial sums of a split-k forward GEMM: part[worker][split][m][n].
@@ -181,13 +199,14 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
         DBW_HIP(bgemm::launch<64>(A, Bm, E, B, dims[l], dims[l - 1], N, s));
     }
     {
+        const int threads = B > 256 ? 1024 : 256;
         dbw_timer tm(c, "softmax_loss_kernel", s);
         if (a.loss_kind == DBW_LOSS_MSE)
-            hipLaunchKernelGGL(softmax_loss_kernel<DBW_LOSS_MSE>, dim3(N), dim3(256), 0, s, B, dims[L], act + a_off[L],
-                               wstride, a.y, act + dz_off[L], wstride, a.loss);
+            hipLaunchKernelGGL(softmax_loss_kernel<DBW_LOSS_MSE>, dim3(N), dim3(threads), 0, s, B, dims[L],
+                               act + a_off[L], wstride, a.y, act + dz_off[L], wstride, a.loss);
         else
-            hipLaunchKernelGGL(softmax_loss_kernel<DBW_LOSS_XENT>, dim3(N), dim3(256), 0, s, B, dims[L], act + a_off[L],
-                               wstride, a.y, act + dz_off[L], wstride, a.loss);
+            hipLaunchKernelGGL(softmax_loss_kernel<DBW_LOSS_XENT>, dim3(N), dim3(threads), 0, s, B, dims[L],
+                               act + a_off[L], wstride, a.y, act + dz_off[L], wstride, a.loss);
         DBW_HIP(hipGetLastError());
     }
     // backward
@@ -204,7 +223,7 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
         }
         {
             dbw_timer tm(c, "colsum_kernel", s);
-            hipLaunchKernelGGL(colsum_kernel, dim3((dims[l] + 255) / 256, N), dim3(256), 0, s, B, dims[l],
+            hipLaunchKernelGGL(colsum_kernel, dim3((dims[l] + 31) / 32, N), dim3(256), 0, s, B, dims[l],
                                act + dz_off[l], wstride, grads + b_off[l], c->ld);
             DBW_HIP(hipGetLastError());
         }

@@ -63,12 +63,12 @@ __device__ __forceinline__ void store_stream(float4 *p, float4 v)
 // Persistent workgroup, tiles of N rows x TC4 float4 columns (N * TC4 <= LDS_TILE).
 // Element f of a tile is (row f / TC4, column f % TC4); thread `tid` owns elements
 // tid + u * LDS_THREADS, the same (row, column offset) in every tile.
-template <int ORDER, bool HAS_G, int TC4>
+template <int ORDER, bool HAS_G, int TC4, class LR>
 __global__ __launch_bounds__(LDS_THREADS) void mix_lds_tiles(
     int N, int nnz, int64_t n_vec, int64_t ld4, int64_t n_tiles, const int32_t *__restrict__ rowptr,
     const int32_t *__restrict__ p, const int32_t *__restrict__ sel_idx, const float *__restrict__ sel_w,
     const float *__restrict__ self_w, const float4 *__restrict__ x, const float4 *__restrict__ g,
-    float4 *__restrict__ out, float lr)
+    float4 *__restrict__ out, LR lr)
 {
     extern __shared__ float4 sm[];
     float4 *tiles = sm;                                  // 2 * LDS_TILE
@@ -82,7 +82,7 @@ __global__ __launch_bounds__(LDS_THREADS) void mix_lds_tiles(
         s_w[e] = sel_w[e];
     }
     int beg[LDS_PER], cnt[LDS_PER], col[LDS_PER];
-    float ws[LDS_PER];
+    float ws[LDS_PER], eta[LDS_PER];
     int64_t rowoff[LDS_PER];
 #pragma unroll
     for (int u = 0; u < LDS_PER; ++u) {
@@ -92,6 +92,7 @@ __global__ __launch_bounds__(LDS_THREADS) void mix_lds_tiles(
         beg[u] = rowptr[r];
         cnt[u] = p[r];
         ws[u] = self_w[r];
+        eta[u] = lr.at(r);
         rowoff[u] = (int64_t)r * ld4;
     }
 
@@ -105,7 +106,7 @@ __global__ __launch_bounds__(LDS_THREADS) void mix_lds_tiles(
             if (col[u] < TC4 && c < n_vec) {
                 xs[u] = load_stream(&x[rowoff[u] + c]);
                 if (HAS_G) gs[u] = load_stream(&g[rowoff[u] + c]);
-                if (ORDER == DBW_ORDER_ATC && HAS_G) xs[u] = fma4(-lr, gs[u], xs[u]);
+                if (ORDER == DBW_ORDER_ATC && HAS_G) xs[u] = fma4(-eta[u], gs[u], xs[u]);
             }
         }
     };
@@ -134,7 +135,7 @@ __global__ __launch_bounds__(LDS_THREADS) void mix_lds_tiles(
                 float4 acc = make_float4(ws[u] * v.x, ws[u] * v.y, ws[u] * v.z, ws[u] * v.w);
                 for (int k = 0; k < cnt[u]; ++k)
                     acc = fma4(s_w[beg[u] + k], tl[s_idx[beg[u] + k] * TC4 + col[u]], acc);
-                if (ORDER == DBW_ORDER_CTA && HAS_G) acc = fma4(-lr, gc[u], acc);
+                if (ORDER == DBW_ORDER_CTA && HAS_G) acc = fma4(-eta[u], gc[u], acc);
                 store_stream(&out[rowoff[u] + c], acc);
             }
         }
@@ -148,13 +149,13 @@ __global__ __launch_bounds__(LDS_THREADS) void mix_lds_tiles(
 }
 
 // One workgroup = one worker x one chunk of MIX_THREADS*UNROLL float4 columns.
-template <int ORDER, bool HAS_G, int UNROLL>
+template <int ORDER, bool HAS_G, int UNROLL, class LR>
 __global__ __launch_bounds__(MIX_THREADS) void mix_csr_vec4(
     int N, int64_t n_vec /* float4 columns per row */, int64_t ld4 /* row stride in float4 */,
     int n_chunks, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ p,
     const int32_t *__restrict__ sel_idx, const float *__restrict__ sel_w,
     const float *__restrict__ self_w, const float4 *__restrict__ x, const float4 *__restrict__ g,
-    float4 *__restrict__ out, float lr)
+    float4 *__restrict__ out, LR lr)
 {
     const int64_t L = blockIdx.x;
     const int xcd = (int)(L % MIX_XCDS);
@@ -164,7 +165,7 @@ __global__ __launch_bounds__(MIX_THREADS) void mix_csr_vec4(
     if (chunk >= n_chunks) return;
 
     const int beg = rowptr[i], cnt = p[i];
-    const float ws = self_w[i];
+    const float ws = self_w[i], eta_i = lr.at(i);
     const int64_t c0 = chunk * (int64_t)(MIX_THREADS * UNROLL) + threadIdx.x;
     const float4 *xi = x + (int64_t)i * ld4;
 
@@ -177,20 +178,20 @@ __global__ __launch_bounds__(MIX_THREADS) void mix_csr_vec4(
         if (c < n_vec) {
             float4 v = xi[c];
             if (HAS_G) gv[u] = load_stream(&g[(int64_t)i * ld4 + c]);
-            if (ORDER == DBW_ORDER_ATC && HAS_G) v = fma4(-lr, gv[u], v);
+            if (ORDER == DBW_ORDER_ATC && HAS_G) v = fma4(-eta_i, gv[u], v);
             acc[u] = make_float4(ws * v.x, ws * v.y, ws * v.z, ws * v.w);
         }
     }
     for (int k = 0; k < cnt; ++k) {
         const int j = sel_idx[beg + k];
-        const float w = sel_w[beg + k];
+        const float w = sel_w[beg + k], eta_j = lr.at(j);
         const float4 *xj = x + (int64_t)j * ld4;
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             const int64_t c = c0 + (int64_t)u * MIX_THREADS;
             if (c < n_vec) {
                 float4 v = xj[c];
-                if (ORDER == DBW_ORDER_ATC && HAS_G) v = fma4(-lr, g[(int64_t)j * ld4 + c], v);
+                if (ORDER == DBW_ORDER_ATC && HAS_G) v = fma4(-eta_j, g[(int64_t)j * ld4 + c], v);
                 acc[u] = fma4(w, v, acc[u]);
             }
         }
@@ -200,7 +201,7 @@ __global__ __launch_bounds__(MIX_THREADS) void mix_csr_vec4(
         const int64_t c = c0 + (int64_t)u * MIX_THREADS;
         if (c < n_vec) {
             float4 r = acc[u];
-            if (ORDER == DBW_ORDER_CTA && HAS_G) r = fma4(-lr, gv[u], r);
+            if (ORDER == DBW_ORDER_CTA && HAS_G) r = fma4(-eta_i, gv[u], r);
             store_stream(&out[(int64_t)i * ld4 + c], r);
         }
     }
@@ -208,27 +209,27 @@ __global__ __launch_bounds__(MIX_THREADS) void mix_csr_vec4(
 
 // Scalar columns [c_begin, d): the ragged tail of a row, or everything when rows are
 // not 16-byte aligned.  grid = (ceil(cols / 256), N).
-template <int ORDER, bool HAS_G>
+template <int ORDER, bool HAS_G, class LR>
 __global__ __launch_bounds__(256) void mix_csr_scalar(
     int N, int64_t c_begin, int64_t d, int64_t ld, const int32_t *__restrict__ rowptr,
     const int32_t *__restrict__ p, const int32_t *__restrict__ sel_idx,
     const float *__restrict__ sel_w, const float *__restrict__ self_w, const float *__restrict__ x,
-    const float *__restrict__ g, float *__restrict__ out, float lr)
+    const float *__restrict__ g, float *__restrict__ out, LR lr)
 {
     const int i = blockIdx.y;
     const int64_t c = c_begin + (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (c >= d) return;
     const int beg = rowptr[i], cnt = p[i];
     float v = x[(int64_t)i * ld + c];
-    if (ORDER == DBW_ORDER_ATC && HAS_G) v = fmaf(-lr, g[(int64_t)i * ld + c], v);
+    if (ORDER == DBW_ORDER_ATC && HAS_G) v = fmaf(-lr.at(i), g[(int64_t)i * ld + c], v);
     float acc = self_w[i] * v;
     for (int k = 0; k < cnt; ++k) {
         const int j = sel_idx[beg + k];
         float vj = x[(int64_t)j * ld + c];
-        if (ORDER == DBW_ORDER_ATC && HAS_G) vj = fmaf(-lr, g[(int64_t)j * ld + c], vj);
+        if (ORDER == DBW_ORDER_ATC && HAS_G) vj = fmaf(-lr.at(j), g[(int64_t)j * ld + c], vj);
         acc = fmaf(sel_w[beg + k], vj, acc);
     }
-    if (ORDER == DBW_ORDER_CTA && HAS_G) acc = fmaf(-lr, g[(int64_t)i * ld + c], acc);
+    if (ORDER == DBW_ORDER_CTA && HAS_G) acc = fmaf(-lr.at(i), g[(int64_t)i * ld + c], acc);
     out[(int64_t)i * ld + c] = acc;
 }
 
@@ -244,23 +245,23 @@ int device_cus()
     return cus;
 }
 
-template <int ORDER, bool HAS_G>
-int launch_scalar(dbw_ctx *c, const float *x, const float *g, float *out, float lr, int64_t c_begin, hipStream_t s)
+template <int ORDER, bool HAS_G, class LR>
+int launch_scalar(dbw_ctx *c, const float *x, const float *g, float *out, LR lr, int64_t c_begin, hipStream_t s)
 {
     const int64_t cols = c->d - c_begin;
     dbw_timer tm(c, "mix_csr_scalar", s);
-    hipLaunchKernelGGL((mix_csr_scalar<ORDER, HAS_G>), dim3((unsigned)((cols + 255) / 256), c->N), dim3(256), 0, s,
+    hipLaunchKernelGGL((mix_csr_scalar<ORDER, HAS_G, LR>), dim3((unsigned)((cols + 255) / 256), c->N), dim3(256), 0, s,
                        c->N, c_begin, c->d, c->ld, c->rowptr, c->p, c->sel_idx, c->sel_w, c->self_w, x, g, out, lr);
     DBW_HIP(hipGetLastError());
     return DBW_OK;
 }
 
-template <int ORDER, bool HAS_G, int TC4>
-int launch_lds(dbw_ctx *c, const float *x, const float *g, float *out, float lr, int64_t n_vec, hipStream_t s)
+template <int ORDER, bool HAS_G, int TC4, class LR>
+int launch_lds(dbw_ctx *c, const float *x, const float *g, float *out, LR lr, int64_t n_vec, hipStream_t s)
 {
     const int64_t n_tiles = (n_vec + TC4 - 1) / TC4;
     const size_t lds = sizeof(float4) * 2 * LDS_TILE + (size_t)c->nnz * 8;
-    auto kern = mix_lds_tiles<ORDER, HAS_G, TC4>;
+    auto kern = mix_lds_tiles<ORDER, HAS_G, TC4, LR>;
     static bool attr_set = false;                      // per instantiation
     if (!attr_set) {
         DBW_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
@@ -275,8 +276,8 @@ int launch_lds(dbw_ctx *c, const float *x, const float *g, float *out, float lr,
     return DBW_OK;
 }
 
-template <int ORDER, bool HAS_G>
-int launch(dbw_ctx *c, const float *x, const float *g, float *out, float lr, hipStream_t s)
+template <int ORDER, bool HAS_G, class LR>
+int launch(dbw_ctx *c, const float *x, const float *g, float *out, LR lr, hipStream_t s)
 {
     constexpr int UNROLL = 2;
     const bool aligned = (c->ld % 4 == 0) && ((uintptr_t)x % 16 == 0) && ((uintptr_t)out % 16 == 0) &&
@@ -290,12 +291,12 @@ int launch(dbw_ctx *c, const float *x, const float *g, float *out, float lr, hip
         int rc = DBW_OK;
         if (use_lds) {
             switch (tc4) {
-            case 256: rc = launch_lds<ORDER, HAS_G, 256>(c, x, g, out, lr, n_vec, s); break;
-            case 128: rc = launch_lds<ORDER, HAS_G, 128>(c, x, g, out, lr, n_vec, s); break;
-            case 64: rc = launch_lds<ORDER, HAS_G, 64>(c, x, g, out, lr, n_vec, s); break;
-            case 32: rc = launch_lds<ORDER, HAS_G, 32>(c, x, g, out, lr, n_vec, s); break;
-            case 16: rc = launch_lds<ORDER, HAS_G, 16>(c, x, g, out, lr, n_vec, s); break;
-            default: rc = launch_lds<ORDER, HAS_G, 8>(c, x, g, out, lr, n_vec, s); break;
+            case 256: rc = launch_lds<ORDER, HAS_G, 256, LR>(c, x, g, out, lr, n_vec, s); break;
+            case 128: rc = launch_lds<ORDER, HAS_G, 128, LR>(c, x, g, out, lr, n_vec, s); break;
+            case 64: rc = launch_lds<ORDER, HAS_G, 64, LR>(c, x, g, out, lr, n_vec, s); break;
+            case 32: rc = launch_lds<ORDER, HAS_G, 32, LR>(c, x, g, out, lr, n_vec, s); break;
+            case 16: rc = launch_lds<ORDER, HAS_G, 16, LR>(c, x, g, out, lr, n_vec, s); break;
+            default: rc = launch_lds<ORDER, HAS_G, 8, LR>(c, x, g, out, lr, n_vec, s); break;
             }
             if (rc != DBW_OK) return rc;
         } else {
@@ -305,30 +306,40 @@ int launch(dbw_ctx *c, const float *x, const float *g, float *out, float lr, hip
             const int64_t blocks = per_xcd * MIX_XCDS * c->N;
             if (n_chunks > INT32_MAX || blocks > INT32_MAX) return DBW_ERR_UNSUPPORTED;
             dbw_timer tm(c, "mix_csr_vec4", s);
-            hipLaunchKernelGGL((mix_csr_vec4<ORDER, HAS_G, UNROLL>), dim3((unsigned)blocks), dim3(MIX_THREADS), 0, s,
+            hipLaunchKernelGGL((mix_csr_vec4<ORDER, HAS_G, UNROLL, LR>), dim3((unsigned)blocks), dim3(MIX_THREADS), 0, s,
                                c->N, n_vec, c->ld / 4, (int)n_chunks, c->rowptr, c->p, c->sel_idx, c->sel_w,
                                c->self_w, (const float4 *)x, (const float4 *)g, (float4 *)out, lr);
             DBW_HIP(hipGetLastError());
         }
     }
-    if (n_vec * 4 < c->d) return launch_scalar<ORDER, HAS_G>(c, x, g, out, lr, n_vec * 4, s);
+    if (n_vec * 4 < c->d) return launch_scalar<ORDER, HAS_G, LR>(c, x, g, out, lr, n_vec * 4, s);
     return DBW_OK;
 }
 
 }  // namespace
 
-int dbw_launch_mix_csr(dbw_ctx *c, const float *x, const float *g, float *out, float lr, hipStream_t s)
+int dbw_launch_mix_csr(dbw_ctx *c, const float *x, const float *g, float *out, float lr, const float *lr_vec,
+                       hipStream_t s)
 {
-    if (g == nullptr) return launch<DBW_ORDER_CTA, false>(c, x, g, out, lr, s);
-    if (c->order == DBW_ORDER_ATC) return launch<DBW_ORDER_ATC, true>(c, x, g, out, lr, s);
-    return launch<DBW_ORDER_CTA, true>(c, x, g, out, lr, s);
+    if (g == nullptr) return launch<DBW_ORDER_CTA, false>(c, x, g, out, dbw_lr_scalar{0.f}, s);
+    if (lr_vec) {
+        if (c->order == DBW_ORDER_ATC) return launch<DBW_ORDER_ATC, true>(c, x, g, out, dbw_lr_vector{lr_vec}, s);
+        return launch<DBW_ORDER_CTA, true>(c, x, g, out, dbw_lr_vector{lr_vec}, s);
+    }
+    if (c->order == DBW_ORDER_ATC) return launch<DBW_ORDER_ATC, true>(c, x, g, out, dbw_lr_scalar{lr}, s);
+    return launch<DBW_ORDER_CTA, true>(c, x, g, out, dbw_lr_scalar{lr}, s);
 }
 
 // Scalar evaluation of columns [c_begin, d) only (the ragged tail left by a vector path).
-int dbw_launch_mix_csr_range(dbw_ctx *c, const float *x, const float *g, float *out, float lr, int64_t c_begin,
-                             hipStream_t s)
+int dbw_launch_mix_csr_range(dbw_ctx *c, const float *x, const float *g, float *out, float lr, const float *lr_vec,
+                             int64_t c_begin, hipStream_t s)
 {
-    if (g == nullptr) return launch_scalar<DBW_ORDER_CTA, false>(c, x, g, out, lr, c_begin, s);
-    if (c->order == DBW_ORDER_ATC) return launch_scalar<DBW_ORDER_ATC, true>(c, x, g, out, lr, c_begin, s);
-    return launch_scalar<DBW_ORDER_CTA, true>(c, x, g, out, lr, c_begin, s);
+    if (g == nullptr) return launch_scalar<DBW_ORDER_CTA, false>(c, x, g, out, dbw_lr_scalar{0.f}, c_begin, s);
+    if (lr_vec) {
+        if (c->order == DBW_ORDER_ATC)
+            return launch_scalar<DBW_ORDER_ATC, true>(c, x, g, out, dbw_lr_vector{lr_vec}, c_begin, s);
+        return launch_scalar<DBW_ORDER_CTA, true>(c, x, g, out, dbw_lr_vector{lr_vec}, c_begin, s);
+    }
+    if (c->order == DBW_ORDER_ATC) return launch_scalar<DBW_ORDER_ATC, true>(c, x, g, out, dbw_lr_scalar{lr}, c_begin, s);
+    return launch_scalar<DBW_ORDER_CTA, true>(c, x, g, out, dbw_lr_scalar{lr}, c_begin, s);
 }

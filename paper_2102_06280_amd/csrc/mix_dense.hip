@@ -44,11 +44,11 @@ struct dense_cfg {
 };
 
 // FULL: N == NPAD and every tile has all TC columns, so no access needs a guard.
-template <int MB, int ORDER, bool HAS_G, bool FULL>
+template <int MB, int ORDER, bool HAS_G, bool FULL, class LR>
 __global__ __launch_bounds__(DENSE_THREADS) void mix_dense_kernel(
     int N, int64_t n_vec /* float4 columns covered */, int64_t ld4, const float *__restrict__ Wsw,
     const float4 *__restrict__ x, const float4 *__restrict__ g, float *__restrict__ out,
-    const float *__restrict__ gs, float lr, int n_tiles)
+    const float *__restrict__ gs, LR lr, int n_tiles)
 {
     using C = dense_cfg<MB>;
     constexpr bool DMA = FULL && !(ORDER == DBW_ORDER_ATC && HAS_G);
@@ -78,10 +78,11 @@ __global__ __launch_bounds__(DENSE_THREADS) void mix_dense_kernel(
                 v = xb[fetch_lane_off];
                 if (ORDER == DBW_ORDER_ATC && HAS_G) {
                     const float4 gv = (g + (int64_t)k0 * ld4 + tile * (C::TC / 4))[fetch_lane_off];
-                    v.x = fmaf(-lr, gv.x, v.x);
-                    v.y = fmaf(-lr, gv.y, v.y);
-                    v.z = fmaf(-lr, gv.z, v.z);
-                    v.w = fmaf(-lr, gv.w, v.w);
+                    const float eta = lr.at(k);
+                    v.x = fmaf(-eta, gv.x, v.x);
+                    v.y = fmaf(-eta, gv.y, v.y);
+                    v.z = fmaf(-eta, gv.z, v.z);
+                    v.w = fmaf(-eta, gv.w, v.w);
                 }
             }
             stage[ps] = v;
@@ -186,7 +187,10 @@ __global__ __launch_bounds__(DENSE_THREADS) void mix_dense_kernel(
             for (int v = 0; v < 16; ++v) {
                 const int row0 = 32 * rb + 8 * (v / 4) + (v & 3);
                 float r = acc[sp][v];
-                if (ORDER == DBW_ORDER_CTA && HAS_G) r = fmaf(-lr, gv[sp][v], r);
+                if (ORDER == DBW_ORDER_CTA && HAS_G) {
+                    const int row = row0 + 4 * (lane >> 5);
+                    r = fmaf(-lr.at(FULL || row < N ? row : 0), gv[sp][v], r);
+                }
                 float *ob = out + (int64_t)row0 * ld + col0;
                 if (FULL || (row0 + 4 * (lane >> 5) < N && col0 + (lane & 31) < dcols)) ob[epi_lane_off] = r;
             }
@@ -194,8 +198,8 @@ __global__ __launch_bounds__(DENSE_THREADS) void mix_dense_kernel(
     }
 }
 
-template <int MB, int ORDER, bool HAS_G>
-int launch_mb(dbw_ctx *c, const float *x, const float *g, float *out, float lr, int64_t n_vec, hipStream_t s)
+template <int MB, int ORDER, bool HAS_G, class LR>
+int launch_mb(dbw_ctx *c, const float *x, const float *g, float *out, LR lr, int64_t n_vec, hipStream_t s)
 {
     using C = dense_cfg<MB>;
     const int64_t n_tiles = (n_vec * 4 + C::TC - 1) / C::TC;
@@ -212,35 +216,36 @@ int launch_mb(dbw_ctx *c, const float *x, const float *g, float *out, float lr, 
     const bool full = c->N == C::NPAD && (n_vec * 4) % C::TC == 0;
     dbw_timer tm(c, "mix_dense_kernel", s);
     if (full)
-        hipLaunchKernelGGL((mix_dense_kernel<MB, ORDER, HAS_G, true>), dim3((unsigned)grid), dim3(DENSE_THREADS), 0, s,
+        hipLaunchKernelGGL((mix_dense_kernel<MB, ORDER, HAS_G, true, LR>), dim3((unsigned)grid), dim3(DENSE_THREADS), 0, s,
                            c->N, n_vec, c->ld / 4, c->Wdense, (const float4 *)x, (const float4 *)g, out, g, lr,
                            (int)n_tiles);
     else
-        hipLaunchKernelGGL((mix_dense_kernel<MB, ORDER, HAS_G, false>), dim3((unsigned)grid), dim3(DENSE_THREADS), 0,
+        hipLaunchKernelGGL((mix_dense_kernel<MB, ORDER, HAS_G, false, LR>), dim3((unsigned)grid), dim3(DENSE_THREADS), 0,
                            s, c->N, n_vec, c->ld / 4, c->Wdense, (const float4 *)x, (const float4 *)g, out, g, lr,
                            (int)n_tiles);
     DBW_HIP(hipGetLastError());
     return DBW_OK;
 }
 
-template <int ORDER, bool HAS_G>
-int launch(dbw_ctx *c, const float *x, const float *g, float *out, float lr, int64_t n_vec, hipStream_t s)
+template <int ORDER, bool HAS_G, class LR>
+int launch(dbw_ctx *c, const float *x, const float *g, float *out, LR lr, int64_t n_vec, hipStream_t s)
 {
     switch (c->Npad) {
-    case 32: return launch_mb<1, ORDER, HAS_G>(c, x, g, out, lr, n_vec, s);
-    case 64: return launch_mb<2, ORDER, HAS_G>(c, x, g, out, lr, n_vec, s);
-    case 128: return launch_mb<4, ORDER, HAS_G>(c, x, g, out, lr, n_vec, s);
-    case 256: return launch_mb<8, ORDER, HAS_G>(c, x, g, out, lr, n_vec, s);
+    case 32: return launch_mb<1, ORDER, HAS_G, LR>(c, x, g, out, lr, n_vec, s);
+    case 64: return launch_mb<2, ORDER, HAS_G, LR>(c, x, g, out, lr, n_vec, s);
+    case 128: return launch_mb<4, ORDER, HAS_G, LR>(c, x, g, out, lr, n_vec, s);
+    case 256: return launch_mb<8, ORDER, HAS_G, LR>(c, x, g, out, lr, n_vec, s);
     default: return DBW_ERR_UNSUPPORTED;
     }
 }
 
 }  // namespace
 
-int dbw_launch_mix_csr_range(dbw_ctx *c, const float *x, const float *g, float *out, float lr, int64_t c_begin,
-                             hipStream_t s);
+int dbw_launch_mix_csr_range(dbw_ctx *c, const float *x, const float *g, float *out, float lr, const float *lr_vec,
+                             int64_t c_begin, hipStream_t s);
 
-int dbw_launch_mix_dense(dbw_ctx *c, const float *x, const float *g, float *out, float lr, hipStream_t s)
+int dbw_launch_mix_dense(dbw_ctx *c, const float *x, const float *g, float *out, float lr, const float *lr_vec,
+                         hipStream_t s)
 {
     const bool aligned = (c->ld % 4 == 0) && ((uintptr_t)x % 16 == 0) && ((uintptr_t)out % 16 == 0) &&
                          (!g || (uintptr_t)g % 16 == 0);
@@ -248,14 +253,18 @@ int dbw_launch_mix_dense(dbw_ctx *c, const float *x, const float *g, float *out,
     int rc = DBW_OK;
     if (n_vec > 0) {
         if (!g)
-            rc = launch<DBW_ORDER_CTA, false>(c, x, g, out, lr, n_vec, s);
+            rc = launch<DBW_ORDER_CTA, false>(c, x, g, out, dbw_lr_scalar{0.f}, n_vec, s);
+        else if (lr_vec && c->order == DBW_ORDER_ATC)
+            rc = launch<DBW_ORDER_ATC, true>(c, x, g, out, dbw_lr_vector{lr_vec}, n_vec, s);
+        else if (lr_vec)
+            rc = launch<DBW_ORDER_CTA, true>(c, x, g, out, dbw_lr_vector{lr_vec}, n_vec, s);
         else if (c->order == DBW_ORDER_ATC)
-            rc = launch<DBW_ORDER_ATC, true>(c, x, g, out, lr, n_vec, s);
+            rc = launch<DBW_ORDER_ATC, true>(c, x, g, out, dbw_lr_scalar{lr}, n_vec, s);
         else
-            rc = launch<DBW_ORDER_CTA, true>(c, x, g, out, lr, n_vec, s);
+            rc = launch<DBW_ORDER_CTA, true>(c, x, g, out, dbw_lr_scalar{lr}, n_vec, s);
         if (rc != DBW_OK) return rc;
     }
     // ragged tail (d % 4 columns), or everything when rows are not 16-byte aligned
-    if (n_vec * 4 < c->d) rc = dbw_launch_mix_csr_range(c, x, g, out, lr, n_vec * 4, s);
+    if (n_vec * 4 < c->d) rc = dbw_launch_mix_csr_range(c, x, g, out, lr, lr_vec, n_vec * 4, s);
     return rc;
 }
