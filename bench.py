@@ -145,6 +145,33 @@ def main():
         graph_ms = (time.perf_counter() - t0) / args.steps * 1e3
         del graphs
 
+    # r gradient-free rounds (the consensus-only tail) one by one and collapsed into one pass
+    # through the product of their consensus matrices; outside the timed region
+    tail = None
+    if cfg.model == "none" and cfg.n <= 256:
+        r = min(8, wl.rounds)
+        src, dst = wl.x[wl.cur], wl.x[wl.cur ^ 1]
+
+        def timed(fn, reps=3):
+            fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / reps * 1e3
+
+        def single():
+            a, c = src, dst
+            for q in range(r):
+                B.dbw_select(wl.h, wl.t[q], wl.b[q])
+                B.dbw_round(wl.h, a, c, 0.0)
+                a, c = c, a
+
+        ms_single = timed(single)
+        ms_collapsed = timed(lambda: B.dbw_consensus_rounds(wl.h, src, dst, wl.t[:r], wl.b[:r], r))
+        tail = {"rounds": r, "ms_single_rounds": ms_single, "ms_collapsed": ms_collapsed}
+
     # simulated duration of a round (Section 3.2.2) with the workload's backup counts and with
     # full participation (b = 0) on the same response times; outside the timed region
     T = torch.zeros(2, device="cuda")
@@ -194,6 +221,7 @@ def main():
                    "gradients": "one fixed supplied matrix, reused every round" if cfg.model == "none" else "computed"},
         "roofline": roofline,
         "hip_graph_ms_per_step": graph_ms,
+        "consensus_tail": tail,
         "simulated_round_duration": {"dybw": dur["dybw"], "full_participation": dur["full"],
                                      "shorter_by": 1.0 - dur["dybw"] / dur["full"], "rounds": wl.rounds},
     }

@@ -171,6 +171,19 @@ int dbw_round_eta(dbw_ctx *ctx, const float *params_in, float *params_out, const
                   const int32_t *batch_y, const float *ext_grads, float *loss_out, const float *eta,
                   void *stream);
 
+/* r consecutive gradient-free rounds in one pass over the parameters: the consensus-only
+ * iterations that follow the gradient phase (Section 3.2.1, the remark after the corollary on
+ * the number of iterations), evaluated through the product of their consensus matrices
+ * (Phi of Section 3.1): params_out = P(k+r-1) ... P(k+1) P(k) params_in in this library's
+ * row convention.  resp_times [dev, r*N] and b [dev, r*N]: row q holds round q's response
+ * times and backup counts, used as by dbw_select.  The result equals r times (dbw_select,
+ * dbw_round with ext_grads = NULL) up to fp32 rounding; the parameters are read and written
+ * once instead of r times.  Needs N <= 256 (DBW_ERR_UNSUPPORTED otherwise).  Leaves the
+ * selection state of the last of the r rounds; out-of-range b is reported as by dbw_select.
+ * params_out must not overlap params_in.  Asynchronous on `stream`. */
+int dbw_consensus_rounds(dbw_ctx *ctx, const float *params_in, float *params_out, const float *resp_times,
+                         const int32_t *b, int32_t r, void *stream);
+
 /* Mini-batch gradients only (the first step of dbw_round), written to grads [dev, N*ld]
  * in columns [0, d).  Needs a model.  Asynchronous. */
 int dbw_grad(dbw_ctx *ctx, const float *params, const float *batch_x, const int32_t *batch_y,

@@ -24,7 +24,7 @@ LOSS_XENT, LOSS_MSE = 0, 1
 CAL_HBM_TRIAD, CAL_MFMA_FP32 = 0, 1
 
 EXPORTS = ["dbw_create", "dbw_select", "dbw_dtur_b", "dbw_dtur_reset", "dbw_get_selection",
-           "dbw_get_weights", "dbw_round_time", "dbw_round", "dbw_round_eta", "dbw_grad", "dbw_check", "dbw_get_links", "dbw_mix_path",
+           "dbw_get_weights", "dbw_round_time", "dbw_round", "dbw_round_eta", "dbw_consensus_rounds", "dbw_grad", "dbw_check", "dbw_get_links", "dbw_mix_path",
            "dbw_destroy", "dbw_strerror", "dbw_set_timing", "dbw_get_timing", "dbw_calibrate"]
 
 
@@ -57,6 +57,7 @@ _lib.dbw_get_weights.argtypes = [_vp, _vp, _vp]
 _lib.dbw_round_time.argtypes = [_vp, _vp, _vp]
 _lib.dbw_round.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _f, _vp]
 _lib.dbw_round_eta.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+_lib.dbw_consensus_rounds.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp]
 _lib.dbw_grad.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.dbw_check.argtypes = [_vp, _vp]
 _lib.dbw_get_links.argtypes = [_vp, _vp]
@@ -152,6 +153,12 @@ def dbw_round(h, params_in, params_out, lr: float, batch_x=None, batch_y=None, e
 def dbw_round_eta(h, params_in, params_out, eta, batch_x=None, batch_y=None, ext_grads=None, loss_out=None):
     return _chk(_lib.dbw_round_eta(h, _ptr(params_in), _ptr(params_out), _ptr(batch_x), _ptr(batch_y),
                                    _ptr(ext_grads), _ptr(loss_out), _ptr(eta), _stream()), "dbw_round_eta")
+
+
+def dbw_consensus_rounds(h, params_in, params_out, resp_times, b, r: int):
+    """resp_times [r, N] float32, b [r, N] int32 on the device."""
+    return _chk(_lib.dbw_consensus_rounds(h, _ptr(params_in), _ptr(params_out), _ptr(resp_times), _ptr(b), int(r),
+                                          _stream()), "dbw_consensus_rounds")
 
 
 def dbw_grad(h, params, batch_x, batch_y, grads, loss_out=None):

@@ -89,7 +89,7 @@ int dev_alloc(T **p, size_t n)
 void free_ctx(dbw_ctx *c)
 {
     if (!c) return;
-    void *ptrs[] = {c->rowptr, c->colidx, c->p, c->mask, c->wait, c->listed, c->sel_idx, c->sel_w, c->self_w, c->Wdense,
+    void *ptrs[] = {c->rowptr, c->colidx, c->p, c->mask, c->wait, c->listed, c->sel_idx, c->sel_w, c->self_w, c->Wdense, c->phi[0], c->phi[1], c->phi_frag,
                     c->err, c->links, c->visited, c->n_visited, c->grads, c->act};
     for (void *q : ptrs)
         if (q) (void)hipFree(q);
@@ -203,6 +203,11 @@ int dbw_create(dbw_ctx **out, int32_t N, int64_t d, const int32_t *rowptr, const
     A(dev_alloc(&c->visited, (size_t)std::max(N - 1, 1)));
     A(dev_alloc(&c->n_visited, 1));
     if (c->mix == DBW_MIX_DENSE) A(dev_alloc(&c->Wdense, (size_t)c->Npad * c->Npad));
+    if (N <= DBW_DENSE_MAX_N) {
+        A(dev_alloc(&c->phi[0], (size_t)c->Npad * c->Npad));
+        A(dev_alloc(&c->phi[1], (size_t)c->Npad * c->Npad));
+        A(dev_alloc(&c->phi_frag, (size_t)c->Npad * c->Npad));
+    }
     if (c->model.kind != DBW_MODEL_NONE) {
         A(dev_alloc(&c->grads, (size_t)N * c->ld));
         c->act_floats = c->model.kind == DBW_MODEL_MLP ? dbw_mlp_scratch_floats(c) : dbw_cnn_scratch_floats(c);
@@ -352,6 +357,19 @@ int dbw_round_eta(dbw_ctx *c, const float *params_in, float *params_out, const f
 {
     if (!eta) return DBW_ERR_NULL;
     return round_impl(c, params_in, params_out, batch_x, batch_y, ext_grads, loss_out, 0.f, eta, stream);
+}
+
+int dbw_consensus_rounds(dbw_ctx *c, const float *params_in, float *params_out, const float *resp_times,
+                         const int32_t *b, int32_t r, void *stream)
+{
+    if (!c || !params_in || !params_out || !resp_times || !b) return DBW_ERR_NULL;
+    if (r < 1) return DBW_ERR_INVALID;
+    if (c->N > DBW_DENSE_MAX_N) return DBW_ERR_UNSUPPORTED;
+    const size_t bytes = sizeof(float) * (size_t)c->N * (size_t)c->ld;
+    if (overlaps(params_in, bytes, params_out, bytes)) return DBW_ERR_ALIAS;
+    const int rc = dbw_launch_consensus_rounds(c, params_in, params_out, resp_times, b, r, (hipStream_t)stream);
+    if (rc == DBW_OK) c->selected = true;
+    return rc;
 }
 
 int dbw_get_links(dbw_ctx *c, int32_t *edges)

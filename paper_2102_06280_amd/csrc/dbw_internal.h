@@ -47,6 +47,8 @@ struct dbw_ctx {
     float *sel_w = nullptr;           // [nnz] their weights
     float *self_w = nullptr;          // [N]
     float *Wdense = nullptr;          // [Npad*Npad] in MFMA A-fragment order (dense path only)
+    float *phi[2] = {nullptr, nullptr};   // [Npad*Npad] running product of consensus matrices (N <= 256)
+    float *phi_frag = nullptr;        // the product in MFMA A-fragment order
     int32_t *err = nullptr;           // [1] deferred status
     // device: threshold rule
     int32_t *links = nullptr;         // [2*(N-1)]
@@ -91,8 +93,15 @@ struct dbw_lr_vector {
 int dbw_launch_mix_csr(dbw_ctx *c, const float *x, const float *g, float *out, float lr, const float *lr_vec,
                        hipStream_t s);
 // mix_dense.hip
+// Columns [0, dbw_dense_columns) are the ones the matrix-core kernel covers (0 when rows are not
+// 16-byte aligned).  W (A-fragment order, Npad x Npad) defaults to the matrix of the last
+// selection; with a W of the caller's the remaining columns are left to the caller.
+int64_t dbw_dense_columns(const dbw_ctx *c, const float *x, const float *g, const float *out);
 int dbw_launch_mix_dense(dbw_ctx *c, const float *x, const float *g, float *out, float lr, const float *lr_vec,
-                         hipStream_t s);
+                         hipStream_t s, const float *W = nullptr);
+// consensus.hip
+int dbw_launch_consensus_rounds(dbw_ctx *c, const float *x, float *out, const float *t, const int32_t *b, int r,
+                                hipStream_t s);
 // grad_mlp.hip / grad_cnn.hip
 // A stack of fully connected layers dims[0] -> ... -> dims[L] with ReLU between layers and
 // softmax cross-entropy on top, for all workers.  Parameters of the stack start at float

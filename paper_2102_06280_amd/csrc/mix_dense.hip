@@ -199,7 +199,8 @@ __global__ __launch_bounds__(DENSE_THREADS) void mix_dense_kernel(
 }
 
 template <int MB, int ORDER, bool HAS_G, class LR>
-int launch_mb(dbw_ctx *c, const float *x, const float *g, float *out, LR lr, int64_t n_vec, hipStream_t s)
+int launch_mb(dbw_ctx *c, const float *W, const float *x, const float *g, float *out, LR lr, int64_t n_vec,
+              hipStream_t s)
 {
     using C = dense_cfg<MB>;
     const int64_t n_tiles = (n_vec * 4 + C::TC - 1) / C::TC;
@@ -217,24 +218,25 @@ int launch_mb(dbw_ctx *c, const float *x, const float *g, float *out, LR lr, int
     dbw_timer tm(c, "mix_dense_kernel", s);
     if (full)
         hipLaunchKernelGGL((mix_dense_kernel<MB, ORDER, HAS_G, true, LR>), dim3((unsigned)grid), dim3(DENSE_THREADS), 0, s,
-                           c->N, n_vec, c->ld / 4, c->Wdense, (const float4 *)x, (const float4 *)g, out, g, lr,
+                           c->N, n_vec, c->ld / 4, W, (const float4 *)x, (const float4 *)g, out, g, lr,
                            (int)n_tiles);
     else
         hipLaunchKernelGGL((mix_dense_kernel<MB, ORDER, HAS_G, false, LR>), dim3((unsigned)grid), dim3(DENSE_THREADS), 0,
-                           s, c->N, n_vec, c->ld / 4, c->Wdense, (const float4 *)x, (const float4 *)g, out, g, lr,
+                           s, c->N, n_vec, c->ld / 4, W, (const float4 *)x, (const float4 *)g, out, g, lr,
                            (int)n_tiles);
     DBW_HIP(hipGetLastError());
     return DBW_OK;
 }
 
 template <int ORDER, bool HAS_G, class LR>
-int launch(dbw_ctx *c, const float *x, const float *g, float *out, LR lr, int64_t n_vec, hipStream_t s)
+int launch(dbw_ctx *c, const float *W, const float *x, const float *g, float *out, LR lr, int64_t n_vec,
+           hipStream_t s)
 {
     switch (c->Npad) {
-    case 32: return launch_mb<1, ORDER, HAS_G, LR>(c, x, g, out, lr, n_vec, s);
-    case 64: return launch_mb<2, ORDER, HAS_G, LR>(c, x, g, out, lr, n_vec, s);
-    case 128: return launch_mb<4, ORDER, HAS_G, LR>(c, x, g, out, lr, n_vec, s);
-    case 256: return launch_mb<8, ORDER, HAS_G, LR>(c, x, g, out, lr, n_vec, s);
+    case 32: return launch_mb<1, ORDER, HAS_G, LR>(c, W, x, g, out, lr, n_vec, s);
+    case 64: return launch_mb<2, ORDER, HAS_G, LR>(c, W, x, g, out, lr, n_vec, s);
+    case 128: return launch_mb<4, ORDER, HAS_G, LR>(c, W, x, g, out, lr, n_vec, s);
+    case 256: return launch_mb<8, ORDER, HAS_G, LR>(c, W, x, g, out, lr, n_vec, s);
     default: return DBW_ERR_UNSUPPORTED;
     }
 }
@@ -244,27 +246,36 @@ int launch(dbw_ctx *c, const float *x, const float *g, float *out, LR lr, int64_
 int dbw_launch_mix_csr_range(dbw_ctx *c, const float *x, const float *g, float *out, float lr, const float *lr_vec,
                              int64_t c_begin, hipStream_t s);
 
-int dbw_launch_mix_dense(dbw_ctx *c, const float *x, const float *g, float *out, float lr, const float *lr_vec,
-                         hipStream_t s)
+int64_t dbw_dense_columns(const dbw_ctx *c, const float *x, const float *g, const float *out)
 {
     const bool aligned = (c->ld % 4 == 0) && ((uintptr_t)x % 16 == 0) && ((uintptr_t)out % 16 == 0) &&
                          (!g || (uintptr_t)g % 16 == 0);
-    const int64_t n_vec = aligned ? c->d / 4 : 0;
+    return aligned ? c->d / 4 * 4 : 0;
+}
+
+int dbw_launch_mix_dense(dbw_ctx *c, const float *x, const float *g, float *out, float lr, const float *lr_vec,
+                         hipStream_t s, const float *W)
+{
+    const bool own_matrix = W != nullptr;
+    if (!W) W = c->Wdense;
+    if (!W) return DBW_ERR_STATE;
+    const int64_t n_vec = dbw_dense_columns(c, x, g, out) / 4;
     int rc = DBW_OK;
     if (n_vec > 0) {
         if (!g)
-            rc = launch<DBW_ORDER_CTA, false>(c, x, g, out, dbw_lr_scalar{0.f}, n_vec, s);
+            rc = launch<DBW_ORDER_CTA, false>(c, W, x, g, out, dbw_lr_scalar{0.f}, n_vec, s);
         else if (lr_vec && c->order == DBW_ORDER_ATC)
-            rc = launch<DBW_ORDER_ATC, true>(c, x, g, out, dbw_lr_vector{lr_vec}, n_vec, s);
+            rc = launch<DBW_ORDER_ATC, true>(c, W, x, g, out, dbw_lr_vector{lr_vec}, n_vec, s);
         else if (lr_vec)
-            rc = launch<DBW_ORDER_CTA, true>(c, x, g, out, dbw_lr_vector{lr_vec}, n_vec, s);
+            rc = launch<DBW_ORDER_CTA, true>(c, W, x, g, out, dbw_lr_vector{lr_vec}, n_vec, s);
         else if (c->order == DBW_ORDER_ATC)
-            rc = launch<DBW_ORDER_ATC, true>(c, x, g, out, dbw_lr_scalar{lr}, n_vec, s);
+            rc = launch<DBW_ORDER_ATC, true>(c, W, x, g, out, dbw_lr_scalar{lr}, n_vec, s);
         else
-            rc = launch<DBW_ORDER_CTA, true>(c, x, g, out, dbw_lr_scalar{lr}, n_vec, s);
+            rc = launch<DBW_ORDER_CTA, true>(c, W, x, g, out, dbw_lr_scalar{lr}, n_vec, s);
         if (rc != DBW_OK) return rc;
     }
-    // ragged tail (d % 4 columns), or everything when rows are not 16-byte aligned
-    if (n_vec * 4 < c->d) rc = dbw_launch_mix_csr_range(c, x, g, out, lr, lr_vec, n_vec * 4, s);
+    // ragged tail (d % 4 columns), or everything when rows are not 16-byte aligned; a caller
+    // that brought its own matrix covers those columns itself
+    if (n_vec * 4 < c->d && !own_matrix) rc = dbw_launch_mix_csr_range(c, x, g, out, lr, lr_vec, n_vec * 4, s);
     return rc;
 }
