@@ -7,7 +7,8 @@ plus the per-worker gradients where the configuration has a model) on one MI355X
 A step is one pass of the whole hot path over one round of synthetic input that is already
 resident in HBM.  Prints one JSON line.  The default workload is the consensus-only stress
 configuration (128 workers, 8-regular graph, d = 11.2 M), the one the averaging-bandwidth
-metric is quoted on.
+metric is quoted on; its parameter and gradient matrices are stored tile-major by default
+(--layout rows for one row per worker; the line reports the other layout as well).
 """
 from __future__ import annotations
 
@@ -93,6 +94,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4, 5, 6, 7])
     ap.add_argument("--order", choices=["cta", "atc"], default="cta")
+    ap.add_argument("--layout", choices=["rows", "tiles"], default=None,
+                    help="storage layout of the parameter matrices; default: tile-major for the consensus-only "
+                         "stress (config 4), rows elsewhere; the other layout is timed as well and reported")
+    ap.add_argument("--ld", type=int, default=0, help="row stride in floats (default: d rounded up to 64)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the timed region, run three plain device copies of one N x ld parameter matrix "
@@ -110,8 +115,11 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     cfg = inputs.CONFIGS[args.config]
+    if args.layout is None:
+        args.layout = "tiles" if args.config == 4 else "rows"
     rounds = args.steps + args.warmup
-    wl = Workload(args.config, min(rounds, max(cfg.rounds, 8)), order=B.ORDER_ATC if args.order == "atc" else B.ORDER_CTA)
+    wl = Workload(args.config, min(rounds, max(cfg.rounds, 8)), order=B.ORDER_ATC if args.order == "atc" else B.ORDER_CTA,
+                  ld_override=args.ld or None, layout=B.LAYOUT_TILES if args.layout == "tiles" else B.LAYOUT_ROWS)
 
     for _ in range(args.warmup):
         wl.step()
@@ -148,7 +156,7 @@ def main():
     # r gradient-free rounds (the consensus-only tail) one by one and collapsed into one pass
     # through the product of their consensus matrices; outside the timed region
     tail = None
-    if cfg.model == "none" and cfg.n <= 256:
+    if cfg.model == "none" and cfg.n <= 256 and args.layout == "rows":
         r = min(8, wl.rounds)
         src, dst = wl.x[wl.cur], wl.x[wl.cur ^ 1]
 
@@ -189,7 +197,7 @@ def main():
     mix_path = B.dbw_mix_path(wl.h)
     dominant = max(kern, key=lambda k: kern[k][0])
     dom_ms = kern[dominant][0] / kern[dominant][1]
-    if dominant.startswith(("mix_csr", "mix_lds")):
+    if dominant.startswith(("mix_csr", "mix_lds", "mix_tile")):
         work = 3.0 * cfg.n * cfg.d * 4          # read X, read G, write X' once each
         roofline = {"bound": "hbm", "achieved": work / (dom_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "traffic": None}
@@ -216,7 +224,7 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"config {cfg.cid}: {cfg.name}", "workers": cfg.n, "graph": cfg.graph, "d": cfg.d,
-                   "ld": wl.ld, "model": cfg.model, "batch": cfg.batch, "order": args.order,
+                   "ld": wl.ld, "layout": args.layout, "model": cfg.model, "batch": cfg.batch, "order": args.order,
                    "mix_path": "dense" if mix_path == B.MIX_DENSE else "csr",
                    "gradients": "one fixed supplied matrix, reused every round" if cfg.model == "none" else "computed"},
         "roofline": roofline,
@@ -229,6 +237,29 @@ def main():
     wl.close()
     del wl
     torch.cuda.empty_cache()
+    # the same workload in the other storage layout, same number of steps
+    if args.config == 4 and not args.ld:
+        other = "rows" if args.layout == "tiles" else "tiles"
+        wl2 = Workload(args.config, min(rounds, max(cfg.rounds, 8)), order=B.ORDER_ATC if args.order == "atc" else B.ORDER_CTA,
+                       layout=B.LAYOUT_TILES if other == "tiles" else B.LAYOUT_ROWS)
+        for _ in range(args.warmup):
+            wl2.step()
+        B.dbw_set_timing(wl2.h, True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            wl2.step()
+        torch.cuda.synchronize()
+        el2 = time.perf_counter() - t0
+        k2 = B.dbw_get_timing(wl2.h)
+        dom2 = max(k2, key=lambda k: k2[k][0])
+        ms2 = k2[dom2][0] / k2[dom2][1]
+        out["other_layout"] = {"layout": other, "value": cfg.n * args.steps / el2, "ms_per_step": el2 / args.steps * 1e3,
+                               "kernel": dom2, "kernel_ms": ms2,
+                               "frac": 3.0 * cfg.n * cfg.d * 4 / (ms2 * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        wl2.close()
+        del wl2
+        torch.cuda.empty_cache()
     # what plain kernels reach on this device, next to the nominal peak: a streaming triad
     # over three 1 GiB arrays, or register-resident fp32 matrix instructions
     if roofline["bound"] == "hbm":

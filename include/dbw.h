@@ -9,7 +9,8 @@
  * or keeps caller memory except where stated; caller arrays must stay valid until the
  * stream work that uses them has completed.
  *
- * Layout.  Worker i's parameter vector is row i of a row-major [N][ld] float array,
+ * Layout (the default, DBW_LAYOUT_ROWS; see DBW_LAYOUT_TILES for the alternative).
+ * Worker i's parameter vector is row i of a row-major [N][ld] float array,
  * d <= ld; columns [d, ld) are padding that the library never reads into results and
  * never writes.  This is the transpose of the paper's d x N matrix W(k) (Section 2.2),
  * so the paper's right-multiplication by the consensus matrix P(k) becomes a
@@ -64,6 +65,21 @@ enum {
     DBW_MIX_DENSE = 2  /* materialise P(k) as N x N and multiply on the matrix cores */
 };
 
+/* How the N parameter vectors are laid out in a [N * ld] float array. */
+enum {
+    /* worker i's vector is row i: element (i, c) at i * ld + c */
+    DBW_LAYOUT_ROWS = 0,
+    /* tile-major: the columns are cut into tiles of DBW_TILE_COLUMNS, and the pieces of all
+     * N workers for one tile are stored together: element (i, c) at
+     * (c / 64) * N * 64 + i * 64 + c % 64.  ld must be a multiple of 64.  The masked average
+     * needs every worker's values of a column range at the same time; this layout turns that
+     * into linear memory streams (about 15-20 % faster on MI355X than rows that lie a whole row
+     * apart).  Available without a model (gradients supplied by the caller in the same
+     * layout), N <= 256, sparse mixing path; dbw_convert_layout moves between the two. */
+    DBW_LAYOUT_TILES = 1
+};
+#define DBW_TILE_COLUMNS 64
+
 enum {
     DBW_MODEL_NONE = 0, /* gradients are supplied by the caller (ext_grads) */
     DBW_MODEL_MLP = 1,  /* fully connected dims[0] -> ... -> dims[n_layers], ReLU between
@@ -93,6 +109,7 @@ typedef struct {
     int64_t ld;       /* row stride in floats, >= d; 0 means d */
     int32_t order;    /* DBW_ORDER_* */
     int32_t mix_path; /* DBW_MIX_* */
+    int32_t layout;   /* DBW_LAYOUT_*: applies to params_in, params_out and ext_grads of dbw_round */
     dbw_model model;
 } dbw_opts;
 
@@ -183,6 +200,12 @@ int dbw_round_eta(dbw_ctx *ctx, const float *params_in, float *params_out, const
  * params_out must not overlap params_in.  Asynchronous on `stream`. */
 int dbw_consensus_rounds(dbw_ctx *ctx, const float *params_in, float *params_out, const float *resp_times,
                          const int32_t *b, int32_t r, void *stream);
+
+/* Copy a [N * ld] array from one layout to the other (all ld columns): to_tiles != 0 reads src
+ * in row layout and writes dst tile-major, to_tiles == 0 the reverse.  ld must be a multiple
+ * of 64 and both pointers 16-byte aligned (DBW_ERR_INVALID otherwise); src and dst must not
+ * overlap.  Works on any context, whatever its own layout.  Asynchronous on `stream`. */
+int dbw_convert_layout(dbw_ctx *ctx, const float *src, float *dst, int32_t to_tiles, void *stream);
 
 /* Mini-batch gradients only (the first step of dbw_round), written to grads [dev, N*ld]
  * in columns [0, d).  Needs a model.  Asynchronous. */

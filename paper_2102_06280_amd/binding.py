@@ -22,9 +22,11 @@ MIX_AUTO, MIX_CSR, MIX_DENSE = 0, 1, 2
 MODEL_NONE, MODEL_MLP, MODEL_CNN = 0, 1, 2
 LOSS_XENT, LOSS_MSE = 0, 1
 CAL_HBM_TRIAD, CAL_MFMA_FP32 = 0, 1
+LAYOUT_ROWS, LAYOUT_TILES = 0, 1
+TILE_COLUMNS = 64
 
 EXPORTS = ["dbw_create", "dbw_select", "dbw_dtur_b", "dbw_dtur_reset", "dbw_get_selection",
-           "dbw_get_weights", "dbw_round_time", "dbw_round", "dbw_round_eta", "dbw_consensus_rounds", "dbw_grad", "dbw_check", "dbw_get_links", "dbw_mix_path",
+           "dbw_get_weights", "dbw_round_time", "dbw_round", "dbw_round_eta", "dbw_consensus_rounds", "dbw_convert_layout", "dbw_grad", "dbw_check", "dbw_get_links", "dbw_mix_path",
            "dbw_destroy", "dbw_strerror", "dbw_set_timing", "dbw_get_timing", "dbw_calibrate"]
 
 
@@ -34,7 +36,8 @@ class dbw_model(C.Structure):
 
 
 class dbw_opts(C.Structure):
-    _fields_ = [("ld", C.c_int64), ("order", C.c_int32), ("mix_path", C.c_int32), ("model", dbw_model)]
+    _fields_ = [("ld", C.c_int64), ("order", C.c_int32), ("mix_path", C.c_int32), ("layout", C.c_int32),
+                ("model", dbw_model)]
 
 
 class dbw_kernel_time(C.Structure):
@@ -58,6 +61,7 @@ _lib.dbw_round_time.argtypes = [_vp, _vp, _vp]
 _lib.dbw_round.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _f, _vp]
 _lib.dbw_round_eta.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.dbw_consensus_rounds.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp]
+_lib.dbw_convert_layout.argtypes = [_vp, _vp, _vp, _i32, _vp]
 _lib.dbw_grad.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.dbw_check.argtypes = [_vp, _vp]
 _lib.dbw_get_links.argtypes = [_vp, _vp]
@@ -108,12 +112,12 @@ def make_model(kind: int = MODEL_NONE, batch: int = 0, dims=(), loss: int = LOSS
 
 
 def dbw_create(rowptr, colidx, N: int, d: int, ld: int = 0, order: int = ORDER_CTA,
-               mix_path: int = MIX_AUTO, model: dbw_model | None = None):
+               mix_path: int = MIX_AUTO, model: dbw_model | None = None, layout: int = LAYOUT_ROWS):
     """rowptr / colidx: host int32 arrays (NumPy).  Returns an opaque handle."""
     rowptr = np.ascontiguousarray(rowptr, dtype=np.int32)
     colidx = np.ascontiguousarray(colidx, dtype=np.int32)
     opts = dbw_opts()
-    opts.ld, opts.order, opts.mix_path = ld, order, mix_path
+    opts.ld, opts.order, opts.mix_path, opts.layout = ld, order, mix_path, layout
     opts.model = model if model is not None else make_model()
     h = _vp()
     _chk(_lib.dbw_create(C.byref(h), N, d, rowptr.ctypes.data, colidx.ctypes.data if colidx.size else None,
@@ -159,6 +163,11 @@ def dbw_consensus_rounds(h, params_in, params_out, resp_times, b, r: int):
     """resp_times [r, N] float32, b [r, N] int32 on the device."""
     return _chk(_lib.dbw_consensus_rounds(h, _ptr(params_in), _ptr(params_out), _ptr(resp_times), _ptr(b), int(r),
                                           _stream()), "dbw_consensus_rounds")
+
+
+def dbw_convert_layout(h, src, dst, to_tiles: bool):
+    return _chk(_lib.dbw_convert_layout(h, _ptr(src), _ptr(dst), 1 if to_tiles else 0, _stream()),
+                "dbw_convert_layout")
 
 
 def dbw_grad(h, params, batch_x, batch_y, grads, loss_out=None):

@@ -155,12 +155,28 @@ int dbw_create(dbw_ctx **out, int32_t N, int64_t d, const int32_t *rowptr, const
         if (opts->ld != 0) c->ld = opts->ld;
         c->order = opts->order;
         c->mix = opts->mix_path;
+        c->layout = opts->layout;
         c->model = opts->model;
     }
     if (c->ld < d || (c->order != DBW_ORDER_CTA && c->order != DBW_ORDER_ATC) || c->mix < DBW_MIX_AUTO ||
         c->mix > DBW_MIX_DENSE) {
         delete c;
         return DBW_ERR_INVALID;
+    }
+    if (c->layout != DBW_LAYOUT_ROWS && c->layout != DBW_LAYOUT_TILES) {
+        delete c;
+        return DBW_ERR_INVALID;
+    }
+    if (c->layout == DBW_LAYOUT_TILES) {
+        if (c->ld % DBW_TILE_COLUMNS) {
+            delete c;
+            return DBW_ERR_INVALID;
+        }
+        if (c->model.kind != DBW_MODEL_NONE || N > DBW_TILES_MAX_N || c->mix == DBW_MIX_DENSE) {
+            delete c;
+            return DBW_ERR_UNSUPPORTED;
+        }
+        c->mix = DBW_MIX_CSR;
     }
     if (c->model.kind != DBW_MODEL_NONE) {
         const int64_t want = model_param_count(c->model, &c->in_dim);
@@ -342,8 +358,18 @@ static int round_impl(dbw_ctx *c, const float *params_in, float *params_out, con
     } else if (g && overlaps(g, bytes, params_out, bytes)) {
         return DBW_ERR_ALIAS;
     }
+    if (c->layout == DBW_LAYOUT_TILES) return dbw_launch_mix_tiles(c, params_in, g, params_out, lr, lr_vec, s);
     if (c->mix == DBW_MIX_DENSE) return dbw_launch_mix_dense(c, params_in, g, params_out, lr, lr_vec, s);
     return dbw_launch_mix_csr(c, params_in, g, params_out, lr, lr_vec, s);
+}
+
+int dbw_convert_layout(dbw_ctx *c, const float *src, float *dst, int32_t to_tiles, void *stream)
+{
+    if (!c || !src || !dst) return DBW_ERR_NULL;
+    if (c->ld % DBW_TILE_COLUMNS || (uintptr_t)src % 16 || (uintptr_t)dst % 16) return DBW_ERR_INVALID;
+    const size_t bytes = sizeof(float) * (size_t)c->N * (size_t)c->ld;
+    if (overlaps(src, bytes, dst, bytes)) return DBW_ERR_ALIAS;
+    return dbw_launch_layout_convert(c, src, dst, to_tiles != 0, (hipStream_t)stream);
 }
 
 int dbw_round(dbw_ctx *c, const float *params_in, float *params_out, const float *batch_x,
@@ -364,7 +390,7 @@ int dbw_consensus_rounds(dbw_ctx *c, const float *params_in, float *params_out, 
 {
     if (!c || !params_in || !params_out || !resp_times || !b) return DBW_ERR_NULL;
     if (r < 1) return DBW_ERR_INVALID;
-    if (c->N > DBW_DENSE_MAX_N) return DBW_ERR_UNSUPPORTED;
+    if (c->N > DBW_DENSE_MAX_N || c->layout != DBW_LAYOUT_ROWS) return DBW_ERR_UNSUPPORTED;
     const size_t bytes = sizeof(float) * (size_t)c->N * (size_t)c->ld;
     if (overlaps(params_in, bytes, params_out, bytes)) return DBW_ERR_ALIAS;
     const int rc = dbw_launch_consensus_rounds(c, params_in, params_out, resp_times, b, r, (hipStream_t)stream);

@@ -17,6 +17,7 @@
 
 constexpr int DBW_DENSE_MAX_N = 256;   // the dense mixing kernel keeps all of P(k) in registers
 constexpr int DBW_SELECT_LDS_KEYS = 2048;
+constexpr int DBW_TILES_MAX_N = 256;   // the tile-major mixing kernel holds one 256-byte piece per worker in LDS
 
 struct dbw_timing_slot {
     const char *name;
@@ -29,6 +30,7 @@ struct dbw_ctx {
     int32_t nnz = 0, max_deg = 0;
     int32_t order = DBW_ORDER_CTA;
     int32_t mix = DBW_MIX_CSR;
+    int32_t layout = DBW_LAYOUT_ROWS;
     int32_t Npad = 0;                 // N rounded up to a power of two >= 32 (dense path)
     dbw_model model{};
     int64_t in_dim = 0;               // floats per sample
@@ -99,6 +101,10 @@ int dbw_launch_mix_csr(dbw_ctx *c, const float *x, const float *g, float *out, f
 int64_t dbw_dense_columns(const dbw_ctx *c, const float *x, const float *g, const float *out);
 int dbw_launch_mix_dense(dbw_ctx *c, const float *x, const float *g, float *out, float lr, const float *lr_vec,
                          hipStream_t s, const float *W = nullptr);
+// mix_tiles.hip (tile-major layout)
+int dbw_launch_mix_tiles(dbw_ctx *c, const float *x, const float *g, float *out, float lr, const float *lr_vec,
+                         hipStream_t s);
+int dbw_launch_layout_convert(dbw_ctx *c, const float *src, float *dst, int to_tiles, hipStream_t s);
 // consensus.hip
 int dbw_launch_consensus_rounds(dbw_ctx *c, const float *x, float *out, const float *t, const int32_t *b, int r,
                                 hipStream_t s);

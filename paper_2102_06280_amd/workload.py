@@ -16,13 +16,14 @@ class Workload:
     """All inputs of `rounds` rounds of one configuration, resident in HBM."""
 
     def __init__(self, cid: int, rounds: int, order: int = B.ORDER_CTA, mix_path: int = B.MIX_AUTO,
-                 d_override: int | None = None):
+                 d_override: int | None = None, ld_override: int | None = None, layout: int = B.LAYOUT_ROWS):
         cfg = inputs.CONFIGS[cid]
         self.cfg, self.cid, self.rounds, self.order = cfg, cid, rounds, order
         self.rowptr, self.colidx = inputs.make_graph(cfg)
         self.n = cfg.n
         self.d = d_override or cfg.d
-        self.ld = inputs.pad_ld(self.d)
+        self.ld = ld_override or inputs.pad_ld(self.d)
+        assert self.ld >= self.d
         self.desc = inputs.model_dims(cfg.model) if cfg.model != "none" else None
         model = None
         if self.desc is not None:
@@ -33,8 +34,9 @@ class Workload:
                 c, h, w = self.desc["in"]
                 model = B.make_model(B.MODEL_CNN, cfg.batch, [c, h, w, self.desc["c1"], self.desc["c2"],
                                                               self.desc["k"], self.desc["fc"], self.desc["classes"]])
+        self.layout = layout
         self.h = B.dbw_create(self.rowptr, self.colidx, self.n, self.d, ld=self.ld, order=order,
-                              mix_path=mix_path, model=model)
+                              mix_path=mix_path, model=model, layout=layout)
         dev = torch.device("cuda")
         # response times and backup counts of every round
         self.t_host = np.stack([inputs.response_times(cfg, r) for r in range(rounds)])
@@ -55,6 +57,14 @@ class Workload:
             self.x[1].zero_()
             self.g = torch.empty((self.n, self.ld), dtype=torch.float32, device=dev)
             self.g.normal_(0.0, 0.01, generator=gen)          # one fixed gradient matrix for all rounds
+            if layout == B.LAYOUT_TILES:                      # the same values, stored tile-major
+                B.dbw_convert_layout(self.h, self.x[0], self.x[1], True)
+                self.x[0].zero_()
+                self.x.reverse()
+                tmp = torch.empty_like(self.g)
+                B.dbw_convert_layout(self.h, self.g, tmp, True)
+                self.g = tmp
+                torch.cuda.synchronize()
             self.bx = self.by = None
         else:
             x0 = inputs.init_params(self.desc, self.n, self.ld, inputs.rng(cid, inputs.P_PARAMS), zero=cfg.zero_init)
@@ -109,6 +119,16 @@ class Workload:
 
     def params(self):
         return self.x[self.cur]
+
+    def columns(self, t, start: int, stop: int):
+        """Columns [start, stop) of all workers as an [N, stop - start] tensor, whatever the
+        layout `t` (one of this workload's [N * ld] arrays) is stored in."""
+        if self.layout == B.LAYOUT_ROWS:
+            return t[:, start:stop]
+        w = B.TILE_COLUMNS
+        t0, t1 = start // w, (stop + w - 1) // w
+        block = t.view(self.ld // w, self.n, w)[t0:t1].permute(1, 0, 2).reshape(self.n, (t1 - t0) * w)
+        return block[:, start - t0 * w: stop - t0 * w]
 
     def close(self):
         if self.h is not None:

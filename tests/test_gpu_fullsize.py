@@ -1,6 +1,6 @@
 """Parity at the full benchmark sizes, in the launch configuration bench.py times: the
 consensus-only stress (N = 128, d = 11.2 M, sparse path) and the dense-mixing stress
-(N = 256, d = 1 M, matrix-core path).  The averaging is column-separable, so the oracle
+(N = 256, d = 1 M, matrix-core path), the former in both storage layouts.  The averaging is column-separable, so the oracle
 is evaluated on sampled column blocks (first, last, and random ones) of the device data."""
 import numpy as np
 import pytest
@@ -11,11 +11,13 @@ from gpu_util import assert_params_close
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("cid,order", [(4, 0), (4, 1), (5, 0), (5, 1)], ids=["c4-cta", "c4-atc", "c5-cta", "c5-atc"])
-def test_full_size_sampled_columns(orc, cid, order):
+@pytest.mark.parametrize("cid,order,tiles", [(4, 0, False), (4, 1, False), (5, 0, False), (5, 1, False),
+                                             (4, 0, True), (4, 1, True)],
+                         ids=["c4-cta", "c4-atc", "c5-cta", "c5-atc", "c4-cta-tiles", "c4-atc-tiles"])
+def test_full_size_sampled_columns(orc, cid, order, tiles):
     from paper_2102_06280_amd import binding as B
     from paper_2102_06280_amd.workload import Workload
-    wl = Workload(cid, rounds=2, order=order)
+    wl = Workload(cid, rounds=2, order=order, layout=B.LAYOUT_TILES if tiles else B.LAYOUT_ROWS)
     try:
         cfg = wl.cfg
         blk = 4096
@@ -24,8 +26,8 @@ def test_full_size_sampled_columns(orc, cid, order):
         starts.append(int(g.integers(0, wl.d - blk)) | 1)       # an odd, unaligned start
         for rnd in range(2):
             src = wl.params()
-            before = [src[:, s:s + blk].cpu().numpy() for s in starts]
-            grads = [wl.g[:, s:s + blk].cpu().numpy() for s in starts]
+            before = [wl.columns(src, s, s + blk).cpu().numpy() for s in starts]
+            grads = [wl.columns(wl.g, s, s + blk).cpu().numpy() for s in starts]
             wl.step()
             assert B.dbw_check(wl.h) == 0
             dst = wl.params()
@@ -36,9 +38,9 @@ def test_full_size_sampled_columns(orc, cid, order):
             assert np.array_equal(mask_d.cpu().numpy(), mask) and np.array_equal(p_d.cpu().numpy(), p)
             for s, xb, gb in zip(starts, before, grads):
                 want = orc.round_(wl.rowptr, wl.colidx, mask, p, xb, gb, cfg.lr, order)
-                got = dst[:, s:s + blk].cpu().numpy()
+                got = wl.columns(dst, s, s + blk).cpu().numpy()
                 assert_params_close(got, want, what=f"config {cid} round {rnd} columns {s}..{s + blk}")
             # padding columns (if any) and the source buffer are untouched
-            assert torch.equal(src[:, :blk], torch.from_numpy(before[0]).cuda())
+            assert torch.equal(wl.columns(src, 0, blk), torch.from_numpy(before[0]).cuda())
     finally:
         wl.close()
