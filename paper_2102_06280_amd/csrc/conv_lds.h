@@ -243,25 +243,43 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void conv_wgrad_kernel(
             }
             __syncthreads();
             const int chunk_row = chunk * (PC / W);                  // first image row of the chunk
+            // k runs over the wave's pixel groups i (16 pixels each) and the four k-slots j of a
+            // group; the B values of step (i, j) + 1 are requested before the multiplies of step
+            // (i, j), and scheduling barriers keep the compiler from requesting more than that
+            // ahead (hundreds of values otherwise, which spill)
+            auto pixel_offset = [&](int i) {
+                const int kgl = wk * C::KG_WAVE + i;                 // k group inside the chunk (wave-uniform)
+                // W % 16 == 0 keeps a group inside one image row
+                return (chunk_row + (16 * kgl) / W) * C::WP + (16 * kgl) % W;
+            };
+            float fb[2][NT];
+            {
+                const int poff = pixel_offset(0);
+#pragma unroll
+                for (int nf = 0; nf < NT; ++nf) fb[0][nf] = img[bbase[nf] + poff];
+            }
 #pragma unroll
             for (int i = 0; i < C::KG_WAVE; ++i) {
-                const int kgl = wk * C::KG_WAVE + i;                 // k group inside the chunk (wave-uniform)
-                // pixel offset of the group's first pixel; W % 16 == 0 keeps a group inside one row
-                const int poff = (chunk_row + (16 * kgl) / W) * C::WP + (16 * kgl) % W;
+                const int kgl = wk * C::KG_WAVE + i;
                 f32x4 fa[MT];
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
                     fa[mt] = *(const f32x4 *)&dzs[(16 * (wm * MT + mt) + (lane & 15)) * C::LDD + 16 * kgl + 4 * (lane >> 4)];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    float fb[NT];
+                    const int step = 4 * i + j;
+                    if (step + 1 < 4 * C::KG_WAVE) {
+                        const int poff = pixel_offset((step + 1) / 4) + (step + 1) % 4;
 #pragma unroll
-                    for (int nf = 0; nf < NT; ++nf) fb[nf] = img[bbase[nf] + poff + j];
+                        for (int nf = 0; nf < NT; ++nf) fb[(step + 1) & 1][nf] = img[bbase[nf] + poff];
+                    }
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                         for (int nf = 0; nf < NT; ++nf)
-                            acc[mt][nf] = __builtin_amdgcn_mfma_f32_16x16x4f32(fa[mt][j], fb[nf], acc[mt][nf], 0, 0, 0);
+                            acc[mt][nf] =
+                                __builtin_amdgcn_mfma_f32_16x16x4f32(fa[mt][j], fb[step & 1][nf], acc[mt][nf], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
         }

@@ -30,6 +30,20 @@ typedef __attribute__((address_space(3))) void *lds_ptr;
 
 constexpr int DENSE_THREADS = 512;
 
+// A wave-uniform address, pinned to scalar registers.  Global loads and stores take a scalar
+// base plus a 32-bit lane offset; without the pin the compiler folds the lane offset into one
+// loop-invariant 64-bit vector address per row, and those dozens of register pairs push the
+// P block out to scratch memory.
+__device__ __forceinline__ const char *uniform_base(const void *p)
+{
+    const uint64_t a = (uint64_t)p;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+    uint64_t v = ((uint64_t)hi << 32) | lo;
+    asm volatile("" : "+s"(v));
+    return (const char *)v;
+}
+
 template <int MB>
 struct dense_cfg {
     static constexpr int NPAD = 32 * MB;              // padded number of workers
@@ -65,7 +79,9 @@ __global__ __launch_bounds__(DENSE_THREADS) void mix_dense_kernel(
 
     // ---- next-tile staging through registers (guards / ATC prologue)
     float4 stage[DMA ? 1 : C::PASSES];
-    const uint32_t fetch_lane_off = (uint32_t)((tid / (C::TC / 4)) * ld4 + tid % (C::TC / 4));
+    // lane offsets are kept in bytes: uniform 64-bit base + 32-bit lane offset is an addressing mode of
+    // the global memory instructions, so no 64-bit address has to live in vector registers
+    const uint32_t fetch_lane_off = 16u * (uint32_t)((tid / (C::TC / 4)) * ld4 + tid % (C::TC / 4));
     auto fetch = [&](int64_t tile) {
 #pragma unroll
         for (int ps = 0; ps < (DMA ? 0 : C::PASSES); ++ps) {
@@ -75,9 +91,10 @@ __global__ __launch_bounds__(DENSE_THREADS) void mix_dense_kernel(
             const float4 *xb = x + (int64_t)k0 * ld4 + tile * (C::TC / 4);        // uniform base
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
             if (FULL || (k < N && col4 < n_vec)) {
-                v = xb[fetch_lane_off];
+                v = *(const float4 *)(uniform_base(xb) + fetch_lane_off);
                 if (ORDER == DBW_ORDER_ATC && HAS_G) {
-                    const float4 gv = (g + (int64_t)k0 * ld4 + tile * (C::TC / 4))[fetch_lane_off];
+                    const float4 gv =
+                        *(const float4 *)(uniform_base(g + (int64_t)k0 * ld4 + tile * (C::TC / 4)) + fetch_lane_off);
                     const float eta = lr.at(k);
                     v.x = fmaf(-eta, gv.x, v.x);
                     v.y = fmaf(-eta, gv.y, v.y);
@@ -100,14 +117,14 @@ __global__ __launch_bounds__(DENSE_THREADS) void mix_dense_kernel(
     };
     // ---- next-tile staging straight into LDS.  One instruction fills 1 KB = the 64-lane
     // rows of four consecutive k-steps of one sub-tile; lane -> (row, 4 columns) follows.
-    const uint32_t dma_lane_off = (uint32_t)((2 * (lane >> 4) + ((lane >> 3) & 1)) * ld4 + (lane & 7));
+    const uint32_t dma_lane_off = 16u * (uint32_t)((2 * (lane >> 4) + ((lane >> 3) & 1)) * ld4 + (lane & 7));
     auto dma = [&](int64_t tile, int buf) {
 #pragma unroll
         for (int i = 0; i < (DMA ? C::DMA_PER_WAVE : 0); ++i) {
             const int q = w + 8 * i;                                             // uniform block id
             const int s = q / (C::KB / 4), kq = q % (C::KB / 4);
             const float4 *src = x + (int64_t)(8 * kq) * ld4 + tile * (C::TC / 4) + s * 8;   // uniform base
-            __builtin_amdgcn_global_load_lds((global_cptr)(src + dma_lane_off),
+            __builtin_amdgcn_global_load_lds((global_cptr)(uniform_base(src) + dma_lane_off),
                                              (lds_ptr)&lds[buf * C::TILE + q * 256], 16, 0, 0);
         }
     };
@@ -124,7 +141,7 @@ __global__ __launch_bounds__(DENSE_THREADS) void mix_dense_kernel(
     __syncthreads();
 
     // epilogue addressing: uniform base per (tile, row block, sub-tile, v) + one lane offset
-    const uint32_t epi_lane_off = (uint32_t)(4 * (lane >> 5) * ld + (lane & 31));
+    const uint32_t epi_lane_off = 4u * (uint32_t)(4 * (lane >> 5) * ld + (lane & 31));
 
     int buf = 0;
     for (; tile < n_tiles; tile += gridDim.x) {
@@ -133,11 +150,15 @@ __global__ __launch_bounds__(DENSE_THREADS) void mix_dense_kernel(
             if (DMA) dma(next, buf ^ 1); else fetch(next);
         }
 
-        // gradient values of the epilogue, requested now, used after the multiply loop
+        // Per 32-column sub-tile: request its gradient values, multiply, correct and store.  The
+        // sub-tiles of a wave go one after the other so that only one accumulator and one set of
+        // gradient values are live at a time (the P block already takes half of the registers);
+        // the other wave of the SIMD fills the gaps of the dependent chain.  The last sub-tile's
+        // stores come after the barrier and drain under the next tile's multiplies.
         float gv[C::SPW][16];
-        if (ORDER == DBW_ORDER_CTA && HAS_G) {
-#pragma unroll
-            for (int sp = 0; sp < C::SPW; ++sp) {
+        f32x16 acc[C::SPW];
+        auto load_g = [&](int sp) {
+            if (ORDER == DBW_ORDER_CTA && HAS_G) {
                 const int s = cg * C::SPW + sp;
                 const int64_t col0 = tile * C::TC + 32 * s;
 #pragma unroll
@@ -145,42 +166,39 @@ __global__ __launch_bounds__(DENSE_THREADS) void mix_dense_kernel(
                     const int row0 = 32 * rb + 8 * (v / 4) + (v & 3);             // uniform
                     const float *gb = gs + (int64_t)row0 * ld + col0;
                     if (FULL) {
-                        gv[sp][v] = gb[epi_lane_off];
+                        gv[sp][v] = *(const float *)(uniform_base(gb) + epi_lane_off);
                     } else {
                         const bool ok = row0 + 4 * (lane >> 5) < N && col0 + (lane & 31) < dcols;
-                        gv[sp][v] = ok ? gb[epi_lane_off] : 0.f;
+                        gv[sp][v] = ok ? *(const float *)(uniform_base(gb) + epi_lane_off) : 0.f;
                     }
                 }
             }
-        }
-
-        f32x16 acc[C::SPW];
-#pragma unroll
-        for (int sp = 0; sp < C::SPW; ++sp)
+        };
+        const float *bbase = &lds[buf * C::TILE + lane];
+        auto multiply = [&](int sp) {
+            const int s = cg * C::SPW + sp;
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[sp][v] = 0.f;
-
-        const float *bbase = &lds[buf * C::TILE + lane];
+            // B fragments come from LDS eight k-steps at a time, one group ahead of the multiplies;
+            // the scheduling barriers keep the compiler from requesting all of them up front,
+            // which would push the P block out of the registers
+            float bq[2][8];
 #pragma unroll
-        for (int kk = 0; kk < C::KB; ++kk) {
+            for (int j = 0; j < 8; ++j) bq[0][j] = bbase[(s * C::KB + j) * 64];
 #pragma unroll
-            for (int sp = 0; sp < C::SPW; ++sp) {
-                const int s = cg * C::SPW + sp;
-                const float b = bbase[(s * C::KB + kk) * 64];
-                acc[sp] = __builtin_amdgcn_mfma_f32_32x32x2f32(wreg[kk], b, acc[sp], 0, 0, 0);
+            for (int q = 0; q < C::KB / 8; ++q) {
+                if (q + 1 < C::KB / 8) {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) bq[(q + 1) & 1][j] = bbase[(s * C::KB + 8 * (q + 1) + j) * 64];
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    acc[sp] = __builtin_amdgcn_mfma_f32_32x32x2f32(wreg[8 * q + j], bq[q & 1][j], acc[sp], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
-        }
-
-        // the next tile is complete in LDS before anybody starts on it; the barrier sits
-        // before this tile's stores so that they drain while the next tile is multiplied
-        if (next < n_tiles && !DMA) commit(buf ^ 1);
-        if (DMA) __builtin_amdgcn_s_waitcnt(0);      // the tile written by global_load_lds has landed
-        __syncthreads();
-        buf ^= 1;
-
-        // epilogue: local SGD correction and store, 32 consecutive columns per row
-#pragma unroll
-        for (int sp = 0; sp < C::SPW; ++sp) {
+        };
+        // local SGD correction and store, 32 consecutive columns per row
+        auto epilogue = [&](int sp) {
             const int s = cg * C::SPW + sp;
             const int64_t col0 = tile * C::TC + 32 * s;
 #pragma unroll
@@ -192,9 +210,27 @@ __global__ __launch_bounds__(DENSE_THREADS) void mix_dense_kernel(
                     r = fmaf(-lr.at(FULL || row < N ? row : 0), gv[sp][v], r);
                 }
                 float *ob = out + (int64_t)row0 * ld + col0;
-                if (FULL || (row0 + 4 * (lane >> 5) < N && col0 + (lane & 31) < dcols)) ob[epi_lane_off] = r;
+                if (FULL || (row0 + 4 * (lane >> 5) < N && col0 + (lane & 31) < dcols)) *(float *)(const_cast<char *>(uniform_base(ob)) + epi_lane_off) = r;
             }
+        };
+
+        load_g(0);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int sp = 0; sp + 1 < C::SPW; ++sp) {
+            multiply(sp);
+            load_g(sp + 1);
+            epilogue(sp);
+            __builtin_amdgcn_sched_barrier(0);
         }
+        multiply(C::SPW - 1);
+
+        // the next tile is complete in LDS before anybody starts on it
+        if (next < n_tiles && !DMA) commit(buf ^ 1);
+        if (DMA) __builtin_amdgcn_s_waitcnt(0);      // the tile written by global_load_lds has landed
+        __syncthreads();
+        buf ^= 1;
+        epilogue(C::SPW - 1);
     }
 }
 
