@@ -356,7 +356,7 @@ int launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const int3
     }
     if (fast2) {
         dbw_timer tm(c, "conv2_forward", s);
-        hipLaunchKernelGGL((convlds::conv_forward_kernel<32, 4, 2, 16, 16, 5, 8>), dim3(B, N), dim3(512), 0, s,
+        hipLaunchKernelGGL((convlds::conv_forward_kernel<16, 4, 2, 16, 16, 5, 8>), dim3(B, N), dim3(512), 0, s,
                            A + L.p1, ws, params + L.w2, ld, L.C1 * KK, params + L.b2, ld, A + L.z2, ws, L.C1);
         DBW_HIP(hipGetLastError());
     } else {   // conv2 forward
@@ -431,7 +431,7 @@ int launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const int3
             DBW_HIP(hipGetLastError());
         }
         dbw_timer tm(c, "conv2_dgrad", s);
-        hipLaunchKernelGGL((convlds::conv_forward_kernel<32, 2, 2, 16, 16, 5, 8>), dim3(B, N), dim3(512), 0, s,
+        hipLaunchKernelGGL((convlds::conv_forward_kernel<16, 2, 2, 16, 16, 5, 8>), dim3(B, N), dim3(512), 0, s,
                            A + L.dz2, ws, A + L.wflip, ws, L.C2 * KK, (const float *)nullptr, (int64_t)0, A + L.dp1,
                            ws, L.C2);
         DBW_HIP(hipGetLastError());

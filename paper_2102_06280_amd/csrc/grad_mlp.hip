@@ -9,6 +9,7 @@
 #include <algorithm>
 
 #include "bgemm.h"
+#include "fc_batch32.h"
 #include "dbw_internal.h"
 
 namespace {
@@ -125,13 +126,22 @@ __global__ __launch_bounds__(256) void fc_reduce_kernel(const float *__restrict_
 // A long reduction with few output tiles (e.g. batch 32 x 512 outputs over k = 4096, or any
 // small model) leaves most of the chip idle and each workgroup waiting on its own chain of
 // loads; split k then, up to MAX_SPLITS ways, keeping at least two k-steps per split.
-constexpr int MAX_SPLITS = 8;
+constexpr int MAX_SPLITS = 16;          // partial-sum slots per output in the scratch block
+constexpr int GEMM_MAX_SPLITS = 8;
 int forward_splits(int M, int N, int K, int workers)
 {
     const int64_t tiles = (int64_t)((M + 63) / 64) * ((N + 63) / 64) * workers;
     int splits = 1;
-    while (splits < MAX_SPLITS && tiles * splits < 2048 && K / (splits * 2) >= 2 * bgemm::BK) splits *= 2;
+    while (splits < GEMM_MAX_SPLITS && tiles * splits < 2048 && K / (splits * 2) >= 2 * bgemm::BK) splits *= 2;
     return splits;
+}
+
+// The streaming kernels for a batch of exactly 32 apply to a layer in -> out when the shapes
+// divide evenly and every operand row starts on a 16-byte boundary.
+bool batch32_layer(int B, int in, int out, int64_t ld_params, int64_t w_off, const float *params, const float *grads)
+{
+    return B == 32 && in % 512 == 0 && out % 32 == 0 && ld_params % 4 == 0 && w_off % 4 == 0 &&
+           fc32::aligned16(params) && fc32::aligned16(grads);
 }
 
 int64_t act_floats(int L, const int32_t *dims, int B)
@@ -179,6 +189,38 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
         else
             A = {act + a_off[l - 1], dims[l - 1], wstride};
         Bm = {params + w_off[l], dims[l - 1], c->ld};
+        if (batch32_layer(B, dims[l - 1], dims[l], c->ld, w_off[l], params, grads) && A.ld % 4 == 0 &&
+            A.stride % 4 == 0 && fc32::aligned16(A.p) && wstride % 4 == 0 && a_off[l] % 4 == 0 && fc32::aligned16(act)) {
+            const int slices = dims[l - 1] / fc32::KSLICE, nf = dims[l] / 128;
+            if (dims[l] % 128 == 0 && nf <= 4 && slices <= MAX_SPLITS) {      // split along k, inputs read once
+                float *part = act + 2 * per;
+                {
+                    dbw_timer tm(c, "fc32_forward", s);
+                    const dim3 grid(slices, N), block(fc32::THREADS);
+                    const float *Wl = params + w_off[l];
+                    switch (nf) {
+                    case 1: hipLaunchKernelGGL(fc32::forward_ksplit_kernel<1>, grid, block, 0, s, dims[l - 1], A.p, A.ld, A.stride, Wl, c->ld, part, wstride); break;
+                    case 2: hipLaunchKernelGGL(fc32::forward_ksplit_kernel<2>, grid, block, 0, s, dims[l - 1], A.p, A.ld, A.stride, Wl, c->ld, part, wstride); break;
+                    case 3: hipLaunchKernelGGL(fc32::forward_ksplit_kernel<3>, grid, block, 0, s, dims[l - 1], A.p, A.ld, A.stride, Wl, c->ld, part, wstride); break;
+                    default: hipLaunchKernelGGL(fc32::forward_ksplit_kernel<4>, grid, block, 0, s, dims[l - 1], A.p, A.ld, A.stride, Wl, c->ld, part, wstride); break;
+                    }
+                    DBW_HIP(hipGetLastError());
+                }
+                dbw_timer tm(c, "fc_reduce_kernel", s);
+                hipLaunchKernelGGL(fc_reduce_kernel, dim3((B * dims[l] + 255) / 256, N), dim3(256), 0, s, part, wstride,
+                                   slices, B, dims[l], params + b_off[l], c->ld, l < L ? 1 : 0, act + a_off[l],
+                                   (int64_t)dims[l], wstride);
+                DBW_HIP(hipGetLastError());
+                continue;
+            }
+            const int blocks = (N + fc32::XCDS - 1) / fc32::XCDS * fc32::XCDS * (dims[l] / 32);
+            dbw_timer tm(c, "fc32_forward", s);
+            hipLaunchKernelGGL(fc32::forward_kernel, dim3(blocks), dim3(fc32::THREADS), 0, s, N, dims[l], dims[l - 1],
+                               A.p, A.ld, A.stride, params + w_off[l], c->ld, params + b_off[l], c->ld, l < L ? 1 : 0,
+                               act + a_off[l], (int64_t)dims[l], wstride);
+            DBW_HIP(hipGetLastError());
+            continue;
+        }
         const int splits = forward_splits(B, dims[l], dims[l - 1], N);
         if (splits > 1) {
             float *part = act + 2 * per;
@@ -211,15 +253,25 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
     }
     // backward
     for (int l = L; l >= 1; --l) {
+        const bool fast = batch32_layer(B, dims[l - 1], dims[l], c->ld, w_off[l], params, grads) && wstride % 4 == 0 &&
+                          dz_off[l] % 4 == 0 && fc32::aligned16(act);
         {   // dW_l = dz_l^T a_{l-1}
             Dense<false> A{act + dz_off[l], dims[l], wstride}, Bm;
             if (l == 1)
                 Bm = {a.in, a.in_ld, a.in_stride};
             else
                 Bm = {act + a_off[l - 1], dims[l - 1], wstride};
+            if (fast && Bm.ld % 4 == 0 && Bm.stride % 4 == 0 && fc32::aligned16(Bm.p)) {
+                dbw_timer tm(c, "fc32_wgrad", s);
+                hipLaunchKernelGGL(fc32::wgrad_kernel, dim3(dims[l - 1] / 512, dims[l] / 32, N), dim3(fc32::THREADS), 0, s,
+                                   dims[l], dims[l - 1], act + dz_off[l], (int64_t)dims[l], wstride, Bm.p, Bm.ld, Bm.stride,
+                                   grads + w_off[l], c->ld);
+                DBW_HIP(hipGetLastError());
+            } else {
             Epilogue E{grads + w_off[l], dims[l - 1], c->ld, nullptr, 0, nullptr, 0, 0, 0};
             dbw_timer tm(c, "mlp_wgrad_gemm", s);
             DBW_HIP(bgemm::launch<64>(A, Bm, E, dims[l], dims[l - 1], B, N, s));
+            }
         }
         {
             dbw_timer tm(c, "colsum_kernel", s);
@@ -227,7 +279,20 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
                                act + dz_off[l], wstride, grads + b_off[l], c->ld);
             DBW_HIP(hipGetLastError());
         }
-        if (l > 1) {   // dz_{l-1} = (dz_l W_l) masked by a_{l-1} > 0
+        if (l > 1 && fast && a_off[l - 1] % 4 == 0 && dz_off[l - 1] % 4 == 0) {
+            dbw_timer tm(c, "fc32_dgrad", s);
+            hipLaunchKernelGGL(fc32::dgrad_kernel, dim3(dims[l - 1] / 128, N), dim3(fc32::THREADS), 0, s, dims[l],
+                               dims[l - 1], act + dz_off[l], (int64_t)dims[l], wstride, params + w_off[l], c->ld,
+                               act + a_off[l - 1], (int64_t)dims[l - 1], wstride, act + dz_off[l - 1],
+                               (int64_t)dims[l - 1], wstride);
+            DBW_HIP(hipGetLastError());
+        } else if (l == 1 && a.din && fast && a.din_ld % 4 == 0 && a.din_stride % 4 == 0 && fc32::aligned16(a.din)) {
+            dbw_timer tm(c, "fc32_dgrad", s);
+            hipLaunchKernelGGL(fc32::dgrad_kernel, dim3(dims[0] / 128, N), dim3(fc32::THREADS), 0, s, dims[1], dims[0],
+                               act + dz_off[1], (int64_t)dims[1], wstride, params + w_off[1], c->ld,
+                               (const float *)nullptr, (int64_t)0, (int64_t)0, a.din, a.din_ld, a.din_stride);
+            DBW_HIP(hipGetLastError());
+        } else if (l > 1) {   // dz_{l-1} = (dz_l W_l) masked by a_{l-1} > 0
             Dense<true> A{act + dz_off[l], dims[l], wstride};
             Dense<false> Bm{params + w_off[l], dims[l - 1], c->ld};
             Epilogue E{act + dz_off[l - 1], dims[l - 1], wstride, nullptr, 0, act + a_off[l - 1], dims[l - 1],

@@ -23,9 +23,15 @@ def _cnn(cfg, desc):
     conv2 = 2 * B * (h // 2) * (w // 2) * c2 * c1 * k * k
     flat = c2 * (h // 4) * (w // 4)
     fc = [2 * B * flat * f, 2 * B * f * nc]
-    return {"conv1_forward": n * conv1, "conv1_wgrad": n * conv1,
-            "conv2_forward": n * conv2, "conv2_wgrad": n * conv2, "conv2_dgrad": n * conv2,
-            "mlp_forward_gemm": n * sum(fc) / 2, "mlp_wgrad_gemm": n * sum(fc) / 2, "mlp_dgrad_gemm": n * sum(fc) / 2}
+    table = {"conv1_forward": n * conv1, "conv1_wgrad": n * conv1,
+             "conv2_forward": n * conv2, "conv2_wgrad": n * conv2, "conv2_dgrad": n * conv2}
+    if B == 32 and flat % 512 == 0 and f % 32 == 0:      # the first FC layer runs on the batch-32 kernels
+        table.update({"fc32_forward": n * fc[0], "fc32_wgrad": n * fc[0], "fc32_dgrad": n * fc[0],
+                      "mlp_forward_gemm": n * fc[1], "mlp_wgrad_gemm": n * fc[1], "mlp_dgrad_gemm": n * fc[1]})
+    else:
+        table.update({"mlp_forward_gemm": n * sum(fc) / 2, "mlp_wgrad_gemm": n * sum(fc) / 2,
+                      "mlp_dgrad_gemm": n * sum(fc) / 2})
+    return table
 
 
 def kernel_flops(cfg, kernel_name: str) -> float:
