@@ -48,10 +48,16 @@ struct Cfg {
 // in  [worker][B][Cin][H][W]   (worker stride in_stride)
 // wgt [worker][COUT][ldw]      (row co holds its Cin * KK filter taps, worker stride w_stride)
 // out [worker][B][COUT][H][W]  (worker stride out_stride);  grid = (B, workers)
-template <int CG, int MT, int NT, int H, int W, int KS, int WAVES>
+// POOL: the epilogue applies ReLU and 2 x 2 max pooling and writes out [worker][B][COUT][H/2][W/2]
+// together with code [worker][B][COUT][H/2][W/2] (one byte: which element of the window, in the
+// order (0,0) (0,1) (1,0) (1,1), was the first to attain the maximum, or 4 when the maximum is
+// not positive); the pre-activation map is not written at all.  A wave's fragments cover whole
+// pairs of image rows, so a window is two accumulators of one lane and of its neighbour.
+template <int CG, int MT, int NT, int H, int W, int KS, int WAVES, bool POOL = false>
 __global__ __launch_bounds__(64 * WAVES) void conv_forward_kernel(
     const float *__restrict__ in, int64_t in_stride, const float *__restrict__ wgt, int64_t w_stride, int ldw,
-    const float *__restrict__ bias, int64_t bias_stride, float *__restrict__ out, int64_t out_stride, int Cin)
+    const float *__restrict__ bias, int64_t bias_stride, float *__restrict__ out, int64_t out_stride, int Cin,
+    uint8_t *__restrict__ code = nullptr, int64_t code_stride = 0)
 {
     using C = Cfg<CG, MT, NT, H, W, KS, WAVES>;
     __shared__ __attribute__((aligned(16))) float img[C::IMG];
@@ -144,6 +150,37 @@ __global__ __launch_bounds__(64 * WAVES) void conv_forward_kernel(
         }
     }
 
+    if (POOL) {
+        constexpr int FR = W / 16;                       // fragments per image row
+        static_assert(!POOL || ((NT * 16) % (2 * W) == 0 && H % 2 == 0), "a wave must cover whole pairs of rows");
+        constexpr int PP = (H / 2) * (W / 2);
+        float *ob = out + w * out_stride + (int64_t)b * C::COUT * PP;
+        uint8_t *cb = code + w * code_stride + (int64_t)b * C::COUT * PP;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int co = 16 * mt + 4 * (lane >> 4) + v;
+                const float bv = bias ? bias[w * bias_stride + co] : 0.f;
+#pragma unroll
+                for (int nf = 0; nf < NT; ++nf) {
+                    if ((nf / FR) % 2) continue;         // lower row of a pair: handled with the upper one
+                    const int p = (wave * NT + nf) * 16 + (lane & 15);
+                    const int y = p / W, x = p % W;
+                    const float a = acc[mt][nf][v] + bv, c = acc[mt][nf + FR][v] + bv;
+                    const float a1 = __shfl_xor(a, 1), c1 = __shfl_xor(c, 1);
+                    if ((lane & 1) == 0) {               // even x: window (y, x) (y, x+1) (y+1, x) (y+1, x+1)
+                        const float m = fmaxf(fmaxf(a, a1), fmaxf(c, c1));
+                        int arg = 4;
+                        if (m > 0.f) arg = (a == m) ? 0 : (a1 == m) ? 1 : (c == m) ? 2 : 3;
+                        const int o = co * PP + (y / 2) * (W / 2) + x / 2;
+                        ob[o] = fmaxf(m, 0.f);
+                        cb[o] = (uint8_t)arg;
+                    }
+                }
+            }
+        return;
+    }
     float *ob = out + w * out_stride + (int64_t)b * C::COUT * C::PIX;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)

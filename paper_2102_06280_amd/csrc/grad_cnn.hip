@@ -238,6 +238,48 @@ __global__ __launch_bounds__(256) void relu_pool_bwd_kernel(const float *__restr
     dz[base + W + 1] = arg == 3 ? gsrc : 0.f;
 }
 
+// The same backward step from the window codes written by the fused convolution epilogue
+// (0..3: position of the first maximum, 4: maximum not positive); z is not needed.
+__global__ __launch_bounds__(256) void pool_bwd_code_kernel(const uint8_t *__restrict__ code, int64_t cstride,
+                                                            const float *__restrict__ dp, int64_t pstride,
+                                                            float *__restrict__ dz, int64_t zstride, int planes, int H,
+                                                            int W)
+{
+    const int w = blockIdx.y;
+    const int Ho = H / 2, Wo = W / 2, total = planes * Ho * Wo;
+    const int o = blockIdx.x * 256 + threadIdx.x;
+    if (o >= total) return;
+    const int pl = o / (Ho * Wo), rem = o - pl * Ho * Wo, oh = rem / Wo, ow = rem - oh * Wo;
+    const int64_t base = w * zstride + ((int64_t)pl * H + 2 * oh) * W + 2 * ow;
+    const int arg = code[w * cstride + o];
+    const float gsrc = dp[w * pstride + o];
+    *(float2 *)&dz[base] = make_float2(arg == 0 ? gsrc : 0.f, arg == 1 ? gsrc : 0.f);
+    *(float2 *)&dz[base + W] = make_float2(arg == 2 ? gsrc : 0.f, arg == 3 ? gsrc : 0.f);
+}
+
+// db[ch] = sum of dz over batch and pixels = sum of the pooled gradients of the windows whose
+// maximum was positive (each passes its gradient to exactly one pixel): a quarter of the reads.
+__global__ __launch_bounds__(256) void channel_sum_code_kernel(const uint8_t *__restrict__ code, int64_t cstride,
+                                                               const float *__restrict__ dp, int64_t pstride, int B,
+                                                               int C, int HWo, float *__restrict__ db, int64_t dbstride)
+{
+    __shared__ float red[256];
+    const int ch = blockIdx.x, w = blockIdx.y, tid = threadIdx.x;
+    float s = 0.f;
+    for (int i = tid; i < B * HWo; i += 256) {
+        const int b = i / HWo, hw = i - b * HWo;
+        const int64_t o = (int64_t)(b * C + ch) * HWo + hw;
+        s += code[w * cstride + o] < 4 ? dp[w * pstride + o] : 0.f;
+    }
+    red[tid] = s;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if (tid < o) red[tid] += red[tid + o];
+        __syncthreads();
+    }
+    if (tid == 0) db[w * dbstride + ch] = red[0];
+}
+
 // db[ch] = sum over batch and pixels of dz[b][ch][hw]; one workgroup per (channel, worker).
 __global__ __launch_bounds__(256) void channel_sum_kernel(const float *__restrict__ dz, int64_t stride, int B, int C,
                                                           int HW, float *__restrict__ db, int64_t dbstride)
@@ -267,7 +309,7 @@ struct cnn_layout {
     // parameter offsets inside a row
     int64_t w1, b1, w2, b2, fc;
     // scratch offsets inside a worker's block (floats)
-    int64_t z1, p1, z2, p2, dp2, dz2, dp1, dz1, fc_act, part, wflip, total;
+    int64_t z1, p1, z2, p2, dp2, dz2, dp1, dz1, fc_act, part, wflip, code1, code2, total;
     int splits1, splits2;
 };
 
@@ -307,6 +349,8 @@ cnn_layout make_layout(const dbw_model &m)
     const int64_t p1n = s1 * L.C1 * L.C0 * KK, p2n = s2 * L.C2 * L.C1 * KK;
     L.part = take(p1n > p2n ? p1n : p2n);
     L.wflip = take((int64_t)L.C1 * L.C2 * KK);
+    L.code1 = take((B * L.C1 * L.H2 * L.W2 + 3) / 4);     // one byte per pooled element
+    L.code2 = take((B * L.flat + 3) / 4);
     L.total = o;
     return L;
 }
@@ -337,10 +381,12 @@ int launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const int3
     const bool fast1 = KS_ == 5 && L.C0 == 3 && L.H == 32 && L.W == 32 && L.C1 == 32 && (uintptr_t)bx % 16 == 0;
     const bool fast2 = KS_ == 5 && L.C1 == 32 && L.H2 == 16 && L.W2 == 16 && L.C2 == 64;
 
-    if (fast1) {
+    uint8_t *code1 = (uint8_t *)(A + L.code1), *code2 = (uint8_t *)(A + L.code2);
+    const int64_t cs = ws * 4;                         // worker stride of the code maps in bytes
+    if (fast1) {   // convolution + ReLU + pooling in one kernel
         dbw_timer tm(c, "conv1_forward", s);
-        hipLaunchKernelGGL((convlds::conv_forward_kernel<3, 2, 8, 32, 32, 5, 8>), dim3(B, N), dim3(512), 0, s, bx,
-                           xstride, params + L.w1, ld, L.C0 * KK, params + L.b1, ld, A + L.z1, ws, L.C0);
+        hipLaunchKernelGGL((convlds::conv_forward_kernel<3, 2, 8, 32, 32, 5, 8, true>), dim3(B, N), dim3(512), 0, s, bx,
+                           xstride, params + L.w1, ld, L.C0 * KK, params + L.b1, ld, A + L.p1, ws, L.C0, code1, cs);
         DBW_HIP(hipGetLastError());
     } else {   // conv1 forward
         dbw_timer tm(c, "conv1_forward", s);
@@ -348,7 +394,7 @@ int launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const int3
                               ChannelPixelOut{A + L.z1, ws, L.C1, L.H * L.W, params + L.b1, ld}, L.C1, pix1,
                               L.C0 * KK, N, s));
     }
-    {
+    if (!fast1) {
         dbw_timer tm(c, "relu_pool_fwd_kernel", s);
         hipLaunchKernelGGL(relu_pool_fwd_kernel, dim3(blocks((int64_t)B * L.C1 * L.H2 * L.W2), N), dim3(256), 0, s,
                            A + L.z1, ws, A + L.p1, ws, B * L.C1, L.H, L.W);
@@ -356,8 +402,8 @@ int launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const int3
     }
     if (fast2) {
         dbw_timer tm(c, "conv2_forward", s);
-        hipLaunchKernelGGL((convlds::conv_forward_kernel<16, 4, 2, 16, 16, 5, 8>), dim3(B, N), dim3(512), 0, s,
-                           A + L.p1, ws, params + L.w2, ld, L.C1 * KK, params + L.b2, ld, A + L.z2, ws, L.C1);
+        hipLaunchKernelGGL((convlds::conv_forward_kernel<16, 4, 2, 16, 16, 5, 8, true>), dim3(B, N), dim3(512), 0, s,
+                           A + L.p1, ws, params + L.w2, ld, L.C1 * KK, params + L.b2, ld, A + L.p2, ws, L.C1, code2, cs);
         DBW_HIP(hipGetLastError());
     } else {   // conv2 forward
         dbw_timer tm(c, "conv2_forward", s);
@@ -365,7 +411,7 @@ int launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const int3
                               ChannelPixelOut{A + L.z2, ws, L.C2, L.H2 * L.W2, params + L.b2, ld}, L.C2, pix2,
                               L.C1 * KK, N, s));
     }
-    {
+    if (!fast2) {
         dbw_timer tm(c, "relu_pool_fwd_kernel", s);
         hipLaunchKernelGGL(relu_pool_fwd_kernel, dim3(blocks((int64_t)B * L.flat), N), dim3(256), 0, s, A + L.z2, ws,
                            A + L.p2, ws, B * L.C2, L.H2, L.W2);
@@ -392,7 +438,12 @@ int launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const int3
         const int rc = dbw_fc_forward_backward(c, a, s);
         if (rc != DBW_OK) return rc;
     }
-    {
+    if (fast2) {
+        dbw_timer tm(c, "pool_bwd_code_kernel", s);
+        hipLaunchKernelGGL(pool_bwd_code_kernel, dim3(blocks((int64_t)B * L.flat), N), dim3(256), 0, s, code2, cs,
+                           A + L.dp2, ws, A + L.dz2, ws, B * L.C2, L.H2, L.W2);
+        DBW_HIP(hipGetLastError());
+    } else {
         dbw_timer tm(c, "relu_pool_bwd_kernel", s);
         hipLaunchKernelGGL(relu_pool_bwd_kernel, dim3(blocks((int64_t)B * L.flat), N), dim3(256), 0, s, A + L.z2, ws,
                            A + L.dp2, ws, A + L.dz2, B * L.C2, L.H2, L.W2);
@@ -417,7 +468,12 @@ int launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const int3
                            A + L.part, ws, splits2, L.C2 * L.C1 * KK, grads + L.w2, ld);
         DBW_HIP(hipGetLastError());
     }
-    {
+    if (fast2) {
+        dbw_timer tm(c, "channel_sum_code_kernel", s);
+        hipLaunchKernelGGL(channel_sum_code_kernel, dim3(L.C2, N), dim3(256), 0, s, code2, cs, A + L.dp2, ws, B, L.C2,
+                           L.H4 * L.W4, grads + L.b2, ld);
+        DBW_HIP(hipGetLastError());
+    } else {
         dbw_timer tm(c, "channel_sum_kernel", s);
         hipLaunchKernelGGL(channel_sum_kernel, dim3(L.C2, N), dim3(256), 0, s, A + L.dz2, ws, B, L.C2, L.H2 * L.W2,
                            grads + L.b2, ld);
@@ -441,7 +497,12 @@ int launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const int3
                               ChannelPixelOut{A + L.dp1, ws, L.C1, L.H2 * L.W2, nullptr, 0}, L.C1, pix2, L.C2 * KK, N,
                               s));
     }
-    {
+    if (fast1) {
+        dbw_timer tm(c, "pool_bwd_code_kernel", s);
+        hipLaunchKernelGGL(pool_bwd_code_kernel, dim3(blocks((int64_t)B * L.C1 * L.H2 * L.W2), N), dim3(256), 0, s, code1,
+                           cs, A + L.dp1, ws, A + L.dz1, ws, B * L.C1, L.H, L.W);
+        DBW_HIP(hipGetLastError());
+    } else {
         dbw_timer tm(c, "relu_pool_bwd_kernel", s);
         hipLaunchKernelGGL(relu_pool_bwd_kernel, dim3(blocks((int64_t)B * L.C1 * L.H2 * L.W2), N), dim3(256), 0, s,
                            A + L.z1, ws, A + L.dp1, ws, A + L.dz1, B * L.C1, L.H, L.W);
@@ -466,7 +527,12 @@ int launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const int3
                            A + L.part, ws, splits1, L.C1 * L.C0 * KK, grads + L.w1, ld);
         DBW_HIP(hipGetLastError());
     }
-    {
+    if (fast1) {
+        dbw_timer tm(c, "channel_sum_code_kernel", s);
+        hipLaunchKernelGGL(channel_sum_code_kernel, dim3(L.C1, N), dim3(256), 0, s, code1, cs, A + L.dp1, ws, B, L.C1,
+                           L.H2 * L.W2, grads + L.b1, ld);
+        DBW_HIP(hipGetLastError());
+    } else {
         dbw_timer tm(c, "channel_sum_kernel", s);
         hipLaunchKernelGGL(channel_sum_kernel, dim3(L.C1, N), dim3(256), 0, s, A + L.dz1, ws, B, L.C1, L.H * L.W,
                            grads + L.b1, ld);
