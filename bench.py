@@ -28,7 +28,7 @@ MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix
 # HBM bytes per launch from hardware counters (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors
 # from a plain copy of known size; profiles/ holds the runs).  Keyed by (kernel, config);
 # an entry is removed when its kernel changes.
-MEASURED_TRAFFIC = {("mix_tile_major", 4): 17.203e9, ("mix_lds_tiles", 4): 17.203e9}
+MEASURED_TRAFFIC = {("mix_tile_major", 4): 17.203e9, ("mix_lds_tiles", 4): 17.203e9, ("mix_dense_kernel", 5): 3.074e9}
 
 
 def cpu_baseline(cid: int, wl_rowptr, wl_colidx, budget_s: float = 15.0):
