@@ -27,6 +27,19 @@ namespace convlds {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 
+// Four horizontally adjacent pixels (x = 4 x4 .. 4 x4 + 3 of image row y) of a map that is stored
+// as its 2 x 2 max-pooled gradient plus the window codes written by the POOL epilogue: a pixel
+// holds the pooled gradient of its window if it was the window's first maximum, else zero.
+// `pooled` / `code` point at the plane [H/2][W/2] of one (sample, channel).
+__device__ __forceinline__ float4 expand_pooled(const float *pooled, const uint8_t *code, int y, int x4, int W)
+{
+    const int o = (y >> 1) * (W >> 1) + 2 * x4;
+    const float2 g = *(const float2 *)&pooled[o];
+    const uint32_t c = *(const uint16_t *)&code[o];
+    const uint32_t c0 = c & 0xffu, c1 = c >> 8, pos = (uint32_t)(y & 1) * 2u;
+    return make_float4(c0 == pos ? g.x : 0.f, c0 == pos + 1 ? g.x : 0.f, c1 == pos ? g.y : 0.f, c1 == pos + 1 ? g.y : 0.f);
+}
+
 // CG: input channels per LDS fill; MT: 16-row output-channel fragments (all held by every
 // wave); NT: 16-pixel fragments per wave; WAVES * NT * 16 = H * W pixels per sample.
 template <int CG, int MT, int NT, int H, int W, int KS, int WAVES>
@@ -53,11 +66,15 @@ struct Cfg {
 // order (0,0) (0,1) (1,0) (1,1), was the first to attain the maximum, or 4 when the maximum is
 // not positive); the pre-activation map is not written at all.  A wave's fragments cover whole
 // pairs of image rows, so a window is two accumulators of one lane and of its neighbour.
-template <int CG, int MT, int NT, int H, int W, int KS, int WAVES, bool POOL = false>
+// EXPAND: the input is given as in [worker][B][Cin][H/2][W/2] (pooled gradients) with in_code of the same
+// shape and is expanded to [Cin][H][W] while it is copied into LDS (see expand_pooled): the data-gradient
+// convolution then needs no un-pooled delta map in memory.
+template <int CG, int MT, int NT, int H, int W, int KS, int WAVES, bool POOL = false, bool EXPAND = false>
 __global__ __launch_bounds__(64 * WAVES) void conv_forward_kernel(
     const float *__restrict__ in, int64_t in_stride, const float *__restrict__ wgt, int64_t w_stride, int ldw,
     const float *__restrict__ bias, int64_t bias_stride, float *__restrict__ out, int64_t out_stride, int Cin,
-    uint8_t *__restrict__ code = nullptr, int64_t code_stride = 0)
+    uint8_t *__restrict__ code = nullptr, int64_t code_stride = 0, const uint8_t *__restrict__ in_code = nullptr,
+    int64_t in_code_stride = 0)
 {
     using C = Cfg<CG, MT, NT, H, W, KS, WAVES>;
     __shared__ __attribute__((aligned(16))) float img[C::IMG];
@@ -86,7 +103,8 @@ __global__ __launch_bounds__(64 * WAVES) void conv_forward_kernel(
 #pragma unroll
         for (int nf = 0; nf < NT; ++nf) acc[mt][nf] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const float *inb = in + w * in_stride + (int64_t)b * Cin * C::PIX;
+    const float *inb = in + w * in_stride + (int64_t)b * Cin * (EXPAND ? C::PIX / 4 : C::PIX);
+    const uint8_t *icb = EXPAND ? in_code + w * in_code_stride + (int64_t)b * Cin * (C::PIX / 4) : nullptr;
     const float *ww = wgt + w * w_stride;
     const int groups = (Cin + CG - 1) / CG;
 
@@ -113,7 +131,12 @@ __global__ __launch_bounds__(64 * WAVES) void conv_forward_kernel(
             const int c = e / (H * (W / 4)), rem = e % (H * (W / 4)), y = rem / (W / 4), x4 = rem % (W / 4);
             const int ch = g * CG + c;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (ch < Cin) v = *(const float4 *)&inb[(ch * H + y) * W + 4 * x4];
+            if (ch < Cin) {
+                if (EXPAND)
+                    v = expand_pooled(inb + ch * (C::PIX / 4), icb + ch * (C::PIX / 4), y, x4, W);
+                else
+                    v = *(const float4 *)&inb[(ch * H + y) * W + 4 * x4];
+            }
             float *dst = &img[c * C::HP * C::WP + (y + C::PAD) * C::WP + C::PAD + 4 * x4];
             dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
         }
@@ -231,10 +254,13 @@ struct WCfg {
     static constexpr size_t lds_bytes = sizeof(float) * (IMG + COUT * LDD);
 };
 
-template <int CIN, int MT, int NT, int WM, int WN, int WK, int H, int W, int KS, int PC>
+// EXPAND: dz is given as the pooled gradients [worker][B][COUT][H/2][W/2] with dz_code of the same shape
+// and is expanded while the delta tile is copied into LDS (see expand_pooled).
+template <int CIN, int MT, int NT, int WM, int WN, int WK, int H, int W, int KS, int PC, bool EXPAND = false>
 __global__ __launch_bounds__(64 * WM * WN * WK) void conv_wgrad_kernel(
     const float *__restrict__ in, int64_t in_stride, const float *__restrict__ dz, int64_t dz_stride,
-    float *__restrict__ part, int64_t part_stride, int B, int SB)
+    float *__restrict__ part, int64_t part_stride, int B, int SB, const uint8_t *__restrict__ dz_code = nullptr,
+    int64_t dz_code_stride = 0)
 {
     using C = WCfg<CIN, MT, NT, WM, WN, WK, H, W, KS, PC>;
     __shared__ __attribute__((aligned(16))) float img[C::IMG];
@@ -263,7 +289,8 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void conv_wgrad_kernel(
 
     for (int b = b0; b < b1; ++b) {
         const float *inb = in + w * in_stride + (int64_t)b * CIN * C::PIX;
-        const float *dzb = dz + w * dz_stride + (int64_t)b * C::COUT * C::PIX;
+        const float *dzb = dz + w * dz_stride + (int64_t)b * C::COUT * (EXPAND ? C::PIX / 4 : C::PIX);
+        const uint8_t *dcb = EXPAND ? dz_code + w * dz_code_stride + (int64_t)b * C::COUT * (C::PIX / 4) : nullptr;
         for (int chunk = 0; chunk < C::PIX / PC; ++chunk) {
             __syncthreads();                   // previous tile fully consumed
             if (chunk == 0) {
@@ -276,7 +303,14 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void conv_wgrad_kernel(
             }
             for (int e = tid; e < C::COUT * (PC / 4); e += C::THREADS) {
                 const int co = e / (PC / 4), p4 = e % (PC / 4);
-                *(float4 *)&dzs[co * C::LDD + 4 * p4] = *(const float4 *)&dzb[co * C::PIX + chunk * PC + 4 * p4];
+                float4 v;
+                if (EXPAND) {
+                    const int p = chunk * PC + 4 * p4;
+                    v = expand_pooled(dzb + co * (C::PIX / 4), dcb + co * (C::PIX / 4), p / W, (p % W) / 4, W);
+                } else {
+                    v = *(const float4 *)&dzb[co * C::PIX + chunk * PC + 4 * p4];
+                }
+                *(float4 *)&dzs[co * C::LDD + 4 * p4] = v;
             }
             __syncthreads();
             const int chunk_row = chunk * (PC / W);                  // first image row of the chunk

@@ -238,27 +238,9 @@ __global__ __launch_bounds__(256) void relu_pool_bwd_kernel(const float *__restr
     dz[base + W + 1] = arg == 3 ? gsrc : 0.f;
 }
 
-// The same backward step from the window codes written by the fused convolution epilogue
-// (0..3: position of the first maximum, 4: maximum not positive); z is not needed.
-__global__ __launch_bounds__(256) void pool_bwd_code_kernel(const uint8_t *__restrict__ code, int64_t cstride,
-                                                            const float *__restrict__ dp, int64_t pstride,
-                                                            float *__restrict__ dz, int64_t zstride, int planes, int H,
-                                                            int W)
-{
-    const int w = blockIdx.y;
-    const int Ho = H / 2, Wo = W / 2, total = planes * Ho * Wo;
-    const int o = blockIdx.x * 256 + threadIdx.x;
-    if (o >= total) return;
-    const int pl = o / (Ho * Wo), rem = o - pl * Ho * Wo, oh = rem / Wo, ow = rem - oh * Wo;
-    const int64_t base = w * zstride + ((int64_t)pl * H + 2 * oh) * W + 2 * ow;
-    const int arg = code[w * cstride + o];
-    const float gsrc = dp[w * pstride + o];
-    *(float2 *)&dz[base] = make_float2(arg == 0 ? gsrc : 0.f, arg == 1 ? gsrc : 0.f);
-    *(float2 *)&dz[base + W] = make_float2(arg == 2 ? gsrc : 0.f, arg == 3 ? gsrc : 0.f);
-}
-
-// db[ch] = sum of dz over batch and pixels = sum of the pooled gradients of the windows whose
-// maximum was positive (each passes its gradient to exactly one pixel): a quarter of the reads.
+// With the window codes of the fused convolution epilogue (0..3: position of the first maximum,
+// 4: maximum not positive): db[ch] = sum of dz over batch and pixels = sum of the pooled gradients
+// of the windows whose maximum was positive (each passes its gradient to exactly one pixel).
 __global__ __launch_bounds__(256) void channel_sum_code_kernel(const uint8_t *__restrict__ code, int64_t cstride,
                                                                const float *__restrict__ dp, int64_t pstride, int B,
                                                                int C, int HWo, float *__restrict__ db, int64_t dbstride)
@@ -438,12 +420,9 @@ int launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const int3
         const int rc = dbw_fc_forward_backward(c, a, s);
         if (rc != DBW_OK) return rc;
     }
-    if (fast2) {
-        dbw_timer tm(c, "pool_bwd_code_kernel", s);
-        hipLaunchKernelGGL(pool_bwd_code_kernel, dim3(blocks((int64_t)B * L.flat), N), dim3(256), 0, s, code2, cs,
-                           A + L.dp2, ws, A + L.dz2, ws, B * L.C2, L.H2, L.W2);
-        DBW_HIP(hipGetLastError());
-    } else {
+    // with the fused pooling the un-pooled delta maps are never materialised: their consumers
+    // expand the pooled gradients and the window codes on the fly
+    if (!fast2) {
         dbw_timer tm(c, "relu_pool_bwd_kernel", s);
         hipLaunchKernelGGL(relu_pool_bwd_kernel, dim3(blocks((int64_t)B * L.flat), N), dim3(256), 0, s, A + L.z2, ws,
                            A + L.dp2, ws, A + L.dz2, B * L.C2, L.H2, L.W2);
@@ -453,8 +432,8 @@ int launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const int3
     if (fast2) {
         splits2 = (B + WGRAD_SB - 1) / WGRAD_SB;
         dbw_timer tm(c, "conv2_wgrad", s);
-        hipLaunchKernelGGL((convlds::conv_wgrad_kernel<32, 2, 13, 2, 4, 1, 16, 16, 5, 256>), dim3(splits2, N), dim3(512),
-                           0, s, A + L.p1, ws, A + L.dz2, ws, A + L.part, ws, B, WGRAD_SB);
+        hipLaunchKernelGGL((convlds::conv_wgrad_kernel<32, 2, 13, 2, 4, 1, 16, 16, 5, 256, true>), dim3(splits2, N),
+                           dim3(512), 0, s, A + L.p1, ws, A + L.dp2, ws, A + L.part, ws, B, WGRAD_SB, code2, cs);
         DBW_HIP(hipGetLastError());
     } else {   // conv2 weight gradient (split over pixels, then summed in split order) and bias gradient
         dbw_timer tm(c, "conv2_wgrad", s);
@@ -487,9 +466,9 @@ int launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const int3
             DBW_HIP(hipGetLastError());
         }
         dbw_timer tm(c, "conv2_dgrad", s);
-        hipLaunchKernelGGL((convlds::conv_forward_kernel<16, 2, 2, 16, 16, 5, 8>), dim3(B, N), dim3(512), 0, s,
-                           A + L.dz2, ws, A + L.wflip, ws, L.C2 * KK, (const float *)nullptr, (int64_t)0, A + L.dp1,
-                           ws, L.C2);
+        hipLaunchKernelGGL((convlds::conv_forward_kernel<16, 2, 2, 16, 16, 5, 8, false, true>), dim3(B, N), dim3(512), 0,
+                           s, A + L.dp2, ws, A + L.wflip, ws, L.C2 * KK, (const float *)nullptr, (int64_t)0, A + L.dp1,
+                           ws, L.C2, (uint8_t *)nullptr, (int64_t)0, code2, cs);
         DBW_HIP(hipGetLastError());
     } else {   // conv2 data gradient -> gradient of the first pooled map
         dbw_timer tm(c, "conv2_dgrad", s);
@@ -497,12 +476,7 @@ int launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const int3
                               ChannelPixelOut{A + L.dp1, ws, L.C1, L.H2 * L.W2, nullptr, 0}, L.C1, pix2, L.C2 * KK, N,
                               s));
     }
-    if (fast1) {
-        dbw_timer tm(c, "pool_bwd_code_kernel", s);
-        hipLaunchKernelGGL(pool_bwd_code_kernel, dim3(blocks((int64_t)B * L.C1 * L.H2 * L.W2), N), dim3(256), 0, s, code1,
-                           cs, A + L.dp1, ws, A + L.dz1, ws, B * L.C1, L.H, L.W);
-        DBW_HIP(hipGetLastError());
-    } else {
+    if (!fast1) {
         dbw_timer tm(c, "relu_pool_bwd_kernel", s);
         hipLaunchKernelGGL(relu_pool_bwd_kernel, dim3(blocks((int64_t)B * L.C1 * L.H2 * L.W2), N), dim3(256), 0, s,
                            A + L.z1, ws, A + L.dp1, ws, A + L.dz1, B * L.C1, L.H, L.W);
@@ -512,8 +486,8 @@ int launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const int3
         const int nb = (B + WGRAD_SB - 1) / WGRAD_SB;
         splits1 = nb * 8;
         dbw_timer tm(c, "conv1_wgrad", s);
-        hipLaunchKernelGGL((convlds::conv_wgrad_kernel<3, 2, 5, 1, 1, 8, 32, 32, 5, 512>), dim3(nb, N), dim3(512), 0, s,
-                           bx, xstride, A + L.dz1, ws, A + L.part, ws, B, WGRAD_SB);
+        hipLaunchKernelGGL((convlds::conv_wgrad_kernel<3, 2, 5, 1, 1, 8, 32, 32, 5, 512, true>), dim3(nb, N), dim3(512), 0,
+                           s, bx, xstride, A + L.dp1, ws, A + L.part, ws, B, WGRAD_SB, code1, cs);
         DBW_HIP(hipGetLastError());
     } else {   // conv1 weight and bias gradients
         dbw_timer tm(c, "conv1_wgrad", s);

@@ -184,21 +184,33 @@ __global__ __launch_bounds__(256) void dtur_kernel(
 }
 
 // Round duration (Section 3.2.2): max of the wait times over all workers and over the
-// workers that appear in some selected set.  One block; `listed` is context scratch [N].
-__global__ __launch_bounds__(256) void round_time_kernel(int N, int nnz, const int32_t *__restrict__ colidx,
-                                                         const uint8_t *__restrict__ mask,
-                                                         const float *__restrict__ wait, uint8_t *__restrict__ listed,
-                                                         float *__restrict__ out)
+// workers that appear in some selected set.  One block of 1024 threads; the mask is read four
+// entries at a time; `listed` is context scratch [N].
+__global__ __launch_bounds__(1024) void round_time_kernel(int N, int nnz, const int32_t *__restrict__ colidx,
+                                                          const uint8_t *__restrict__ mask,
+                                                          const float *__restrict__ wait, uint8_t *__restrict__ listed,
+                                                          float *__restrict__ out)
 {
-    __shared__ float red[2][256];
+    __shared__ float red[2][1024];
     const int tid = threadIdx.x;
-    for (int i = tid; i < N; i += 256) listed[i] = 0;
+    for (int i = tid; i < N; i += 1024) listed[i] = 0;
     __syncthreads();
-    for (int e = tid; e < nnz; e += 256)
-        if (mask[e]) listed[colidx[e]] = 1;       // benign race: every writer stores the same value
+    const int words = nnz / 4;
+    for (int q = tid; q < words; q += 1024) {
+        const uint32_t m = ((const uint32_t *)mask)[q];
+        if (m) {
+            // benign race: every writer stores the same value
+            if (m & 0x000000ffu) listed[colidx[4 * q]] = 1;
+            if (m & 0x0000ff00u) listed[colidx[4 * q + 1]] = 1;
+            if (m & 0x00ff0000u) listed[colidx[4 * q + 2]] = 1;
+            if (m & 0xff000000u) listed[colidx[4 * q + 3]] = 1;
+        }
+    }
+    for (int e = 4 * words + tid; e < nnz; e += 1024)
+        if (mask[e]) listed[colidx[e]] = 1;
     __syncthreads();
     float all = 0.f, sel = 0.f;
-    for (int i = tid; i < N; i += 256) {
+    for (int i = tid; i < N; i += 1024) {
         const float t = wait[i];
         all = fmaxf(all, t);
         if (listed[i]) sel = fmaxf(sel, t);
@@ -206,7 +218,7 @@ __global__ __launch_bounds__(256) void round_time_kernel(int N, int nnz, const i
     red[0][tid] = all;
     red[1][tid] = sel;
     __syncthreads();
-    for (int o = 128; o > 0; o >>= 1) {
+    for (int o = 512; o > 0; o >>= 1) {
         if (tid < o) {
             red[0][tid] = fmaxf(red[0][tid], red[0][tid + o]);
             red[1][tid] = fmaxf(red[1][tid], red[1][tid + o]);
@@ -224,7 +236,7 @@ __global__ __launch_bounds__(256) void round_time_kernel(int N, int nnz, const i
 int dbw_launch_round_time(dbw_ctx *c, float *out, hipStream_t s)
 {
     dbw_timer tm(c, "round_time_kernel", s);
-    hipLaunchKernelGGL(round_time_kernel, dim3(1), dim3(256), 0, s, c->N, c->nnz, c->colidx, c->mask, c->wait,
+    hipLaunchKernelGGL(round_time_kernel, dim3(1), dim3(1024), 0, s, c->N, c->nnz, c->colidx, c->mask, c->wait,
                        c->listed, out);
     DBW_HIP(hipGetLastError());
     return DBW_OK;
