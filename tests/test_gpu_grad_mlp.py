@@ -32,6 +32,12 @@ SHAPES = [
     ([256, 10], 1024, 6, "xent"),            # the LRM of Section 5
     ([37, 19, 5], 7, 3, "mse"),
     ([5, 2], 1, 2, "mse"),
+    # batch 32 with wide layers: the streaming kernels (forward split along k or along the outputs,
+    # masked data gradient, weight gradient), worker counts that are not multiples of 8
+    ([512, 96, 10], 32, 9, "xent"),
+    ([1024, 256, 128, 10], 32, 5, "xent"),
+    ([64, 512, 64, 10], 32, 11, "xent"),
+    ([1536, 384, 10], 32, 3, "mse"),
 ]
 
 
@@ -53,7 +59,14 @@ def test_mlp_gradients_match_oracle(B, orc, dims, batch, n, loss_kind):
     try:
         grads = torch.full((n, ld), 7.0, dtype=torch.float32, device="cuda")
         loss = torch.zeros(n, dtype=torch.float32, device="cuda")
+        B.dbw_set_timing(h, True)
         B.dbw_grad(h, dev(params), dev(x), dev(y), grads, loss)
+        kernels = set(B.dbw_get_timing(h))
+        B.dbw_set_timing(h, False)
+        if batch == 32 and any(a % 512 == 0 and b % 32 == 0 for a, b in zip(dims[:-1], dims[1:])):
+            assert {"fc32_forward", "fc32_wgrad"} <= kernels, kernels       # the streaming kernels really ran
+            if any(a % 512 == 0 and b % 32 == 0 for a, b in zip(dims[1:-1], dims[2:])):
+                assert "fc32_dgrad" in kernels, kernels
         got, gl = grads.cpu().numpy(), loss.cpu().numpy()
         kind, od = orc.model_desc(desc)
         want, wl = orc.grad_all(kind, od, d, params, x, y)
