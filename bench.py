@@ -63,6 +63,13 @@ def cpu_baseline(cid: int, wl_rowptr, wl_colidx, budget_s: float = 15.0):
                 break
         value = n / (per_round * frac)
         sample = f"{done} rounds on the first d/{frac} = {cols} columns (columns are independent), time scaled x{frac}"
+        # the same on one thread, on an eighth of those columns
+        oracle.set_threads(1)
+        c1 = max(cols // 8, 1)
+        x1, g1 = np.ascontiguousarray(x[:, :c1]), np.ascontiguousarray(g[:, :c1])
+        t1 = time.perf_counter()
+        oracle.round_(wl_rowptr, wl_colidx, mask, p, x1, g1, cfg.lr, 0)
+        value_1 = n / ((time.perf_counter() - t1) * (cfg.d / c1))
     else:
         desc = inputs.model_dims(cfg.model)
         kind, od = oracle.model_desc(desc)
@@ -83,8 +90,17 @@ def cpu_baseline(cid: int, wl_rowptr, wl_colidx, budget_s: float = 15.0):
         value = n / (t_grad + t_mix)
         sample = (f"1 round: gradients of {len(workers)} of {n} workers (time scaled to {n}) "
                   f"+ selection and averaging of all workers")
+        # the same on one thread: one worker's gradient, scaled
+        oracle.set_threads(1)
+        t1 = time.perf_counter()
+        oracle.grad_all(kind, od, cfg.d, x[:1], bx[:1], by[:1])
+        t_grad1 = (time.perf_counter() - t1) * n
+        t1 = time.perf_counter()
+        oracle.round_(wl_rowptr, wl_colidx, mask, p, x, g, cfg.lr, 0, d=cfg.d)
+        value_1 = n / (t_grad1 + (time.perf_counter() - t1))
     oracle.set_threads(1)
-    return {"value": value, "unit": "worker-rounds/s", "cores": threads, "kind": "oracle", "sample": sample}
+    return {"value": value, "unit": "worker-rounds/s", "cores": threads, "kind": "oracle", "sample": sample,
+            "value_1core": value_1}
 
 
 def main():
