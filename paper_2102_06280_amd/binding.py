@@ -26,7 +26,8 @@ LAYOUT_ROWS, LAYOUT_TILES = 0, 1
 TILE_COLUMNS = 64
 
 EXPORTS = ["dbw_create", "dbw_select", "dbw_dtur_b", "dbw_dtur_reset", "dbw_get_selection",
-           "dbw_get_weights", "dbw_round_time", "dbw_round", "dbw_round_eta", "dbw_consensus_rounds", "dbw_convert_layout", "dbw_grad", "dbw_check", "dbw_get_links", "dbw_mix_path",
+           "dbw_get_weights", "dbw_round_time", "dbw_round", "dbw_round_eta", "dbw_consensus_rounds",
+           "dbw_convert_layout", "dbw_grad", "dbw_check", "dbw_get_links", "dbw_mix_path",
            "dbw_destroy", "dbw_strerror", "dbw_set_timing", "dbw_get_timing", "dbw_calibrate"]
 
 

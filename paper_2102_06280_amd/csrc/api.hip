@@ -89,7 +89,8 @@ int dev_alloc(T **p, size_t n)
 void free_ctx(dbw_ctx *c)
 {
     if (!c) return;
-    void *ptrs[] = {c->rowptr, c->colidx, c->p, c->mask, c->wait, c->listed, c->sel_idx, c->sel_w, c->self_w, c->Wdense, c->phi[0], c->phi[1], c->phi_frag,
+    void *ptrs[] = {c->rowptr, c->colidx, c->p, c->mask, c->wait, c->listed, c->sel_idx, c->sel_w, c->self_w, c->Wdense,
+                    c->phi[0], c->phi[1], c->phi_frag,
                     c->err, c->links, c->visited, c->n_visited, c->grads, c->act};
     for (void *q : ptrs)
         if (q) (void)hipFree(q);

@@ -198,11 +198,15 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
                     dbw_timer tm(c, "fc32_forward", s);
                     const dim3 grid(slices, N), block(fc32::THREADS);
                     const float *Wl = params + w_off[l];
+                    auto go = [&](auto kern) {
+                        hipLaunchKernelGGL(kern, grid, block, 0, s, dims[l - 1], A.p, A.ld, A.stride, Wl, c->ld, part,
+                                           wstride);
+                    };
                     switch (nf) {
-                    case 1: hipLaunchKernelGGL(fc32::forward_ksplit_kernel<1>, grid, block, 0, s, dims[l - 1], A.p, A.ld, A.stride, Wl, c->ld, part, wstride); break;
-                    case 2: hipLaunchKernelGGL(fc32::forward_ksplit_kernel<2>, grid, block, 0, s, dims[l - 1], A.p, A.ld, A.stride, Wl, c->ld, part, wstride); break;
-                    case 3: hipLaunchKernelGGL(fc32::forward_ksplit_kernel<3>, grid, block, 0, s, dims[l - 1], A.p, A.ld, A.stride, Wl, c->ld, part, wstride); break;
-                    default: hipLaunchKernelGGL(fc32::forward_ksplit_kernel<4>, grid, block, 0, s, dims[l - 1], A.p, A.ld, A.stride, Wl, c->ld, part, wstride); break;
+                    case 1: go(fc32::forward_ksplit_kernel<1>); break;
+                    case 2: go(fc32::forward_ksplit_kernel<2>); break;
+                    case 3: go(fc32::forward_ksplit_kernel<3>); break;
+                    default: go(fc32::forward_ksplit_kernel<4>); break;
                     }
                     DBW_HIP(hipGetLastError());
                 }

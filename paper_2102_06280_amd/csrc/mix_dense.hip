@@ -210,7 +210,8 @@ __global__ __launch_bounds__(DENSE_THREADS) void mix_dense_kernel(
                     r = fmaf(-lr.at(FULL || row < N ? row : 0), gv[sp][v], r);
                 }
                 float *ob = out + (int64_t)row0 * ld + col0;
-                if (FULL || (row0 + 4 * (lane >> 5) < N && col0 + (lane & 31) < dcols)) *(float *)(const_cast<char *>(uniform_base(ob)) + epi_lane_off) = r;
+                if (FULL || (row0 + 4 * (lane >> 5) < N && col0 + (lane & 31) < dcols))
+                    *(float *)(const_cast<char *>(uniform_base(ob)) + epi_lane_off) = r;
             }
         };
 
