@@ -38,11 +38,15 @@ constexpr int lds_floats(bool kc, int rows) { return kc ? rows * LDS_KC : BK * l
 
 // Dense operand.  KC: element (r, k) at p[w * stride + r * ld + k]; otherwise at
 // p[w * stride + k * ld + r].  Offsets inside one worker's block fit 32 bits.
+// `vec` (set by launch() when every row of the operand starts on a 16-byte boundary and the
+// extents divide by 4) lets the tile be fetched with 128-bit loads.
 template <bool KC_>
 struct Dense {
     static constexpr bool KC = KC_;
+    static constexpr bool CAN_VEC = true;
     const float *p;
     int64_t ld, stride;
+    bool vec;
     struct RowCtx { int off; bool ok; };
     struct KCtx { int off; bool ok; };
     __device__ __forceinline__ RowCtx row_ctx(int r, bool ok) const { return {KC ? r * (int)ld : r, ok}; }
@@ -117,6 +121,60 @@ __device__ __forceinline__ void fetch_tile(const L &op, int w, int r0, int R, in
     }
 }
 
+// 128-bit variants for dense operands (ROWS / 16 float4 per thread, float4 index f = tid + 256 j):
+//   KC: (row = f / 16, k = 4 (f % 16)): a wave instruction reads 256 contiguous bytes of four rows
+//   RC: (k = f / (ROWS / 4), row = 4 (f % (ROWS / 4))): ROWS contiguous floats of one k
+template <class L, int ROWS>
+__device__ __forceinline__ void fetch_tile_vec(const L &op, int w, int r0, int R, int k0, int K, int tid,
+                                               float (&v)[ROWS / 4])
+{
+    const float *base = op.p + w * op.stride;
+#pragma unroll
+    for (int j = 0; j < ROWS / 16; ++j) {
+        const int f = tid + 256 * j;
+        int r, k;
+        if (L::KC) {
+            r = r0 + (f >> 4);
+            k = k0 + 4 * (f & 15);
+        } else {
+            r = r0 + 4 * (f % (ROWS / 4));
+            k = k0 + f / (ROWS / 4);
+        }
+        const bool ok = r < R && k < K;
+        const int off = ok ? (L::KC ? r * (int)op.ld + k : k * (int)op.ld + r) : 0;
+        const f32x4 q = *(const f32x4 *)(base + off);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[4 * j + e] = ok ? q[e] : 0.f;
+    }
+}
+
+template <class L, int ROWS>
+__device__ __forceinline__ void commit_tile_vec(float *lds, int tid, const float (&v)[ROWS / 4])
+{
+#pragma unroll
+    for (int j = 0; j < ROWS / 16; ++j) {
+        const int f = tid + 256 * j;
+        const f32x4 q = {v[4 * j], v[4 * j + 1], v[4 * j + 2], v[4 * j + 3]};
+        if (L::KC)
+            *(f32x4 *)&lds[(f >> 4) * LDS_KC + 4 * (f & 15)] = q;
+        else
+            *(f32x4 *)&lds[(f / (ROWS / 4)) * lds_rc(ROWS) + 4 * (f % (ROWS / 4))] = q;
+    }
+}
+
+template <class L>
+struct can_vec {
+    template <class T> static constexpr auto test(int) -> decltype(T::CAN_VEC, true) { return T::CAN_VEC; }
+    template <class T> static constexpr bool test(...) { return false; }
+    static constexpr bool value = test<L>(0);
+};
+template <class L>
+__host__ __device__ __forceinline__ bool use_vec(const L &op)
+{
+    if constexpr (can_vec<L>::value) return op.vec;
+    else return false;
+}
+
 template <class L, int ROWS>
 __device__ __forceinline__ void commit_tile(float *lds, int wave, int lane, const float (&v)[ROWS / 4])
 {
@@ -146,7 +204,8 @@ __device__ __forceinline__ f32x4 frag(const float *lds, int rbase, int kg, int l
 // blockIdx.z = worker * splits + split; a split covers k in [split * kper, (split + 1) * kper)
 // (kper a multiple of BK) and hands its partial sum to the epilogue, which decides where it
 // goes; with splits == 1 the result is final.
-template <class LA, class LB, class EP, int BM, int BN>
+// VA / VB: fetch the A / B tile with 128-bit loads (see mark_vec).
+template <class LA, class LB, class EP, int BM, int BN, bool VA, bool VB>
 __global__ __launch_bounds__(THREADS) void kernel(LA A, LB B, EP E, int M, int N, int K, int splits, int kper)
 {
     static_assert((BM == 64 && BN == 64) || (BM == 32 && BN == 128), "supported tiles: 64 x 64, 32 x 128");
@@ -172,17 +231,19 @@ __global__ __launch_bounds__(THREADS) void kernel(LA A, LB B, EP E, int M, int N
     make_rows<LA, BM>(A, m0, M, lane, arows);
     make_rows<LB, BN>(B, n0, N, lane, brows);
     float ra[BM / 4], rb[BN / 4];
-    fetch_tile<LA, BM>(A, w, m0, M, kbeg, kend, wave, lane, arows, ra);
-    fetch_tile<LB, BN>(B, w, n0, N, kbeg, kend, wave, lane, brows, rb);
+    auto fetch = [&](int k0) {
+        if constexpr (VA) fetch_tile_vec<LA, BM>(A, w, m0, M, k0, kend, tid, ra);
+        else fetch_tile<LA, BM>(A, w, m0, M, k0, kend, wave, lane, arows, ra);
+        if constexpr (VB) fetch_tile_vec<LB, BN>(B, w, n0, N, k0, kend, tid, rb);
+        else fetch_tile<LB, BN>(B, w, n0, N, k0, kend, wave, lane, brows, rb);
+    };
+    fetch(kbeg);
     for (int k0 = kbeg; k0 < kend; k0 += BK) {
         __syncthreads();                       // previous tile fully consumed
-        commit_tile<LA, BM>(As, wave, lane, ra);
-        commit_tile<LB, BN>(Bs, wave, lane, rb);
+        if constexpr (VA) commit_tile_vec<LA, BM>(As, tid, ra); else commit_tile<LA, BM>(As, wave, lane, ra);
+        if constexpr (VB) commit_tile_vec<LB, BN>(Bs, tid, rb); else commit_tile<LB, BN>(Bs, wave, lane, rb);
         __syncthreads();
-        if (k0 + BK < kend) {                  // next tile's loads fly during the MFMAs
-            fetch_tile<LA, BM>(A, w, m0, M, k0 + BK, kend, wave, lane, arows, ra);
-            fetch_tile<LB, BN>(B, w, n0, N, k0 + BK, kend, wave, lane, brows, rb);
-        }
+        if (k0 + BK < kend) fetch(k0 + BK);    // next tile's loads fly during the MFMAs
 #pragma unroll
         for (int kg = 0; kg < BK / 16; ++kg) {
             f32x4 fa[2], fb[2];
@@ -212,6 +273,20 @@ __global__ __launch_bounds__(THREADS) void kernel(LA A, LB B, EP E, int M, int N
         }
 }
 
+// 128-bit tile fetches need every row of the operand on a 16-byte boundary and the contiguous
+// extent (k for a k-contiguous operand, rows otherwise) divisible by 4.  They are switched on for
+// k-contiguous operands only: measured, a row-contiguous operand gains nothing (its 32-bit fetch
+// already reads 256 contiguous bytes per instruction) and loses on the wider LDS writes
+// (weight-gradient GEMMs 10-20 % slower).
+template <class L>
+inline void mark_vec(L &op, int rows, int K)
+{
+    if constexpr (can_vec<L>::value) {
+        const int contiguous = L::KC ? K : rows;
+        op.vec = L::KC && ((uintptr_t)op.p % 16 == 0) && op.ld % 4 == 0 && op.stride % 4 == 0 && contiguous % 4 == 0;
+    }
+}
+
 // BM = 32 uses 32 x 128 tiles (for problems with at most 32 rows), otherwise 64 x 64.
 template <int BM, class LA, class LB, class EP>
 inline hipError_t launch(const LA &A, const LB &B, const EP &E, int M, int N, int K, int batch, hipStream_t s,
@@ -221,7 +296,27 @@ inline hipError_t launch(const LA &A, const LB &B, const EP &E, int M, int N, in
     int kper = (K + splits - 1) / splits;
     kper = (kper + BK - 1) / BK * BK;
     dim3 grid((N + BN - 1) / BN, (M + BM - 1) / BM, batch * splits);
-    hipLaunchKernelGGL((kernel<LA, LB, EP, BM, BN>), grid, dim3(THREADS), 0, s, A, B, E, M, N, K, splits, kper);
+    LA a = A;
+    LB b = B;
+    mark_vec(a, M, K);
+    mark_vec(b, N, K);
+    const bool va = use_vec(a), vb = use_vec(b);
+    auto go = [&](auto kern) { hipLaunchKernelGGL(kern, grid, dim3(THREADS), 0, s, a, b, E, M, N, K, splits, kper); };
+    constexpr bool CA = can_vec<LA>::value && LA::KC, CB = can_vec<LB>::value && LB::KC;
+    if constexpr (CA && CB) {
+        if (va && vb) go(kernel<LA, LB, EP, BM, BN, true, true>);
+        else if (va) go(kernel<LA, LB, EP, BM, BN, true, false>);
+        else if (vb) go(kernel<LA, LB, EP, BM, BN, false, true>);
+        else go(kernel<LA, LB, EP, BM, BN, false, false>);
+    } else if constexpr (CA) {
+        if (va) go(kernel<LA, LB, EP, BM, BN, true, false>);
+        else go(kernel<LA, LB, EP, BM, BN, false, false>);
+    } else if constexpr (CB) {
+        if (vb) go(kernel<LA, LB, EP, BM, BN, false, true>);
+        else go(kernel<LA, LB, EP, BM, BN, false, false>);
+    } else {
+        go(kernel<LA, LB, EP, BM, BN, false, false>);
+    }
     return hipGetLastError();
 }
 
