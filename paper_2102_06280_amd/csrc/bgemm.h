@@ -274,16 +274,14 @@ __global__ __launch_bounds__(THREADS) void kernel(LA A, LB B, EP E, int M, int N
 }
 
 // 128-bit tile fetches need every row of the operand on a 16-byte boundary and the contiguous
-// extent (k for a k-contiguous operand, rows otherwise) divisible by 4.  They are switched on for
-// k-contiguous operands only: measured, a row-contiguous operand gains nothing (its 32-bit fetch
-// already reads 256 contiguous bytes per instruction) and loses on the wider LDS writes
-// (weight-gradient GEMMs 10-20 % slower).
+// extent (k for a k-contiguous operand, rows otherwise) divisible by 4.  The choice is a template
+// parameter of the kernel: as a run-time branch inside it, it cost the 32-bit path 15-20 %.
 template <class L>
 inline void mark_vec(L &op, int rows, int K)
 {
     if constexpr (can_vec<L>::value) {
         const int contiguous = L::KC ? K : rows;
-        op.vec = L::KC && ((uintptr_t)op.p % 16 == 0) && op.ld % 4 == 0 && op.stride % 4 == 0 && contiguous % 4 == 0;
+        op.vec = ((uintptr_t)op.p % 16 == 0) && op.ld % 4 == 0 && op.stride % 4 == 0 && contiguous % 4 == 0;
     }
 }
 
@@ -302,7 +300,7 @@ inline hipError_t launch(const LA &A, const LB &B, const EP &E, int M, int N, in
     mark_vec(b, N, K);
     const bool va = use_vec(a), vb = use_vec(b);
     auto go = [&](auto kern) { hipLaunchKernelGGL(kern, grid, dim3(THREADS), 0, s, a, b, E, M, N, K, splits, kper); };
-    constexpr bool CA = can_vec<LA>::value && LA::KC, CB = can_vec<LB>::value && LB::KC;
+    constexpr bool CA = can_vec<LA>::value, CB = can_vec<LB>::value;
     if constexpr (CA && CB) {
         if (va && vb) go(kernel<LA, LB, EP, BM, BN, true, true>);
         else if (va) go(kernel<LA, LB, EP, BM, BN, true, false>);
