@@ -159,7 +159,7 @@ def main():
     # the same rounds replayed as HIP graphs (one per round): what a launch-bound
     # configuration gains from a single submission per round; reported next to the eager figure
     graph_ms = None
-    if cfg.model != "none" and cfg.cid != 3:
+    if cfg.model != "none":
         graphs = wl.capture_steps(args.steps)
         wl.replay(graphs[:2])
         torch.cuda.synchronize()
