@@ -367,7 +367,7 @@ int launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const int3
     const int64_t cs = ws * 4;                         // worker stride of the code maps in bytes
     if (fast1) {   // convolution + ReLU + pooling in one kernel
         dbw_timer tm(c, "conv1_forward", s);
-        hipLaunchKernelGGL((convlds::conv_forward_kernel<3, 2, 8, 32, 32, 5, 8, true>), dim3(B, N), dim3(512), 0, s, bx,
+        hipLaunchKernelGGL((convlds::conv_forward_kernel<3, 2, 4, 32, 32, 5, 16, true>), dim3(B, N), dim3(1024), 0, s, bx,
                            xstride, params + L.w1, ld, L.C0 * KK, params + L.b1, ld, A + L.p1, ws, L.C0, code1, cs);
         DBW_HIP(hipGetLastError());
     } else {   // conv1 forward
