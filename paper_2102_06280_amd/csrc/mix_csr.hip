@@ -68,7 +68,7 @@ __global__ __launch_bounds__(LDS_THREADS) void mix_lds_tiles(
     int N, int nnz, int64_t n_vec, int64_t ld4, int64_t n_tiles, const int32_t *__restrict__ rowptr,
     const int32_t *__restrict__ p, const int32_t *__restrict__ sel_idx, const float *__restrict__ sel_w,
     const float *__restrict__ self_w, const float4 *__restrict__ x, const float4 *__restrict__ g,
-    float4 *__restrict__ out, LR lr)
+    float4 *__restrict__ out, LR lr, int64_t d)
 {
     extern __shared__ float4 sm[];
     float4 *tiles = sm;                                  // 2 * LDS_TILE
@@ -136,7 +136,14 @@ __global__ __launch_bounds__(LDS_THREADS) void mix_lds_tiles(
                 for (int k = 0; k < cnt[u]; ++k)
                     acc = fma4(s_w[beg[u] + k], tl[s_idx[beg[u] + k] * TC4 + col[u]], acc);
                 if (ORDER == DBW_ORDER_CTA && HAS_G) acc = fma4(-eta[u], gc[u], acc);
-                store_stream(&out[rowoff[u] + c], acc);
+                if (4 * c + 4 <= d) {
+                    store_stream(&out[rowoff[u] + c], acc);
+                } else {                           // the float4 that straddles column d: padding stays untouched
+                    float *o = (float *)&out[rowoff[u] + c];
+                    o[0] = acc.x;
+                    if (4 * c + 1 < d) o[1] = acc.y;
+                    if (4 * c + 2 < d) o[2] = acc.z;
+                }
             }
         }
         if (nx < n_tiles) {
@@ -271,7 +278,7 @@ int launch_lds(dbw_ctx *c, const float *x, const float *g, float *out, LR lr, in
     dbw_timer tm(c, "mix_lds_tiles", s);
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(LDS_THREADS), lds, s, c->N, c->nnz, n_vec, c->ld / 4, n_tiles,
                        c->rowptr, c->p, c->sel_idx, c->sel_w, c->self_w, (const float4 *)x, (const float4 *)g,
-                       (float4 *)out, lr);
+                       (float4 *)out, lr, c->d);
     DBW_HIP(hipGetLastError());
     return DBW_OK;
 }
@@ -282,7 +289,7 @@ int launch(dbw_ctx *c, const float *x, const float *g, float *out, LR lr, hipStr
     constexpr int UNROLL = 2;
     const bool aligned = (c->ld % 4 == 0) && ((uintptr_t)x % 16 == 0) && ((uintptr_t)out % 16 == 0) &&
                          (!HAS_G || (uintptr_t)g % 16 == 0);
-    const int64_t n_vec = aligned ? c->d / 4 : 0;
+    int64_t n_vec = aligned ? c->d / 4 : 0;
     if (n_vec > 0) {
         // widest tile (power of two float4 columns, 8..256) that holds all N rows in 64 KB
         int tc4 = 256;
@@ -290,6 +297,9 @@ int launch(dbw_ctx *c, const float *x, const float *g, float *out, LR lr, hipStr
         const bool use_lds = tc4 >= 8 && c->nnz <= LDS_MAX_EDGES && (n_vec + tc4 - 1) / tc4 >= device_cus() / 2;
         int rc = DBW_OK;
         if (use_lds) {
+            // the LDS kernel also takes the float4 that straddles column d (rows are aligned and
+            // ld is a multiple of 4, so that float4 lies inside the row): no separate tail launch
+            n_vec = (c->d + 3) / 4;
             switch (tc4) {
             case 256: rc = launch_lds<ORDER, HAS_G, 256, LR>(c, x, g, out, lr, n_vec, s); break;
             case 128: rc = launch_lds<ORDER, HAS_G, 128, LR>(c, x, g, out, lr, n_vec, s); break;
