@@ -23,10 +23,26 @@ __global__ void phi_step_kernel(int Npad, const int32_t *__restrict__ rowptr, co
                                 const float *__restrict__ self_w, const float *__restrict__ prev,
                                 float *__restrict__ next)
 {
+    __shared__ int32_t s_idx[DBW_DENSE_MAX_N];
+    __shared__ float s_w[DBW_DENSE_MAX_N];
     const int i = blockIdx.x, c = threadIdx.x;
     const int beg = rowptr[i], cnt = p[i];
+    if (c < cnt) {                                     // cnt <= N - 1 < Npad = blockDim.x
+        s_idx[c] = sel_idx[beg + c];
+        s_w[c] = sel_w[beg + c];
+    }
+    __syncthreads();
     float acc = self_w[i] * prev[(size_t)i * Npad + c];
-    for (int k = 0; k < cnt; ++k) acc = fmaf(sel_w[beg + k], prev[(size_t)sel_idx[beg + k] * Npad + c], acc);
+    // the loads of eight neighbours are in flight together; the sum keeps its order
+    int k = 0;
+    for (; k + 8 <= cnt; k += 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = prev[(size_t)s_idx[k + u] * Npad + c];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc = fmaf(s_w[k + u], v[u], acc);
+    }
+    for (; k < cnt; ++k) acc = fmaf(s_w[k], prev[(size_t)s_idx[k] * Npad + c], acc);
     next[(size_t)i * Npad + c] = acc;
 }
 
