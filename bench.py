@@ -240,7 +240,8 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"config {cfg.cid}: {cfg.name}", "workers": cfg.n, "graph": cfg.graph, "d": cfg.d,
-                   "ld": wl.ld, "layout": args.layout, "model": cfg.model, "batch": cfg.batch, "order": args.order,
+                   "ld": wl.ld, "layout": args.layout, "per_worker_network": cfg.model, "per_worker_batch": cfg.batch,
+                   "order": args.order,
                    "mix_path": "dense" if mix_path == B.MIX_DENSE else "csr",
                    "gradients": "one fixed supplied matrix, reused every round" if cfg.model == "none" else "computed"},
         "roofline": roofline,
