@@ -108,6 +108,89 @@ bool overlaps(const void *a, size_t na, const void *b, size_t nb)
     return a0 < b0 + nb && b0 < a0 + na;
 }
 
+// Everything of dbw_create after the graph has been validated; the caller frees `c` on any
+// error return (host containers may throw: the caller turns that into DBW_ERR_ALLOC).
+int fill_ctx(dbw_ctx *c, int32_t N, int64_t d, int64_t nnz64, const int32_t *rowptr, const int32_t *colidx,
+             const dbw_opts *opts)
+{
+    c->N = N;
+    c->d = d;
+    c->ld = d;
+    c->nnz = (int32_t)nnz64;
+    if (opts) {
+        if (opts->ld != 0) c->ld = opts->ld;
+        c->order = opts->order;
+        c->mix = opts->mix_path;
+        c->layout = opts->layout;
+        c->model = opts->model;
+    }
+    if (c->ld < d || (c->order != DBW_ORDER_CTA && c->order != DBW_ORDER_ATC) || c->mix < DBW_MIX_AUTO ||
+        c->mix > DBW_MIX_DENSE)
+        return DBW_ERR_INVALID;
+    if (c->layout != DBW_LAYOUT_ROWS && c->layout != DBW_LAYOUT_TILES) return DBW_ERR_INVALID;
+    if (c->layout == DBW_LAYOUT_TILES) {
+        if (c->ld % DBW_TILE_COLUMNS) return DBW_ERR_INVALID;
+        if (c->model.kind != DBW_MODEL_NONE || N > DBW_TILES_MAX_N || c->mix == DBW_MIX_DENSE)
+            return DBW_ERR_UNSUPPORTED;
+        c->mix = DBW_MIX_CSR;
+    }
+    if (c->model.kind != DBW_MODEL_NONE) {
+        const int64_t want = model_param_count(c->model, &c->in_dim);
+        const bool loss_ok = c->model.loss == DBW_LOSS_XENT ||
+                             (c->model.loss == DBW_LOSS_MSE && c->model.kind == DBW_MODEL_MLP);
+        if (want != d || c->model.batch < 1 || !loss_ok) return DBW_ERR_INVALID;
+    }
+    c->h_rowptr.assign(rowptr, rowptr + N + 1);
+    c->h_colidx.assign(colidx, colidx + c->nnz);
+    for (int i = 0; i < N; ++i) c->max_deg = std::max(c->max_deg, rowptr[i + 1] - rowptr[i]);
+    if (!spanning_links(N, rowptr, colidx, c->h_links)) return DBW_ERR_GRAPH;
+    if (c->mix == DBW_MIX_AUTO)
+        c->mix = (N <= DBW_DENSE_MAX_N && (int64_t)c->nnz * 4 > (int64_t)N * N) ? DBW_MIX_DENSE : DBW_MIX_CSR;
+    if (c->mix == DBW_MIX_DENSE && N > DBW_DENSE_MAX_N) return DBW_ERR_UNSUPPORTED;
+    c->Npad = 32;                                   // dense path: padded to a power of two
+    while (c->Npad < N) c->Npad *= 2;
+
+    int rc = DBW_OK;
+    auto A = [&](int r) { if (rc == DBW_OK) rc = r; };
+    A(dev_alloc(&c->rowptr, (size_t)N + 1));
+    A(dev_alloc(&c->colidx, (size_t)c->nnz));
+    A(dev_alloc(&c->p, (size_t)N));
+    A(dev_alloc(&c->mask, (size_t)c->nnz));
+    A(dev_alloc(&c->wait, (size_t)N));
+    A(dev_alloc(&c->listed, (size_t)N));
+    A(dev_alloc(&c->sel_idx, (size_t)c->nnz));
+    A(dev_alloc(&c->sel_w, (size_t)c->nnz));
+    A(dev_alloc(&c->self_w, (size_t)N));
+    A(dev_alloc(&c->err, 1));
+    A(dev_alloc(&c->links, c->h_links.size()));
+    A(dev_alloc(&c->visited, (size_t)std::max(N - 1, 1)));
+    A(dev_alloc(&c->n_visited, 1));
+    if (c->mix == DBW_MIX_DENSE) A(dev_alloc(&c->Wdense, (size_t)c->Npad * c->Npad));
+    if (N <= DBW_DENSE_MAX_N) {
+        A(dev_alloc(&c->phi[0], (size_t)c->Npad * c->Npad));
+        A(dev_alloc(&c->phi[1], (size_t)c->Npad * c->Npad));
+        A(dev_alloc(&c->phi_frag, (size_t)c->Npad * c->Npad));
+    }
+    if (c->model.kind != DBW_MODEL_NONE) {
+        A(dev_alloc(&c->grads, (size_t)N * c->ld));
+        c->act_floats = c->model.kind == DBW_MODEL_MLP ? dbw_mlp_scratch_floats(c) : dbw_cnn_scratch_floats(c);
+        A(dev_alloc(&c->act, c->act_floats));
+    }
+    if (rc != DBW_OK) return rc;
+    auto H = [&](hipError_t e) { if (rc == DBW_OK && e != hipSuccess) rc = DBW_ERR_HIP; };
+    H(hipMemcpy(c->rowptr, rowptr, sizeof(int32_t) * ((size_t)N + 1), hipMemcpyHostToDevice));
+    if (c->nnz) H(hipMemcpy(c->colidx, colidx, sizeof(int32_t) * (size_t)c->nnz, hipMemcpyHostToDevice));
+    if (!c->h_links.empty())
+        H(hipMemcpy(c->links, c->h_links.data(), sizeof(int32_t) * c->h_links.size(), hipMemcpyHostToDevice));
+    H(hipMemset(c->err, 0, sizeof(int32_t)));
+    H(hipMemset(c->visited, 0, (size_t)std::max(N - 1, 1)));
+    H(hipMemset(c->n_visited, 0, sizeof(int32_t)));
+    if (c->Wdense) H(hipMemset(c->Wdense, 0, sizeof(float) * (size_t)c->Npad * c->Npad));
+    if (c->grads) H(hipMemset(c->grads, 0, sizeof(float) * (size_t)N * c->ld));
+    H(hipDeviceSynchronize());
+    return rc;
+}
+
 }  // namespace
 
 dbw_timer::dbw_timer(dbw_ctx *ctx, const char *name, hipStream_t st) : c(ctx), s(st)
@@ -148,103 +231,11 @@ int dbw_create(dbw_ctx **out, int32_t N, int64_t d, const int32_t *rowptr, const
 
     dbw_ctx *c = new (std::nothrow) dbw_ctx();
     if (!c) return DBW_ERR_ALLOC;
-    c->N = N;
-    c->d = d;
-    c->ld = d;
-    c->nnz = (int32_t)nnz64;
-    if (opts) {
-        if (opts->ld != 0) c->ld = opts->ld;
-        c->order = opts->order;
-        c->mix = opts->mix_path;
-        c->layout = opts->layout;
-        c->model = opts->model;
+    try {
+        rc = fill_ctx(c, N, d, nnz64, rowptr, colidx, opts);
+    } catch (const std::bad_alloc &) {
+        rc = DBW_ERR_ALLOC;
     }
-    if (c->ld < d || (c->order != DBW_ORDER_CTA && c->order != DBW_ORDER_ATC) || c->mix < DBW_MIX_AUTO ||
-        c->mix > DBW_MIX_DENSE) {
-        delete c;
-        return DBW_ERR_INVALID;
-    }
-    if (c->layout != DBW_LAYOUT_ROWS && c->layout != DBW_LAYOUT_TILES) {
-        delete c;
-        return DBW_ERR_INVALID;
-    }
-    if (c->layout == DBW_LAYOUT_TILES) {
-        if (c->ld % DBW_TILE_COLUMNS) {
-            delete c;
-            return DBW_ERR_INVALID;
-        }
-        if (c->model.kind != DBW_MODEL_NONE || N > DBW_TILES_MAX_N || c->mix == DBW_MIX_DENSE) {
-            delete c;
-            return DBW_ERR_UNSUPPORTED;
-        }
-        c->mix = DBW_MIX_CSR;
-    }
-    if (c->model.kind != DBW_MODEL_NONE) {
-        const int64_t want = model_param_count(c->model, &c->in_dim);
-        const bool loss_ok = c->model.loss == DBW_LOSS_XENT ||
-                             (c->model.loss == DBW_LOSS_MSE && c->model.kind == DBW_MODEL_MLP);
-        if (want != d || c->model.batch < 1 || !loss_ok) {
-            delete c;
-            return DBW_ERR_INVALID;
-        }
-    }
-    c->h_rowptr.assign(rowptr, rowptr + N + 1);
-    c->h_colidx.assign(colidx, colidx + c->nnz);
-    for (int i = 0; i < N; ++i) c->max_deg = std::max(c->max_deg, rowptr[i + 1] - rowptr[i]);
-    if (!spanning_links(N, rowptr, colidx, c->h_links)) {
-        delete c;
-        return DBW_ERR_GRAPH;
-    }
-    if (c->mix == DBW_MIX_AUTO)
-        c->mix = (N <= DBW_DENSE_MAX_N && (int64_t)c->nnz * 4 > (int64_t)N * N) ? DBW_MIX_DENSE : DBW_MIX_CSR;
-    if (c->mix == DBW_MIX_DENSE && N > DBW_DENSE_MAX_N) {
-        delete c;
-        return DBW_ERR_UNSUPPORTED;
-    }
-    c->Npad = 32;                                   // dense path: padded to a power of two
-    while (c->Npad < N) c->Npad *= 2;
-
-    rc = DBW_OK;
-    auto A = [&](int r) { if (rc == DBW_OK) rc = r; };
-    A(dev_alloc(&c->rowptr, (size_t)N + 1));
-    A(dev_alloc(&c->colidx, (size_t)c->nnz));
-    A(dev_alloc(&c->p, (size_t)N));
-    A(dev_alloc(&c->mask, (size_t)c->nnz));
-    A(dev_alloc(&c->wait, (size_t)N));
-    A(dev_alloc(&c->listed, (size_t)N));
-    A(dev_alloc(&c->sel_idx, (size_t)c->nnz));
-    A(dev_alloc(&c->sel_w, (size_t)c->nnz));
-    A(dev_alloc(&c->self_w, (size_t)N));
-    A(dev_alloc(&c->err, 1));
-    A(dev_alloc(&c->links, c->h_links.size()));
-    A(dev_alloc(&c->visited, (size_t)std::max(N - 1, 1)));
-    A(dev_alloc(&c->n_visited, 1));
-    if (c->mix == DBW_MIX_DENSE) A(dev_alloc(&c->Wdense, (size_t)c->Npad * c->Npad));
-    if (N <= DBW_DENSE_MAX_N) {
-        A(dev_alloc(&c->phi[0], (size_t)c->Npad * c->Npad));
-        A(dev_alloc(&c->phi[1], (size_t)c->Npad * c->Npad));
-        A(dev_alloc(&c->phi_frag, (size_t)c->Npad * c->Npad));
-    }
-    if (c->model.kind != DBW_MODEL_NONE) {
-        A(dev_alloc(&c->grads, (size_t)N * c->ld));
-        c->act_floats = c->model.kind == DBW_MODEL_MLP ? dbw_mlp_scratch_floats(c) : dbw_cnn_scratch_floats(c);
-        A(dev_alloc(&c->act, c->act_floats));
-    }
-    if (rc != DBW_OK) {
-        free_ctx(c);
-        return rc;
-    }
-    auto H = [&](hipError_t e) { if (rc == DBW_OK && e != hipSuccess) rc = DBW_ERR_HIP; };
-    H(hipMemcpy(c->rowptr, rowptr, sizeof(int32_t) * ((size_t)N + 1), hipMemcpyHostToDevice));
-    if (c->nnz) H(hipMemcpy(c->colidx, colidx, sizeof(int32_t) * (size_t)c->nnz, hipMemcpyHostToDevice));
-    if (!c->h_links.empty())
-        H(hipMemcpy(c->links, c->h_links.data(), sizeof(int32_t) * c->h_links.size(), hipMemcpyHostToDevice));
-    H(hipMemset(c->err, 0, sizeof(int32_t)));
-    H(hipMemset(c->visited, 0, (size_t)std::max(N - 1, 1)));
-    H(hipMemset(c->n_visited, 0, sizeof(int32_t)));
-    if (c->Wdense) H(hipMemset(c->Wdense, 0, sizeof(float) * (size_t)c->Npad * c->Npad));
-    if (c->grads) H(hipMemset(c->grads, 0, sizeof(float) * (size_t)N * c->ld));
-    H(hipDeviceSynchronize());
     if (rc != DBW_OK) {
         free_ctx(c);
         return rc;
@@ -309,7 +300,7 @@ int dbw_round_time(dbw_ctx *c, float *T_out, void *stream)
 }
 
 int dbw_get_weights(dbw_ctx *c, float *P, void *stream)
-{
+try {
     if (!c || !P) return DBW_ERR_NULL;
     if (!c->selected) return DBW_ERR_STATE;
     hipStream_t s = (hipStream_t)stream;
@@ -329,6 +320,8 @@ int dbw_get_weights(dbw_ctx *c, float *P, void *stream)
     }
     DBW_HIP(hipMemcpy(P, dense.data(), sizeof(float) * (size_t)N * N, hipMemcpyHostToDevice));
     return DBW_OK;
+} catch (const std::bad_alloc &) {
+    return DBW_ERR_ALLOC;
 }
 
 int dbw_grad(dbw_ctx *c, const float *params, const float *batch_x, const int32_t *batch_y, float *grads,

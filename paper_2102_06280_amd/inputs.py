@@ -18,7 +18,7 @@ import numpy as np
 SEED = 210206280
 
 # purpose ids of the independent random streams
-P_GRAPH, P_PARAMS, P_GRADS, P_BATCH_X, P_BATCH_Y, P_TIMES, P_BACKUP, P_SLOW = range(1, 9)
+P_GRAPH, P_PARAMS, P_GRADS, P_BATCH_X, P_BATCH_Y, P_TIMES, P_BACKUP, P_SLOW, P_TEACHER = range(1, 10)
 
 
 def rng(config: int, purpose: int, rnd: int = 0) -> np.random.Generator:
@@ -191,6 +191,7 @@ class Config:
     x_dist: str = "normal"   # batch input distribution: uniform | normal
     zero_init: bool = False
     lr_decay: float = 1.0    # lr(k) = lr * lr_decay ** k (Section 5: 0.95)
+    labels: str = "uniform"  # uniform: labels independent of the inputs | teacher: a learnable rule
 
 
 CONFIGS = {
@@ -256,11 +257,19 @@ def learning_rate(cfg: Config, rnd: int) -> float:
     return cfg.lr * cfg.lr_decay ** rnd
 
 
+def teacher(cfg: Config, in_dim: int) -> np.ndarray:
+    """[in_dim, 10] fixed random linear map: with labels == "teacher" a sample's class is the
+    largest of its ten scores, so that a model can learn the labels and a loss curve means
+    something (the stand-in for a real data set's structure)."""
+    return rng(cfg.cid, P_TEACHER).standard_normal((in_dim, 10))
+
+
 def batch(cfg: Config, rnd: int, workers=None):
     """(x [n, B, in] fp32, y [n, B] int32) for the given workers (default all)."""
     desc = model_dims(cfg.model)
     in_dim = desc["dims"][0] if desc["kind"] == "mlp" else int(np.prod(desc["in"]))
     workers = range(cfg.n) if workers is None else workers
+    scores = teacher(cfg, in_dim) if cfg.labels == "teacher" else None
     xs, ys = [], []
     for i in workers:
         gx = rng(cfg.cid, P_BATCH_X, rnd * 4096 + i)
@@ -269,7 +278,10 @@ def batch(cfg: Config, rnd: int, workers=None):
             xs.append(gx.random((cfg.batch, in_dim), dtype=np.float32))
         else:
             xs.append(gx.standard_normal((cfg.batch, in_dim), dtype=np.float32))
-        ys.append(gy.integers(0, 10, cfg.batch).astype(np.int32))
+        if scores is None:
+            ys.append(gy.integers(0, 10, cfg.batch).astype(np.int32))
+        else:
+            ys.append(np.argmax(xs[-1].astype(np.float64) @ scores, axis=1).astype(np.int32))
     return np.stack(xs), np.stack(ys)
 
 

@@ -1,9 +1,11 @@
-"""Device-resident synthetic workloads for the five benchmark configurations, and the
+"""Device-resident synthetic workloads for the benchmark configurations, and the
 round loop that drives the library over them.  Plumbing only: tensors are allocated and
 filled here (torch is used for memory, random fills and streams), every step of a round
 runs inside the library.
 """
 from __future__ import annotations
+
+import dataclasses
 
 import numpy as np
 import torch
@@ -16,8 +18,11 @@ class Workload:
     """All inputs of `rounds` rounds of one configuration, resident in HBM."""
 
     def __init__(self, cid: int, rounds: int, order: int = B.ORDER_CTA, mix_path: int = B.MIX_AUTO,
-                 d_override: int | None = None, ld_override: int | None = None, layout: int = B.LAYOUT_ROWS):
+                 d_override: int | None = None, ld_override: int | None = None, layout: int = B.LAYOUT_ROWS,
+                 labels: str | None = None):
         cfg = inputs.CONFIGS[cid]
+        if labels is not None:
+            cfg = dataclasses.replace(cfg, labels=labels)
         self.cfg, self.cid, self.rounds, self.order = cfg, cid, rounds, order
         self.rowptr, self.colidx = inputs.make_graph(cfg)
         self.n = cfg.n
