@@ -3,7 +3,8 @@
 // Selection (Section 1 "Dynamic Backup Workers", Section 2.2): worker i waits for the
 // p_i = deg_i - b_i neighbours that answer first; the rest are backups.  One 64-lane
 // wavefront per worker ranks the row's neighbours by the 64-bit key (time, index): a
-// neighbour is selected iff fewer than p_i keys in the row are smaller than its own.
+// neighbour is selected iff fewer than p_i keys in the row are smaller than its own (rows
+// longer than 64 neighbours are shared by four wavefronts).
 // Keys are distinct (indices are), so the ranks form a permutation and the result does
 // not depend on any scheduling order.
 //
@@ -43,36 +44,41 @@ __device__ __forceinline__ float wave_max(float v)
     return v;
 }
 
-// grid = N blocks of one wavefront.
-__global__ __launch_bounds__(64) void select_kernel(
+// grid = N blocks of WAVES wavefronts: one block per worker.  Each wave ranks one 64-wide slice
+// of the row at a time; slices are compacted in ascending order through per-wave counts.
+template <int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void select_kernel(
     int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
     const float *__restrict__ t, const int32_t *__restrict__ b, int32_t *__restrict__ p_out,
     uint8_t *__restrict__ mask, float *__restrict__ wait, int32_t *__restrict__ sel_idx,
     float *__restrict__ sel_w, float *__restrict__ self_w, float *__restrict__ Wdense, int Npad,
     int32_t *__restrict__ err)
 {
+    constexpr int T = 64 * WAVES;
     __shared__ uint64_t keys[DBW_SELECT_LDS_KEYS];
     __shared__ float wrow[DBW_DENSE_MAX_N];
-    const int i = blockIdx.x, lane = threadIdx.x;
+    __shared__ int slice_cnt[WAVES];
+    __shared__ float red[2][WAVES];
+    const int i = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int beg = rowptr[i], deg = rowptr[i + 1] - beg;
     const int bi_raw = b[i];
-    if ((bi_raw < 0 || bi_raw > deg) && lane == 0) *err = DBW_ERR_INVALID;
+    if ((bi_raw < 0 || bi_raw > deg) && tid == 0) *err = DBW_ERR_INVALID;
     const int pi = deg - clamp_b(bi_raw, deg);
     const bool in_lds = deg <= DBW_SELECT_LDS_KEYS;
 
     if (in_lds)
-        for (int k = lane; k < deg; k += 64) {
+        for (int k = tid; k < deg; k += T) {
             int j = colidx[beg + k];
             keys[k] = make_key(t[j], j);
         }
     if (Wdense)
-        for (int c = lane; c < Npad; c += 64) wrow[c] = 0.0f;
+        for (int c = tid; c < Npad; c += T) wrow[c] = 0.0f;
     __syncthreads();
 
     float wsum = 0.0f, tmax = canon_time(t[i]);
     int base = 0;
-    for (int k0 = 0; k0 < deg; k0 += 64) {
-        const int k = k0 + lane;
+    for (int k0 = 0; k0 < deg; k0 += T) {
+        const int k = k0 + tid;
         bool sel = false;
         int j = 0;
         float w = 0.0f;
@@ -99,32 +105,57 @@ __global__ __launch_bounds__(64) void select_kernel(
                 tmax = fmaxf(tmax, canon_time(tj));
             }
         }
-        // compact the selected neighbours of this 64-wide slice, keeping ascending order
+        // compact the selected neighbours of this slice, keeping ascending order
         const uint64_t ballot = __ballot(sel);
+        int before = 0, total = __popcll(ballot);
+        if (WAVES > 1) {
+            if (lane == 0) slice_cnt[wave] = total;
+            __syncthreads();
+            total = 0;
+#pragma unroll
+            for (int q = 0; q < WAVES; ++q) {
+                before += q < wave ? slice_cnt[q] : 0;
+                total += slice_cnt[q];
+            }
+            __syncthreads();                          // slice_cnt is rewritten in the next pass
+        }
         if (sel) {
-            const int pos = base + __popcll(ballot & ((1ull << lane) - 1ull));
+            const int pos = base + before + __popcll(ballot & ((1ull << lane) - 1ull));
             sel_idx[beg + pos] = j;
             sel_w[beg + pos] = w;
             if (Wdense) wrow[j] = w;
         }
-        base += __popcll(ballot);
+        base += total;
     }
     wsum = wave_sum(wsum);
     tmax = wave_max(tmax);
+    if (WAVES > 1) {
+        if (lane == 0) {
+            red[0][wave] = wsum;
+            red[1][wave] = tmax;
+        }
+        __syncthreads();
+        wsum = 0.0f;
+#pragma unroll
+        for (int q = 0; q < WAVES; ++q) {
+            wsum += red[0][q];
+            tmax = fmaxf(tmax, red[1][q]);
+        }
+    }
     const float ws = 1.0f - wsum;
-    if (lane == 0) {
+    if (tid == 0) {
         p_out[i] = pi;
         wait[i] = tmax;
         self_w[i] = ws;
     }
     if (Wdense) {
         __syncthreads();
-        if (lane == 0) wrow[i] = ws;
+        if (tid == 0) wrow[i] = ws;
         __syncthreads();
         // A-operand fragment order of the dense kernel: [row block][k-step][lane], with
         // lane = (k % 2) * 32 + row % 32 holding P[row][k]
         const int KB = Npad / 2;
-        for (int c = lane; c < Npad; c += 64)
+        for (int c = tid; c < Npad; c += T)
             Wdense[((size_t)(i >> 5) * KB + (c >> 1)) * 64 + (c & 1) * 32 + (i & 31)] = wrow[c];
     }
 }
@@ -245,8 +276,13 @@ int dbw_launch_round_time(dbw_ctx *c, float *out, hipStream_t s)
 int dbw_launch_select(dbw_ctx *c, const float *t, const int32_t *b, hipStream_t s)
 {
     dbw_timer tm(c, "select_kernel", s);
-    hipLaunchKernelGGL(select_kernel, dim3(c->N), dim3(64), 0, s, c->N, c->rowptr, c->colidx, t, b, c->p,
-                       c->mask, c->wait, c->sel_idx, c->sel_w, c->self_w, c->Wdense, c->Npad, c->err);
+    // rows longer than one wavefront are ranked by four wavefronts side by side
+    if (c->max_deg > 64)
+        hipLaunchKernelGGL(select_kernel<4>, dim3(c->N), dim3(256), 0, s, c->N, c->rowptr, c->colidx, t, b, c->p,
+                           c->mask, c->wait, c->sel_idx, c->sel_w, c->self_w, c->Wdense, c->Npad, c->err);
+    else
+        hipLaunchKernelGGL(select_kernel<1>, dim3(c->N), dim3(64), 0, s, c->N, c->rowptr, c->colidx, t, b, c->p,
+                           c->mask, c->wait, c->sel_idx, c->sel_w, c->self_w, c->Wdense, c->Npad, c->err);
     DBW_HIP(hipGetLastError());
     return DBW_OK;
 }
