@@ -60,9 +60,10 @@ enum {
 
 /* How the masked consensus average is evaluated. */
 enum {
-    DBW_MIX_AUTO = 0,  /* dense when N <= 256 and the graph holds more than N*N/4 links */
+    DBW_MIX_AUTO = 0,  /* dense when it is supported and the graph holds more than N*N/4 links */
     DBW_MIX_CSR = 1,   /* gather over the selected neighbours only (HBM bound) */
-    DBW_MIX_DENSE = 2  /* materialise P(k) as N x N and multiply on the matrix cores */
+    DBW_MIX_DENSE = 2  /* materialise P(k) as N x N and multiply on the matrix cores; needs N <= 256
+                        * and ld <= 26 843 545 (DBW_ERR_UNSUPPORTED from dbw_create otherwise) */
 };
 
 /* How the N parameter vectors are laid out in a [N * ld] float array. */
@@ -195,7 +196,8 @@ int dbw_round_eta(dbw_ctx *ctx, const float *params_in, float *params_out, const
  * row convention.  resp_times [dev, r*N] and b [dev, r*N]: row q holds round q's response
  * times and backup counts, used as by dbw_select.  The result equals r times (dbw_select,
  * dbw_round with ext_grads = NULL) up to fp32 rounding; the parameters are read and written
- * once instead of r times.  Needs N <= 256 (DBW_ERR_UNSUPPORTED otherwise).  Leaves the
+ * once instead of r times.  Needs N <= 256, ld <= 26 843 545 and the rows layout
+ * (DBW_ERR_UNSUPPORTED otherwise).  Leaves the
  * selection state of the last of the r rounds; out-of-range b is reported as by dbw_select.
  * params_out must not overlap params_in.  Asynchronous on `stream`. */
 int dbw_consensus_rounds(dbw_ctx *ctx, const float *params_in, float *params_out, const float *resp_times,

@@ -144,9 +144,10 @@ int fill_ctx(dbw_ctx *c, int32_t N, int64_t d, int64_t nnz64, const int32_t *row
     c->h_colidx.assign(colidx, colidx + c->nnz);
     for (int i = 0; i < N; ++i) c->max_deg = std::max(c->max_deg, rowptr[i + 1] - rowptr[i]);
     if (!spanning_links(N, rowptr, colidx, c->h_links)) return DBW_ERR_GRAPH;
+    const bool dense_fits = N <= DBW_DENSE_MAX_N && c->ld <= DBW_DENSE_MAX_LD;
     if (c->mix == DBW_MIX_AUTO)
-        c->mix = (N <= DBW_DENSE_MAX_N && (int64_t)c->nnz * 4 > (int64_t)N * N) ? DBW_MIX_DENSE : DBW_MIX_CSR;
-    if (c->mix == DBW_MIX_DENSE && N > DBW_DENSE_MAX_N) return DBW_ERR_UNSUPPORTED;
+        c->mix = (dense_fits && (int64_t)c->nnz * 4 > (int64_t)N * N) ? DBW_MIX_DENSE : DBW_MIX_CSR;
+    if (c->mix == DBW_MIX_DENSE && !dense_fits) return DBW_ERR_UNSUPPORTED;
     c->Npad = 32;                                   // dense path: padded to a power of two
     while (c->Npad < N) c->Npad *= 2;
 
@@ -384,7 +385,8 @@ int dbw_consensus_rounds(dbw_ctx *c, const float *params_in, float *params_out, 
 {
     if (!c || !params_in || !params_out || !resp_times || !b) return DBW_ERR_NULL;
     if (r < 1) return DBW_ERR_INVALID;
-    if (c->N > DBW_DENSE_MAX_N || c->layout != DBW_LAYOUT_ROWS) return DBW_ERR_UNSUPPORTED;
+    if (c->N > DBW_DENSE_MAX_N || c->ld > DBW_DENSE_MAX_LD || c->layout != DBW_LAYOUT_ROWS)
+        return DBW_ERR_UNSUPPORTED;
     const size_t bytes = sizeof(float) * (size_t)c->N * (size_t)c->ld;
     if (overlaps(params_in, bytes, params_out, bytes)) return DBW_ERR_ALIAS;
     const int rc = dbw_launch_consensus_rounds(c, params_in, params_out, resp_times, b, r, (hipStream_t)stream);

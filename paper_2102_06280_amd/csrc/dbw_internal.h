@@ -16,6 +16,8 @@
     } while (0)
 
 constexpr int DBW_DENSE_MAX_N = 256;   // the dense mixing kernel keeps all of P(k) in registers
+// the dense mixing kernel adds 32-bit per-lane byte offsets of up to 40 rows to 64-bit uniform bases
+constexpr int64_t DBW_DENSE_MAX_LD = (int64_t)UINT32_MAX / (40 * 4);
 constexpr int DBW_SELECT_LDS_KEYS = 2048;
 constexpr int DBW_TILES_MAX_N = 256;   // the tile-major mixing kernel holds one 256-byte piece per worker in LDS
 

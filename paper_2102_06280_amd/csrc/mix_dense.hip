@@ -242,8 +242,7 @@ int launch_mb(dbw_ctx *c, const float *W, const float *x, const float *g, float 
     using C = dense_cfg<MB>;
     const int64_t n_tiles = (n_vec * 4 + C::TC - 1) / C::TC;
     if (n_tiles > INT32_MAX) return DBW_ERR_UNSUPPORTED;
-    // 32-bit lane offsets inside the kernel cover up to 32 rows
-    if ((int64_t)40 * c->ld * 4 > (int64_t)UINT32_MAX) return DBW_ERR_UNSUPPORTED;
+    if (c->ld > DBW_DENSE_MAX_LD) return DBW_ERR_UNSUPPORTED;
     int cus = 256;
     int dev = 0;
     hipDeviceProp_t prop;

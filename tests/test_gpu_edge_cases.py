@@ -92,3 +92,22 @@ def test_rows_longer_than_the_key_buffer(B, orc):
     t = np.round(g.standard_exponential(n) * 8).astype(np.float32) / 8      # many ties
     b = g.integers(0, n, n).astype(np.int32)
     one_round(B, orc, rowptr, colidx, 8, 8, 0, t, b, mix=B.MIX_CSR)
+
+
+def test_dense_path_limits(B):
+    """The matrix-core path is refused at create beyond its limits (N > 256 workers, or rows so
+    long that its 32-bit lane offsets would wrap), and the automatic choice avoids it there."""
+    rowptr, colidx = inputs.graph_complete(16)
+    too_long = 26_843_545 + 1 + 63
+    too_long -= too_long % 64
+    with pytest.raises(RuntimeError, match="not supported"):
+        B.dbw_create(rowptr, colidx, 16, too_long, ld=too_long, mix_path=B.MIX_DENSE)
+    h = B.dbw_create(rowptr, colidx, 16, too_long, ld=too_long)
+    assert B.dbw_mix_path(h) == B.MIX_CSR
+    B.dbw_destroy(h)
+    h = B.dbw_create(rowptr, colidx, 16, 4096)
+    assert B.dbw_mix_path(h) == B.MIX_DENSE
+    B.dbw_destroy(h)
+    rowptr, colidx = inputs.graph_complete(300)
+    with pytest.raises(RuntimeError, match="not supported"):
+        B.dbw_create(rowptr, colidx, 300, 64, mix_path=B.MIX_DENSE)

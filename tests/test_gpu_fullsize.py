@@ -11,14 +11,21 @@ from gpu_util import assert_params_close
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("cid,order,tiles", [(4, 0, False), (4, 1, False), (5, 0, False), (5, 1, False),
-                                             (4, 0, True), (4, 1, True)],
-                         ids=["c4-cta", "c4-atc", "c5-cta", "c5-atc", "c4-cta-tiles", "c4-atc-tiles"])
-def test_full_size_sampled_columns(orc, cid, order, tiles):
+# d = None: the benchmark's own size.  The larger d make N * d exceed 2^31 elements per matrix
+# (8.7 GB each), so that element offsets no longer fit 32 bits: N = 128 x 17 M on both sparse
+# kernels, N = 256 x 8.5 M on the matrix-core kernel.
+@pytest.mark.parametrize("cid,order,tiles,d", [(4, 0, False, None), (4, 1, False, None), (5, 0, False, None),
+                                               (5, 1, False, None), (4, 0, True, None), (4, 1, True, None),
+                                               (4, 0, False, 17_000_006), (4, 1, True, 17_000_006),
+                                               (5, 0, False, 8_500_003)],
+                         ids=["c4-cta", "c4-atc", "c5-cta", "c5-atc", "c4-cta-tiles", "c4-atc-tiles",
+                              "c4-rows-2g-elements", "c4-tiles-2g-elements", "c5-2g-elements"])
+def test_full_size_sampled_columns(orc, cid, order, tiles, d):
     from paper_2102_06280_amd import binding as B
     from paper_2102_06280_amd.workload import Workload
-    wl = Workload(cid, rounds=2, order=order, layout=B.LAYOUT_TILES if tiles else B.LAYOUT_ROWS)
+    wl = Workload(cid, rounds=2, order=order, layout=B.LAYOUT_TILES if tiles else B.LAYOUT_ROWS, d_override=d)
     try:
+        assert d is None or wl.n * wl.ld > 2 ** 31
         cfg = wl.cfg
         blk = 4096
         g = np.random.default_rng(311 + cid)
