@@ -108,8 +108,14 @@ __global__ __launch_bounds__(THREADS) void forward_kernel(
 // k0 = 256 slice .. of x (held in LDS, read from memory once) with the matching 1 KB piece of
 // every row of W and writes the partial sums part[worker][slice][m][n]; a separate pass adds the
 // slices in order, then bias and activation.  Wave q owns the output units [q N / 4, (q + 1) N / 4)
-// as NF fragments of 32; a step is one (32-wide k window, fragment) pair = 16 instructions, and
-// the W values of step s + 2 are requested before the multiplies of step s.
+// as NF fragments of 32; a step is one (32-wide k window, fragment) pair = 16 instructions.
+// The B operand wants lane (r, slot) to hold 16 consecutive floats of row r, which as a load
+// touches only 32 bytes of each 128-byte line per instruction.  Instead the wave fetches the
+// step's 32 x 128 B block of W with whole lines per instruction (lane l: row 8 i + l / 8,
+// 16-byte piece l % 8, for i = 0..3), requested two steps ahead, and turns it through a
+// 4 KB LDS area of its own (no barrier: one wave writes and reads it, in order).  Piece p of
+// row r sits at position p ^ (r % 8) of the row, which spreads both access patterns over all
+// banks.
 // Compared with forward_kernel the inputs are fetched once instead of once per 32 output units.
 // Needs N == 128 NF, K % 256 == 0.  grid = (K / 256, workers).
 constexpr int KSLICE = 256;
@@ -120,6 +126,7 @@ __global__ __launch_bounds__(THREADS) void forward_ksplit_kernel(
 {
     constexpr int LDX = KSLICE + 4, N = 128 * NF, WINDOWS = KSLICE / 32, STEPS = WINDOWS * NF;
     __shared__ __attribute__((aligned(16))) float xs[32 * LDX];
+    __shared__ __attribute__((aligned(16))) float turn[4][32 * 32];
     const int slice = blockIdx.x, w = blockIdx.y, k0 = slice * KSLICE;
     const int tid = threadIdx.x, lane = tid & 63;
     const int q = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -128,26 +135,38 @@ __global__ __launch_bounds__(THREADS) void forward_ksplit_kernel(
         const int m = e / (KSLICE / 4), c4 = e % (KSLICE / 4);
         *(f32x4 *)&xs[m * LDX + 4 * c4] = *(const f32x4 *)(x + w * x_stride + (int64_t)m * ldx + k0 + 4 * c4);
     }
-    const float *wr = W + w * w_stride + (int64_t)(q * (N / 4) + r) * K + k0 + 16 * ks;
+    const int lrow = lane >> 3, piece = lane & 7;
+    const float *wl = W + w * w_stride + (int64_t)(q * (N / 4) + lrow) * K + k0 + 4 * piece;
     auto request = [&](int step, f32x4 (&b)[4]) {
         const int win = step / NF, f = step % NF;
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            b[j] = __builtin_nontemporal_load((const f32x4 *)(wr + (int64_t)(32 * f) * K + 32 * win + 4 * j));
+        for (int i = 0; i < 4; ++i)
+            b[i] = __builtin_nontemporal_load((const f32x4 *)(wl + (int64_t)(32 * f + 8 * i) * K + 32 * win));
     };
+    float *mine = turn[q];
+    const int put = lrow * 32 + 4 * (piece ^ lrow);                  // + 256 i: row 8 i + lrow
+    int get[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) get[j] = r * 32 + 4 * ((4 * ks + j) ^ (r & 7));
     f32x16 acc[NF];
 #pragma unroll
     for (int f = 0; f < NF; ++f)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[f][v] = 0.f;
-    f32x4 wb[3][4], xa[4];
-    request(0, wb[0]);
-    if (STEPS > 1) request(1, wb[1]);
+    constexpr int AHEAD = 2;                                          // steps requested before they are used
+    f32x4 st[AHEAD + 1][4], wb[4], xa[4];
+#pragma unroll
+    for (int a = 0; a < AHEAD; ++a)
+        if (a < STEPS) request(a, st[a]);
     __syncthreads();
 #pragma unroll
     for (int step = 0; step < STEPS; ++step) {
         const int win = step / NF, f = step % NF;
-        if (step + 2 < STEPS) request(step + 2, wb[(step + 2) % 3]);
+        if (step + AHEAD < STEPS) request(step + AHEAD, st[(step + AHEAD) % (AHEAD + 1)]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) *(f32x4 *)&mine[put + 256 * i] = st[step % (AHEAD + 1)][i];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) wb[j] = *(const f32x4 *)&mine[get[j]];
         if (f == 0) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) xa[j] = *(const f32x4 *)&xs[r * LDX + 32 * win + 16 * ks + 4 * j];
@@ -156,7 +175,7 @@ __global__ __launch_bounds__(THREADS) void forward_ksplit_kernel(
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-                acc[f] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa[j][e], wb[step % 3][j][e], acc[f], 0, 0, 0);
+                acc[f] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa[j][e], wb[j][e], acc[f], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
     }
     float *pb = part + w * part_stride + (int64_t)slice * 32 * N + q * (N / 4) + r;
@@ -168,24 +187,30 @@ __global__ __launch_bounds__(THREADS) void forward_ksplit_kernel(
 
 // ---------------------------------------------------------------------------------------------
 // dx[m][k] = sum_n dz[m][n] W[n][k]   (kept only where mask[m][k] > 0 when mask is given).
-// A workgroup owns 128 columns k; wave q reduces over the q-th quarter of n.  Lane (c, slot)
-// loads W[n][k0 + 4 c .. + 3] as one 128-bit value and feeds four column fragments with it
+// A wave owns 128 columns k and one of NSPLIT parts of n; a workgroup's four waves cover
+// 4 / NSPLIT adjacent column groups, so that NSPLIT = 1 reads 2 KB runs of every row of W (the
+// four waves walk down the same rows side by side) and needs no reduction, while NSPLIT = 4
+// gives four times as many workgroups for small layers.  Lane (c, slot) loads
+// W[n][k0 + 4 c .. + 3] as one 128-bit value and feeds four column fragments with it
 // (fragment f, lane column c <-> k = k0 + 4 c + f), so a wave instruction reads 512 contiguous
 // bytes of each of two rows and the result leaves as 128-bit stores.  The reduction index of
 // instruction (step, j) and slot is n = base + 8 step + 4 slot + j, which makes dz a 128-bit
-// load too.  Partial sums of waves 1..3 go through LDS; wave 0 adds them in order and stores.
-// Needs N % 32 == 0, K % 128 == 0.  grid = (K / 128, workers).
+// load too.  Partial sums of the other parts go through LDS; part 0 adds them in order and stores.
+// Needs N % (8 NSPLIT) == 0, K % (512 / NSPLIT) == 0.  grid = (K / (512 / NSPLIT), workers).
+template <int NSPLIT>
 __global__ __launch_bounds__(THREADS) void dgrad_kernel(
     int N, int K, const float *__restrict__ dz, int64_t lddz, int64_t dz_stride, const float *__restrict__ W,
     int64_t w_stride, const float *__restrict__ mask, int64_t ldmask, int64_t mask_stride, float *__restrict__ dx,
     int64_t lddx, int64_t dx_stride)
 {
-    __shared__ __attribute__((aligned(16))) float red[3][32 * 132];
-    const int w = blockIdx.y, k0 = blockIdx.x * 128;
+    constexpr int CW = 4 / NSPLIT;                                   // column groups per workgroup
+    __shared__ __attribute__((aligned(16))) float red[NSPLIT > 1 ? (NSPLIT - 1) * CW : 1][NSPLIT > 1 ? 32 * 132 : 4];
     const int tid = threadIdx.x, lane = tid & 63;
     const int q = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int part = q % NSPLIT, cgp = q / NSPLIT;
+    const int w = blockIdx.y, k0 = (blockIdx.x * CW + cgp) * 128;
     const int c = lane & 31, ks = lane >> 5;
-    const int nper = N / 4, nb = q * nper;
+    const int nper = N / NSPLIT, nb = part * nper;
     const float *zr = dz + w * dz_stride + (int64_t)c * lddz + nb + 4 * ks;            // row m = c
     const float *wc = W + w * w_stride + (int64_t)(nb + 4 * ks) * K + k0 + 4 * c;
 
@@ -219,22 +244,23 @@ __global__ __launch_bounds__(THREADS) void dgrad_kernel(
             __builtin_amdgcn_sched_barrier(0);
         }
     }
-    if (q > 0) {
+    if (NSPLIT > 1) {
+        if (part > 0) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            f32x4 t = {acc[0][v], acc[1][v], acc[2][v], acc[3][v]};
-            *(f32x4 *)&red[q - 1][d_row(v, lane) * 132 + 4 * c] = t;
+            for (int v = 0; v < 16; ++v) {
+                f32x4 t = {acc[0][v], acc[1][v], acc[2][v], acc[3][v]};
+                *(f32x4 *)&red[(part - 1) * CW + cgp][d_row(v, lane) * 132 + 4 * c] = t;
+            }
         }
+        __syncthreads();
     }
-    __syncthreads();
-    if (q == 0) {
+    if (part == 0) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int m = d_row(v, lane);
             f32x4 t = {acc[0][v], acc[1][v], acc[2][v], acc[3][v]};
-            t += *(const f32x4 *)&red[0][m * 132 + 4 * c];
-            t += *(const f32x4 *)&red[1][m * 132 + 4 * c];
-            t += *(const f32x4 *)&red[2][m * 132 + 4 * c];
+#pragma unroll
+            for (int o = 1; o < NSPLIT; ++o) t += *(const f32x4 *)&red[(o - 1) * CW + cgp][m * 132 + 4 * c];
             if (mask) {
                 const f32x4 a = *(const f32x4 *)(mask + w * mask_stride + (int64_t)m * ldmask + k0 + 4 * c);
 #pragma unroll

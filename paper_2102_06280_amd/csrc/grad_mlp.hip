@@ -285,14 +285,14 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
         }
         if (l > 1 && fast && a_off[l - 1] % 4 == 0 && dz_off[l - 1] % 4 == 0) {
             dbw_timer tm(c, "fc32_dgrad", s);
-            hipLaunchKernelGGL(fc32::dgrad_kernel, dim3(dims[l - 1] / 128, N), dim3(fc32::THREADS), 0, s, dims[l],
+            hipLaunchKernelGGL(fc32::dgrad_kernel<4>, dim3(dims[l - 1] / 128, N), dim3(fc32::THREADS), 0, s, dims[l],
                                dims[l - 1], act + dz_off[l], (int64_t)dims[l], wstride, params + w_off[l], c->ld,
                                act + a_off[l - 1], (int64_t)dims[l - 1], wstride, act + dz_off[l - 1],
                                (int64_t)dims[l - 1], wstride);
             DBW_HIP(hipGetLastError());
         } else if (l == 1 && a.din && fast && a.din_ld % 4 == 0 && a.din_stride % 4 == 0 && fc32::aligned16(a.din)) {
             dbw_timer tm(c, "fc32_dgrad", s);
-            hipLaunchKernelGGL(fc32::dgrad_kernel, dim3(dims[0] / 128, N), dim3(fc32::THREADS), 0, s, dims[1], dims[0],
+            hipLaunchKernelGGL(fc32::dgrad_kernel<1>, dim3(dims[0] / 512, N), dim3(fc32::THREADS), 0, s, dims[1], dims[0],
                                act + dz_off[1], (int64_t)dims[1], wstride, params + w_off[1], c->ld,
                                (const float *)nullptr, (int64_t)0, (int64_t)0, a.din, a.din_ld, a.din_stride);
             DBW_HIP(hipGetLastError());
