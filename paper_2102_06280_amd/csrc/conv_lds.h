@@ -58,6 +58,41 @@ struct Cfg {
     static constexpr size_t lds_bytes = sizeof(float) * (IMG + 2 * COUT * LDA) + sizeof(int) * KGS * 16;
 };
 
+// ReLU + 2 x 2 max pooling of one sample's accumulators, written as the pooled map ob [COUT][H/2][W/2]
+// and the window codes cb of the same shape (see conv_forward_kernel).  A wave's fragments cover
+// whole pairs of image rows, so a window is two accumulators of one lane and of its neighbour.
+template <int MT, int NT, int H, int W>
+__device__ __forceinline__ void relu_pool_store(const f32x4 (&acc)[MT][NT], const float *bias, float *ob, uint8_t *cb,
+                                                int wave, int lane)
+{
+    constexpr int FR = W / 16;                       // fragments per image row
+    static_assert((NT * 16) % (2 * W) == 0 && H % 2 == 0, "a wave must cover whole pairs of rows");
+    constexpr int PP = (H / 2) * (W / 2);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int co = 16 * mt + 4 * (lane >> 4) + v;
+            const float bv = bias ? bias[co] : 0.f;
+#pragma unroll
+            for (int nf = 0; nf < NT; ++nf) {
+                if ((nf / FR) % 2) continue;         // lower row of a pair: handled with the upper one
+                const int p = (wave * NT + nf) * 16 + (lane & 15);
+                const int y = p / W, x = p % W;
+                const float a = acc[mt][nf][v] + bv, c = acc[mt][nf + FR][v] + bv;
+                const float a1 = __shfl_xor(a, 1), c1 = __shfl_xor(c, 1);
+                if ((lane & 1) == 0) {               // even x: window (y, x) (y, x+1) (y+1, x) (y+1, x+1)
+                    const float m = fmaxf(fmaxf(a, a1), fmaxf(c, c1));
+                    int arg = 4;
+                    if (m > 0.f) arg = (a == m) ? 0 : (a1 == m) ? 1 : (c == m) ? 2 : 3;
+                    const int o = co * PP + (y / 2) * (W / 2) + x / 2;
+                    ob[o] = fmaxf(m, 0.f);
+                    cb[o] = (uint8_t)arg;
+                }
+            }
+        }
+}
+
 // in  [worker][B][Cin][H][W]   (worker stride in_stride)
 // wgt [worker][COUT][ldw]      (row co holds its Cin * KK filter taps, worker stride w_stride)
 // out [worker][B][COUT][H][W]  (worker stride out_stride);  grid = (B, workers)
@@ -174,34 +209,10 @@ __global__ __launch_bounds__(64 * WAVES) void conv_forward_kernel(
     }
 
     if (POOL) {
-        constexpr int FR = W / 16;                       // fragments per image row
-        static_assert(!POOL || ((NT * 16) % (2 * W) == 0 && H % 2 == 0), "a wave must cover whole pairs of rows");
         constexpr int PP = (H / 2) * (W / 2);
-        float *ob = out + w * out_stride + (int64_t)b * C::COUT * PP;
-        uint8_t *cb = code + w * code_stride + (int64_t)b * C::COUT * PP;
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int co = 16 * mt + 4 * (lane >> 4) + v;
-                const float bv = bias ? bias[w * bias_stride + co] : 0.f;
-#pragma unroll
-                for (int nf = 0; nf < NT; ++nf) {
-                    if ((nf / FR) % 2) continue;         // lower row of a pair: handled with the upper one
-                    const int p = (wave * NT + nf) * 16 + (lane & 15);
-                    const int y = p / W, x = p % W;
-                    const float a = acc[mt][nf][v] + bv, c = acc[mt][nf + FR][v] + bv;
-                    const float a1 = __shfl_xor(a, 1), c1 = __shfl_xor(c, 1);
-                    if ((lane & 1) == 0) {               // even x: window (y, x) (y, x+1) (y+1, x) (y+1, x+1)
-                        const float m = fmaxf(fmaxf(a, a1), fmaxf(c, c1));
-                        int arg = 4;
-                        if (m > 0.f) arg = (a == m) ? 0 : (a1 == m) ? 1 : (c == m) ? 2 : 3;
-                        const int o = co * PP + (y / 2) * (W / 2) + x / 2;
-                        ob[o] = fmaxf(m, 0.f);
-                        cb[o] = (uint8_t)arg;
-                    }
-                }
-            }
+        relu_pool_store<MT, NT, H, W>(acc, bias ? bias + w * bias_stride : nullptr,
+                                      out + w * out_stride + (int64_t)b * C::COUT * PP,
+                                      code + w * code_stride + (int64_t)b * C::COUT * PP, wave, lane);
         return;
     }
     float *ob = out + w * out_stride + (int64_t)b * C::COUT * C::PIX;
@@ -217,6 +228,119 @@ __global__ __launch_bounds__(64 * WAVES) void conv_forward_kernel(
                 ob[co * C::PIX + p] = acc[mt][nf][v] + bv;
             }
         }
+}
+
+// conv_forward_kernel with POOL for a layer whose input channels all fit one LDS fill (Cin <= CG)
+// and whose filters fit the two weight buffers: a workgroup keeps the filters in LDS and runs
+// through SB consecutive samples.  The next sample's image is requested before the multiplies
+// of the current one and put into LDS after them, so that neither the filter fetch nor the
+// image fetch is waited for more than once per workgroup.  grid = (ceil(B / SB), workers).
+template <int CG, int MT, int NT, int H, int W, int KS, int WAVES, int SB>
+__global__ __launch_bounds__(64 * WAVES) void conv_forward_pool_multi_kernel(
+    const float *__restrict__ in, int64_t in_stride, const float *__restrict__ wgt, int64_t w_stride, int ldw,
+    const float *__restrict__ bias, int64_t bias_stride, float *__restrict__ out, int64_t out_stride, int Cin, int B,
+    uint8_t *__restrict__ code, int64_t code_stride)
+{
+    using C = Cfg<CG, MT, NT, H, W, KS, WAVES>;
+    static_assert(C::CHUNKS <= 2, "the filters must fit the two weight buffers");
+    constexpr int QUADS = CG * H * (W / 4), PER = (QUADS + C::THREADS - 1) / C::THREADS, PP = (H / 2) * (W / 2);
+    __shared__ __attribute__((aligned(16))) float img[C::IMG];
+    __shared__ __attribute__((aligned(16))) float As[2][C::COUT * C::LDA];
+    __shared__ __attribute__((aligned(16))) int taptab[C::KGS * 16];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int b0 = blockIdx.x * SB, w = blockIdx.y;
+
+    for (int k = tid; k < C::KGS * 16; k += C::THREADS) {
+        const int c = k / C::KK, rr = k % C::KK, kh = rr / KS, kw = rr % KS;
+        taptab[k] = k < C::TAPS ? c * C::HP * C::WP + kh * C::WP + kw : 0;
+    }
+    for (int e = tid; e < C::IMG; e += C::THREADS) img[e] = 0.f;     // the halo stays zero
+
+    int pixoff[NT];
+#pragma unroll
+    for (int nf = 0; nf < NT; ++nf) {
+        const int p = (wave * NT + nf) * 16 + (lane & 15);
+        pixoff[nf] = (p / W) * C::WP + (p % W);
+    }
+    const float *ww = wgt + w * w_stride;
+#pragma unroll
+    for (int chunk = 0; chunk < C::CHUNKS; ++chunk) {
+        const int kloc = chunk * 64 + lane;
+        const bool ok = kloc < C::TAPS && kloc / C::KK < Cin;
+#pragma unroll
+        for (int j = 0; j < C::AROWS; ++j) {
+            const float v = ww[(wave + WAVES * j) * ldw + (ok ? kloc : 0)];
+            As[chunk][(wave + WAVES * j) * C::LDA + lane] = ok ? v : 0.f;
+        }
+    }
+
+    float4 iv[PER];
+    auto request_image = [&](int b) {
+        const float *inb = in + w * in_stride + (int64_t)b * Cin * C::PIX;
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int e = tid + u * C::THREADS;
+            const int c = e / (H * (W / 4)), rem = e % (H * (W / 4));
+            iv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (e < QUADS && c < Cin) iv[u] = *(const float4 *)&inb[c * C::PIX + 4 * rem];
+        }
+    };
+    auto put_image = [&]() {
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int e = tid + u * C::THREADS;
+            if (e < QUADS) {
+                const int c = e / (H * (W / 4)), rem = e % (H * (W / 4)), y = rem / (W / 4), x4 = rem % (W / 4);
+                float *dst = &img[c * C::HP * C::WP + (y + C::PAD) * C::WP + C::PAD + 4 * x4];
+                dst[0] = iv[u].x; dst[1] = iv[u].y; dst[2] = iv[u].z; dst[3] = iv[u].w;
+            }
+        }
+    };
+    request_image(b0);
+    __syncthreads();                                   // the zero fill is complete
+    put_image();
+    __syncthreads();
+
+    for (int sidx = 0; sidx < SB; ++sidx) {
+        const int b = b0 + sidx;
+        const bool more = sidx + 1 < SB && b + 1 < B;  // uniform over the workgroup
+        if (more) request_image(b + 1);
+        f32x4 acc[MT][NT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int nf = 0; nf < NT; ++nf) acc[mt][nf] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+        for (int kg = 0; kg < C::KGS; ++kg) {
+            const i32x4 tap = *(const i32x4 *)&taptab[kg * 16 + 4 * (lane >> 4)];
+            f32x4 fa[MT], fb[NT];
+            const float *ab = &As[0][0] + (kg >> 2) * (C::COUT * C::LDA) + (kg & 3) * 16;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+                fa[mt] = *(const f32x4 *)&ab[(16 * mt + (lane & 15)) * C::LDA + 4 * (lane >> 4)];
+#pragma unroll
+            for (int nf = 0; nf < NT; ++nf)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) fb[nf][j] = img[pixoff[nf] + tap[j]];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int nf = 0; nf < NT; ++nf)
+                        acc[mt][nf] = __builtin_amdgcn_mfma_f32_16x16x4f32(fa[mt][j], fb[nf][j], acc[mt][nf], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);         // keeps the LDS reads of later groups from piling up in registers
+        }
+        relu_pool_store<MT, NT, H, W>(acc, bias ? bias + w * bias_stride : nullptr,
+                                      out + w * out_stride + (int64_t)b * C::COUT * PP,
+                                      code + w * code_stride + (int64_t)b * C::COUT * PP, wave, lane);
+        if (!more) break;
+        __syncthreads();                               // every wave has read this sample's image
+        put_image();
+        __syncthreads();
+    }
 }
 
 // dst[ci][(co, kh, kw)] = src[co][ci][KS - 1 - kh][KS - 1 - kw] per worker: the filters of the

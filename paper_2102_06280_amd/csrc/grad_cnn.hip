@@ -367,8 +367,10 @@ int launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const int3
     const int64_t cs = ws * 4;                         // worker stride of the code maps in bytes
     if (fast1) {   // convolution + ReLU + pooling in one kernel
         dbw_timer tm(c, "conv1_forward", s);
-        hipLaunchKernelGGL((convlds::conv_forward_kernel<3, 2, 4, 32, 32, 5, 16, true>), dim3(B, N), dim3(1024), 0, s, bx,
-                           xstride, params + L.w1, ld, L.C0 * KK, params + L.b1, ld, A + L.p1, ws, L.C0, code1, cs);
+        constexpr int SB1 = 4;                         // samples per workgroup
+        hipLaunchKernelGGL((convlds::conv_forward_pool_multi_kernel<3, 2, 4, 32, 32, 5, 16, SB1>),
+                           dim3((B + SB1 - 1) / SB1, N), dim3(1024), 0, s, bx, xstride, params + L.w1, ld, L.C0 * KK,
+                           params + L.b1, ld, A + L.p1, ws, L.C0, B, code1, cs);
         DBW_HIP(hipGetLastError());
     } else {   // conv1 forward
         dbw_timer tm(c, "conv1_forward", s);
