@@ -65,6 +65,26 @@ MUTANTS = [
     ("mse-gradient-without-the-inner-product", "grad", "dz[c] = 2.0 * p * (e - inner) * scale;", "dz[c] = 2.0 * p * e * scale;"),
     ("softmax-gradient-sign", "grad", "dz[c] = (exp(z[c] - m) / s - (c == y ? 1.0 : 0.0)) * scale;",
      "dz[c] = ((c == y ? 1.0 : 0.0) - exp(z[c] - m) / s) * scale;"),
+    ("nan-time-sorts-first", "select", "static float canon_time(float t) { return isnan(t) ? INFINITY : t; }",
+     "static float canon_time(float t) { return isnan(t) ? -INFINITY : t; }"),
+    ("wait-time-over-all-neighbours", "select",
+     "if (k < pi && canon_time(t[colidx[order[k]]]) > w) w = canon_time(t[colidx[order[k]]]);",
+     "if (canon_time(t[colidx[order[k]]]) > w) w = canon_time(t[colidx[order[k]]]);"),
+    ("round-time-ignores-who-is-waited-for", "select", "if (listed[i] && wait[i] > sel) sel = wait[i];",
+     "if (wait[i] > sel) sel = wait[i];"),
+    ("round-time-lists-unselected-neighbours", "select", "if (mask[e]) listed[colidx[e]] = 1;",
+     "listed[colidx[e]] = 1;"),
+    ("weights-use-own-count-only", "weights", "int m = p[i] > p[j] ? p[i] : p[j];", "int m = p[i];"),
+    ("average-includes-backup-workers", "round",
+     "if (mask[e]) acc += we[e] * (double)x[(size_t)colidx[e] * ld + c];\n                if (gi) acc -= eta * (double)gi[c];",
+     "acc += (1.0 / (1.0 + (double)(rowptr[i + 1] - rowptr[i]))) * (double)x[(size_t)colidx[e] * ld + c];\n                if (gi) acc -= eta * (double)gi[c];"),
+    ("average-of-own-row-only", "round",
+     "if (mask[e]) acc += we[e] * (double)x[(size_t)colidx[e] * ld + c];\n                if (gi) acc -= eta * (double)gi[c];",
+     "if (mask[e]) acc += we[e] * (double)xi[c];\n                if (gi) acc -= eta * (double)gi[c];"),
+    ("epoch-never-restarts", "dtur", "if (*n_visited >= n_edges) {", "if (*n_visited > n_edges) {"),
+    ("threshold-ties-go-to-the-last-link", "dtur", "if (best < 0 || est < theta) {", "if (best < 0 || est <= theta) {"),
+    ("slow-workers-wait-for-everybody", "dtur", "            b[j] = deg;\n", "            b[j] = 0;\n"),
+    ("visited-links-are-chosen-again", "dtur", "        if (visited[e]) continue;\n", ""),
 ]
 
 
