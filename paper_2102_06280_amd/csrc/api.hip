@@ -188,6 +188,9 @@ int fill_ctx(dbw_ctx *c, int32_t N, int64_t d, int64_t nnz64, const int32_t *row
     H(hipMemset(c->n_visited, 0, sizeof(int32_t)));
     if (c->Wdense) H(hipMemset(c->Wdense, 0, sizeof(float) * (size_t)c->Npad * c->Npad));
     if (c->grads) H(hipMemset(c->grads, 0, sizeof(float) * (size_t)N * c->ld));
+    // Scratch starts as NaN (all bits set), so that a kernel reading a value no kernel wrote shows
+    // up in every result instead of depending on what the allocation happened to hold.
+    if (c->act) H(hipMemset(c->act, 0xFF, sizeof(float) * c->act_floats));
     H(hipDeviceSynchronize());
     return rc;
 }
