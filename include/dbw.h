@@ -9,6 +9,13 @@
  * or keeps caller memory except where stated; caller arrays must stay valid until the
  * stream work that uses them has completed.
  *
+ * Concurrency.  A context holds the state of one run (selection, weights, threshold-rule
+ * epoch, gradient scratch) in device memory that its kernels read and write: calls on one
+ * context must be ordered, i.e. issued from one host thread at a time and on one stream
+ * (or on streams the caller orders with events).  Different contexts are independent.
+ * The device that is current when dbw_create is called owns the context; make it current
+ * again for every later call on that context.
+ *
  * Layout (the default, DBW_LAYOUT_ROWS; see DBW_LAYOUT_TILES for the alternative).
  * Worker i's parameter vector is row i of a row-major [N][ld] float array,
  * d <= ld; columns [d, ld) are padding that the library never reads into results and
