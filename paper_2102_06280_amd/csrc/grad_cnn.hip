@@ -241,17 +241,30 @@ __global__ __launch_bounds__(256) void relu_pool_bwd_kernel(const float *__restr
 // With the window codes of the fused convolution epilogue (0..3: position of the first maximum,
 // 4: maximum not positive): db[ch] = sum of dz over batch and pixels = sum of the pooled gradients
 // of the windows whose maximum was positive (each passes its gradient to exactly one pixel).
+// One workgroup per (channel, worker); HWo % 4 == 0 and 16-byte aligned planes: a thread takes four
+// windows at a time (one 128-bit load of gradients, one 32-bit load of codes).
 __global__ __launch_bounds__(256) void channel_sum_code_kernel(const uint8_t *__restrict__ code, int64_t cstride,
                                                                const float *__restrict__ dp, int64_t pstride, int B,
                                                                int C, int HWo, float *__restrict__ db, int64_t dbstride)
 {
     __shared__ float red[256];
     const int ch = blockIdx.x, w = blockIdx.y, tid = threadIdx.x;
+    const int quads = HWo / 4;                       // per (sample, channel) plane
+    const int q = tid % quads, b0 = tid / quads, bstep = 256 / quads > 0 ? 256 / quads : 1;
     float s = 0.f;
-    for (int i = tid; i < B * HWo; i += 256) {
-        const int b = i / HWo, hw = i - b * HWo;
-        const int64_t o = (int64_t)(b * C + ch) * HWo + hw;
-        s += code[w * cstride + o] < 4 ? dp[w * pstride + o] : 0.f;
+    if (b0 < bstep) {
+#pragma unroll 4
+        for (int b = b0; b < B; b += bstep) {
+            for (int qq = q; qq < quads; qq += 256) {    // planes wider than 1024 windows
+                const int64_t o = (int64_t)(b * C + ch) * HWo + 4 * qq;
+                const float4 g = *(const float4 *)&dp[w * pstride + o];
+                const uint32_t cd = *(const uint32_t *)&code[w * cstride + o];
+                s += (cd & 0xffu) < 4u ? g.x : 0.f;
+                s += ((cd >> 8) & 0xffu) < 4u ? g.y : 0.f;
+                s += ((cd >> 16) & 0xffu) < 4u ? g.z : 0.f;
+                s += (cd >> 24) < 4u ? g.w : 0.f;
+            }
+        }
     }
     red[tid] = s;
     __syncthreads();
@@ -282,7 +295,8 @@ __global__ __launch_bounds__(256) void channel_sum_kernel(const float *__restric
     if (tid == 0) db[w * dbstride + ch] = red[0];
 }
 
-constexpr int WGRAD_SB = 4;     // samples per workgroup in the LDS-resident weight-gradient kernels
+constexpr int WGRAD_SB = 4;     // samples per workgroup in the LDS-resident weight-gradient kernels (scratch is sized for it)
+constexpr int WGRAD_SB2 = 8;    // the same for conv2: 64 workers x 4 workgroups are one per compute unit
 
 struct cnn_layout {
     int C0, H, W, C1, C2, KS, F, NC, B;
@@ -432,10 +446,10 @@ int launch_grad_cnn(dbw_ctx *c, const float *params, const float *bx, const int3
     }
     int splits2 = L.splits2, splits1 = L.splits1;
     if (fast2) {
-        splits2 = (B + WGRAD_SB - 1) / WGRAD_SB;
+        splits2 = (B + WGRAD_SB2 - 1) / WGRAD_SB2;
         dbw_timer tm(c, "conv2_wgrad", s);
         hipLaunchKernelGGL((convlds::conv_wgrad_kernel<32, 2, 13, 2, 4, 1, 16, 16, 5, 256, true>), dim3(splits2, N),
-                           dim3(512), 0, s, A + L.p1, ws, A + L.dp2, ws, A + L.part, ws, B, WGRAD_SB, code2, cs);
+                           dim3(512), 0, s, A + L.p1, ws, A + L.dp2, ws, A + L.part, ws, B, WGRAD_SB2, code2, cs);
         DBW_HIP(hipGetLastError());
     } else {   // conv2 weight gradient (split over pixels, then summed in split order) and bias gradient
         dbw_timer tm(c, "conv2_wgrad", s);
