@@ -107,7 +107,7 @@ struct SplitOut {
     }
 };
 
-// C[m][n] = act(sum over splits of part[split][m][n] + bias[n]); grid = (ceil(M N / 256), workers).
+// C[m][n] = act(sum over splits of part[split][m][n] + bias[n]) (bias may be NULL); grid = (ceil(M N / 256), workers).
 __global__ __launch_bounds__(256) void fc_reduce_kernel(const float *__restrict__ part, int64_t pstride, int splits,
                                                         int M, int N, const float *__restrict__ bias,
                                                         int64_t bias_stride, int relu, float *__restrict__ C,
@@ -118,7 +118,7 @@ __global__ __launch_bounds__(256) void fc_reduce_kernel(const float *__restrict_
     const int m = i / N, n = i - m * N;
     float s = 0.f;
     for (int sp = 0; sp < splits; ++sp) s += part[w * pstride + (int64_t)sp * M * N + i];
-    s += bias[w * bias_stride + n];
+    if (bias) s += bias[w * bias_stride + n];
     if (relu) s = s > 0.f ? s : 0.f;
     C[w * cstride + (int64_t)m * ldc + n] = s;
 }
@@ -272,9 +272,28 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
                                    grads + w_off[l], c->ld);
                 DBW_HIP(hipGetLastError());
             } else {
-            Epilogue E{grads + w_off[l], dims[l - 1], c->ld, nullptr, 0, nullptr, 0, 0, 0};
-            dbw_timer tm(c, "mlp_wgrad_gemm", s);
-            DBW_HIP(bgemm::launch<64>(A, Bm, E, dims[l], dims[l - 1], B, N, s));
+                // few output tiles and a long batch: split the reduction like the forward pass does
+                int splits = forward_splits(dims[l], dims[l - 1], B, N);
+                int64_t part_cap = 0;
+                for (int q = 1; q <= L; ++q) part_cap = std::max<int64_t>(part_cap, (int64_t)MAX_SPLITS * B * dims[q]);
+                if ((int64_t)splits * dims[l] * dims[l - 1] > part_cap) splits = 1;
+                if (splits > 1) {
+                    float *part = act + 2 * per;
+                    {
+                        dbw_timer tm(c, "mlp_wgrad_gemm", s);
+                        DBW_HIP(bgemm::launch<64>(A, Bm, SplitOut{part, wstride, dims[l], dims[l - 1]}, dims[l], dims[l - 1],
+                                                  B, N, s, splits));
+                    }
+                    dbw_timer tm(c, "fc_reduce_kernel", s);
+                    hipLaunchKernelGGL(fc_reduce_kernel, dim3((dims[l] * dims[l - 1] + 255) / 256, N), dim3(256), 0, s, part,
+                                       wstride, splits, dims[l], dims[l - 1], (const float *)nullptr, (int64_t)0, 0,
+                                       grads + w_off[l], (int64_t)dims[l - 1], c->ld);
+                    DBW_HIP(hipGetLastError());
+                } else {
+                    Epilogue E{grads + w_off[l], dims[l - 1], c->ld, nullptr, 0, nullptr, 0, 0, 0};
+                    dbw_timer tm(c, "mlp_wgrad_gemm", s);
+                    DBW_HIP(bgemm::launch<64>(A, Bm, E, dims[l], dims[l - 1], B, N, s));
+                }
             }
         }
         {
