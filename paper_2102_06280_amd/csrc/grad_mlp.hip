@@ -67,31 +67,32 @@ __global__ __launch_bounds__(1024) void softmax_loss_kernel(
 }
 
 // Bias gradient: db[o] = sum over the batch of dz[s][o].  grid = (ceil(C / 32), workers); a
-// workgroup covers 32 columns with 8 groups of threads that stride over the batch, four
+// workgroup covers 32 columns with RG groups of 32 threads that stride over the batch, four
 // independent partial sums each, combined in a fixed order.
-__global__ __launch_bounds__(256) void colsum_kernel(int B, int C, const float *__restrict__ dz, int64_t stride_dz,
-                                                     float *__restrict__ db, int64_t stride_db)
+template <int RG>
+__global__ __launch_bounds__(32 * RG) void colsum_kernel(int B, int C, const float *__restrict__ dz, int64_t stride_dz,
+                                                         float *__restrict__ db, int64_t stride_db)
 {
-    __shared__ float part[8][32];
+    __shared__ float part[RG][32];
     const int w = blockIdx.y, cl = threadIdx.x & 31, rg = threadIdx.x >> 5;
     const int o = blockIdx.x * 32 + cl;
     const float *d = dz + w * stride_dz;
     float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
     if (o < C) {
         int b = rg;
-        for (; b + 24 < B; b += 32) {
+        for (; b + 3 * RG < B; b += 4 * RG) {
             s0 += d[(int64_t)b * C + o];
-            s1 += d[(int64_t)(b + 8) * C + o];
-            s2 += d[(int64_t)(b + 16) * C + o];
-            s3 += d[(int64_t)(b + 24) * C + o];
+            s1 += d[(int64_t)(b + RG) * C + o];
+            s2 += d[(int64_t)(b + 2 * RG) * C + o];
+            s3 += d[(int64_t)(b + 3 * RG) * C + o];
         }
-        for (; b < B; b += 8) s0 += d[(int64_t)b * C + o];
+        for (; b < B; b += RG) s0 += d[(int64_t)b * C + o];
     }
     part[rg][cl] = (s0 + s1) + (s2 + s3);
     __syncthreads();
     if (rg == 0 && o < C) {
         float s = part[0][cl];
-        for (int r = 1; r < 8; ++r) s += part[r][cl];
+        for (int r = 1; r < RG; ++r) s += part[r][cl];
         db[w * stride_db + o] = s;
     }
 }
@@ -298,8 +299,12 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
         }
         {
             dbw_timer tm(c, "colsum_kernel", s);
-            hipLaunchKernelGGL(colsum_kernel, dim3((dims[l] + 31) / 32, N), dim3(256), 0, s, B, dims[l],
-                               act + dz_off[l], wstride, grads + b_off[l], c->ld);
+            if (B >= 512)    // long batches: 32 row groups per workgroup
+                hipLaunchKernelGGL(colsum_kernel<32>, dim3((dims[l] + 31) / 32, N), dim3(1024), 0, s, B, dims[l],
+                                   act + dz_off[l], wstride, grads + b_off[l], c->ld);
+            else
+                hipLaunchKernelGGL(colsum_kernel<8>, dim3((dims[l] + 31) / 32, N), dim3(256), 0, s, B, dims[l],
+                                   act + dz_off[l], wstride, grads + b_off[l], c->ld);
             DBW_HIP(hipGetLastError());
         }
         if (l > 1 && fast && a_off[l - 1] % 4 == 0 && dz_off[l - 1] % 4 == 0) {
