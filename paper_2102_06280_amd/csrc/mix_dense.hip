@@ -60,9 +60,9 @@ struct dense_cfg {
 // FULL: N == NPAD and every tile has all TC columns, so no access needs a guard.
 template <int MB, int ORDER, bool HAS_G, bool FULL, class LR>
 __global__ __launch_bounds__(DENSE_THREADS) void mix_dense_kernel(
-    int N, int64_t n_vec /* float4 columns covered */, int64_t ld4, const float *__restrict__ Wsw,
-    const float4 *__restrict__ x, const float4 *__restrict__ g, float *__restrict__ out,
-    const float *__restrict__ gs, LR lr, int n_tiles)
+    int N, int64_t n_vec /* float4 columns covered, the last may straddle column d */, int64_t dcols /* = d */,
+    int64_t ld4, const float *__restrict__ Wsw, const float4 *__restrict__ x, const float4 *__restrict__ g,
+    float *__restrict__ out, const float *__restrict__ gs, LR lr, int n_tiles)
 {
     using C = dense_cfg<MB>;
     constexpr bool DMA = FULL && !(ORDER == DBW_ORDER_ATC && HAS_G);
@@ -71,7 +71,7 @@ __global__ __launch_bounds__(DENSE_THREADS) void mix_dense_kernel(
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave index, kept scalar
     const int rb = w % MB, cg = w / MB;
-    const int64_t ld = ld4 * 4, dcols = n_vec * 4;
+    const int64_t ld = ld4 * 4;
 
     float wreg[C::KB];
 #pragma unroll
@@ -250,15 +250,15 @@ int launch_mb(dbw_ctx *c, const float *W, const float *x, const float *g, float 
         cus = prop.multiProcessorCount;
     const int blocks_per_cu = (int)((160 * 1024) / (sizeof(float) * 2 * C::TILE));
     const int64_t grid = std::min<int64_t>(n_tiles, (int64_t)cus * std::max(1, std::min(blocks_per_cu, 4)));
-    const bool full = c->N == C::NPAD && (n_vec * 4) % C::TC == 0;
+    const bool full = c->N == C::NPAD && c->d % C::TC == 0;
     dbw_timer tm(c, "mix_dense_kernel", s);
     if (full)
         hipLaunchKernelGGL((mix_dense_kernel<MB, ORDER, HAS_G, true, LR>), dim3((unsigned)grid), dim3(DENSE_THREADS), 0, s,
-                           c->N, n_vec, c->ld / 4, W, (const float4 *)x, (const float4 *)g, out, g, lr,
+                           c->N, n_vec, c->d, c->ld / 4, W, (const float4 *)x, (const float4 *)g, out, g, lr,
                            (int)n_tiles);
     else
         hipLaunchKernelGGL((mix_dense_kernel<MB, ORDER, HAS_G, false, LR>), dim3((unsigned)grid), dim3(DENSE_THREADS), 0,
-                           s, c->N, n_vec, c->ld / 4, W, (const float4 *)x, (const float4 *)g, out, g, lr,
+                           s, c->N, n_vec, c->d, c->ld / 4, W, (const float4 *)x, (const float4 *)g, out, g, lr,
                            (int)n_tiles);
     DBW_HIP(hipGetLastError());
     return DBW_OK;
@@ -286,7 +286,7 @@ int64_t dbw_dense_columns(const dbw_ctx *c, const float *x, const float *g, cons
 {
     const bool aligned = (c->ld % 4 == 0) && ((uintptr_t)x % 16 == 0) && ((uintptr_t)out % 16 == 0) &&
                          (!g || (uintptr_t)g % 16 == 0);
-    return aligned ? c->d / 4 * 4 : 0;
+    return aligned ? c->d : 0;
 }
 
 int dbw_launch_mix_dense(dbw_ctx *c, const float *x, const float *g, float *out, float lr, const float *lr_vec,
@@ -295,7 +295,9 @@ int dbw_launch_mix_dense(dbw_ctx *c, const float *x, const float *g, float *out,
     const bool own_matrix = W != nullptr;
     if (!W) W = c->Wdense;
     if (!W) return DBW_ERR_STATE;
-    const int64_t n_vec = dbw_dense_columns(c, x, g, out) / 4;
+    // rows are aligned and padded to a multiple of four floats: the float4 that straddles column d is
+    // read whole and stored up to d
+    const int64_t covered = dbw_dense_columns(c, x, g, out), n_vec = (covered + 3) / 4;
     int rc = DBW_OK;
     if (n_vec > 0) {
         if (!g)
@@ -310,8 +312,8 @@ int dbw_launch_mix_dense(dbw_ctx *c, const float *x, const float *g, float *out,
             rc = launch<DBW_ORDER_CTA, true>(c, W, x, g, out, dbw_lr_scalar{lr}, n_vec, s);
         if (rc != DBW_OK) return rc;
     }
-    // ragged tail (d % 4 columns), or everything when rows are not 16-byte aligned; a caller
-    // that brought its own matrix covers those columns itself
-    if (n_vec * 4 < c->d && !own_matrix) rc = dbw_launch_mix_csr_range(c, x, g, out, lr, lr_vec, n_vec * 4, s);
+    // everything when rows are not 16-byte aligned; a caller that brought its own matrix covers
+    // those columns itself
+    if (covered < c->d && !own_matrix) rc = dbw_launch_mix_csr_range(c, x, g, out, lr, lr_vec, covered, s);
     return rc;
 }
