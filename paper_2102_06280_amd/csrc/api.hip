@@ -91,7 +91,7 @@ void free_ctx(dbw_ctx *c)
     if (!c) return;
     void *ptrs[] = {c->rowptr, c->colidx, c->p, c->mask, c->wait, c->listed, c->sel_idx, c->sel_w, c->self_w, c->Wdense,
                     c->phi[0], c->phi[1], c->phi_frag,
-                    c->err, c->links, c->visited, c->n_visited, c->grads, c->act};
+                    c->err, c->links, c->visited, c->n_visited, c->grads, c->act, c->loss_part, c->loss_ticket};
     for (void *q : ptrs)
         if (q) (void)hipFree(q);
     for (auto &sl : c->slots) {
@@ -176,6 +176,8 @@ int fill_ctx(dbw_ctx *c, int32_t N, int64_t d, int64_t nnz64, const int32_t *row
         A(dev_alloc(&c->grads, (size_t)N * c->ld));
         c->act_floats = c->model.kind == DBW_MODEL_MLP ? dbw_mlp_scratch_floats(c) : dbw_cnn_scratch_floats(c);
         A(dev_alloc(&c->act, c->act_floats));
+        A(dev_alloc(&c->loss_part, (size_t)N * DBW_LOSS_CHUNKS));
+        A(dev_alloc(&c->loss_ticket, (size_t)N));
     }
     if (rc != DBW_OK) return rc;
     auto H = [&](hipError_t e) { if (rc == DBW_OK && e != hipSuccess) rc = DBW_ERR_HIP; };
@@ -191,6 +193,7 @@ int fill_ctx(dbw_ctx *c, int32_t N, int64_t d, int64_t nnz64, const int32_t *row
     // Scratch starts as NaN (all bits set), so that a kernel reading a value no kernel wrote shows
     // up in every result instead of depending on what the allocation happened to hold.
     if (c->act) H(hipMemset(c->act, 0xFF, sizeof(float) * c->act_floats));
+    if (c->loss_ticket) H(hipMemset(c->loss_ticket, 0, sizeof(uint32_t) * (size_t)N));
     H(hipDeviceSynchronize());
     return rc;
 }

@@ -19,6 +19,7 @@ constexpr int DBW_DENSE_MAX_N = 256;   // the dense mixing kernel keeps all of P
 // the dense mixing kernel adds 32-bit per-lane byte offsets of up to 40 rows to 64-bit uniform bases
 constexpr int64_t DBW_DENSE_MAX_LD = (int64_t)UINT32_MAX / (40 * 4);
 constexpr int DBW_SELECT_LDS_KEYS = 2048;
+constexpr int DBW_LOSS_CHUNKS = 16;     // workgroups per worker in the loss kernel, at most
 constexpr int DBW_TILES_MAX_N = 256;   // the tile-major mixing kernel holds one 256-byte piece per worker in LDS
 
 struct dbw_timing_slot {
@@ -61,6 +62,8 @@ struct dbw_ctx {
     // device: model scratch
     float *grads = nullptr;           // [N*ld] when a model is attached
     float *act = nullptr;             // activations / deltas
+    float *loss_part = nullptr;       // [N][DBW_LOSS_CHUNKS] partial loss sums of the loss kernel
+    uint32_t *loss_ticket = nullptr;  // [N] arrival counters of the loss kernel, zero between launches
     size_t act_floats = 0;
 
     // timing

@@ -17,21 +17,26 @@ namespace {
 using bgemm::Dense;
 using bgemm::Epilogue;
 
-// One workgroup (256 or 1024 threads) per worker: softmax, mean loss over the batch and its gradient with respect
-// to the logits.  Cross-entropy: dz = (p - onehot(y)) / B.  MSE on the softmax outputs
-// (Appendix B, 2NN): f = sum_c (p_c - o_c)^2, dz_k = 2 p_k ((p_k - o_k) - sum_c p_c (p_c - o_c)) / B.
+// Softmax, mean loss over the batch and its gradient with respect to the logits; one thread per
+// sample, grid = (chunks, workers) with 256 samples per workgroup.  Cross-entropy:
+// dz = (p - onehot(y)) / B.  MSE on the softmax outputs (Appendix B, 2NN): f = sum_c (p_c - o_c)^2,
+// dz_k = 2 p_k ((p_k - o_k) - sum_c p_c (p_c - o_c)) / B.
+// The loss of a worker is the sum of its workgroups' partial sums: each writes its own to
+// loss_part[worker][chunk] and takes a ticket; the last one to arrive adds them in chunk order (so
+// the result does not depend on the order of arrival) and puts the ticket counter back to zero.
 template <int LOSS>
-__global__ __launch_bounds__(1024) void softmax_loss_kernel(
+__global__ __launch_bounds__(256) void softmax_loss_kernel(
     int B, int C, const float *__restrict__ logits, int64_t stride_logits, const int32_t *__restrict__ y,
-    float *__restrict__ dz, int64_t stride_dz, float *__restrict__ loss)
+    float *__restrict__ dz, int64_t stride_dz, float *__restrict__ loss, float *__restrict__ loss_part,
+    uint32_t *__restrict__ ticket)
 {
-    __shared__ float red[1024];
-    const int w = blockIdx.x, tid = threadIdx.x, nt = blockDim.x;
+    __shared__ float red[256];
+    const int chunk = blockIdx.x, chunks = gridDim.x, w = blockIdx.y, tid = threadIdx.x;
     const float *z = logits + w * stride_logits;
     float *d = dz + w * stride_dz;
     const float inv_b = 1.0f / (float)B;
     float part = 0.f;
-    for (int s = tid; s < B; s += nt) {
+    for (int s = chunk * 256 + tid; s < B; s += chunks * 256) {
         const float *zs = z + (int64_t)s * C;
         float m = zs[0];
         for (int c = 1; c < C; ++c) m = fmaxf(m, zs[c]);
@@ -57,13 +62,29 @@ __global__ __launch_bounds__(1024) void softmax_loss_kernel(
             part += f;
         }
     }
+    if (!loss) return;                                  // uniform: nobody asked for the loss
     red[tid] = part;
     __syncthreads();
-    for (int o = nt / 2; o > 0; o >>= 1) {
+    for (int o = 128; o > 0; o >>= 1) {
         if (tid < o) red[tid] += red[tid + o];
         __syncthreads();
     }
-    if (tid == 0 && loss) loss[w] = red[0] * inv_b;
+    if (chunks == 1) {
+        if (tid == 0) loss[w] = red[0] * inv_b;
+        return;
+    }
+    if (tid == 0) {
+        __hip_atomic_store(&loss_part[w * chunks + chunk], red[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __threadfence();                                // the partial sum is visible before the ticket is taken
+        if (atomicAdd(&ticket[w], 1u) == (uint32_t)(chunks - 1)) {
+            __threadfence();
+            float sum = 0.f;
+            for (int k = 0; k < chunks; ++k)
+                sum += __hip_atomic_load(&loss_part[w * chunks + k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            loss[w] = sum * inv_b;
+            ticket[w] = 0;                              // ready for the next launch
+        }
+    }
 }
 
 // Bias gradient: db[o] = sum over the batch of dz[s][o].  grid = (ceil(C / 32), workers); a
@@ -246,14 +267,15 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
         DBW_HIP(bgemm::launch<64>(A, Bm, E, B, dims[l], dims[l - 1], N, s));
     }
     {
-        const int threads = B > 256 ? 1024 : 256;
+        const int chunks = std::min((B + 255) / 256, DBW_LOSS_CHUNKS);
+        const dim3 grid(chunks, N);
         dbw_timer tm(c, "softmax_loss_kernel", s);
         if (a.loss_kind == DBW_LOSS_MSE)
-            hipLaunchKernelGGL(softmax_loss_kernel<DBW_LOSS_MSE>, dim3(N), dim3(threads), 0, s, B, dims[L],
-                               act + a_off[L], wstride, a.y, act + dz_off[L], wstride, a.loss);
+            hipLaunchKernelGGL(softmax_loss_kernel<DBW_LOSS_MSE>, grid, dim3(256), 0, s, B, dims[L], act + a_off[L], wstride,
+                               a.y, act + dz_off[L], wstride, a.loss, c->loss_part, c->loss_ticket);
         else
-            hipLaunchKernelGGL(softmax_loss_kernel<DBW_LOSS_XENT>, dim3(N), dim3(threads), 0, s, B, dims[L],
-                               act + a_off[L], wstride, a.y, act + dz_off[L], wstride, a.loss);
+            hipLaunchKernelGGL(softmax_loss_kernel<DBW_LOSS_XENT>, grid, dim3(256), 0, s, B, dims[L], act + a_off[L], wstride,
+                               a.y, act + dz_off[L], wstride, a.loss, c->loss_part, c->loss_ticket);
         DBW_HIP(hipGetLastError());
     }
     // backward
