@@ -154,7 +154,7 @@ int forward_splits(int M, int N, int K, int workers)
 {
     const int64_t tiles = (int64_t)((M + 63) / 64) * ((N + 63) / 64) * workers;
     int splits = 1;
-    while (splits < GEMM_MAX_SPLITS && tiles * splits < 2048 && K / (splits * 2) >= 2 * bgemm::BK) splits *= 2;
+    while (splits < GEMM_MAX_SPLITS && tiles * splits < 640 && K / (splits * 2) >= 2 * bgemm::BK) splits *= 2;
     return splits;
 }
 
