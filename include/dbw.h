@@ -210,6 +210,30 @@ int dbw_round_eta(dbw_ctx *ctx, const float *params_in, float *params_out, const
 int dbw_consensus_rounds(dbw_ctx *ctx, const float *params_in, float *params_out, const float *resp_times,
                          const int32_t *b, int32_t r, void *stream);
 
+/* dbw_consensus_rounds for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  No context and no dbw_create:
+ * the graph is passed with every call, as device CSR arrays (same form as dbw_create's host
+ * arrays: rowptr [dev, N+1], colidx [dev, nnz], nnz = rowptr[N] given by the host as well), and
+ * all working memory (a checked copy of the graph, the selection state of each round, the product
+ * of the consensus matrices) is a fixed array of about 1.7 MB inside the library's device image,
+ * which every GPU the library runs on holds until the process ends.  The call allocates and frees
+ * nothing, records no memset, and does not synchronise.
+ *   Limits: N <= 256, nnz <= 256 * 255, ld <= 26 843 545 (DBW_ERR_UNSUPPORTED beyond them); ld = 0
+ *   means d; rows layout only.
+ *   params_in / params_out [dev, N*ld], resp_times [dev, r*N], b [dev, r*N]: as dbw_consensus_rounds;
+ *   the result is the same, bit for bit, as that of dbw_consensus_rounds on a context of this graph.
+ *   status_out [dev, 1] int32 or NULL: receives DBW_OK, DBW_ERR_GRAPH (the graph is checked on the
+ *   device for everything dbw_create checks except connectivity; a graph that fails is treated
+ *   as the graph without links, so params_out = params_in) or DBW_ERR_INVALID (some b_i outside
+ *   [0, deg_i], clamped as by dbw_select) when the stream work has run.
+ * All calls on one GPU share the one array, which keeps the previous call's contents (the call
+ * itself clears what must start at zero): calls that overlap in time on one GPU, on whatever
+ * streams, race with each other.  Asynchronous on `stream`. */
+int dbw_consensus_rounds_static(int32_t N, int64_t d, int64_t ld, int32_t nnz, const int32_t *rowptr,
+                                const int32_t *colidx, const float *params_in, float *params_out,
+                                const float *resp_times, const int32_t *b, int32_t r, int32_t *status_out,
+                                void *stream);
+
 /* Copy a [N * ld] array from one layout to the other (all ld columns): to_tiles != 0 reads src
  * in row layout and writes dst tile-major, to_tiles == 0 the reverse.  ld must be a multiple
  * of 64 and both pointers 16-byte aligned (DBW_ERR_INVALID otherwise); src and dst must not

@@ -27,6 +27,7 @@ TILE_COLUMNS = 64
 
 EXPORTS = ["dbw_create", "dbw_select", "dbw_dtur_b", "dbw_dtur_reset", "dbw_get_selection",
            "dbw_get_weights", "dbw_round_time", "dbw_round", "dbw_round_eta", "dbw_consensus_rounds",
+           "dbw_consensus_rounds_static",
            "dbw_convert_layout", "dbw_grad", "dbw_check", "dbw_get_links", "dbw_mix_path",
            "dbw_destroy", "dbw_strerror", "dbw_set_timing", "dbw_get_timing", "dbw_calibrate"]
 
@@ -62,6 +63,7 @@ _lib.dbw_round_time.argtypes = [_vp, _vp, _vp]
 _lib.dbw_round.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _f, _vp]
 _lib.dbw_round_eta.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.dbw_consensus_rounds.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp]
+_lib.dbw_consensus_rounds_static.argtypes = [_i32, _i64, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp]
 _lib.dbw_convert_layout.argtypes = [_vp, _vp, _vp, _i32, _vp]
 _lib.dbw_grad.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.dbw_check.argtypes = [_vp, _vp]
@@ -164,6 +166,15 @@ def dbw_consensus_rounds(h, params_in, params_out, resp_times, b, r: int):
     """resp_times [r, N] float32, b [r, N] int32 on the device."""
     return _chk(_lib.dbw_consensus_rounds(h, _ptr(params_in), _ptr(params_out), _ptr(resp_times), _ptr(b), int(r),
                                           _stream()), "dbw_consensus_rounds")
+
+
+def dbw_consensus_rounds_static(N: int, d: int, ld: int, rowptr, colidx, params_in, params_out, resp_times, b,
+                                r: int, status_out=None):
+    """rowptr [N+1] / colidx [nnz] int32 on the device; nothing is allocated by the call."""
+    return _chk(_lib.dbw_consensus_rounds_static(int(N), int(d), int(ld), int(colidx.numel()), _ptr(rowptr),
+                                                 _ptr(colidx) if colidx.numel() else None, _ptr(params_in),
+                                                 _ptr(params_out), _ptr(resp_times), _ptr(b), int(r),
+                                                 _ptr(status_out), _stream()), "dbw_consensus_rounds_static")
 
 
 def dbw_convert_layout(h, src, dst, to_tiles: bool):

@@ -7,9 +7,7 @@
 
 #include "dbw_internal.h"
 
-namespace {
-
-int validate_graph(int32_t N, const int32_t *rowptr, const int32_t *colidx)
+int dbw_validate_graph(int32_t N, const int32_t *rowptr, const int32_t *colidx)
 {
     if (rowptr[0] != 0) return DBW_ERR_GRAPH;
     for (int i = 0; i < N; ++i)
@@ -29,6 +27,8 @@ int validate_graph(int32_t N, const int32_t *rowptr, const int32_t *colidx)
     }
     return DBW_OK;
 }
+
+namespace {
 
 // Breadth-first spanning tree from worker 0, neighbours in ascending index; the order of
 // discovery numbers the links.  Returns false if some worker is unreachable.
@@ -233,7 +233,7 @@ int dbw_create(dbw_ctx **out, int32_t N, int64_t d, const int32_t *rowptr, const
     const int64_t nnz64 = rowptr[N];
     if (nnz64 < 0) return DBW_ERR_GRAPH;
     if (nnz64 > 0 && !colidx) return DBW_ERR_NULL;
-    int rc = validate_graph(N, rowptr, colidx);
+    int rc = dbw_validate_graph(N, rowptr, colidx);
     if (rc != DBW_OK) return rc;
 
     dbw_ctx *c = new (std::nothrow) dbw_ctx();

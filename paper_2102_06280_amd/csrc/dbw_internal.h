@@ -80,6 +80,8 @@ struct dbw_timer {
     ~dbw_timer();
 };
 
+// api.hip: CSR rows strictly ascending, in range, loop-free, symmetric (DBW_ERR_GRAPH otherwise)
+int dbw_validate_graph(int32_t N, const int32_t *rowptr, const int32_t *colidx);
 // select.hip
 int dbw_launch_select(dbw_ctx *c, const float *t, const int32_t *b, hipStream_t s);
 int dbw_launch_round_time(dbw_ctx *c, float *out, hipStream_t s);
