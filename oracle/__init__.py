@@ -159,35 +159,102 @@ class Dtur:
         return b, float(theta.value)
 
 
-def grad_mlp(dims, params, x, y, loss_kind="xent"):
+class Decision(C.Structure):
+    """One branch decision of a gradient evaluation (orc_decision in the C source): stage 0 / 1 =
+    ReLU + pooling window of a convolutional stage, 16 + l = ReLU after fully connected layer l;
+    alt = the outcome on the other side; gap = distance from turning in rounding units."""
+    _fields_ = [("stage", C.c_int32), ("sample", C.c_int32), ("unit", C.c_int32), ("alt", C.c_int32),
+                ("gap", C.c_double)]
+
+    def key(self):
+        return (self.stage, self.sample, self.unit, self.alt)
+
+    def __repr__(self):
+        return f"Decision(stage={self.stage}, sample={self.sample}, unit={self.unit}, alt={self.alt}, gap={self.gap:.3g})"
+
+
+class _Branch(C.Structure):
+    _fields_ = [("flips", C.POINTER(Decision)), ("n_flips", C.c_int32), ("near", C.POINTER(Decision)),
+                ("near_cap", C.c_int32), ("n_near", C.c_int32), ("near_scale", C.c_double)]
+
+
+NEAR_CAP = 4096
+
+
+def _branch(flips, near_scale):
+    """-> (orc_branch or None, keep-alive objects)."""
+    if not flips and near_scale is None:
+        return None, None
+    br = _Branch()
+    fl = (Decision * max(len(flips or ()), 1))()
+    for k, f in enumerate(flips or ()):
+        fl[k].stage, fl[k].sample, fl[k].unit, fl[k].alt = f.stage, f.sample, f.unit, f.alt
+    br.flips, br.n_flips = fl, len(flips or ())
+    near = (Decision * NEAR_CAP)() if near_scale is not None else None
+    if near is not None:
+        br.near, br.near_cap, br.near_scale = near, NEAR_CAP, float(near_scale)
+    return br, (fl, near)
+
+
+def _near_list(br, keep):
+    if br is None or keep[1] is None:
+        return None
+    if br.n_near > NEAR_CAP:
+        raise ValueError(f"{br.n_near} near decisions exceed the list capacity {NEAR_CAP}")
+    out = []
+    for k in range(br.n_near):
+        e = keep[1][k]
+        out.append(Decision(e.stage, e.sample, e.unit, e.alt, e.gap))
+    return out
+
+
+def grad_mlp(dims, params, x, y, loss_kind="xent", flips=None, near_scale=None):
     """One worker: params [d], x [B, dims[0]], y [B] -> (grad [d] fp32, loss float).
-    loss_kind: "xent" (softmax cross-entropy) or "mse" (squared error of the softmax outputs)."""
+    loss_kind: "xent" (softmax cross-entropy) or "mse" (squared error of the softmax outputs).
+    flips: decisions to take the other way; near_scale: also return, as a third result, the
+    decisions closer than that many rounding units to turning."""
     dims = _i32(dims)
     params, x, y = _f32(params), _f32(x), _i32(y)
     grad = np.zeros_like(params)
     loss = C.c_double(0)
+    br, keep = _branch(flips, near_scale)
     lib().orc_grad_mlp_loss(len(dims) - 1, _p(dims, C.c_int32), x.shape[0], _p(params, C.c_float),
                             _p(x, C.c_float), _p(y, C.c_int32), 1 if loss_kind == "mse" else 0,
-                            _p(grad, C.c_float), C.byref(loss), None)
+                            _p(grad, C.c_float), C.byref(loss), C.byref(br) if br is not None else None)
+    if near_scale is not None:
+        return grad, loss.value, _near_list(br, keep)
     return grad, loss.value
 
 
-def grad_cnn(shape, params, x, y):
-    """One worker: shape = (C0, H, W, C1, C2, K, F, classes)."""
+def grad_cnn(shape, params, x, y, flips=None, near_scale=None):
+    """One worker: shape = (C0, H, W, C1, C2, K, F, classes); flips / near_scale as grad_mlp."""
     shape = _i32(shape)
     params, x, y = _f32(params), _f32(x), _i32(y)
     grad = np.zeros_like(params)
     loss = C.c_double(0)
+    br, keep = _branch(flips, near_scale)
     lib().orc_grad_cnn(_p(shape, C.c_int32), x.shape[0], _p(params, C.c_float), _p(x, C.c_float),
-                       _p(y, C.c_int32), _p(grad, C.c_float), C.byref(loss), None)
+                       _p(y, C.c_int32), _p(grad, C.c_float), C.byref(loss), C.byref(br) if br is not None else None)
+    if near_scale is not None:
+        return grad, loss.value, _near_list(br, keep)
     return grad, loss.value
 
 
-def grad_all(kind, desc, d, params, x, y, with_margin=False):
+def grad_one(kind, desc, d, params_row, x, y, flips=None):
+    """Worker-level entry with grad_all's (kind, descriptor): gradient [d] of one worker, with
+    `flips` taken the other way."""
+    desc = _i32(desc)
+    if kind == 1:
+        return grad_cnn(desc, params_row[:d], x.reshape(x.shape[0], -1), y, flips=flips)[0]
+    return grad_mlp(desc[1:], params_row[:d], x.reshape(x.shape[0], -1), y,
+                    loss_kind="mse" if kind == 2 else "xent", flips=flips)[0]
+
+
+def grad_all(kind, desc, d, params, x, y, near_scale=None):
     """All workers: params [N, ld], x [N, B, in], y [N, B] -> (grad [N, ld], loss [N]).
-    with_margin adds a third result [N, 2]: how close each worker's nearest decision was to
-    flipping (the gradient is discontinuous there): column 0 ReLU + max-pooling windows of
-    convolutional stages, column 1 ReLU inputs of fully connected layers."""
+    near_scale adds a third result: per worker, the list of decisions (ReLU signs, pooling
+    maxima) closer than that many rounding units to turning (the gradient is discontinuous
+    there, see grad_one's `flips`)."""
     desc = _i32(desc)
     params, x, y = _f32(params), _f32(x), _i32(y)
     n, ld = params.shape
@@ -195,11 +262,24 @@ def grad_all(kind, desc, d, params, x, y, with_margin=False):
     in_dim = int(np.prod(x.shape[2:]))
     grad = np.zeros_like(params)
     loss = np.zeros(n, dtype=np.float64)
-    margin = np.zeros((n, 2), dtype=np.float64)
+    near = n_near = None
+    if near_scale is not None:
+        near = (Decision * (n * NEAR_CAP))()
+        n_near = np.zeros(n, dtype=np.int32)
     lib().orc_grad_all(int(kind), _p(desc, C.c_int32), n, C.c_int64(d), C.c_int64(ld), B,
                        C.c_int64(in_dim), _p(params, C.c_float), _p(x, C.c_float), _p(y, C.c_int32),
-                       _p(grad, C.c_float), _p(loss, C.c_double), _p(margin, C.c_double))
-    return (grad, loss, margin) if with_margin else (grad, loss)
+                       _p(grad, C.c_float), _p(loss, C.c_double), near, NEAR_CAP,
+                       _p(n_near, C.c_int32) if n_near is not None else None,
+                       C.c_double(near_scale if near_scale is not None else 0.0))
+    if near_scale is None:
+        return grad, loss
+    if n_near.max(initial=0) > NEAR_CAP:
+        raise ValueError(f"{n_near.max()} near decisions exceed the list capacity {NEAR_CAP}")
+    lists = []
+    for i in range(n):
+        lists.append([Decision(e.stage, e.sample, e.unit, e.alt, e.gap)
+                      for e in (near[i * NEAR_CAP + k] for k in range(n_near[i]))])
+    return grad, loss, lists
 
 
 def model_desc(desc):

@@ -23,13 +23,16 @@
  *   orc_grad_mlp       Section 2.1, the mini-batch stochastic gradient, for fully connected models
  *                      with the cross-entropy loss of Section 5.
  *   orc_grad_cnn       the same for a two-convolution network on 3 x 32 x 32 inputs.
+ *   orc_decision /     diagnostics for the tests, not part of the method: which ReLU / pooling
+ *   orc_branch         decisions of a gradient lie within rounding of turning (where the gradient
+ *                      of Section 2.1 is not unique), and the gradient with such decisions turned.
  *
  * Pins (tests/test_oracle_*.py): brute force over all neighbour subsets, Metropolis
  * invariants, b = 0 reduction to full participation with static Metropolis-Hastings
  * weights, closed forms on ring / regular / complete graphs, the worker-mean recursion,
  * the unrolled product recursion, consensus limit, threshold-rule connectivity,
- * finite differences and PyTorch-CPU autograd for the gradients.  No function here is
- * "parity unpinned".
+ * finite differences and PyTorch-CPU autograd for the gradients (also with forced branches),
+ * NumPy recomputation of the listed near decisions.  No function here is "parity unpinned".
  *
  * Conventions: worker i's vector is row i of a row-major [N][ld] float array, d <= ld.
  * The graph is CSR without self loops; deg_i = rowptr[i+1] - rowptr[i].
@@ -299,14 +302,56 @@ void orc_dtur(int N, const int32_t *rowptr, const int32_t *colidx, int n_edges,
 
 /* ------------------------------------------------------------------ gradients */
 
-/* Diagnostic for the tests, not part of the method: the gradients are discontinuous where a
- * ReLU input is zero or two pooled values tie, so a finite-precision evaluation can
- * legitimately take the other branch there.  The gradient routines report how close the
- * nearest such decision was: margin[0] = smallest gap at a ReLU + max-pooling window of a
- * convolutional stage, margin[1] = smallest |z| at a ReLU of a fully connected layer. */
-static void margin_update(double *margin, double v)
+/* Branch decisions.  The models are piecewise linear up to the loss: a ReLU unit is active or
+ * not, a pooling window hands its gradient to one of its four positions or (when no value is
+ * positive) to none.  Where a ReLU input is zero or two pooled values tie, the mini-batch
+ * gradient of Section 2.1 is not unique: either branch gives a valid subgradient, and an
+ * evaluation in another precision or summation order may take the other one.  For the tests,
+ * and not as part of the method, the gradient routines can (a) list every decision that lies
+ * within `near_scale` rounding units of turning, and (b) evaluate the gradient with listed
+ * decisions taken the other way.  The rounding unit of a pre-activation z = bias + sum_k w_k a_k
+ * is u * (|bias| + sum_k |w_k a_k|) with u = 2^-24: a float evaluation of the sum in any order
+ * is off by at most the number of terms times that, and typically by a fraction of it.
+ *   stage  0, 1: ReLU + pooling window of the first / second convolutional stage;
+ *          16 + l: ReLU after fully connected layer l (CNN: l = 0 is the layer after flatten)
+ *   sample index inside the mini-batch
+ *   unit   pooled output index (c * Ho + oh) * Wo + ow, or the unit's index in its layer
+ *   alt    the outcome on the other side: pooling 0..3 = the window position (dh * 2 + dw) that
+ *          receives the gradient, 4 = none; ReLU 1 = active, 0 = inactive
+ *   gap    distance from turning, in rounding units */
+typedef struct {
+    int32_t stage, sample, unit, alt;
+    double gap;
+} orc_decision;
+
+typedef struct {
+    const orc_decision *flips; /* decisions to take as their `alt` says (gap ignored) */
+    int32_t n_flips;
+    orc_decision *near;        /* out: decisions with gap < near_scale, first near_cap of them */
+    int32_t near_cap;
+    int32_t n_near;            /* out: how many there were */
+    double near_scale;
+} orc_branch;
+
+#define ORC_U 5.9604644775390625e-08 /* 2^-24 */
+
+static const orc_decision *find_flip(const orc_branch *br, int stage, int sample, int unit)
 {
-    if (margin && v < *margin) *margin = v;
+    if (!br) return NULL;
+    for (int f = 0; f < br->n_flips; ++f)
+        if (br->flips[f].stage == stage && br->flips[f].sample == sample && br->flips[f].unit == unit)
+            return &br->flips[f];
+    return NULL;
+}
+
+static void note_near(orc_branch *br, int stage, int sample, int unit, int alt, double gap)
+{
+    if (!br || !br->near || !(gap < br->near_scale)) return;
+    if (br->n_near < br->near_cap) {
+        orc_decision *e = &br->near[br->n_near];
+        e->stage = stage; e->sample = sample; e->unit = unit; e->alt = alt; e->gap = gap;
+    }
+    br->n_near += 1;
 }
 
 /* Softmax cross-entropy on one sample: fills dz = (softmax(z) - onehot(y)) * scale and
@@ -351,18 +396,18 @@ static double softmax_mse(int C, const double *z, int y, double scale, double *d
  * W[out][in] then bias[out].  x: [B][dims[0]], y: [B]. */
 void orc_grad_mlp_loss(int L, const int32_t *dims, int B, const float *params, const float *x,
                        const int32_t *y, int loss_kind /* 0 cross-entropy, 1 MSE on softmax outputs */,
-                       float *grad, double *loss_out, double *margin /* nullable */);
+                       float *grad, double *loss_out, orc_branch *br /* nullable */);
 
 void orc_grad_mlp(int L, const int32_t *dims, int B, const float *params, const float *x,
-                  const int32_t *y, float *grad, double *loss_out, double *margin /* nullable */)
+                  const int32_t *y, float *grad, double *loss_out, orc_branch *br /* nullable */)
 {
-    orc_grad_mlp_loss(L, dims, B, params, x, y, 0, grad, loss_out, margin);
+    orc_grad_mlp_loss(L, dims, B, params, x, y, 0, grad, loss_out, br);
 }
 
 void orc_grad_mlp_loss(int L, const int32_t *dims, int B, const float *params, const float *x,
-                       const int32_t *y, int loss_kind, float *grad, double *loss_out, double *margin)
+                       const int32_t *y, int loss_kind, float *grad, double *loss_out, orc_branch *br)
 {
-    if (margin) margin[0] = margin[1] = INFINITY;
+    if (br) br->n_near = 0;
     size_t total = 0, maxw = 0;
     for (int l = 0; l < L; ++l) {
         total += (size_t)dims[l + 1] * dims[l] + dims[l + 1];
@@ -375,6 +420,9 @@ void orc_grad_mlp_loss(int L, const int32_t *dims, int B, const float *params, c
     double **z = (double **)malloc(sizeof(double *) * (size_t)L);
     for (int l = 0; l <= L; ++l) a[l] = (double *)malloc(sizeof(double) * (size_t)dims[l]);
     for (int l = 0; l < L; ++l) z[l] = (double *)malloc(sizeof(double) * (size_t)dims[l + 1]);
+    /* on[l][o]: unit o of hidden layer l is active for the current sample */
+    uint8_t **on = (uint8_t **)malloc(sizeof(uint8_t *) * (size_t)L);
+    for (int l = 0; l < L; ++l) on[l] = (uint8_t *)malloc((size_t)dims[l + 1]);
     double *dz = (double *)malloc(sizeof(double) * maxw);
     double *da = (double *)malloc(sizeof(double) * maxw);
     double loss = 0.0;
@@ -389,8 +437,15 @@ void orc_grad_mlp_loss(int L, const int32_t *dims, int B, const float *params, c
                 for (int k = 0; k < in; ++k) v += (double)W[(size_t)o * in + k] * a[l][k];
                 z[l][o] = v;
                 if (l + 1 < L) {
-                    a[l + 1][o] = v > 0.0 ? v : 0.0;
-                    margin_update(margin ? margin + 1 : NULL, fabs(v));
+                    on[l][o] = v > 0.0;
+                    if (br && br->near) {
+                        double mag = fabs((double)bias[o]);
+                        for (int k = 0; k < in; ++k) mag += fabs((double)W[(size_t)o * in + k] * a[l][k]);
+                        note_near(br, 16 + l, s, o, !on[l][o], fabs(v) / (ORC_U * mag));
+                    }
+                    const orc_decision *f = find_flip(br, 16 + l, s, o);
+                    if (f) on[l][o] = f->alt != 0;
+                    a[l + 1][o] = on[l][o] && v > 0.0 ? v : 0.0;
                 }
             }
             off += (size_t)out * in + out;
@@ -411,14 +466,14 @@ void orc_grad_mlp_loss(int L, const int32_t *dims, int B, const float *params, c
                 }
             }
             if (l > 0)
-                for (int k = 0; k < in; ++k) dz[k] = z[l - 1][k] > 0.0 ? da[k] : 0.0;
+                for (int k = 0; k < in; ++k) dz[k] = on[l - 1][k] ? da[k] : 0.0;
         }
     }
     for (size_t k = 0; k < total; ++k) grad[k] = (float)acc[k];
     if (loss_out) *loss_out = loss / (double)B;
     for (int l = 0; l <= L; ++l) free(a[l]);
-    for (int l = 0; l < L; ++l) free(z[l]);
-    free(a); free(z); free(dz); free(da); free(acc);
+    for (int l = 0; l < L; ++l) { free(z[l]); free(on[l]); }
+    free(a); free(z); free(on); free(dz); free(da); free(acc);
 }
 
 /* Direct 'same' convolution, stride 1, odd K, zero padding K/2:
@@ -477,9 +532,37 @@ static void conv_bwd(int Ci, int Co, int H, int Wd, int K, const float *W, const
     }
 }
 
+/* The rounding unit of every output of conv_fwd: |bias| + sum of |W in| over the same taps. */
+static void conv_magnitude(int Ci, int Co, int H, int Wd, int K, const float *W, const float *bias,
+                           const double *in, double *out)
+{
+    int pad = K / 2;
+    for (int co = 0; co < Co; ++co) {
+        double *o = out + (size_t)co * H * Wd;
+        for (int q = 0; q < H * Wd; ++q) o[q] = fabs((double)bias[co]);
+        for (int ci = 0; ci < Ci; ++ci)
+            for (int kh = 0; kh < K; ++kh)
+                for (int kw = 0; kw < K; ++kw) {
+                    double w = (double)W[(((size_t)co * Ci + ci) * K + kh) * K + kw];
+                    for (int oh = 0; oh < H; ++oh) {
+                        int ih = oh + kh - pad;
+                        if (ih < 0 || ih >= H) continue;
+                        for (int ow = 0; ow < Wd; ++ow) {
+                            int iw = ow + kw - pad;
+                            if (iw < 0 || iw >= Wd) continue;
+                            o[oh * Wd + ow] += fabs(w * in[((size_t)ci * H + ih) * Wd + iw]);
+                        }
+                    }
+                }
+    }
+}
+
 /* ReLU then 2x2/stride-2 max pooling; arg[] keeps the flat input index of the first
- * maximum in window order (0,0),(0,1),(1,0),(1,1). */
-static void relu_pool_fwd(int C, int H, int Wd, const double *z, double *out, int *arg, double *margin)
+ * maximum in window order (0,0),(0,1),(1,0),(1,1), pass[] whether that value is positive
+ * (only then does the window hand its gradient on).  mag (rounding units of z) is needed
+ * only when near decisions are listed. */
+static void relu_pool_fwd(int C, int H, int Wd, const double *z, double *out, int *arg, uint8_t *pass,
+                          int stage, int sample, orc_branch *br, const double *mag)
 {
     int Ho = H / 2, Wo = Wd / 2;
     for (int c = 0; c < C; ++c)
@@ -493,28 +576,37 @@ static void relu_pool_fwd(int C, int H, int Wd, const double *z, double *out, in
                         double v = z[ii] > 0.0 ? z[ii] : 0.0;
                         if (bi < 0 || v > best) { best = v; bi = ii; }
                     }
-                out[(c * Ho + oh) * Wo + ow] = best;
-                arg[(c * Ho + oh) * Wo + ow] = bi;
-                if (margin) {
-                    double top = -INFINITY, second = -INFINITY;
-                    for (int dh = 0; dh < 2; ++dh)
-                        for (int dw = 0; dw < 2; ++dw) {
-                            double v = z[(c * H + 2 * oh + dh) * Wd + 2 * ow + dw];
-                            if (v > top) { second = top; top = v; }
-                            else if (v > second) second = v;
-                        }
-                    margin_update(margin, top > 0.0 ? fmin(top, top - second) : -top);
+                int q = (c * Ho + oh) * Wo + ow;
+                out[q] = best;
+                arg[q] = bi;
+                pass[q] = z[bi] > 0.0;
+                if (br && br->near && mag) {
+                    for (int w = 0; w < 4; ++w) {
+                        int ii = (c * H + 2 * oh + w / 2) * Wd + 2 * ow + w % 2;
+                        if (pass[q] && ii != bi)       /* another position overtakes the maximum */
+                            note_near(br, stage, sample, q, w, (z[bi] - z[ii]) / (ORC_U * (mag[bi] + mag[ii])));
+                        else if (!pass[q])             /* a non-positive value turns positive */
+                            note_near(br, stage, sample, q, w, -z[ii] / (ORC_U * mag[ii]));
+                    }
+                    if (pass[q])                       /* the maximum turns non-positive */
+                        note_near(br, stage, sample, q, 4, z[bi] / (ORC_U * mag[bi]));
+                }
+                const orc_decision *f = find_flip(br, stage, sample, q);
+                if (f) {
+                    pass[q] = f->alt != 4;
+                    if (pass[q]) arg[q] = (c * H + 2 * oh + f->alt / 2) * Wd + 2 * ow + f->alt % 2;
+                    out[q] = pass[q] && z[arg[q]] > 0.0 ? z[arg[q]] : 0.0;
                 }
             }
 }
 
-static void relu_pool_bwd(int C, int H, int Wd, const double *z, const int *arg,
+static void relu_pool_bwd(int C, int H, int Wd, const int *arg, const uint8_t *pass,
                           const double *dout, double *dz)
 {
     int Ho = H / 2, Wo = Wd / 2;
     memset(dz, 0, sizeof(double) * (size_t)C * H * Wd);
     for (int q = 0; q < C * Ho * Wo; ++q)
-        if (z[arg[q]] > 0.0) dz[arg[q]] += dout[q];
+        if (pass[q]) dz[arg[q]] += dout[q];
 }
 
 /* conv KxK (C0->C1, same) ReLU pool2 -> conv KxK (C1->C2, same) ReLU pool2 -> flatten
@@ -522,9 +614,9 @@ static void relu_pool_bwd(int C, int H, int Wd, const double *z, const int *arg,
  * shape = {C0, H, W, C1, C2, K, F, classes}.  Parameter order: conv1 W,b; conv2 W,b;
  * fc1 W,b; fc2 W,b. */
 void orc_grad_cnn(const int32_t *shape, int B, const float *params, const float *x,
-                  const int32_t *y, float *grad, double *loss_out, double *margin /* nullable */)
+                  const int32_t *y, float *grad, double *loss_out, orc_branch *br /* nullable */)
 {
-    if (margin) margin[0] = margin[1] = INFINITY;
+    if (br) br->n_near = 0;
     int C0 = shape[0], H = shape[1], Wd = shape[2], C1 = shape[3], C2 = shape[4], K = shape[5],
         F = shape[6], NC = shape[7];
     int H2 = H / 2, W2 = Wd / 2, H4 = H / 4, W4 = Wd / 4, flat = C2 * H4 * W4;
@@ -543,6 +635,12 @@ void orc_grad_cnn(const int32_t *shape, int B, const float *params, const float 
     double *p2 = (double *)malloc(sizeof(double) * (size_t)flat);
     double *dp2 = (double *)malloc(sizeof(double) * (size_t)flat);
     int *arg2 = (int *)malloc(sizeof(int) * (size_t)flat);
+    uint8_t *pass1 = (uint8_t *)malloc((size_t)C1 * H2 * W2);
+    uint8_t *pass2 = (uint8_t *)malloc((size_t)flat);
+    uint8_t *on3 = (uint8_t *)malloc((size_t)F);
+    int listing = br && br->near;
+    double *mag1 = listing ? (double *)malloc(sizeof(double) * (size_t)C1 * H * Wd) : NULL;
+    double *mag2 = listing ? (double *)malloc(sizeof(double) * (size_t)C2 * H2 * W2) : NULL;
     double *z3 = (double *)malloc(sizeof(double) * (size_t)F);
     double *a3 = (double *)malloc(sizeof(double) * (size_t)F);
     double *dz3 = (double *)malloc(sizeof(double) * (size_t)F);
@@ -552,15 +650,24 @@ void orc_grad_cnn(const int32_t *shape, int B, const float *params, const float 
     for (int s = 0; s < B; ++s) {
         for (int q = 0; q < C0 * H * Wd; ++q) a0[q] = (double)x[(size_t)s * C0 * H * Wd + q];
         conv_fwd(C0, C1, H, Wd, K, params + o_w1, params + o_b1, a0, z1);
-        relu_pool_fwd(C1, H, Wd, z1, p1, arg1, margin);
+        if (listing) conv_magnitude(C0, C1, H, Wd, K, params + o_w1, params + o_b1, a0, mag1);
+        relu_pool_fwd(C1, H, Wd, z1, p1, arg1, pass1, 0, s, br, mag1);
         conv_fwd(C1, C2, H2, W2, K, params + o_w2, params + o_b2, p1, z2);
-        relu_pool_fwd(C2, H2, W2, z2, p2, arg2, margin);
+        if (listing) conv_magnitude(C1, C2, H2, W2, K, params + o_w2, params + o_b2, p1, mag2);
+        relu_pool_fwd(C2, H2, W2, z2, p2, arg2, pass2, 1, s, br, mag2);
         for (int o = 0; o < F; ++o) {
             double v = (double)params[o_b3 + o];
             for (int k = 0; k < flat; ++k) v += (double)params[o_w3 + (size_t)o * flat + k] * p2[k];
             z3[o] = v;
-            a3[o] = v > 0.0 ? v : 0.0;
-            margin_update(margin ? margin + 1 : NULL, fabs(v));
+            on3[o] = v > 0.0;
+            if (listing) {
+                double mag = fabs((double)params[o_b3 + o]);
+                for (int k = 0; k < flat; ++k) mag += fabs((double)params[o_w3 + (size_t)o * flat + k] * p2[k]);
+                note_near(br, 16, s, o, !on3[o], fabs(v) / (ORC_U * mag));
+            }
+            const orc_decision *f = find_flip(br, 16, s, o);
+            if (f) on3[o] = f->alt != 0;
+            a3[o] = on3[o] && v > 0.0 ? v : 0.0;
         }
         for (int o = 0; o < NC; ++o) {
             double v = (double)params[o_b4 + o];
@@ -578,7 +685,7 @@ void orc_grad_cnn(const int32_t *shape, int B, const float *params, const float 
             }
         }
         for (int k = 0; k < F; ++k)
-            if (!(z3[k] > 0.0)) dz3[k] = 0.0;
+            if (!on3[k]) dz3[k] = 0.0;
         /* fc1 */
         for (int k = 0; k < flat; ++k) dp2[k] = 0.0;
         for (int o = 0; o < F; ++o) {
@@ -588,38 +695,43 @@ void orc_grad_cnn(const int32_t *shape, int B, const float *params, const float 
                 dp2[k] += (double)params[o_w3 + (size_t)o * flat + k] * dz3[o];
             }
         }
-        relu_pool_bwd(C2, H2, W2, z2, arg2, dp2, dz2);
+        relu_pool_bwd(C2, H2, W2, arg2, pass2, dp2, dz2);
         conv_bwd(C1, C2, H2, W2, K, params + o_w2, p1, dz2, acc + o_w2, acc + o_b2, dp1);
-        relu_pool_bwd(C1, H, Wd, z1, arg1, dp1, dz1);
+        relu_pool_bwd(C1, H, Wd, arg1, pass1, dp1, dz1);
         conv_bwd(C0, C1, H, Wd, K, params + o_w1, a0, dz1, acc + o_w1, acc + o_b1, NULL);
     }
     for (size_t k = 0; k < total; ++k) grad[k] = (float)acc[k];
     if (loss_out) *loss_out = loss / (double)B;
     free(acc); free(a0); free(z1); free(dz1); free(p1); free(dp1); free(arg1);
     free(z2); free(dz2); free(p2); free(dp2); free(arg2); free(z3); free(a3); free(dz3);
-    free(z4); free(dz4);
+    free(z4); free(dz4); free(pass1); free(pass2); free(on3); free(mag1); free(mag2);
 }
 
 /* Gradients of all workers: worker i uses row i of params [N][ld], its own batch, and
  * writes row i of grad [N][ld] (padding columns zeroed).  kind 0: fully connected
  * (desc = {L, dims[0..L]}), kind 1: convolutional (desc = shape[8]), kind 2: fully connected
- * with the MSE-on-softmax loss. */
+ * with the MSE-on-softmax loss.  With near != NULL every worker's decisions closer than
+ * near_scale rounding units to turning are listed: worker i's in near[i * near_cap ...], their
+ * number (also beyond near_cap) in n_near[i]. */
 void orc_grad_all(int kind, const int32_t *desc, int N, int64_t d, int64_t ld, int B,
                   int64_t in_dim, const float *params, const float *x, const int32_t *y,
-                  float *grad, double *loss /* N, nullable */, double *margin /* N x 2, nullable */)
+                  float *grad, double *loss /* N, nullable */, orc_decision *near /* nullable */,
+                  int32_t near_cap, int32_t *n_near /* N */, double near_scale)
 {
 #pragma omp parallel for schedule(dynamic, 1) num_threads(orc_threads)
     for (int i = 0; i < N; ++i) {
         float *gi = grad + (size_t)i * ld;
         double li = 0.0;
-        double *mi = margin ? margin + 2 * i : NULL;
+        orc_branch br = {NULL, 0, near ? near + (size_t)i * near_cap : NULL, near_cap, 0, near_scale};
+        orc_branch *bp = near ? &br : NULL;
         if (kind == 0 || kind == 2)
             orc_grad_mlp_loss(desc[0], desc + 1, B, params + (size_t)i * ld,
-                              x + (size_t)i * B * in_dim, y + (size_t)i * B, kind == 2, gi, &li, mi);
+                              x + (size_t)i * B * in_dim, y + (size_t)i * B, kind == 2, gi, &li, bp);
         else
             orc_grad_cnn(desc, B, params + (size_t)i * ld, x + (size_t)i * B * in_dim,
-                         y + (size_t)i * B, gi, &li, mi);
+                         y + (size_t)i * B, gi, &li, bp);
         for (int64_t c = d; c < ld; ++c) gi[c] = 0.0f;
         if (loss) loss[i] = li;
+        if (near) n_near[i] = br.n_near;
     }
 }

@@ -5,7 +5,7 @@ import pytest
 import torch
 
 from paper_2102_06280_amd import inputs
-from gpu_util import AMBIGUOUS_FC_256, assert_mostly_tight, assert_params_close, dev, row_tolerances
+from gpu_util import GradientResolver, assert_params_close, dev, involved_workers, match_gradients, match_round
 
 pytestmark = pytest.mark.gpu
 
@@ -69,16 +69,24 @@ def test_mlp_gradients_match_oracle(B, orc, dims, batch, n, loss_kind):
                 assert "fc32_dgrad" in kernels, kernels
         got, gl = grads.cpu().numpy(), loss.cpu().numpy()
         kind, od = orc.model_desc(desc)
-        want, wl = orc.grad_all(kind, od, d, params, x, y)
-        assert np.allclose(gl, wl, rtol=2e-6, atol=1e-6)
+        res = GradientResolver(orc, kind, od, d, params, x, y, threads=min(n, 8))
+        assert np.allclose(gl, res.loss, rtol=2e-6, atol=1e-6)
         assert np.all(got[:, d:] == 7.0)
-        off = 0
-        for fan_in, nw, nb in inputs.layer_shapes(desc):
-            for lo, hi, what in ((off, off + nw, "W"), (off + nw, off + nw + nb, "b")):
-                for i in range(n):
-                    r = rel_l2(got[i, lo:hi], want[i, lo:hi])
-                    assert r <= 2e-5, f"worker {i} {what}[{lo}:{hi}] rel L2 {r:.2e}"
-            off += nw + nb
+
+        def layers_close(g_row, w_row, tol=2e-5):
+            # every layer's weights and biases: relative L2 error, and the largest element error
+            # relative to the layer's largest element
+            off = 0
+            for fan_in, nw, nb in inputs.layer_shapes(desc):
+                for lo, hi in ((off, off + nw), (off + nw, off + nw + nb)):
+                    w = w_row[lo:hi].astype(np.float64)
+                    diff = g_row[lo:hi] - w
+                    if np.linalg.norm(diff) > tol * np.linalg.norm(w) or np.abs(diff).max() > tol * np.abs(w).max():
+                        return False
+                off += nw + nb
+            return True
+        match_gradients(res, got, layers_close, d, what=f"dims {dims} batch {batch}")
+        print(res.summary())
     finally:
         B.dbw_destroy(h)
 
@@ -99,12 +107,15 @@ def test_softmax_zero_init_round_one(B, orc):
         B.dbw_destroy(h)
 
 
-@pytest.mark.parametrize("cid,rounds,order", [(1, 10, 0), (1, 10, 1), (2, 6, 0), (2, 3, 1)],
+@pytest.mark.parametrize("cid,rounds,order", [(1, 10, 0), (1, 10, 1), (2, 100, 0), (2, 100, 1)],
                          ids=["config1-cta", "config1-atc", "config2-cta", "config2-atc"])
 def test_rounds_lock_step(B, orc, cid, rounds, order):
-    """Whole rounds of configurations 1 and 2.  Each round both sides start from the
-    oracle's previous output; the free-running GPU trajectory is carried along and must
-    stay close as well (reported, loosely bounded)."""
+    """All rounds of configurations 1 and 2 (10 and 100).  Each round both sides start from the
+    oracle's previous output, and every worker's parameters must agree to 1e-5 (a row that
+    misses the oracle's default evaluation must match its evaluation for one common assignment of
+    the ReLU decisions it lists as within rounding of zero).  The free-running GPU trajectory is
+    carried along and its drift reported; it is discontinuous in those decisions and not gated
+    beyond a sanity bound."""
     cfg = inputs.CONFIGS[cid]
     desc = inputs.model_dims(cfg.model)
     rowptr, colidx = inputs.make_graph(cfg)
@@ -128,17 +139,22 @@ def test_rounds_lock_step(B, orc, cid, rounds, order):
             B.dbw_round(h, free, free_out, cfg.lr, batch_x=dbx, batch_y=dby)
             free = free_out
             mask, p, _ = orc.select(rowptr, colidx, t, b)
-            grad, oloss = orc.grad_all(kind, od, cfg.d, x, bx, by)
-            want = orc.round_(rowptr, colidx, mask, p, x, grad, cfg.lr, order, d=cfg.d)
             mask_d = torch.empty(colidx.size, dtype=torch.uint8, device="cuda")
             B.dbw_get_selection(h, None, mask_d, None)
             assert np.array_equal(mask_d.cpu().numpy(), mask)
-            assert_params_close(out.cpu().numpy(), want, d=cfg.d, what=f"config {cid} round {rnd}")
-            assert np.allclose(loss.cpu().numpy(), oloss, rtol=1e-5, atol=1e-6)
+            res = GradientResolver(orc, kind, od, cfg.d, x, bx, by)
+            round_fn = lambda grad: orc.round_(rowptr, colidx, mask, p, x, grad, cfg.lr, order, d=cfg.d)
+            inv = involved_workers(order, cfg.lr, rowptr, colidx, mask, lambda: orc.weights(rowptr, colidx, mask, p))
+            got = out.cpu().numpy()
+            want = match_round(res, got, round_fn, inv, cfg.d, what=f"config {cid} round {rnd}")
+            assert_params_close(got, want, d=cfg.d, what=f"config {cid} round {rnd}")
+            if any(res.resolved.values()):
+                print(f"round {rnd}: {res.summary()}", flush=True)
+            assert np.allclose(loss.cpu().numpy(), res.loss, rtol=1e-5, atol=1e-6)
             x = want
         drift = rel_l2(free.cpu().numpy()[:, :cfg.d], x[:, :cfg.d])
         print(f"config {cid}: free-running drift after {rounds} rounds: {drift:.2e}")
-        assert drift < 1e-3
+        assert drift < 0.1
     finally:
         B.dbw_destroy(h)
 
@@ -148,10 +164,10 @@ def test_paper_models_lock_step(B, orc, cid, order):
     """The experiment shapes of Section 5 / Appendix B (LRM with cross-entropy, 2NN with MSE
     on the softmax outputs, batch 1024, learning rate decayed by 0.95 per round, backup
     counts from the threshold rule, at least one straggler per round) through the Workload
-    helper, round by round against the oracle.  With 1024 x 512 ReLU inputs per worker and
-    round, some land within fp32 rounding of zero: a worker for which the oracle reports
-    such a near-tie is compared loosely, and three quarters of all workers must meet the
-    full tolerance in every round whatever their margins."""
+    helper, round by round against the oracle, every worker to 1e-5.  With 1024 x 512 ReLU
+    inputs per worker and round, some land within fp32 rounding of zero: a row that misses the
+    oracle's default evaluation must match its evaluation for one common assignment of the
+    decisions it lists as that close."""
     from paper_2102_06280_amd.workload import Workload
     cfg = inputs.CONFIGS[cid]
     rounds = 8
@@ -170,17 +186,18 @@ def test_paper_models_lock_step(B, orc, cid, order):
             got = wl.params().cpu().numpy()
             bx, by = inputs.batch(cfg, rnd)
             mask, p, _ = orc.select(wl.rowptr, wl.colidx, t, b)
-            grad, oloss, margin = orc.grad_all(kind, od, cfg.d, x, bx, by, with_margin=True)
-            want = orc.round_(wl.rowptr, wl.colidx, mask, p, x, grad, inputs.learning_rate(cfg, rnd), order, d=cfg.d)
             mask_d = torch.empty(wl.colidx.size, dtype=torch.uint8, device="cuda")
             B.dbw_get_selection(wl.h, None, mask_d, None)
             assert np.array_equal(mask_d.cpu().numpy(), mask), f"round {rnd}"
-            tol = row_tolerances(margin, fc=AMBIGUOUS_FC_256,
-                                 selection=(wl.rowptr, wl.colidx, mask) if order == 1 else None)
-            assert_params_close(got, want, d=cfg.d, tol=tol, what=f"config {cid} round {rnd}")
-            rel = assert_mostly_tight(got, want, cfg.d, what=f"config {cid} round {rnd}")
-            print(f"round {rnd}: {(tol > 1e-5).sum()} workers flagged, {(rel > 1e-6).sum()} rows above 1e-6")
-            assert np.allclose(wl.loss.cpu().numpy(), oloss, rtol=1e-5, atol=1e-6)
+            lr = inputs.learning_rate(cfg, rnd)
+            res = GradientResolver(orc, kind, od, cfg.d, x, bx, by)
+            round_fn = lambda grad: orc.round_(wl.rowptr, wl.colidx, mask, p, x, grad, lr, order, d=cfg.d)
+            inv = involved_workers(order, lr, wl.rowptr, wl.colidx, mask,
+                                   lambda: orc.weights(wl.rowptr, wl.colidx, mask, p))
+            want = match_round(res, got, round_fn, inv, cfg.d, what=f"config {cid} round {rnd}")
+            assert_params_close(got, want, d=cfg.d, what=f"config {cid} round {rnd}")
+            print(f"round {rnd}: {res.summary()}", flush=True)
+            assert np.allclose(wl.loss.cpu().numpy(), res.loss, rtol=1e-5, atol=1e-6)
             x = want
         # the decayed step really is in use
         assert inputs.learning_rate(cfg, rounds - 1) == pytest.approx(cfg.lr * 0.95 ** (rounds - 1))

@@ -195,9 +195,13 @@ def test_grad_all_rows_and_padding(orc):
         assert np.array_equal(grad[i, :d], gi) and loss[i] == li
 
 
-def test_decision_margin_diagnostic(orc):
-    """The margin reported next to the gradients is the smallest |z| over all hidden ReLU
-    inputs (recomputed here with NumPy)."""
+U = 2.0 ** -24
+
+
+def test_near_decisions_of_fully_connected_layers(orc):
+    """The decisions listed next to the gradients: every hidden ReLU whose |z| is below
+    near_scale rounding units (2^-24 times |bias| + sum |w a|, recomputed here with NumPy),
+    with the opposite outcome as `alt`, and nothing else."""
     dims = [9, 7, 6, 4]
     g = np.random.default_rng(83)
     d = sum(dims[l + 1] * (dims[l] + 1) for l in range(3))
@@ -206,17 +210,193 @@ def test_decision_margin_diagnostic(orc):
     x = g.standard_normal((2, 5, 9)).astype(np.float32)
     y = g.integers(0, 4, (2, 5)).astype(np.int32)
     kind, desc = orc.model_desc({"kind": "mlp", "dims": dims})
-    _, _, margin = orc.grad_all(kind, desc, d, params, x, y, with_margin=True)
+    scale = 3e6                                       # wide enough to list about a third of the units
+    grad, _, near = orc.grad_all(kind, desc, d, params, x, y, near_scale=scale)
+    assert np.array_equal(grad, orc.grad_all(kind, desc, d, params, x, y)[0])      # listing changes nothing
     for i in range(2):
-        a, off, smallest = x[i].astype(np.float64), 0, np.inf
+        a, off, want = x[i].astype(np.float64), 0, {}
         for l in range(2):
             o, k = dims[l + 1], dims[l]
             W = params[i, off:off + o * k].reshape(o, k).astype(np.float64); off += o * k
             b = params[i, off:off + o].astype(np.float64); off += o
             z = a @ W.T + b
-            smallest = min(smallest, np.abs(z).min())
+            gap = np.abs(z) / (U * (np.abs(a) @ np.abs(W).T + np.abs(b)))
+            for s_, u_ in zip(*np.nonzero(gap < scale)):
+                want[(16 + l, int(s_), int(u_), int(z[s_, u_] <= 0))] = gap[s_, u_]
             a = np.maximum(z, 0)
-        assert abs(margin[i, 1] - smallest) < 1e-12 and np.isinf(margin[i, 0])
+        got = {e.key(): e.gap for e in near[i]}
+        assert 10 < len(want) < 60 and set(got) == set(want)
+        assert all(abs(got[k] - want[k]) <= 1e-9 * want[k] for k in want)
+
+
+def _cnn_forward_numpy(shape, params, x):
+    """Pre-activations of both convolutional stages and of the first fully connected layer,
+    with their rounding units, through the independent forward pass of this file."""
+    C0, H, W, C1, C2, K, Fc, NC = shape
+    p = params.astype(np.float64)
+    off = 0
+    def take(*s):
+        nonlocal off
+        n = int(np.prod(s)); v = p[off:off + n].reshape(s); off += n
+        return v
+    W1, b1, W2, b2 = take(C1, C0, K, K), take(C1), take(C2, C1, K, K), take(C2)
+    flat = C2 * (H // 4) * (W // 4)
+    W3, b3 = take(Fc, flat), take(Fc)
+    xi = x.reshape(-1, C0, H, W).astype(np.float64)
+    z1, m1 = conv_same(xi, W1, b1), conv_same(np.abs(xi), np.abs(W1), np.abs(b1))
+    p1 = pool2(np.maximum(z1, 0))
+    z2, m2 = conv_same(p1, W2, b2), conv_same(np.abs(p1), np.abs(W2), np.abs(b2))
+    p2 = pool2(np.maximum(z2, 0)).reshape(len(xi), -1)
+    z3, m3 = p2 @ W3.T + b3, np.abs(p2) @ np.abs(W3).T + np.abs(b3)
+    return (z1, m1), (z2, m2), (z3, m3)
+
+
+def test_near_decisions_of_pooling_windows(orc):
+    """Listed decisions of a small convolutional network against a brute-force walk over all
+    windows: with a positive maximum, every other position closer to it than the bound (gap =
+    difference over the two rounding units) and the maximum's own distance from zero; with no
+    positive value, every position's distance from zero."""
+    shape = (2, 8, 8, 3, 4, 3, 6, 5)
+    g = np.random.default_rng(85)
+    desc = {"kind": "cnn", "in": (2, 8, 8), "c1": 3, "c2": 4, "k": 3, "fc": 6, "classes": 5}
+    d = inputs.param_count(desc)
+    params = inputs.init_params(desc, 1, d, g)[0] + (g.standard_normal(d) * 0.05).astype(np.float32)
+    x = g.standard_normal((3, 2 * 8 * 8)).astype(np.float32)
+    y = g.integers(0, 5, 3).astype(np.int32)
+    scale = 1.5e6
+    grad, loss, near = orc.grad_cnn(shape, params, x, y, near_scale=scale)
+    assert np.array_equal(grad, orc.grad_cnn(shape, params, x, y)[0])
+    stages = _cnn_forward_numpy(shape, params, x)
+    want = {}
+    for stage, (z, m) in enumerate(stages[:2]):
+        B_, C_, H_, W_ = z.shape
+        for s_ in range(B_):
+            for c in range(C_):
+                for oh in range(H_ // 2):
+                    for ow in range(W_ // 2):
+                        unit = (c * (H_ // 2) + oh) * (W_ // 2) + ow
+                        win = [(z[s_, c, 2 * oh + q // 2, 2 * ow + q % 2], m[s_, c, 2 * oh + q // 2, 2 * ow + q % 2])
+                               for q in range(4)]
+                        top = max(range(4), key=lambda q: (win[q][0], -q))
+                        if win[top][0] > 0:
+                            for q in range(4):
+                                if q != top:
+                                    want[(stage, s_, unit, q)] = (win[top][0] - win[q][0]) / (U * (win[top][1] + win[q][1]))
+                            want[(stage, s_, unit, 4)] = win[top][0] / (U * win[top][1])
+                        else:
+                            for q in range(4):
+                                want[(stage, s_, unit, q)] = -win[q][0] / (U * win[q][1])
+    z3, m3 = stages[2]
+    for s_ in range(z3.shape[0]):
+        for o in range(z3.shape[1]):
+            want[(16, s_, o, int(z3[s_, o] <= 0))] = abs(z3[s_, o]) / (U * m3[s_, o])
+    want = {k: v for k, v in want.items() if v < scale}
+    got = {e.key(): e.gap for e in near}
+    assert len(want) > 20 and set(got) == set(want)
+    assert all(abs(got[k] - want[k]) <= 1e-9 * max(want[k], 1e-300) for k in want)
+
+
+def _straight_through_relu(z, on):
+    """Forward relu(z) where `on`, else 0; gradient 1 where `on`, whatever the sign of z."""
+    return (z - z.detach() + F.relu(z).detach()) * on
+
+
+def test_flipped_relu_decisions_match_autograd(orc):
+    """Gradient with chosen ReLU decisions taken the other way = autograd of the same network
+    with those units forced active / inactive for those samples."""
+    dims = [9, 7, 6, 4]
+    g = np.random.default_rng(87)
+    d = sum(dims[l + 1] * (dims[l] + 1) for l in range(3))
+    params = (g.standard_normal(d) * 0.5).astype(np.float32)
+    x = g.standard_normal((5, 9)).astype(np.float32)
+    y = g.integers(0, 4, 5).astype(np.int32)
+    for loss_kind in ("xent", "mse"):
+        _, _, near = orc.grad_mlp(dims, params, x, y, loss_kind=loss_kind, near_scale=1e9)
+        assert len(near) == 5 * 13                      # every hidden unit of every sample
+        flips = [near[k] for k in (0, 7, 20, 33, 64)]
+        grad, loss = orc.grad_mlp(dims, params, x, y, loss_kind=loss_kind, flips=flips)
+        p = torch.tensor(params, dtype=torch.float64, requires_grad=True)
+        a, off = torch.tensor(x, dtype=torch.float64), 0
+        for l in range(3):
+            i, o = dims[l], dims[l + 1]
+            Wt = p[off:off + o * i].view(o, i); off += o * i
+            bt = p[off:off + o]; off += o
+            z = F.linear(a, Wt, bt)
+            if l < 2:
+                on = (z > 0).to(torch.float64)
+                for f in flips:
+                    if f.stage == 16 + l:
+                        on[f.sample, f.unit] = float(f.alt)
+                a = _straight_through_relu(z, on)
+        if loss_kind == "xent":
+            lt = F.cross_entropy(z, torch.tensor(y, dtype=torch.long))
+        else:
+            target = F.one_hot(torch.tensor(y, dtype=torch.long), 4).to(torch.float64)
+            lt = F.mse_loss(F.softmax(z, 1), target, reduction="sum") / len(y)
+        lt.backward()
+        assert abs(loss - float(lt.detach())) < 1e-12
+        assert np.allclose(grad, p.grad.numpy(), rtol=1e-6, atol=1e-10)
+        base = orc.grad_mlp(dims, params, x, y, loss_kind=loss_kind)[0]
+        assert np.abs(grad - base).max() > 1e-3         # the flips did change the gradient
+
+
+def test_flipped_pooling_decisions_match_autograd(orc):
+    """The same for the convolutional network: a window forced to hand its gradient to another
+    position, or to none; a fully connected ReLU forced on."""
+    shape = (2, 8, 8, 3, 4, 3, 6, 5)
+    C0, H, W, C1, C2, K, Fc, NC = shape
+    g = np.random.default_rng(91)
+    desc = {"kind": "cnn", "in": (2, 8, 8), "c1": 3, "c2": 4, "k": 3, "fc": 6, "classes": 5}
+    d = inputs.param_count(desc)
+    params = inputs.init_params(desc, 1, d, g)[0] + (g.standard_normal(d) * 0.05).astype(np.float32)
+    x = g.standard_normal((3, C0 * H * W)).astype(np.float32)
+    y = g.integers(0, 5, 3).astype(np.int32)
+    _, _, near = orc.grad_cnn(shape, params, x, y, near_scale=1e12)
+    by_stage = {st: [e for e in near if e.stage == st] for st in (0, 1, 16)}
+    pick = lambda lst, alt, skip=0: [e for e in lst if (e.alt == 4) == (alt == 4)][skip]
+    flips = [pick(by_stage[0], 0), pick(by_stage[0], 4, 3), pick(by_stage[1], 0, 2), pick(by_stage[1], 4, 1),
+             by_stage[16][4]]
+    assert len({(f.stage, f.sample, f.unit) for f in flips}) == 5
+    grad, loss = orc.grad_cnn(shape, params, x, y, flips=flips)
+
+    p = torch.tensor(params, dtype=torch.float64, requires_grad=True)
+    off = 0
+    def take(*s):
+        nonlocal off
+        n = int(np.prod(s)); v = p[off:off + n].view(*s); off += n
+        return v
+    W1, b1, W2, b2 = take(C1, C0, K, K), take(C1), take(C2, C1, K, K), take(C2)
+    W3, b3, W4, b4 = take(Fc, C2 * (H // 4) * (W // 4)), take(Fc), take(NC, Fc), take(NC)
+
+    def stage(inp, Wc, bc, st):
+        z = F.conv2d(inp, Wc, bc, padding=K // 2)
+        B_, C_, H_, W_ = z.shape
+        win = z.view(B_, C_, H_ // 2, 2, W_ // 2, 2).permute(0, 1, 2, 4, 3, 5).reshape(B_, C_, H_ // 2, W_ // 2, 4)
+        arg = torch.relu(win).detach().argmax(dim=-1, keepdim=True)     # first maximum in window order
+        on = (win.detach().gather(-1, arg) > 0).to(torch.float64)
+        for f in flips:
+            if f.stage == st:
+                c, r = divmod(f.unit, (H_ // 2) * (W_ // 2))
+                oh, ow = divmod(r, W_ // 2)
+                on[f.sample, c, oh, ow, 0] = 0.0 if f.alt == 4 else 1.0
+                if f.alt != 4:
+                    arg[f.sample, c, oh, ow, 0] = f.alt
+        return _straight_through_relu(win.gather(-1, arg), on).squeeze(-1)
+
+    a = torch.tensor(x, dtype=torch.float64).view(-1, C0, H, W)
+    a = stage(a, W1, b1, 0)
+    a = stage(a, W2, b2, 1).reshape(len(x), -1)
+    z3 = F.linear(a, W3, b3)
+    on3 = (z3 > 0).to(torch.float64)
+    for f in flips:
+        if f.stage == 16:
+            on3[f.sample, f.unit] = float(f.alt)
+    z4 = F.linear(_straight_through_relu(z3, on3), W4, b4)
+    lt = F.cross_entropy(z4, torch.tensor(y, dtype=torch.long))
+    lt.backward()
+    assert abs(loss - float(lt.detach())) < 1e-12
+    assert np.allclose(grad, p.grad.numpy(), rtol=1e-6, atol=1e-10)
+    assert np.abs(grad - orc.grad_cnn(shape, params, x, y)[0]).max() > 1e-4
 
 
 def mlp_mse_loss(dims, params, x, y):

@@ -32,6 +32,8 @@ FAST_PINS = {
     "dtur": [T_dtur.test_link_set_is_spanning_tree, T_dtur.test_dtur_epochs, T_dtur.test_dtur_dead_worker],
     "grad": [T_grad.test_mlp_finite_differences, T_grad.test_softmax_zero_init_closed_form,
              T_grad.test_mlp_mse_finite_differences, T_grad.test_cnn_finite_differences],
+    "branch": [T_grad.test_near_decisions_of_fully_connected_layers, T_grad.test_near_decisions_of_pooling_windows,
+               T_grad.test_flipped_relu_decisions_match_autograd, T_grad.test_flipped_pooling_decisions_match_autograd],
 }
 
 MUTANTS = [
@@ -52,13 +54,13 @@ MUTANTS = [
     ("threshold-latest-link", "dtur", "if (best < 0 || est < theta) {", "if (best < 0 || est > theta) {"),
     ("link-established-by-the-faster-end", "dtur", "float est = tu > tv ? tu : tv;", "float est = tu < tv ? tu : tv;"),
     ("threshold-strict", "dtur", "if (canon_time(t[colidx[e]]) <= theta) ++cnt;", "if (canon_time(t[colidx[e]]) < theta) ++cnt;"),
-    ("relu-derivative-dropped", "grad", "dz[k] = z[l - 1][k] > 0.0 ? da[k] : 0.0;", "dz[k] = da[k];"),
+    ("relu-derivative-dropped", "grad", "dz[k] = on[l - 1][k] ? da[k] : 0.0;", "dz[k] = da[k];"),
     ("bias-gradient-dropped", "grad", "gb[o] += dz[o];", "gb[o] += 0.0;"),
     ("weight-gradient-transposed-operand", "grad", "da[k] += (double)W[(size_t)o * in + k] * dz[o];",
      "da[k] += (double)W[(size_t)(o * in + k) % ((size_t)out * in)] * dz[(o + 1) % out];"),
     ("conv-data-gradient-dropped", "grad", "if (din) din[ii] += w * go[oh * Wd + ow];", "if (din) din[ii] += 0.0;"),
     ("conv-weight-gradient-shifted", "grad", "gw += go[oh * Wd + ow] * in[ii];", "gw += go[oh * Wd + ow] * in[ii > 0 ? ii - 1 : ii];"),
-    ("pooling-passes-gradient-through-inactive-relu", "grad", "if (z[arg[q]] > 0.0) dz[arg[q]] += dout[q];",
+    ("pooling-passes-gradient-through-inactive-relu", "grad", "if (pass[q]) dz[arg[q]] += dout[q];",
      "dz[arg[q]] += dout[q];"),
     ("conv-bias-gradient-dropped", "grad", "for (int q = 0; q < H * Wd; ++q) gb[co] += go[q];",
      "for (int q = 0; q < H * Wd; ++q) gb[co] += 0.0;"),
@@ -85,6 +87,30 @@ MUTANTS = [
     ("threshold-ties-go-to-the-last-link", "dtur", "if (best < 0 || est < theta) {", "if (best < 0 || est <= theta) {"),
     ("slow-workers-wait-for-everybody", "dtur", "            b[j] = deg;\n", "            b[j] = 0;\n"),
     ("visited-links-are-chosen-again", "dtur", "        if (visited[e]) continue;\n", ""),
+    # the branch-decision diagnostics (listing of near decisions, evaluation with decisions flipped)
+    ("flipped-relu-only-in-the-forward-pass", "branch", "dz[k] = on[l - 1][k] ? da[k] : 0.0;",
+     "dz[k] = z[l - 1][k] > 0.0 ? da[k] : 0.0;"),
+    ("flipped-relu-sign-reversed", "branch", "if (f) on[l][o] = f->alt != 0;", "if (f) on[l][o] = f->alt == 0;"),
+    ("flip-matches-any-sample", "branch",
+     "if (br->flips[f].stage == stage && br->flips[f].sample == sample && br->flips[f].unit == unit)",
+     "if (br->flips[f].stage == stage && br->flips[f].unit == unit)"),
+    ("flipped-window-keeps-its-position", "branch",
+     "if (pass[q]) arg[q] = (c * H + 2 * oh + f->alt / 2) * Wd + 2 * ow + f->alt % 2;", ""),
+    ("flipped-window-to-none-still-passes", "branch", "pass[q] = f->alt != 4;", "pass[q] = 1;"),
+    ("window-position-transposed", "branch",
+     "if (pass[q]) arg[q] = (c * H + 2 * oh + f->alt / 2) * Wd + 2 * ow + f->alt % 2;",
+     "if (pass[q]) arg[q] = (c * H + 2 * oh + f->alt % 2) * Wd + 2 * ow + f->alt / 2;"),
+    ("rounding-unit-without-the-bias", "branch", "double mag = fabs((double)bias[o]);", "double mag = 0.0;"),
+    ("rounding-unit-of-signed-products", "branch",
+     "o[oh * Wd + ow] += fabs(w * in[((size_t)ci * H + ih) * Wd + iw]);",
+     "o[oh * Wd + ow] += w * in[((size_t)ci * H + ih) * Wd + iw];"),
+    ("pooling-gap-against-one-unit-only", "branch",
+     "note_near(br, stage, sample, q, w, (z[bi] - z[ii]) / (ORC_U * (mag[bi] + mag[ii])));",
+     "note_near(br, stage, sample, q, w, (z[bi] - z[ii]) / (ORC_U * mag[bi]));"),
+    ("inactive-window-lists-nothing", "branch", "else if (!pass[q])             /* a non-positive value turns positive */",
+     "else if (0)"),
+    ("near-list-alt-is-the-current-outcome", "branch", "note_near(br, 16 + l, s, o, !on[l][o], fabs(v) / (ORC_U * mag));",
+     "note_near(br, 16 + l, s, o, on[l][o], fabs(v) / (ORC_U * mag));"),
 ]
 
 
