@@ -25,10 +25,25 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix
 
-# HBM bytes per launch from hardware counters (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors
-# from a plain copy of known size; profiles/ holds the runs).  Keyed by (kernel, config);
-# an entry is removed when its kernel changes.
-MEASURED_TRAFFIC = {("mix_tile_major", 4): 17.203e9, ("mix_lds_tiles", 4): 17.203e9, ("mix_dense_kernel", 5): 3.074e9}
+def measured_traffic(kernel: str, cid: int):
+    """HBM bytes per launch from hardware counters, as tabulated in profiles/hbm_traffic.md, or None
+    when there is no row for (kernel, configuration) or the kernel's source has changed since the
+    counters were taken."""
+    import hashlib
+    try:
+        rows = open(os.path.join(ROOT, "profiles", "hbm_traffic.md")).read().splitlines()
+    except OSError:
+        return None
+    for line in rows:
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) != 5 or cells[0] != kernel or cells[1] != str(cid):
+            continue
+        try:
+            digest = hashlib.sha256(open(os.path.join(ROOT, cells[3]), "rb").read()).hexdigest()[:16]
+        except OSError:
+            return None
+        return float(cells[2]) if digest == cells[4] else None
+    return None
 
 
 def cpu_baseline(cid: int, wl_rowptr, wl_colidx, budget_s: float = 15.0):
@@ -137,25 +152,28 @@ def main():
     for _ in range(args.warmup):
         wl.step()
     B.dbw_check(wl.h)
-    B.dbw_set_timing(wl.h, True)          # HIP events around every kernel, on the launch stream
+    # The timed region: K plain steps, nothing but the library's launches on the stream.
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         wl.step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    kern = B.dbw_get_timing(wl.h)
-    B.dbw_set_timing(wl.h, False)
     B.dbw_check(wl.h)
 
-    # The two event records per kernel in the timed region cost a launch-bound round up to half
-    # of its time; the same rounds once more without them, reported next to the timed figure.
+    # Per-kernel durations: the same K steps once more with HIP events recorded around every
+    # kernel on the launch stream.  Kept out of the timed region because two event records per
+    # kernel slow a launch-bound round down by up to half; reported next to the timed figure.
+    B.dbw_set_timing(wl.h, True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         wl.step()
     torch.cuda.synchronize()
-    plain_ms = (time.perf_counter() - t0) / args.steps * 1e3
+    events_ms = (time.perf_counter() - t0) / args.steps * 1e3
+    kern = B.dbw_get_timing(wl.h)
+    B.dbw_set_timing(wl.h, False)
+    B.dbw_check(wl.h)
 
     if args.copy_calibration:
         for _ in range(3):
@@ -235,7 +253,7 @@ def main():
         work = kernel_flops(cfg, dominant)
         roofline = {"bound": "mfma", "achieved": work / (dom_ms * 1e-3) / 1e12, "peak": MFMA_FP32_PEAK_TFLOPS,
                     "unit": "TFLOP/s", "traffic": None}
-    roofline["traffic"] = MEASURED_TRAFFIC.get((dominant, cfg.cid))
+    roofline["traffic"] = measured_traffic(dominant, cfg.cid)
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
     roofline["kernel"] = dominant
     roofline["kernel_ms"] = dom_ms
@@ -251,7 +269,7 @@ def main():
                    "mix_path": "dense" if mix_path == B.MIX_DENSE else "csr",
                    "gradients": "one fixed supplied matrix, reused every round" if cfg.model == "none" else "computed"},
         "roofline": roofline,
-        "ms_per_step_without_kernel_events": plain_ms,
+        "ms_per_step_with_kernel_events": events_ms,
         "hip_graph_ms_per_step": graph_ms,
         "consensus_tail": tail,
         "simulated_round_duration": {"dybw": dur["dybw"], "full_participation": dur["full"],
@@ -268,13 +286,15 @@ def main():
                        layout=B.LAYOUT_TILES if other == "tiles" else B.LAYOUT_ROWS)
         for _ in range(args.warmup):
             wl2.step()
-        B.dbw_set_timing(wl2.h, True)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(args.steps):
             wl2.step()
         torch.cuda.synchronize()
         el2 = time.perf_counter() - t0
+        B.dbw_set_timing(wl2.h, True)
+        for _ in range(args.steps):
+            wl2.step()
         k2 = B.dbw_get_timing(wl2.h)
         dom2 = max(k2, key=lambda k: k2[k][0])
         ms2 = k2[dom2][0] / k2[dom2][1]

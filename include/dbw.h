@@ -51,7 +51,12 @@ enum {
     DBW_ERR_STATE = -5,       /* dbw_round or dbw_get_selection before any dbw_select */
     DBW_ERR_ALLOC = -6,       /* device or host allocation failed */
     DBW_ERR_HIP = -7,         /* a HIP call failed */
-    DBW_ERR_UNSUPPORTED = -8  /* combination not implemented (e.g. dense mixing for N > 256) */
+    DBW_ERR_UNSUPPORTED = -8, /* combination not implemented (e.g. dense mixing for N > 256) */
+    /* Deferred warning (positive, reported by dbw_check / dbw_get_selection like the deferred
+     * errors, never by the call itself): dbw_dtur_b found no link of its set that can still be
+     * established in this round (a worker with an infinite response time on every unvisited
+     * link), so theta = +inf.  The backup counts it wrote are still the rule's. */
+    DBW_WARN_THETA_INF = 1
 };
 
 /* Order of averaging and local step inside one round. */
@@ -70,7 +75,13 @@ enum {
     DBW_MIX_AUTO = 0,  /* dense when it is supported and the graph holds more than N*N/4 links */
     DBW_MIX_CSR = 1,   /* gather over the selected neighbours only (HBM bound) */
     DBW_MIX_DENSE = 2  /* materialise P(k) as N x N and multiply on the matrix cores; needs N <= 256
-                        * and ld <= 26 843 545 (DBW_ERR_UNSUPPORTED from dbw_create otherwise) */
+                        * and ld <= 26 843 545 (DBW_ERR_UNSUPPORTED from dbw_create otherwise).
+                        * Every worker's row enters every product, backup workers with weight 0:
+                        * if a worker's parameters or gradients hold inf or NaN, every output row
+                        * becomes NaN (0 x inf), whereas the sparse path, which reads selected rows
+                        * only, keeps the rows that do not wait for that worker finite.  The same
+                        * holds for dbw_consensus_rounds.  Use DBW_MIX_CSR where diverged workers
+                        * must stay contained. */
 };
 
 /* How the N parameter vectors are laid out in a [N * ld] float array. */
@@ -89,20 +100,22 @@ enum {
 #define DBW_TILE_COLUMNS 64
 
 enum {
-    DBW_MODEL_NONE = 0, /* gradients are supplied by the caller (ext_grads) */
-    DBW_MODEL_MLP = 1,  /* fully connected dims[0] -> ... -> dims[n_layers], ReLU between
-                           layers, softmax cross-entropy; n_layers = 1 is multinomial
-                           logistic regression (the LRM of Section 5) */
-    DBW_MODEL_CNN = 2   /* conv KxK (C0->C1, same padding) ReLU maxpool2, conv KxK (C1->C2)
-                           ReLU maxpool2, flatten, FC F ReLU, FC classes, cross-entropy;
-                           dims = {C0, H, W, C1, C2, K, F, classes} */
+    DBW_MODEL_NONE = 0,    /* gradients are supplied by the caller (ext_grads) */
+    DBW_MODEL_SOFTMAX = 1, /* multinomial logistic regression dims[0] -> dims[1] (the LRM of
+                              Section 5): the fully connected model with one layer; n_layers is
+                              ignored */
+    DBW_MODEL_MLP = 2,     /* fully connected dims[0] -> ... -> dims[n_layers], ReLU between
+                              layers, softmax on top */
+    DBW_MODEL_CNN = 3      /* conv KxK (C0->C1, same padding) ReLU maxpool2, conv KxK (C1->C2)
+                              ReLU maxpool2, flatten, FC F ReLU, FC classes, cross-entropy;
+                              dims = {C0, H, W, C1, C2, K, F, classes} */
 };
 
 /* Loss on top of the model's outputs. */
 enum {
     DBW_LOSS_XENT = 0, /* softmax cross-entropy (Section 5) */
     DBW_LOSS_MSE = 1   /* squared error of the softmax outputs against the one-hot label, summed
-                          over classes (the 2NN of Appendix B); DBW_MODEL_MLP only */
+                          over classes (the 2NN of Appendix B); fully connected models only */
 };
 
 typedef struct {
@@ -151,7 +164,15 @@ int dbw_select(dbw_ctx *ctx, const float *resp_times, const int32_t *b, void *st
  * dbw_select.  The epoch state lives in the context (dbw_dtur_reset empties it).
  * resp_times [dev, N], b_out [dev, N], theta_out [dev, 1] or NULL.  Asynchronous. */
 int dbw_dtur_b(dbw_ctx *ctx, const float *resp_times, int32_t *b_out, float *theta_out, void *stream);
+/* Empty the visited set: the next dbw_dtur_b starts a fresh epoch.  Asynchronous on `stream`. */
 int dbw_dtur_reset(dbw_ctx *ctx, void *stream);
+/* The epoch state of the threshold rule, for checkpoint and resume (everything else a run needs
+ * to resume is caller-owned: parameters, round number).  visited [host, N-1] uint8: 1 for the
+ * links of the link set already visited in the current epoch; n_visited [host, 1] / value: their
+ * number (N - 1 with every link marked = the epoch is complete, the next call starts a new one).
+ * dbw_dtur_set_state checks that the two agree (DBW_ERR_INVALID).  Both synchronise the stream. */
+int dbw_dtur_get_state(dbw_ctx *ctx, uint8_t *visited, int32_t *n_visited, void *stream);
+int dbw_dtur_set_state(dbw_ctx *ctx, const uint8_t *visited, int32_t n_visited, void *stream);
 
 /* Copy out the last selection: p [dev, N] int32 (number of neighbours waited for),
  * mask [dev, nnz] uint8 aligned with colidx (1 = selected), wait_time [dev, N] float
@@ -168,8 +189,8 @@ int dbw_get_selection(dbw_ctx *ctx, int32_t *p, uint8_t *mask, float *wait_time,
  * Asynchronous on `stream`. */
 int dbw_round_time(dbw_ctx *ctx, float *T_out, void *stream);
 
-/* Copy out the dense consensus matrix P(k) [dev, N*N] float, row i = worker i's weights,
- * built from the last selection.  Synchronises the stream. */
+/* Write the dense consensus matrix P(k) [dev, N*N] float, row i = worker i's weights, built
+ * from the last selection.  Asynchronous on `stream`. */
 int dbw_get_weights(dbw_ctx *ctx, float *P, void *stream);
 
 /* One training round for all N workers (Algorithm 1, one pass of its loop body):
@@ -179,7 +200,8 @@ int dbw_get_weights(dbw_ctx *ctx, float *P, void *stream);
  *   params_in  [dev, N*ld]  read only
  *   params_out [dev, N*ld]  written in columns [0, d); must not overlap params_in
  *   batch_x    [dev, N*batch*in] float, batch_y [dev, N*batch] int32 labels in
- *              [0, classes): used iff the context has a model
+ *              [0, classes) (a label outside is clamped and reported by dbw_check as
+ *              DBW_ERR_INVALID): used iff the context has a model
  *   ext_grads  [dev, N*ld]: used iff the context has no model; NULL there means a
  *              gradient-free consensus round (the truncated model of Section 3.2.1)
  *   loss_out   [dev, N] float mean loss per worker, or NULL
@@ -245,8 +267,10 @@ int dbw_convert_layout(dbw_ctx *ctx, const float *src, float *dst, int32_t to_ti
 int dbw_grad(dbw_ctx *ctx, const float *params, const float *batch_x, const int32_t *batch_y,
              float *grads, float *loss_out, void *stream);
 
-/* Synchronise `stream` and return the deferred device-side status (DBW_OK or
- * DBW_ERR_INVALID), clearing it. */
+/* Synchronise `stream` and return the deferred device-side status, clearing it: DBW_OK,
+ * DBW_ERR_INVALID (a backup count outside [0, deg_i] in dbw_select / dbw_consensus_rounds, or a
+ * label outside [0, classes) in dbw_round / dbw_grad; both are clamped for memory safety and the
+ * round's results are then those of the clamped values), or DBW_WARN_THETA_INF. */
 int dbw_check(dbw_ctx *ctx, void *stream);
 
 /* Link set used by dbw_dtur_b: edges [host, 2*(N-1)] int32 as (u, v) pairs in link-id
@@ -261,31 +285,6 @@ int dbw_mix_path(const dbw_ctx *ctx);
 int dbw_destroy(dbw_ctx *ctx);
 
 const char *dbw_strerror(int code);
-
-/* Names and average durations (milliseconds, measured with HIP events on the launch
- * stream) of the kernels of the most recent dbw_round when timing was switched on with
- * dbw_set_timing(ctx, 1); used to report achieved bandwidth / FLOP rate per kernel.
- * dbw_get_timing synchronises, writes up to `cap` entries and returns the entry count. */
-typedef struct {
-    const char *name;
-    double ms_total;
-    int64_t launches;
-} dbw_kernel_time;
-int dbw_set_timing(dbw_ctx *ctx, int32_t on);
-int dbw_get_timing(dbw_ctx *ctx, dbw_kernel_time *out, int32_t cap);
-
-/* Achievable ceilings of the device the roofline figures are read against, measured with
- * plain kernels (the nominal peaks are 8 TB/s and 157.3 TFLOP/s fp32 matrix):
- *   DBW_CAL_HBM_TRIAD  a = b + s c over three freshly allocated device arrays of `size` bytes
- *                      each (a multiple of 16, at most 16 GiB), streaming loads and stores;
- *                      *result = 3 size / time in GB/s
- *   DBW_CAL_MFMA_FP32  every wave of a grid that fills the chip runs `size` (<= 2^24) iterations
- *                      of four independent 32x32x2 fp32 matrix instructions on register
- *                      operands; *result in TFLOP/s
- * Timed over `repeats` (1..1000) launches with HIP events on `stream`; result [host].
- * Allocates and frees its own device memory and synchronises; not part of a round. */
-enum { DBW_CAL_HBM_TRIAD = 0, DBW_CAL_MFMA_FP32 = 1 };
-int dbw_calibrate(int32_t what, int64_t size, int32_t repeats, double *result, void *stream);
 
 #ifdef __cplusplus
 }

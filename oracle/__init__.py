@@ -24,15 +24,26 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def build_sanitized(path: str) -> str:
+    """The same source with AddressSanitizer and UndefinedBehaviorSanitizer (host code only),
+    for the test that runs the pins over it."""
+    subprocess.check_call(["gcc", "-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+                           "-fno-sanitize-recover=undefined", "-fopenmp", "-shared", "-fPIC", "-Wall", "-o", path,
+                           _SRC, "-lm"])
+    return path
+
+
 _lib = None
 
 
 def lib():
     global _lib
     if _lib is None:
-        build()
         os.environ.setdefault("OMP_WAIT_POLICY", "passive")   # idle workers sleep instead of spinning
-        _lib = C.CDLL(_LIB)
+        override = os.environ.get("DBW_ORACLE_LIB")           # a build of the same source, e.g. with sanitizers
+        if not override:
+            build()
+        _lib = C.CDLL(override or _LIB)
         _lib.orc_select.restype = C.c_int
         _lib.orc_spanning_tree.restype = C.c_int
     return _lib

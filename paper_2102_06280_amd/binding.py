@@ -19,13 +19,15 @@ OK, ERR_NULL, ERR_INVALID, ERR_GRAPH, ERR_ALIAS, ERR_STATE, ERR_ALLOC, ERR_HIP, 
     0, -1, -2, -3, -4, -5, -6, -7, -8)
 ORDER_CTA, ORDER_ATC = 0, 1
 MIX_AUTO, MIX_CSR, MIX_DENSE = 0, 1, 2
-MODEL_NONE, MODEL_MLP, MODEL_CNN = 0, 1, 2
+MODEL_NONE, MODEL_SOFTMAX, MODEL_MLP, MODEL_CNN = 0, 1, 2, 3
+WARN_THETA_INF = 1
 LOSS_XENT, LOSS_MSE = 0, 1
 CAL_HBM_TRIAD, CAL_MFMA_FP32 = 0, 1
 LAYOUT_ROWS, LAYOUT_TILES = 0, 1
 TILE_COLUMNS = 64
 
-EXPORTS = ["dbw_create", "dbw_select", "dbw_dtur_b", "dbw_dtur_reset", "dbw_get_selection",
+EXPORTS = ["dbw_create", "dbw_select", "dbw_dtur_b", "dbw_dtur_reset", "dbw_dtur_get_state", "dbw_dtur_set_state",
+           "dbw_get_selection",
            "dbw_get_weights", "dbw_round_time", "dbw_round", "dbw_round_eta", "dbw_consensus_rounds",
            "dbw_consensus_rounds_static",
            "dbw_convert_layout", "dbw_grad", "dbw_check", "dbw_get_links", "dbw_mix_path",
@@ -57,6 +59,8 @@ _lib.dbw_create.argtypes = [C.POINTER(_vp), _i32, _i64, _vp, _vp, C.POINTER(dbw_
 _lib.dbw_select.argtypes = [_vp, _vp, _vp, _vp]
 _lib.dbw_dtur_b.argtypes = [_vp, _vp, _vp, _vp, _vp]
 _lib.dbw_dtur_reset.argtypes = [_vp, _vp]
+_lib.dbw_dtur_get_state.argtypes = [_vp, _vp, _vp, _vp]
+_lib.dbw_dtur_set_state.argtypes = [_vp, _vp, _i32, _vp]
 _lib.dbw_get_selection.argtypes = [_vp, _vp, _vp, _vp, _vp]
 _lib.dbw_get_weights.argtypes = [_vp, _vp, _vp]
 _lib.dbw_round_time.argtypes = [_vp, _vp, _vp]
@@ -108,7 +112,7 @@ def make_model(kind: int = MODEL_NONE, batch: int = 0, dims=(), loss: int = LOSS
     m = dbw_model()
     m.kind, m.batch, m.loss = kind, batch, loss
     dims = list(dims)
-    m.n_layers = len(dims) - 1 if kind == MODEL_MLP else 0
+    m.n_layers = len(dims) - 1 if kind in (MODEL_MLP, MODEL_SOFTMAX) else 0
     for k, v in enumerate(dims):
         m.dims[k] = int(v)
     return m
@@ -138,6 +142,20 @@ def dbw_dtur_b(h, resp_times, b_out, theta_out=None):
 
 def dbw_dtur_reset(h):
     return _chk(_lib.dbw_dtur_reset(h, _stream()), "dbw_dtur_reset")
+
+
+def dbw_dtur_get_state(h, N: int):
+    """-> (visited [N-1] uint8, n_visited) on the host."""
+    visited = np.zeros(max(N - 1, 1), dtype=np.uint8)
+    n = C.c_int32(0)
+    _chk(_lib.dbw_dtur_get_state(h, visited.ctypes.data, C.addressof(n), _stream()), "dbw_dtur_get_state")
+    return visited[:N - 1], int(n.value)
+
+
+def dbw_dtur_set_state(h, visited, n_visited: int):
+    visited = np.ascontiguousarray(visited, dtype=np.uint8)
+    keep = visited if visited.size else np.zeros(1, np.uint8)
+    return _chk(_lib.dbw_dtur_set_state(h, keep.ctypes.data, int(n_visited), _stream()), "dbw_dtur_set_state")
 
 
 def dbw_get_selection(h, p=None, mask=None, wait_time=None):

@@ -123,6 +123,10 @@ int fill_ctx(dbw_ctx *c, int32_t N, int64_t d, int64_t nnz64, const int32_t *row
         c->mix = opts->mix_path;
         c->layout = opts->layout;
         c->model = opts->model;
+        if (c->model.kind == DBW_MODEL_SOFTMAX) {       // multinomial logistic regression dims[0] -> dims[1]
+            c->model.kind = DBW_MODEL_MLP;
+            c->model.n_layers = 1;
+        }
     }
     if (c->ld < d || (c->order != DBW_ORDER_CTA && c->order != DBW_ORDER_ATC) || c->mix < DBW_MIX_AUTO ||
         c->mix > DBW_MIX_DENSE)
@@ -268,10 +272,33 @@ int dbw_dtur_b(dbw_ctx *c, const float *resp_times, int32_t *b_out, float *theta
 int dbw_dtur_reset(dbw_ctx *c, void *stream)
 {
     if (!c) return DBW_ERR_NULL;
-    // n_visited = number of links: the next dbw_dtur_b starts a fresh epoch
-    const int32_t full = c->N - 1;
-    DBW_HIP(hipMemcpyAsync(c->n_visited, &full, sizeof(int32_t), hipMemcpyHostToDevice, (hipStream_t)stream));
-    DBW_HIP(hipStreamSynchronize((hipStream_t)stream));
+    return dbw_launch_dtur_reset(c, (hipStream_t)stream);
+}
+
+int dbw_dtur_get_state(dbw_ctx *c, uint8_t *visited, int32_t *n_visited, void *stream)
+{
+    if (!c || !visited || !n_visited) return DBW_ERR_NULL;
+    hipStream_t s = (hipStream_t)stream;
+    if (c->N > 1) DBW_HIP(hipMemcpyAsync(visited, c->visited, (size_t)(c->N - 1), hipMemcpyDeviceToHost, s));
+    DBW_HIP(hipMemcpyAsync(n_visited, c->n_visited, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    DBW_HIP(hipStreamSynchronize(s));
+    return DBW_OK;
+}
+
+int dbw_dtur_set_state(dbw_ctx *c, const uint8_t *visited, int32_t n_visited, void *stream)
+{
+    if (!c || !visited) return DBW_ERR_NULL;
+    int count = 0;
+    for (int e = 0; e < c->N - 1; ++e) {
+        if (visited[e] > 1) return DBW_ERR_INVALID;
+        count += visited[e];
+    }
+    // n_visited = N - 1 with every link marked is the state after a completed epoch
+    if (n_visited != count) return DBW_ERR_INVALID;
+    hipStream_t s = (hipStream_t)stream;
+    if (c->N > 1) DBW_HIP(hipMemcpyAsync(c->visited, visited, (size_t)(c->N - 1), hipMemcpyHostToDevice, s));
+    DBW_HIP(hipMemcpyAsync(c->n_visited, &n_visited, sizeof(int32_t), hipMemcpyHostToDevice, s));
+    DBW_HIP(hipStreamSynchronize(s));
     return DBW_OK;
 }
 
@@ -307,28 +334,10 @@ int dbw_round_time(dbw_ctx *c, float *T_out, void *stream)
 }
 
 int dbw_get_weights(dbw_ctx *c, float *P, void *stream)
-try {
+{
     if (!c || !P) return DBW_ERR_NULL;
     if (!c->selected) return DBW_ERR_STATE;
-    hipStream_t s = (hipStream_t)stream;
-    const int N = c->N;
-    DBW_HIP(hipStreamSynchronize(s));
-    std::vector<int32_t> p(N), idx(std::max(c->nnz, 1));
-    std::vector<float> w(std::max(c->nnz, 1)), ws(N), dense((size_t)N * N, 0.0f);
-    DBW_HIP(hipMemcpy(p.data(), c->p, sizeof(int32_t) * (size_t)N, hipMemcpyDeviceToHost));
-    DBW_HIP(hipMemcpy(ws.data(), c->self_w, sizeof(float) * (size_t)N, hipMemcpyDeviceToHost));
-    if (c->nnz) {
-        DBW_HIP(hipMemcpy(idx.data(), c->sel_idx, sizeof(int32_t) * (size_t)c->nnz, hipMemcpyDeviceToHost));
-        DBW_HIP(hipMemcpy(w.data(), c->sel_w, sizeof(float) * (size_t)c->nnz, hipMemcpyDeviceToHost));
-    }
-    for (int i = 0; i < N; ++i) {
-        dense[(size_t)i * N + i] = ws[i];
-        for (int k = 0; k < p[i]; ++k) dense[(size_t)i * N + idx[c->h_rowptr[i] + k]] = w[c->h_rowptr[i] + k];
-    }
-    DBW_HIP(hipMemcpy(P, dense.data(), sizeof(float) * (size_t)N * N, hipMemcpyHostToDevice));
-    return DBW_OK;
-} catch (const std::bad_alloc &) {
-    return DBW_ERR_ALLOC;
+    return dbw_launch_dense_weights(c, P, (hipStream_t)stream);
 }
 
 int dbw_grad(dbw_ctx *c, const float *params, const float *batch_x, const int32_t *batch_y, float *grads,
@@ -429,6 +438,7 @@ const char *dbw_strerror(int code)
     case DBW_ERR_ALLOC: return "allocation failed";
     case DBW_ERR_HIP: return "HIP call failed";
     case DBW_ERR_UNSUPPORTED: return "combination not supported";
+    case DBW_WARN_THETA_INF: return "warning: threshold rule found no link that can be established (theta = +inf)";
     default: return "unknown error";
     }
 }

@@ -5,7 +5,7 @@
 
 #include <cstdint>
 
-#include "dbw.h"
+#include "dbw_measure.h"
 
 namespace {
 

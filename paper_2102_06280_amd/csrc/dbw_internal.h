@@ -8,6 +8,7 @@
 #include <vector>
 
 #include "dbw.h"
+#include "dbw_measure.h"
 
 #define DBW_HIP(call)                                   \
     do {                                                \
@@ -86,6 +87,8 @@ int dbw_validate_graph(int32_t N, const int32_t *rowptr, const int32_t *colidx);
 int dbw_launch_select(dbw_ctx *c, const float *t, const int32_t *b, hipStream_t s);
 int dbw_launch_round_time(dbw_ctx *c, float *out, hipStream_t s);
 int dbw_launch_dtur(dbw_ctx *c, const float *t, int32_t *b_out, float *theta_out, hipStream_t s);
+int dbw_launch_dtur_reset(dbw_ctx *c, hipStream_t s);
+int dbw_launch_dense_weights(dbw_ctx *c, float *P, hipStream_t s);
 // mix_csr.hip
 // Learning rate of a round as the mixing kernels see it: one value for all workers, or
 // eta_j per worker read from device memory (Section 2.1).

@@ -28,7 +28,7 @@ template <int LOSS>
 __global__ __launch_bounds__(256) void softmax_loss_kernel(
     int B, int C, const float *__restrict__ logits, int64_t stride_logits, const int32_t *__restrict__ y,
     float *__restrict__ dz, int64_t stride_dz, float *__restrict__ loss, float *__restrict__ loss_part,
-    uint32_t *__restrict__ ticket)
+    uint32_t *__restrict__ ticket, int32_t *__restrict__ err)
 {
     __shared__ float red[256];
     const int chunk = blockIdx.x, chunks = gridDim.x, w = blockIdx.y, tid = threadIdx.x;
@@ -42,7 +42,11 @@ __global__ __launch_bounds__(256) void softmax_loss_kernel(
         for (int c = 1; c < C; ++c) m = fmaxf(m, zs[c]);
         float sum = 0.f;
         for (int c = 0; c < C; ++c) sum += expf(zs[c] - m);
-        const int label = y[(int64_t)w * B + s];
+        int label = y[(int64_t)w * B + s];
+        if (label < 0 || label >= C) {                  // clamped for memory safety, reported by dbw_check
+            *err = DBW_ERR_INVALID;
+            label = label < 0 ? 0 : C - 1;
+        }
         const float inv = 1.0f / sum;
         if (LOSS == DBW_LOSS_XENT) {
             for (int c = 0; c < C; ++c)
@@ -272,10 +276,10 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
         dbw_timer tm(c, "softmax_loss_kernel", s);
         if (a.loss_kind == DBW_LOSS_MSE)
             hipLaunchKernelGGL(softmax_loss_kernel<DBW_LOSS_MSE>, grid, dim3(256), 0, s, B, dims[L], act + a_off[L], wstride,
-                               a.y, act + dz_off[L], wstride, a.loss, c->loss_part, c->loss_ticket);
+                               a.y, act + dz_off[L], wstride, a.loss, c->loss_part, c->loss_ticket, c->err);
         else
             hipLaunchKernelGGL(softmax_loss_kernel<DBW_LOSS_XENT>, grid, dim3(256), 0, s, B, dims[L], act + a_off[L], wstride,
-                               a.y, act + dz_off[L], wstride, a.loss, c->loss_part, c->loss_ticket);
+                               a.y, act + dz_off[L], wstride, a.loss, c->loss_part, c->loss_ticket, c->err);
         DBW_HIP(hipGetLastError());
     }
     // backward

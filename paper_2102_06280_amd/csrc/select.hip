@@ -168,7 +168,8 @@ __global__ __launch_bounds__(64 * WAVES) void select_kernel(
 __global__ __launch_bounds__(256) void dtur_kernel(
     int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx, int n_links,
     const int32_t *__restrict__ links, uint8_t *__restrict__ visited, int32_t *__restrict__ n_visited,
-    const float *__restrict__ t, int32_t *__restrict__ b_out, float *__restrict__ theta_out)
+    const float *__restrict__ t, int32_t *__restrict__ b_out, float *__restrict__ theta_out,
+    int32_t *__restrict__ err)
 {
     __shared__ uint64_t red[256];
     const int tid = threadIdx.x;
@@ -201,6 +202,9 @@ __global__ __launch_bounds__(256) void dtur_kernel(
         if (chosen >= 0) visited[chosen] = 1;
         *n_visited = (fresh ? 0 : *n_visited) + (chosen >= 0 ? 1 : 0);
         if (theta_out) *theta_out = theta;
+        // no link of the set can be established (a dead worker on every unvisited link): every
+        // worker keeps to itself this round.  Recorded as a warning unless an error is pending.
+        if (n_links > 0 && theta == __builtin_inff() && *err == 0) *err = DBW_WARN_THETA_INF;
     }
     for (int j = tid; j < N; j += 256) {
         const int beg = rowptr[j], end = rowptr[j + 1];
@@ -212,6 +216,23 @@ __global__ __launch_bounds__(256) void dtur_kernel(
         }
         b_out[j] = bj;
     }
+}
+
+// The next call of the threshold rule starts a fresh epoch.
+__global__ void dtur_reset_kernel(int n_links, int32_t *__restrict__ n_visited) { *n_visited = n_links; }
+
+// Dense consensus matrix P(k), row-major N x N, from the compacted selection.  grid = N.
+__global__ __launch_bounds__(256) void dense_weights_kernel(int N, const int32_t *__restrict__ rowptr,
+                                                            const int32_t *__restrict__ p,
+                                                            const int32_t *__restrict__ sel_idx,
+                                                            const float *__restrict__ sel_w,
+                                                            const float *__restrict__ self_w, float *__restrict__ P)
+{
+    const int i = blockIdx.x, beg = rowptr[i], cnt = p[i];
+    float *row = P + (size_t)i * N;
+    for (int c = threadIdx.x; c < N; c += 256) row[c] = c == i ? self_w[i] : 0.0f;
+    __syncthreads();
+    for (int k = threadIdx.x; k < cnt; k += 256) row[sel_idx[beg + k]] = sel_w[beg + k];
 }
 
 // Round duration (Section 3.2.2): max of the wait times over all workers and over the
@@ -291,7 +312,22 @@ int dbw_launch_dtur(dbw_ctx *c, const float *t, int32_t *b_out, float *theta_out
 {
     dbw_timer tm(c, "dtur_kernel", s);
     hipLaunchKernelGGL(dtur_kernel, dim3(1), dim3(256), 0, s, c->N, c->rowptr, c->colidx, c->N - 1, c->links,
-                       c->visited, c->n_visited, t, b_out, theta_out);
+                       c->visited, c->n_visited, t, b_out, theta_out, c->err);
+    DBW_HIP(hipGetLastError());
+    return DBW_OK;
+}
+
+int dbw_launch_dtur_reset(dbw_ctx *c, hipStream_t s)
+{
+    hipLaunchKernelGGL(dtur_reset_kernel, dim3(1), dim3(1), 0, s, c->N - 1, c->n_visited);
+    DBW_HIP(hipGetLastError());
+    return DBW_OK;
+}
+
+int dbw_launch_dense_weights(dbw_ctx *c, float *P, hipStream_t s)
+{
+    hipLaunchKernelGGL(dense_weights_kernel, dim3(c->N), dim3(256), 0, s, c->N, c->rowptr, c->p, c->sel_idx, c->sel_w,
+                       c->self_w, P);
     DBW_HIP(hipGetLastError());
     return DBW_OK;
 }

@@ -111,3 +111,118 @@ def test_dense_path_limits(B):
     rowptr, colidx = inputs.graph_complete(300)
     with pytest.raises(RuntimeError, match="not supported"):
         B.dbw_create(rowptr, colidx, 300, 64, mix_path=B.MIX_DENSE)
+
+
+def test_label_out_of_range_is_clamped_and_reported(B, orc):
+    """A label outside [0, classes) cannot index outside the logits: it is clamped, the round's
+    result is that of the clamped label, and dbw_check reports DBW_ERR_INVALID."""
+    dims, batch, n = [20, 6], 5, 3
+    g = np.random.default_rng(711)
+    desc = {"kind": "mlp", "dims": dims}
+    d = inputs.param_count(desc)
+    ld = inputs.pad_ld(d)
+    rowptr, colidx = inputs.graph_ring(n)
+    params = inputs.init_params(desc, n, ld, g)
+    x = g.standard_normal((n, batch, dims[0])).astype(np.float32)
+    y = g.integers(0, dims[-1], (n, batch)).astype(np.int32)
+    bad = y.copy()
+    bad[1, 2], bad[2, 0] = 6 + 1000, -5
+    clamped = bad.clip(0, dims[-1] - 1)
+    for model_kind in (B.MODEL_MLP, B.MODEL_SOFTMAX):       # the one-layer model under both of its names
+        h = B.dbw_create(rowptr, colidx, n, d, ld=ld, model=B.make_model(model_kind, batch, dims))
+        try:
+            grads = torch.zeros((n, ld), device="cuda")
+            loss = torch.zeros(n, device="cuda")
+            B.dbw_grad(h, dev(params), dev(x), dev(bad), grads, loss)
+            with pytest.raises(B.DbwError) as e:
+                B.dbw_check(h)
+            assert e.value.code == B.ERR_INVALID
+            assert B.dbw_check(h) == B.OK                   # cleared by the report
+            kind, od = orc.model_desc(desc)
+            want, wl = orc.grad_all(kind, od, d, params, x, clamped)
+            assert np.allclose(loss.cpu().numpy(), wl, rtol=1e-5)
+            got = grads.cpu().numpy()
+            assert np.allclose(got[:, :d], want[:, :d], rtol=1e-4, atol=1e-7)
+            B.dbw_grad(h, dev(params), dev(x), dev(y), grads, loss)
+            assert B.dbw_check(h) == B.OK
+        finally:
+            B.dbw_destroy(h)
+
+
+def test_threshold_rule_state_round_trip_and_warning(B, orc):
+    """The epoch state of the threshold rule can be taken out and put back (checkpoint / resume);
+    dbw_dtur_reset needs no synchronisation to take effect in stream order; a round in which no
+    unvisited link can be established leaves the theta = +inf warning."""
+    rowptr, colidx = inputs.graph_er(12, 0.3, np.random.default_rng(713))
+    n = 12
+    g = np.random.default_rng(715)
+    ts = g.standard_exponential((9, n)).astype(np.float32)
+    h1 = B.dbw_create(rowptr, colidx, n, 8)
+    h2 = B.dbw_create(rowptr, colidx, n, 8)
+    try:
+        b1 = torch.zeros(n, dtype=torch.int32, device="cuda")
+        b2 = torch.zeros(n, dtype=torch.int32, device="cuda")
+        dt = orc.Dtur(rowptr, colidx)
+        for k in range(5):
+            B.dbw_dtur_b(h1, dev(ts[k]), b1)
+            dt.step(ts[k])
+        visited, nv = B.dbw_dtur_get_state(h1, n)
+        assert nv == 5 and visited.sum() == 5 and np.array_equal(visited, dt.visited[:n - 1])
+        B.dbw_dtur_set_state(h2, visited, nv)               # a fresh context resumes the epoch
+        for k in range(5, 9):
+            B.dbw_dtur_b(h1, dev(ts[k]), b1)
+            B.dbw_dtur_b(h2, dev(ts[k]), b2)
+            assert torch.equal(b1, b2), k
+            assert np.array_equal(b1.cpu().numpy(), dt.step(ts[k])[0]), k
+        with pytest.raises(B.DbwError) as e:
+            B.dbw_dtur_set_state(h2, visited, nv + 1)
+        assert e.value.code == B.ERR_INVALID
+        # reset queued on the stream right before the next step, no synchronisation in between
+        B.dbw_dtur_reset(h1)
+        B.dbw_dtur_b(h1, dev(ts[0]), b1)
+        assert np.array_equal(b1.cpu().numpy(), orc.Dtur(rowptr, colidx).step(ts[0])[0])
+        assert B.dbw_check(h1) == B.OK
+        # every worker dead: no link can be established
+        th = torch.zeros(1, device="cuda")
+        B.dbw_dtur_b(h1, dev(np.full(n, np.inf, np.float32)), b1, th)
+        assert B.dbw_check(h1) == B.WARN_THETA_INF and np.isinf(th.item())
+        assert "theta" in B.dbw_strerror(B.WARN_THETA_INF)
+        assert B.dbw_check(h1) == B.OK
+    finally:
+        B.dbw_destroy(h1)
+        B.dbw_destroy(h2)
+
+
+def test_non_finite_row_of_a_backup_worker(B, orc):
+    """A worker whose parameters hold inf and that nobody waits for: the sparse path never reads
+    its row for the others, so every other row stays finite and equals the oracle; the dense
+    path multiplies the row by its zero weights and turns every row into NaN (documented)."""
+    rowptr, colidx = inputs.graph_complete(40)
+    n, d = 40, 256
+    g = np.random.default_rng(717)
+    x = g.standard_normal((n, d)).astype(np.float32)
+    gr = (g.standard_normal((n, d)) * 0.01).astype(np.float32)
+    x[7, 13] = np.inf
+    t = g.standard_exponential(n).astype(np.float32)
+    t[7] = 1e9                                             # the diverged worker is also the slowest
+    b = np.full(n, 5, np.int32)                            # everybody drops its 5 slowest neighbours
+    mask, p, _ = orc.select(rowptr, colidx, t, b)
+    assert not any(mask[e] for i in range(n) for e in range(rowptr[i], rowptr[i + 1]) if colidx[e] == 7)
+    want = orc.round_(rowptr, colidx, mask, p, x, gr, 0.05, 0)
+    others = np.arange(n) != 7
+    for mix, finite in ((B.MIX_CSR, True), (B.MIX_DENSE, False)):
+        h = B.dbw_create(rowptr, colidx, n, d, mix_path=mix)
+        try:
+            out = torch.zeros((n, d), device="cuda")
+            B.dbw_select(h, dev(t), dev(b))
+            B.dbw_round(h, dev(x), out, 0.05, ext_grads=dev(gr))
+            got = out.cpu().numpy()
+            if finite:
+                assert np.isfinite(got[others]).all()
+                assert_params_close(got[others], want[others], what="sparse path, rows that do not wait for the diverged worker")
+                assert np.isinf(got[7, 13])
+            else:
+                assert np.isnan(got[others][:, 13]).all()   # 0 x inf in column 13 of every row
+                assert np.isfinite(np.delete(got[others], 13, axis=1)).all()
+        finally:
+            B.dbw_destroy(h)

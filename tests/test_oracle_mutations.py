@@ -20,7 +20,8 @@ SRC = open(os.path.join(os.path.dirname(oracle.__file__), "dbw_oracle.c")).read(
 # pins cheap enough to re-run for every mutant (the full-shape autograd comparisons stay out)
 FAST_PINS = {
     "select": [T_sel.test_selection_brute_force, T_sel.test_selection_degenerate, T_sel.test_selection_special_values,
-               T_sel.test_round_time_not_longer_than_full, T_sel.test_worked_example, T_sel.test_round_time],
+               T_sel.test_round_time_not_longer_than_full, T_sel.test_worked_example, T_sel.test_round_time,
+               T_sel.test_round_time_worked_example],
     "weights": [T_sel.test_weight_invariants, T_sel.test_weights_symmetric_mask_doubly_stochastic,
                 T_sel.test_weights_closed_forms, T_sel.test_worked_example],
     "round": [T_round.test_b0_is_full_participation, T_round.test_closed_forms_regular_and_complete,

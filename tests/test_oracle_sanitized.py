@@ -1,0 +1,30 @@
+"""The oracle's pins once more over a build of the same source with AddressSanitizer and
+UndefinedBehaviorSanitizer (host code only, no GPU): an out-of-bounds access, a use after free or
+undefined arithmetic anywhere on the paths the pins walk aborts the child process."""
+import os
+import subprocess
+import sys
+
+import oracle
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+PIN_FILES = ["test_oracle_select_weights.py", "test_oracle_round.py", "test_oracle_dtur.py", "test_oracle_grad.py",
+             "test_flip_matching.py", "test_inputs.py"]
+
+
+def test_pins_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    lib = oracle.build_sanitized(str(tmp_path / "liboracle_san.so"))
+    asan = subprocess.run(["gcc", "-print-file-name=libasan.so"], check=True, capture_output=True, text=True).stdout.strip()
+    env = dict(os.environ)
+    env["DBW_ORACLE_LIB"] = lib
+    # the interpreter is not instrumented, so the sanitizer runtime has to come first in the process;
+    # whatever is already preloaded stays, after it
+    env["LD_PRELOAD"] = ":".join(p for p in (asan, env.get("LD_PRELOAD", "")) if p)
+    env["ASAN_OPTIONS"] = "detect_leaks=0:abort_on_error=1:verify_asan_link_order=0"
+    env["UBSAN_OPTIONS"] = "print_stacktrace=1:halt_on_error=1"
+    cmd = [sys.executable, "-m", "pytest", "-x", "-q", "-m", "not gpu", "-p", "no:cacheprovider",
+           "-k", "not full_shape"] + [os.path.join(ROOT, "tests", f) for f in PIN_FILES]
+    r = subprocess.run(cmd, cwd=ROOT, env=env, capture_output=True, text=True, timeout=900)
+    tail = (r.stdout + r.stderr)[-3000:]
+    assert r.returncode == 0, tail
+    assert "passed" in r.stdout and "liboracle_san" not in r.stderr, tail

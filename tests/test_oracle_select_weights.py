@@ -7,6 +7,8 @@ Assumption 1, degenerate cases of Section 2.2, and a hand-worked example.
 import itertools
 from fractions import Fraction
 
+import os
+
 import numpy as np
 import pytest
 
@@ -233,3 +235,26 @@ def test_round_time(orc):
             m0, _, w0 = orc.select(rowptr, colidx, t, np.zeros(n, np.int32))
             f_all, f_sel = orc.round_time(rowptr, colidx, m0, w0)
             assert t_all <= f_all and f_all == t.max() == f_sel
+
+
+def test_round_time_worked_example(orc):
+    """Hand-worked round duration (tests/golden/worked_example_round_time.txt): the worker with the
+    largest wait time is waited for by nobody, so the maximum over the set V' of Section 3.2.2 is
+    smaller than the maximum over all workers."""
+    vals = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", "worked_example_round_time.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                k, *v = line.split()
+                vals[k] = v
+    rowptr, colidx = np.array(vals["rowptr"], np.int32), np.array(vals["colidx"], np.int32)
+    t, b = np.array(vals["t"], np.float32), np.array(vals["b"], np.int32)
+    mask, p, wait = orc.select(rowptr, colidx, t, b)
+    assert np.array_equal(mask, np.array(vals["mask"], np.uint8))
+    assert np.array_equal(p, np.array(vals["p"], np.int32))
+    assert np.array_equal(wait, np.array(vals["wait"], np.float32))
+    t_all, t_listed = orc.round_time(rowptr, colidx, mask, wait)
+    assert t_all == np.float32(vals["T_all_workers"][0]) and t_listed == np.float32(vals["T_over_listed"][0])
+    m0, _, w0 = orc.select(rowptr, colidx, t, np.zeros(4, np.int32))
+    f_all, f_listed = orc.round_time(rowptr, colidx, m0, w0)
+    assert f_all == np.float32(vals["full_T_all_workers"][0]) and f_listed == np.float32(vals["full_T_over_listed"][0])
