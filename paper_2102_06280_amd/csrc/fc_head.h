@@ -1,0 +1,296 @@
+// The classifier head of a model in one launch: last fully connected layer (H -> C, C <= 16),
+// softmax, loss, and everything of the backward pass that hangs on it (Section 2.1, stochastic
+// gradient of the local loss; cross-entropy as in Section 5, squared error of the softmax outputs
+// as for the 2NN of Appendix B):
+//   z = a W^T + b,  p = softmax(z),  loss,  dz = dloss/dz / B
+//   dW = dz^T a,  db = column sums of dz
+//   da = dz W, masked by a > 0 when a is the output of a ReLU layer (then also its column sums, the
+//        bias gradient of the layer below), unmasked when a is the model's input
+// As separate launches these thin products cost five to eight kernels of 4-13 us each, mostly
+// latency.  Here one workgroup takes S = 16, 32 or 64 samples of one worker, keeps them and W in LDS
+// and runs the three products on the matrix cores with the class dimension padded to the 16
+// columns of v_mfma_f32_16x16x4_f32 (true fp32):
+//   A fragment: lane l holds A[m = l % 16][k = l / 16], B fragment: B[k = l / 16][n = l % 16],
+//   D: d[v] = D[m = 4 * (l / 16) + v][n = l % 16].
+//
+// grid = (chunks, workers).  With one chunk per worker (batches up to 64) the sums over the batch
+// (dW, db, the bias gradient below, the loss) are final.  Otherwise they are written as per-chunk
+// partials and added in chunk order by reduce_kernel, a second launch: a "last workgroup to arrive
+// adds them" scheme inside one launch was measured and rejected, because the memory fence every
+// workgroup needs before it takes its ticket writes back its XCD's whole L2 (46 us for 384
+// workgroups against 6 us of arithmetic).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dbw.h"
+
+namespace fchead {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int THREADS = 512, WAVES = THREADS / 64;
+constexpr int MAX_C = 16;            // classes, padded to 16
+constexpr int MAX_S = 64;            // samples per workgroup: 16, 32 or 64
+constexpr int MAX_CHUNKS = 256;
+constexpr size_t LDS_LIMIT = 159 * 1024;     // dynamic part; the kernel also has a few bytes of static LDS
+
+struct Args {
+    int B, H, C, S;                  // batch, inputs, classes, samples per chunk (16, 32 or 64)
+    const float *a;                  // [B][a_ld] per worker (stride a_stride): the head's input
+    int64_t a_ld, a_stride;
+    const float *params;             // worker rows of stride p_stride; W [C][H] at w_off, bias [C] at b_off
+    float *grads;                    // same offsets and stride: receives dW and db
+    int64_t p_stride, w_off, b_off;
+    const int32_t *y;                // [workers][B]
+    float *da;                       // [B][da_ld] per worker, or nullptr
+    int64_t da_ld, da_stride;
+    int mask;                        // 1: da is kept only where a > 0
+    int64_t bprev_off;               // >= 0: column sums of da go to grads at this offset
+    float *loss;                     // [workers] or nullptr
+    float *part;                     // [workers][part_stride] scratch for the per-chunk partial sums
+    int64_t part_stride;
+    int32_t *err;                    // deferred status word
+};
+
+// Row pitch of the LDS images of a and W: H rounded up to 4 (the k-step of the matrix instruction;
+// the extra columns are zero), made an odd multiple of 4 so that the 16 rows x 4 columns a fragment
+// read touches fall into 64 different banks.
+__host__ __device__ inline int row_pitch(int H)
+{
+    const int h4 = (H + 3) / 4 * 4;
+    return (h4 / 4) % 2 ? h4 : h4 + 4;
+}
+__host__ __device__ inline size_t lds_floats(int H, int C, int S)
+{
+    // dz / logits [64][16], partial logits [8 waves][16][16], W image [C + 1][pitch] (the last row is zero and
+    // stands for the padding classes), a image [S][pitch], 16 floats of slack behind each image (fragment
+    // reads of the last, partly filled 16-column block run past the row)
+    return (size_t)MAX_S * MAX_C + (size_t)WAVES * 16 * 16 + (size_t)(C + 1 + S) * row_pitch(H) + 32;
+}
+__host__ __device__ inline size_t lds_bytes(int H, int C, int S) { return sizeof(float) * lds_floats(H, C, S); }
+__host__ __device__ inline int64_t partial_floats(int H, int C, bool bprev) { return (int64_t)C * H + C + (bprev ? H : 0) + 1; }
+
+// VEC: the input rows start on 16-byte boundaries and H divides by 4 (128-bit staging loads).
+template <int LOSS, bool VEC>
+__global__ __launch_bounds__(THREADS) void kernel(Args g)
+{
+    extern __shared__ __attribute__((aligned(16))) float sm[];
+    const int H = g.H, C = g.C, S = g.S, HP = row_pitch(H);
+    float *zl = sm;                                  // [64][16]: logits, then dz
+    float *zp = zl + MAX_S * MAX_C;                  // [8][16][16]: partial logits of the wavefronts
+    float *Wl = zp + WAVES * 16 * 16;                // [C + 1][HP]: row C and the columns >= H are zero
+    float *al = Wl + (C + 1) * HP + 16;              // [S][HP], rows >= ns and columns >= H zero
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, lq = lane >> 4;
+    const int chunk = blockIdx.x, chunks = gridDim.x, w = blockIdx.y;
+    const int s0 = chunk * S, ns = min(S, g.B - s0);
+    const float *__restrict__ a = g.a + w * g.a_stride + (int64_t)s0 * g.a_ld;
+    const float *__restrict__ Wg = g.params + w * g.p_stride + g.w_off;
+    const float *__restrict__ bg = g.params + w * g.p_stride + g.b_off;
+
+    // ---- stage W and this chunk of a; everything the fragments may touch beyond them is zero
+    {
+        const int total = (C + 1) * HP + 16;
+        for (int e0 = 0; e0 < total; e0 += 8 * THREADS) {       // eight loads in flight per thread
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int e = e0 + tid + u * THREADS, r = e / HP, k = e - r * HP;
+                v[u] = (e < total && r < C && k < H) ? Wg[r * H + k] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int e = e0 + tid + u * THREADS;
+                if (e < total) Wl[e] = v[u];
+            }
+        }
+    }
+    if (VEC) {
+        const int q4 = HP / 4, total = S * q4;
+        for (int e0 = 0; e0 < total; e0 += 8 * THREADS) {
+            float4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int e = e0 + tid + u * THREADS, r = e / q4, k = 4 * (e - r * q4);
+                v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (e < total && r < ns && k < H) v[u] = *(const float4 *)(a + (int64_t)r * g.a_ld + k);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int e = e0 + tid + u * THREADS;
+                if (e < total) *(float4 *)(al + 4 * e) = v[u];
+            }
+        }
+    } else {
+        const int total = S * HP;
+        for (int e0 = 0; e0 < total; e0 += 8 * THREADS) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int e = e0 + tid + u * THREADS, r = e / HP, k = e - r * HP;
+                v[u] = (e < total && r < ns && k < H) ? a[(int64_t)r * g.a_ld + k] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int e = e0 + tid + u * THREADS;
+                if (e < total) al[e] = v[u];
+            }
+        }
+    }
+    if (tid < 16) al[S * HP + tid] = 0.f;
+    __syncthreads();
+
+    // ---- logits z = a W^T: wavefront = (16-sample block, slice of k); partial sums meet in LDS
+    {
+        const int MB = S / 16, KS = WAVES / MB;
+        const int mb = wave % MB, ks = wave / MB;
+        const int quads = HP / 4, per = (quads + KS - 1) / KS;
+        const int q_end = min(quads, (ks + 1) * per);
+        const float *ap = al + (16 * mb + l16) * HP + lq, *wp = Wl + min(l16, C) * HP + lq;
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        for (int q = ks * per; q < q_end; ++q)
+            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ap[4 * q], wp[4 * q], acc, 0, 0, 0);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) zp[(wave * 16 + 4 * lq + v) * 16 + l16] = acc[v];
+        __syncthreads();
+        // sample s, class c: the slices in order, then the bias
+        for (int e = tid; e < S * 16; e += THREADS) {
+            const int s = e >> 4, c = e & 15;
+            float z = 0.f;
+            for (int q = 0; q < KS; ++q) z += zp[((q * MB + (s >> 4)) * 16 + (s & 15)) * 16 + c];
+            zl[e] = c < C ? z + bg[c] : 0.f;
+        }
+    }
+    __syncthreads();
+
+    // ---- softmax, loss and dz per sample (rows of samples beyond the batch stay zero)
+    float loss_part = 0.f;
+    if (tid < MAX_S) {
+        float *zs = zl + tid * MAX_C;
+        if (tid < ns) {
+            float m = zs[0];
+            for (int c = 1; c < C; ++c) m = fmaxf(m, zs[c]);
+            float sum = 0.f;
+            for (int c = 0; c < C; ++c) sum += expf(zs[c] - m);
+            int label = g.y[(int64_t)w * g.B + s0 + tid];
+            if (label < 0 || label >= C) {              // clamped for memory safety, reported by dbw_check
+                *g.err = DBW_ERR_INVALID;
+                label = label < 0 ? 0 : C - 1;
+            }
+            const float inv = 1.0f / sum, inv_b = 1.0f / (float)g.B;
+            if (LOSS == DBW_LOSS_XENT) {
+                loss_part = logf(sum) + m - zs[label];
+                for (int c = 0; c < C; ++c) zs[c] = (expf(zs[c] - m) * inv - (c == label ? 1.f : 0.f)) * inv_b;
+            } else {
+                float f = 0.f, inner = 0.f;
+                for (int c = 0; c < C; ++c) {
+                    const float p = expf(zs[c] - m) * inv, e = p - (c == label ? 1.f : 0.f);
+                    f += e * e;
+                    inner += p * e;
+                }
+                for (int c = 0; c < C; ++c) {
+                    const float p = expf(zs[c] - m) * inv, e = p - (c == label ? 1.f : 0.f);
+                    zs[c] = 2.f * p * (e - inner) * inv_b;
+                }
+                loss_part = f;
+            }
+        } else {
+            for (int c = 0; c < MAX_C; ++c) zs[c] = 0.f;
+        }
+    }
+    __syncthreads();
+
+    float *__restrict__ part = g.part + w * g.part_stride + (int64_t)chunk * partial_floats(H, C, g.bprev_off >= 0);
+    float *__restrict__ out_w = chunks == 1 ? g.grads + w * g.p_stride + g.w_off : part;
+    float *__restrict__ out_b = chunks == 1 ? g.grads + w * g.p_stride + g.b_off : part + (size_t)C * H;
+    float *__restrict__ out_bprev = g.bprev_off < 0 ? nullptr
+                                    : (chunks == 1 ? g.grads + w * g.p_stride + g.bprev_off : part + (size_t)C * H + C);
+    float *__restrict__ da = g.da ? g.da + w * g.da_stride + (int64_t)s0 * g.da_ld : nullptr;
+    const int NB = (H + 15) / 16;                       // 16-column blocks of the input dimension
+
+    for (int nb = wave; nb < NB; nb += WAVES) {
+        const int col = 16 * nb + l16;
+        // ---- dW[class][col] = sum over samples of dz[sample][class] a[sample][col]
+        {
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+            for (int k0 = 0; k0 < S; k0 += 4)
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(zl[(k0 + lq) * MAX_C + l16], al[(k0 + lq) * HP + col], acc,
+                                                           0, 0, 0);
+            if (col < H) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (4 * lq + v < C) out_w[(4 * lq + v) * H + col] = acc[v];
+            }
+        }
+        // ---- da[sample][col] = sum over classes of dz[sample][class] W[class][col], masked; its column sums
+        if (da) {
+            float colsum = 0.f;
+            for (int mb = 0; mb < S / 16; ++mb) {
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(zl[(16 * mb + l16) * MAX_C + 4 * j + lq],
+                                                               Wl[min(4 * j + lq, C) * HP + col], acc, 0, 0, 0);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int s = 16 * mb + 4 * lq + v;
+                    float d = acc[v];
+                    if (g.mask && !(al[s * HP + col] > 0.f)) d = 0.f;
+                    if (s < ns && col < H) da[(int64_t)s * g.da_ld + col] = d;
+                    colsum += d;                        // rows beyond the batch have dz = 0
+                }
+            }
+            colsum += __shfl_xor(colsum, 16, 64);
+            colsum += __shfl_xor(colsum, 32, 64);
+            if (out_bprev && lq == 0 && col < H) out_bprev[col] = colsum;
+        }
+    }
+    if (tid < C) {
+        float sum = 0.f;
+        for (int s = 0; s < ns; ++s) sum += zl[s * MAX_C + tid];
+        out_b[tid] = sum;
+    }
+    // ---- the chunk's loss: its samples in a fixed order (tree in LDS)
+    if (g.loss) {
+        float *red = zp;
+        if (tid < MAX_S) red[tid] = loss_part;
+        __syncthreads();
+        for (int o = MAX_S / 2; o > 0; o >>= 1) {
+            if (tid < o) red[tid] += red[tid + o];
+            __syncthreads();
+        }
+        if (tid == 0) {
+            if (chunks == 1) g.loss[w] = red[0] / (float)g.B;
+            else part[partial_floats(H, C, g.bprev_off >= 0) - 1] = red[0];
+        }
+    }
+}
+
+// Sum of the per-chunk partials in chunk order -> dW, db, the bias gradient below, the loss.
+// grid = (ceil(E / 256), workers), E = partial_floats.
+__global__ __launch_bounds__(256) void reduce_kernel(Args g, int chunks)
+{
+    const int w = blockIdx.y, H = g.H, C = g.C;
+    const int n_w = C * H, n_b = C, n_p = g.bprev_off >= 0 ? H : 0;
+    const int64_t E = partial_floats(H, C, g.bprev_off >= 0);
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    if (e >= E || (e == E - 1 && !g.loss)) return;
+    const float *__restrict__ all = g.part + w * g.part_stride;
+    float *__restrict__ gw = g.grads + w * g.p_stride;
+    float sum = 0.f;
+    for (int q0 = 0; q0 < chunks; q0 += 16) {           // sixteen loads in flight, added in chunk order
+        float v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) v[u] = q0 + u < chunks ? all[(int64_t)(q0 + u) * E + e] : 0.f;
+#pragma unroll
+        for (int u = 0; u < 16; ++u) sum += v[u];
+    }
+    if (e < n_w) gw[g.w_off + e] = sum;
+    else if (e < n_w + n_b) gw[g.b_off + (e - n_w)] = sum;
+    else if (e < n_w + n_b + n_p) gw[g.bprev_off + (e - n_w - n_b)] = sum;
+    else g.loss[w] = sum / (float)g.B;
+}
+
+}  // namespace fchead

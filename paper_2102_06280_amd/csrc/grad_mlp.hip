@@ -10,6 +10,7 @@
 
 #include "bgemm.h"
 #include "fc_batch32.h"
+#include "fc_head.h"
 #include "dbw_internal.h"
 
 namespace {
@@ -170,6 +171,33 @@ bool batch32_layer(int B, int in, int out, int64_t ld_params, int64_t w_off, con
            fc32::aligned16(params) && fc32::aligned16(grads);
 }
 
+// The fused classifier head (fc_head.h) takes the last layer when it is narrow enough.
+struct HeadPlan {
+    bool use;
+    int chunks, S;
+    int64_t part;          // floats of partial sums per worker
+};
+HeadPlan head_plan(int L, const int32_t *dims, int B, int workers)
+{
+    const int H = dims[L - 1], C = dims[L];
+    HeadPlan hp{false, 0, 0, 0};
+    if (C > fchead::MAX_C || fchead::lds_bytes(H, C, 16) > fchead::LDS_LIMIT) return hp;
+    auto fits = [&](int S) { return fchead::lds_bytes(H, C, S) <= fchead::LDS_LIMIT; };
+    int S;
+    const int whole = B <= 16 ? 16 : (B <= 32 ? 32 : 64);
+    if (B <= 64 && fits(whole))
+        S = whole;                                   // one chunk per worker: no partial sums at all
+    else                                             // 32 samples per workgroup when that still fills the chip, else 16
+        S = (fits(32) && (int64_t)((B + 31) / 32) * workers >= 256) ? 32 : 16;
+    const int chunks = (B + S - 1) / S;
+    if (chunks > fchead::MAX_CHUNKS) return hp;
+    hp.use = true;
+    hp.chunks = chunks;
+    hp.S = S;
+    hp.part = chunks > 1 ? (int64_t)chunks * fchead::partial_floats(H, C, L > 1) : 0;
+    return hp;
+}
+
 int64_t act_floats(int L, const int32_t *dims, int B)
 {
     int64_t n = 0;
@@ -183,7 +211,9 @@ int64_t dbw_fc_scratch_per_worker(int L, const int32_t *dims, int B)
 {
     int64_t part = 0;
     for (int l = 1; l <= L; ++l) part = std::max<int64_t>(part, (int64_t)MAX_SPLITS * B * dims[l]);
-    return 2 * act_floats(L, dims, B) + part;
+    if (dims[L] <= fchead::MAX_C)      // partial sums of the fused head, at its smaller chunk size
+        part = std::max(part, (int64_t)((B + 15) / 16) * fchead::partial_floats(dims[L - 1], dims[L], L > 1));
+    return 2 * act_floats(L, dims, B) + (part + 3) / 4 * 4;
 }
 
 // Forward and backward pass of a stack of fully connected layers for all workers.
@@ -207,8 +237,11 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
     const float *params = a.params;
     float *grads = a.grads;
 
+    const HeadPlan head = head_plan(L, dims, B, N);
+    const int L_gemm = head.use ? L - 1 : L;         // layers that go through the GEMM kernels
+
     // forward: a_l = relu(a_{l-1} W_l^T + b_l), no ReLU on the logits
-    for (int l = 1; l <= L; ++l) {
+    for (int l = 1; l <= L_gemm; ++l) {
         Dense<true> A, Bm;
         if (l == 1)
             A = {a.in, a.in_ld, a.in_stride};
@@ -270,7 +303,52 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
         dbw_timer tm(c, "mlp_forward_gemm", s);
         DBW_HIP(bgemm::launch<64>(A, Bm, E, B, dims[l], dims[l - 1], N, s));
     }
-    {
+    if (head.use) {
+        // last layer, loss and its whole backward pass in one launch
+        fchead::Args h{};
+        h.B = B; h.H = dims[L - 1]; h.C = dims[L]; h.S = head.S;
+        if (L == 1) {
+            h.a = a.in; h.a_ld = a.in_ld; h.a_stride = a.in_stride;
+            h.da = a.din; h.da_ld = a.din_ld; h.da_stride = a.din_stride;
+            h.mask = 0;
+            h.bprev_off = -1;
+        } else {
+            h.a = act + a_off[L - 1]; h.a_ld = dims[L - 1]; h.a_stride = wstride;
+            h.da = act + dz_off[L - 1]; h.da_ld = dims[L - 1]; h.da_stride = wstride;
+            h.mask = 1;
+            h.bprev_off = b_off[L - 1];
+        }
+        h.params = params; h.grads = grads; h.p_stride = c->ld; h.w_off = w_off[L]; h.b_off = b_off[L];
+        h.y = a.y; h.loss = a.loss;
+        h.part = act + 2 * per; h.part_stride = wstride;
+        h.err = c->err;
+        const dim3 grid(head.chunks, N);
+        const size_t lds = fchead::lds_bytes(h.H, h.C, h.S);
+        const bool vec = h.H % 4 == 0 && h.a_ld % 4 == 0 && h.a_stride % 4 == 0 && (uintptr_t)h.a % 16 == 0;
+        const bool mse = a.loss_kind == DBW_LOSS_MSE;
+        auto go = [&](auto kern, int slot) -> int {
+            static bool attr_set[4] = {false, false, false, false};      // per instantiation
+            if (!attr_set[slot]) {
+                DBW_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                            (int)fchead::LDS_LIMIT));
+                attr_set[slot] = true;
+            }
+            dbw_timer tm(c, "fc_head_kernel", s);
+            hipLaunchKernelGGL(kern, grid, dim3(fchead::THREADS), lds, s, h);
+            DBW_HIP(hipGetLastError());
+            return DBW_OK;
+        };
+        int rc;
+        if (mse) rc = vec ? go(fchead::kernel<DBW_LOSS_MSE, true>, 0) : go(fchead::kernel<DBW_LOSS_MSE, false>, 1);
+        else rc = vec ? go(fchead::kernel<DBW_LOSS_XENT, true>, 2) : go(fchead::kernel<DBW_LOSS_XENT, false>, 3);
+        if (rc != DBW_OK) return rc;
+        if (head.chunks > 1) {
+            const int64_t E = fchead::partial_floats(h.H, h.C, L > 1);
+            dbw_timer tm(c, "fc_head_reduce", s);
+            hipLaunchKernelGGL(fchead::reduce_kernel, dim3((unsigned)((E + 255) / 256), N), dim3(256), 0, s, h, head.chunks);
+            DBW_HIP(hipGetLastError());
+        }
+    } else {
         const int chunks = std::min((B + 255) / 256, DBW_LOSS_CHUNKS);
         const dim3 grid(chunks, N);
         dbw_timer tm(c, "softmax_loss_kernel", s);
@@ -283,7 +361,7 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
         DBW_HIP(hipGetLastError());
     }
     // backward
-    for (int l = L; l >= 1; --l) {
+    for (int l = L_gemm; l >= 1; --l) {
         const bool fast = batch32_layer(B, dims[l - 1], dims[l], c->ld, w_off[l], params, grads) && wstride % 4 == 0 &&
                           dz_off[l] % 4 == 0 && fc32::aligned16(act);
         {   // dW_l = dz_l^T a_{l-1}
@@ -323,7 +401,7 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
                 }
             }
         }
-        {
+        if (!(head.use && l == L - 1)) {       // the head has written the bias gradient of the layer below it
             dbw_timer tm(c, "colsum_kernel", s);
             if (B >= 512)    // long batches: 32 row groups per workgroup
                 hipLaunchKernelGGL(colsum_kernel<32>, dim3((dims[l] + 31) / 32, N), dim3(1024), 0, s, B, dims[l],

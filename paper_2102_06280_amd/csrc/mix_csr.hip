@@ -162,7 +162,7 @@ __global__ __launch_bounds__(MIX_THREADS) void mix_csr_vec4(
     int n_chunks, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ p,
     const int32_t *__restrict__ sel_idx, const float *__restrict__ sel_w,
     const float *__restrict__ self_w, const float4 *__restrict__ x, const float4 *__restrict__ g,
-    float4 *__restrict__ out, LR lr)
+    float4 *__restrict__ out, LR lr, int64_t d)
 {
     const int64_t L = blockIdx.x;
     const int xcd = (int)(L % MIX_XCDS);
@@ -209,7 +209,14 @@ __global__ __launch_bounds__(MIX_THREADS) void mix_csr_vec4(
         if (c < n_vec) {
             float4 r = acc[u];
             if (ORDER == DBW_ORDER_CTA && HAS_G) r = fma4(-eta_i, gv[u], r);
-            store_stream(&out[(int64_t)i * ld4 + c], r);
+            if (4 * c + 4 <= d) {
+                store_stream(&out[(int64_t)i * ld4 + c], r);
+            } else {                               // the float4 that straddles column d: padding stays untouched
+                float *o = (float *)&out[(int64_t)i * ld4 + c];
+                o[0] = r.x;
+                if (4 * c + 1 < d) o[1] = r.y;
+                if (4 * c + 2 < d) o[2] = r.z;
+            }
         }
     }
 }
@@ -310,6 +317,7 @@ int launch(dbw_ctx *c, const float *x, const float *g, float *out, LR lr, hipStr
             }
             if (rc != DBW_OK) return rc;
         } else {
+            n_vec = (c->d + 3) / 4;                 // as above: the straddling float4 lies inside the aligned row
             const int64_t per = (int64_t)MIX_THREADS * UNROLL;
             const int64_t n_chunks = (n_vec + per - 1) / per;
             const int64_t per_xcd = (n_chunks + MIX_XCDS - 1) / MIX_XCDS;
@@ -318,7 +326,7 @@ int launch(dbw_ctx *c, const float *x, const float *g, float *out, LR lr, hipStr
             dbw_timer tm(c, "mix_csr_vec4", s);
             hipLaunchKernelGGL((mix_csr_vec4<ORDER, HAS_G, UNROLL, LR>), dim3((unsigned)blocks), dim3(MIX_THREADS), 0, s,
                                c->N, n_vec, c->ld / 4, (int)n_chunks, c->rowptr, c->p, c->sel_idx, c->sel_w,
-                               c->self_w, (const float4 *)x, (const float4 *)g, (float4 *)out, lr);
+                               c->self_w, (const float4 *)x, (const float4 *)g, (float4 *)out, lr, c->d);
             DBW_HIP(hipGetLastError());
         }
     }
