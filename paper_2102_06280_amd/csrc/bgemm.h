@@ -124,10 +124,15 @@ __device__ __forceinline__ void fetch_tile(const L &op, int w, int r0, int R, in
 // 128-bit variants for dense operands (ROWS / 16 float4 per thread, float4 index f = tid + 256 j):
 //   KC: (row = f / 16, k = 4 (f % 16)): a wave instruction reads 256 contiguous bytes of four rows
 //   RC: (k = f / (ROWS / 4), row = 4 (f % (ROWS / 4))): ROWS contiguous floats of one k
+// A float4 outside the operand is read from offset 0 instead and its bit in `okbits` stays clear;
+// the value is only replaced by zero when the tile is written to LDS (commit_tile_vec).  Masking
+// right after the load would make the wave wait for the load before its matrix instructions, and
+// the point of fetching one k-step ahead is that the loads are in flight during them.
 template <class L, int ROWS>
 __device__ __forceinline__ void fetch_tile_vec(const L &op, int w, int r0, int R, int k0, int K, int tid,
-                                               float (&v)[ROWS / 4])
+                                               float (&v)[ROWS / 4], uint32_t &okbits)
 {
+    okbits = 0;
     const float *base = op.p + w * op.stride;
 #pragma unroll
     for (int j = 0; j < ROWS / 16; ++j) {
@@ -143,18 +148,20 @@ __device__ __forceinline__ void fetch_tile_vec(const L &op, int w, int r0, int R
         const bool ok = r < R && k < K;
         const int off = ok ? (L::KC ? r * (int)op.ld + k : k * (int)op.ld + r) : 0;
         const f32x4 q = *(const f32x4 *)(base + off);
+        okbits |= (ok ? 1u : 0u) << j;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[4 * j + e] = ok ? q[e] : 0.f;
+        for (int e = 0; e < 4; ++e) v[4 * j + e] = q[e];
     }
 }
 
 template <class L, int ROWS>
-__device__ __forceinline__ void commit_tile_vec(float *lds, int tid, const float (&v)[ROWS / 4])
+__device__ __forceinline__ void commit_tile_vec(float *lds, int tid, const float (&v)[ROWS / 4], uint32_t okbits)
 {
 #pragma unroll
     for (int j = 0; j < ROWS / 16; ++j) {
         const int f = tid + 256 * j;
-        const f32x4 q = {v[4 * j], v[4 * j + 1], v[4 * j + 2], v[4 * j + 3]};
+        const bool ok = (okbits >> j) & 1u;
+        const f32x4 q = {ok ? v[4 * j] : 0.f, ok ? v[4 * j + 1] : 0.f, ok ? v[4 * j + 2] : 0.f, ok ? v[4 * j + 3] : 0.f};
         if (L::KC)
             *(f32x4 *)&lds[(f >> 4) * LDS_KC + 4 * (f & 15)] = q;
         else
@@ -231,19 +238,21 @@ __global__ __launch_bounds__(THREADS) void kernel(LA A, LB B, EP E, int M, int N
     make_rows<LA, BM>(A, m0, M, lane, arows);
     make_rows<LB, BN>(B, n0, N, lane, brows);
     float ra[BM / 4], rb[BN / 4];
+    uint32_t oka = 0, okb = 0;
     auto fetch = [&](int k0) {
-        if constexpr (VA) fetch_tile_vec<LA, BM>(A, w, m0, M, k0, kend, tid, ra);
+        if constexpr (VA) fetch_tile_vec<LA, BM>(A, w, m0, M, k0, kend, tid, ra, oka);
         else fetch_tile<LA, BM>(A, w, m0, M, k0, kend, wave, lane, arows, ra);
-        if constexpr (VB) fetch_tile_vec<LB, BN>(B, w, n0, N, k0, kend, tid, rb);
+        if constexpr (VB) fetch_tile_vec<LB, BN>(B, w, n0, N, k0, kend, tid, rb, okb);
         else fetch_tile<LB, BN>(B, w, n0, N, k0, kend, wave, lane, brows, rb);
     };
     fetch(kbeg);
     for (int k0 = kbeg; k0 < kend; k0 += BK) {
         __syncthreads();                       // previous tile fully consumed
-        if constexpr (VA) commit_tile_vec<LA, BM>(As, tid, ra); else commit_tile<LA, BM>(As, wave, lane, ra);
-        if constexpr (VB) commit_tile_vec<LB, BN>(Bs, tid, rb); else commit_tile<LB, BN>(Bs, wave, lane, rb);
+        if constexpr (VA) commit_tile_vec<LA, BM>(As, tid, ra, oka); else commit_tile<LA, BM>(As, wave, lane, ra);
+        if constexpr (VB) commit_tile_vec<LB, BN>(Bs, tid, rb, okb); else commit_tile<LB, BN>(Bs, wave, lane, rb);
         __syncthreads();
         if (k0 + BK < kend) fetch(k0 + BK);    // next tile's loads fly during the MFMAs
+        if constexpr (VA || VB) __builtin_amdgcn_sched_barrier(0);   // nothing that consumes them moves up here
 #pragma unroll
         for (int kg = 0; kg < BK / 16; ++kg) {
             f32x4 fa[2], fb[2];

@@ -9,11 +9,14 @@
 // whole kernel.  The workgroup walks over column tiles of X; a tile (NPAD rows x TC
 // columns) is staged once through LDS, laid out so that the B-operand fragment of
 // v_mfma_f32_32x32x2_f32 for k-step kk is one conflict-free 64-lane row.  The next tile is
-// on its way while the current one is multiplied: when no element needs a guard or a
-// prologue (FULL tiles, CTA order) it goes from global memory straight into LDS
-// (global_load_lds, 16 bytes per lane), otherwise through registers.  The gradient values
-// of the epilogue are requested before the multiply loop so that they have arrived when it
-// ends.  True fp32 MFMA: no reduced-precision input format anywhere.
+// on its way while the current one is multiplied: when no element needs a guard (FULL
+// tiles) it goes from global memory straight into LDS (global_load_lds, 16 bytes per lane),
+// otherwise through registers.  With the local step first (ATC) the gradient values of the
+// same elements travel in registers meanwhile, and x - lr g is formed in LDS once both have
+// landed, after the multiplies: forming it in registers right behind the loads made every
+// wave wait for them before it could start multiplying.  In the other order the gradient
+// values of the epilogue are requested before the multiply loop so that they have arrived
+// when it ends.  True fp32 MFMA: no reduced-precision input format anywhere.
 //
 // Fragment layout of v_mfma_f32_32x32x2_f32 (M = N = 32, K = 2), lane l in [0, 64):
 //   A: a = A[m = l % 32][k = l / 32]        B: b = B[k = l / 32][n = l % 32]
@@ -65,7 +68,8 @@ __global__ __launch_bounds__(DENSE_THREADS) void mix_dense_kernel(
     float *__restrict__ out, const float *__restrict__ gs, LR lr, int n_tiles)
 {
     using C = dense_cfg<MB>;
-    constexpr bool DMA = FULL && !(ORDER == DBW_ORDER_ATC && HAS_G);
+    constexpr bool DMA = FULL;                                     // tiles go straight into LDS
+    constexpr bool PRO = FULL && ORDER == DBW_ORDER_ATC && HAS_G;  // ... and x - lr g is formed there
     __shared__ __attribute__((aligned(16))) float lds[2 * C::TILE];
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -129,11 +133,42 @@ __global__ __launch_bounds__(DENSE_THREADS) void mix_dense_kernel(
         }
     };
 
+    // ---- local step first: the gradient values of the elements this lane's DMA requests bring in
+    // (same blocks, same lane -> (row, 4 columns) map), and the update of those elements in LDS
+    float4 gstage[PRO ? C::DMA_PER_WAVE : 1];
+    auto load_gdma = [&](int64_t tile) {
+#pragma unroll
+        for (int i = 0; i < (PRO ? C::DMA_PER_WAVE : 0); ++i) {
+            const int q = w + 8 * i;
+            const int s = q / (C::KB / 4), kq = q % (C::KB / 4);
+            const float4 *src = g + (int64_t)(8 * kq) * ld4 + tile * (C::TC / 4) + s * 8;   // uniform base
+            gstage[i] = *(const float4 *)(uniform_base(src) + dma_lane_off);
+        }
+    };
+    auto apply_g = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < (PRO ? C::DMA_PER_WAVE : 0); ++i) {
+            const int q = w + 8 * i;
+            const int kq = q % (C::KB / 4);
+            const float eta = lr.at(8 * kq + 2 * (lane >> 4) + ((lane >> 3) & 1));
+            float4 *p = (float4 *)&lds[buf * C::TILE + q * 256 + 4 * lane];
+            float4 v = *p;
+            v.x = fmaf(-eta, gstage[i].x, v.x);
+            v.y = fmaf(-eta, gstage[i].y, v.y);
+            v.z = fmaf(-eta, gstage[i].z, v.z);
+            v.w = fmaf(-eta, gstage[i].w, v.w);
+            *p = v;
+        }
+    };
+
     int64_t tile = blockIdx.x;
     if (tile >= n_tiles) return;
     if (DMA) {
         dma(tile, 0);
+        load_gdma(tile);
         __builtin_amdgcn_s_waitcnt(0);
+        asm volatile("" ::: "memory");
+        apply_g(0);
     } else {
         fetch(tile);
         commit(0);
@@ -147,8 +182,14 @@ __global__ __launch_bounds__(DENSE_THREADS) void mix_dense_kernel(
     for (; tile < n_tiles; tile += gridDim.x) {
         const int64_t next = tile + gridDim.x;
         if (next < n_tiles) {
-            if (DMA) dma(next, buf ^ 1); else fetch(next);
+            if (DMA) {
+                dma(next, buf ^ 1);
+                load_gdma(next);
+            } else {
+                fetch(next);
+            }
         }
+        if (PRO) __builtin_amdgcn_sched_barrier(0);      // nothing that consumes those values moves up here
 
         // Per 32-column sub-tile: request its gradient values, multiply, correct and store.  The
         // sub-tiles of a wave go one after the other so that only one accumulator and one set of
@@ -229,6 +270,10 @@ __global__ __launch_bounds__(DENSE_THREADS) void mix_dense_kernel(
         // the next tile is complete in LDS before anybody starts on it
         if (next < n_tiles && !DMA) commit(buf ^ 1);
         if (DMA) __builtin_amdgcn_s_waitcnt(0);      // the tile written by global_load_lds has landed
+        if (PRO) {
+            asm volatile("" ::: "memory");               // LDS reads below stay behind the wait
+            if (next < n_tiles) apply_g(buf ^ 1);
+        }
         __syncthreads();
         buf ^= 1;
         epilogue(C::SPW - 1);

@@ -6,13 +6,24 @@ from __future__ import annotations
 from . import inputs
 
 
+def _head(B, n, h, c, with_input_gradient):
+    """The fused classifier head (last layer h -> c, c <= 16): logits, weight gradient and, below a
+    hidden layer, the input gradient."""
+    return n * 2 * B * h * c * (3 if with_input_gradient else 2)
+
+
 def _mlp(cfg, dims):
     B, n = cfg.batch, cfg.n
-    fwd = [2 * B * dims[l] * dims[l + 1] for l in range(len(dims) - 1)]
-    wgrad = list(fwd)
-    dgrad = [2 * B * dims[l] * dims[l + 1] for l in range(1, len(dims) - 1)]
-    return {"mlp_forward_gemm": n * sum(fwd) / len(fwd), "mlp_wgrad_gemm": n * sum(wgrad) / len(wgrad),
-            "mlp_dgrad_gemm": n * sum(dgrad) / max(len(dgrad), 1)}
+    L = len(dims) - 1
+    last = L - 1 if dims[-1] <= 16 else L           # layers [0, last) go through the GEMM kernels
+    fwd = [2 * B * dims[l] * dims[l + 1] for l in range(last)]
+    dgrad = [2 * B * dims[l] * dims[l + 1] for l in range(1, last)]
+    table = {"fc_head_kernel": _head(B, n, dims[-2], dims[-1], L > 1)}
+    if fwd:
+        table.update({"mlp_forward_gemm": n * sum(fwd) / len(fwd), "mlp_wgrad_gemm": n * sum(fwd) / len(fwd)})
+    if dgrad:
+        table["mlp_dgrad_gemm"] = n * sum(dgrad) / len(dgrad)
+    return table
 
 
 def _cnn(cfg, desc):
@@ -25,12 +36,11 @@ def _cnn(cfg, desc):
     fc = [2 * B * flat * f, 2 * B * f * nc]
     table = {"conv1_forward": n * conv1, "conv1_wgrad": n * conv1,
              "conv2_forward": n * conv2, "conv2_wgrad": n * conv2, "conv2_dgrad": n * conv2}
+    table["fc_head_kernel"] = _head(B, n, f, nc, True)
     if B == 32 and flat % 512 == 0 and f % 32 == 0:      # the first FC layer runs on the batch-32 kernels
-        table.update({"fc32_forward": n * fc[0], "fc32_wgrad": n * fc[0], "fc32_dgrad": n * fc[0],
-                      "mlp_forward_gemm": n * fc[1], "mlp_wgrad_gemm": n * fc[1], "mlp_dgrad_gemm": n * fc[1]})
+        table.update({"fc32_forward": n * fc[0], "fc32_wgrad": n * fc[0], "fc32_dgrad": n * fc[0]})
     else:
-        table.update({"mlp_forward_gemm": n * sum(fc) / 2, "mlp_wgrad_gemm": n * sum(fc) / 2,
-                      "mlp_dgrad_gemm": n * sum(fc) / 2})
+        table.update({"mlp_forward_gemm": n * fc[0], "mlp_wgrad_gemm": n * fc[0], "mlp_dgrad_gemm": n * fc[0]})
     return table
 
 

@@ -38,6 +38,14 @@ SHAPES = [
     ([1024, 256, 128, 10], 32, 5, "xent"),
     ([64, 512, 64, 10], 32, 11, "xent"),
     ([1536, 384, 10], 32, 3, "mse"),
+    # the last layer through the fused head in each of its chunk sizes, with ragged chunks, 16 classes,
+    # one class; and around its limits: 20 classes and a 2000-wide last layer take the GEMM kernels
+    ([48, 24, 16], 70, 3, "xent"),
+    ([30, 1], 5, 2, "xent"),
+    ([203, 77, 9], 97, 40, "mse"),
+    ([64, 40, 20], 33, 3, "xent"),
+    ([2000, 12], 20, 2, "xent"),
+    ([1100, 7], 40, 2, "mse"),
 ]
 
 
