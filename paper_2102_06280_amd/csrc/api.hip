@@ -177,6 +177,7 @@ int fill_ctx(dbw_ctx *c, int32_t N, int64_t d, int64_t nnz64, const int32_t *row
         A(dev_alloc(&c->phi_frag, (size_t)c->Npad * c->Npad));
     }
     if (c->model.kind != DBW_MODEL_NONE) {
+        A(dbw_fc_prepare());
         A(dev_alloc(&c->grads, (size_t)N * c->ld));
         c->act_floats = c->model.kind == DBW_MODEL_MLP ? dbw_mlp_scratch_floats(c) : dbw_cnn_scratch_floats(c);
         A(dev_alloc(&c->act, c->act_floats));

@@ -141,6 +141,7 @@ struct dbw_fc_args {
     float *loss;
 };
 int64_t dbw_fc_scratch_per_worker(int L, const int32_t *dims, int B);
+int dbw_fc_prepare();   // one-time kernel attributes of the fully connected path
 int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s);
 size_t dbw_mlp_scratch_floats(const dbw_ctx *c);
 int dbw_launch_grad_mlp(dbw_ctx *c, const float *params, const float *bx, const int32_t *by, float *grads,

@@ -326,21 +326,15 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
         const size_t lds = fchead::lds_bytes(h.H, h.C, h.S);
         const bool vec = h.H % 4 == 0 && h.a_ld % 4 == 0 && h.a_stride % 4 == 0 && (uintptr_t)h.a % 16 == 0;
         const bool mse = a.loss_kind == DBW_LOSS_MSE;
-        auto go = [&](auto kern, int slot) -> int {
-            static bool attr_set[4] = {false, false, false, false};      // per instantiation
-            if (!attr_set[slot]) {
-                DBW_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                            (int)fchead::LDS_LIMIT));
-                attr_set[slot] = true;
-            }
+        auto go = [&](auto kern) -> int {
             dbw_timer tm(c, "fc_head_kernel", s);
             hipLaunchKernelGGL(kern, grid, dim3(fchead::THREADS), lds, s, h);
             DBW_HIP(hipGetLastError());
             return DBW_OK;
         };
         int rc;
-        if (mse) rc = vec ? go(fchead::kernel<DBW_LOSS_MSE, true>, 0) : go(fchead::kernel<DBW_LOSS_MSE, false>, 1);
-        else rc = vec ? go(fchead::kernel<DBW_LOSS_XENT, true>, 2) : go(fchead::kernel<DBW_LOSS_XENT, false>, 3);
+        if (mse) rc = vec ? go(fchead::kernel<DBW_LOSS_MSE, true>) : go(fchead::kernel<DBW_LOSS_MSE, false>);
+        else rc = vec ? go(fchead::kernel<DBW_LOSS_XENT, true>) : go(fchead::kernel<DBW_LOSS_XENT, false>);
         if (rc != DBW_OK) return rc;
         if (head.chunks > 1) {
             const int64_t E = fchead::partial_floats(h.H, h.C, L > 1);
@@ -439,6 +433,21 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
             DBW_HIP(bgemm::launch<64>(A, Bm, E, B, dims[0], dims[1], N, s));
         }
     }
+    return DBW_OK;
+}
+
+// The fused head uses up to 159 KB of dynamic LDS: allow that once, at create, so that no
+// attribute call falls into a stream capture of the first round.
+int dbw_fc_prepare()
+{
+    static bool done = false;
+    if (done) return DBW_OK;
+    const void *kernels[] = {(const void *)fchead::kernel<DBW_LOSS_MSE, true>, (const void *)fchead::kernel<DBW_LOSS_MSE, false>,
+                             (const void *)fchead::kernel<DBW_LOSS_XENT, true>,
+                             (const void *)fchead::kernel<DBW_LOSS_XENT, false>};
+    for (const void *k : kernels)
+        DBW_HIP(hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)fchead::LDS_LIMIT));
+    done = true;
     return DBW_OK;
 }
 

@@ -92,3 +92,48 @@ def test_static_entry_status_and_limits(B):
     with pytest.raises(B.DbwError) as e:
         B.dbw_consensus_rounds_static(8, 64, 32, dev(rowptr), dev(colidx), dx, y, dt, db, r)
     assert e.value.code == B.ERR_INVALID
+
+
+def test_static_entry_under_graph_capture(B):
+    """The entry point is meant for callers that record their work into a HIP graph: capture one
+    call, replay it several times with unrelated eager work and synchronisations in between, and
+    compare every replay with the eager result (new response times are written into the same
+    device arrays between replays)."""
+    rowptr, colidx = inputs.graph_regular(64, 6, np.random.default_rng(905))
+    n, d, ld, r = 64, 3001, 3008, 4
+    g = np.random.default_rng(906)
+    deg = np.diff(rowptr)
+    x = dev(g.standard_normal((n, ld)).astype(np.float32))
+    drow, dcol = dev(rowptr.astype(np.int32)), dev(colidx.astype(np.int32))
+    t = torch.zeros((r, n), dtype=torch.float32, device="cuda")
+    b = torch.zeros((r, n), dtype=torch.int32, device="cuda")
+    out = torch.zeros((n, ld), dtype=torch.float32, device="cuda")
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+
+    def fresh_inputs():
+        t.copy_(dev(g.standard_exponential((r, n)).astype(np.float32)))
+        b.copy_(dev(np.stack([g.integers(0, deg + 1) for _ in range(r)]).astype(np.int32)))
+
+    fresh_inputs()
+    B.dbw_consensus_rounds_static(n, d, ld, drow, dcol, x, out, t, b, r, status)    # set-up happens outside the capture
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        B.dbw_consensus_rounds_static(n, d, ld, drow, dcol, x, out, t, b, r, status)
+    h = B.dbw_create(rowptr, colidx, n, d, ld=ld, mix_path=B.MIX_CSR)
+    try:
+        for rep in range(3):
+            fresh_inputs()
+            out.fill_(7.0)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            _ = torch.randn(1000, device="cuda").sum().item()              # unrelated eager work in between
+            want = torch.full((n, ld), 7.0, dtype=torch.float32, device="cuda")
+            B.dbw_consensus_rounds(h, x, want, t, b, r)
+            torch.cuda.synchronize()
+            assert int(status.item()) == B.OK
+            assert torch.equal(out, want), f"replay {rep}"
+    finally:
+        B.dbw_destroy(h)
