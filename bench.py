@@ -119,7 +119,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4, 5, 6, 7])
     ap.add_argument("--order", choices=["cta", "atc"], default="cta")
     ap.add_argument("--layout", choices=["rows", "tiles"], default=None,
