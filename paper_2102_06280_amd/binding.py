@@ -13,7 +13,8 @@ import numpy as np
 import torch  # noqa: F401  (first: the library must bind to the HIP runtime that torch has already loaded)
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libdbw.so")
+# DBW_LIB: another build of the same sources (e.g. host code under sanitizers); default: the in-tree library
+LIB_PATH = os.environ.get("DBW_LIB") or os.path.join(_HERE, "libdbw.so")
 
 OK, ERR_NULL, ERR_INVALID, ERR_GRAPH, ERR_ALIAS, ERR_STATE, ERR_ALLOC, ERR_HIP, ERR_UNSUPPORTED = (
     0, -1, -2, -3, -4, -5, -6, -7, -8)

@@ -48,5 +48,41 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
+def build_sanitized(out_dir: str) -> str:
+    """The library with AddressSanitizer and UndefinedBehaviorSanitizer on the HOST code only (argument
+    checks, graph validation, context life cycle); device code is compiled as usual.  For the CPU test
+    that walks the host-only paths of the ABI; needs clang's sanitizer runtime preloaded to be loaded."""
+    os.makedirs(out_dir, exist_ok=True)
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-g"]
+    flags = [f if f != "-O3" else "-O1" for f in FLAGS]
+    srcs = sources()
+    objs = [os.path.join(out_dir, os.path.basename(s)[:-4] + ".o") for s in srcs]
+
+    def one(pair):
+        r = subprocess.run([HIPCC, *flags, *san, "-c", pair[0], "-o", pair[1]], capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc failed on {pair[0]}:\n{r.stdout}\n{r.stderr}")
+
+    with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
+        list(ex.map(one, zip(srcs, objs)))
+    lib = os.path.join(out_dir, "libdbw_san.so")
+    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-rdc", *san, "-shared-libsan", *objs,
+                        "-o", lib], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
+    return lib
+
+
+def sanitizer_runtime() -> str:
+    """clang's shared AddressSanitizer runtime (to be preloaded into an uninstrumented interpreter)."""
+    r = subprocess.run([os.path.join(os.path.dirname(HIPCC), "amdclang++"), "-print-file-name=libclang_rt.asan-x86_64.so"],
+                       capture_output=True, text=True)
+    path = r.stdout.strip()
+    if os.path.sep not in path:
+        cands = sorted(glob.glob("/opt/rocm/lib/llvm/lib/clang/*/lib/linux/libclang_rt.asan-x86_64.so"))
+        path = cands[-1] if cands else ""
+    return path
+
+
 if __name__ == "__main__":
     print(build_library(verbose="-v" in sys.argv))

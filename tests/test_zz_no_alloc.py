@@ -78,6 +78,20 @@ def test_static_entry_status_and_limits(B):
     got, status = _static(B, n, d, ld, rowptr, bad_col, dx, dt, zero_b, r)
     assert status == B.ERR_GRAPH
     assert torch.equal(got[:, :d], dx[:, :d])
+    # every way a graph can be wrong is caught by the staging kernel, and the parameters pass through
+    bad_graphs = {
+        "self loop": (rowptr, np.where(np.arange(colidx.size) == 0, 0, colidx)),
+        "out of range": (rowptr, np.where(np.arange(colidx.size) == 5, 99, colidx)),
+        "negative index": (rowptr, np.where(np.arange(colidx.size) == 5, -1, colidx)),
+        "row not ascending": (rowptr, np.concatenate([colidx[:2][::-1], colidx[2:]])),
+        "offsets decrease": (np.concatenate([rowptr[:3], [rowptr[3] - 3], rowptr[4:]]), colidx),
+        "offsets do not start at zero": (np.concatenate([[1], rowptr[1:]]), colidx),
+        "last offset is not the number of entries": (np.concatenate([rowptr[:-1], [rowptr[-1] - 1]]), colidx),
+    }
+    for what, (rp_bad, ci_bad) in bad_graphs.items():
+        got, status = _static(B, n, d, ld, rp_bad.astype(np.int32), ci_bad.astype(np.int32), dx, dt, zero_b, r)
+        assert status == B.ERR_GRAPH, what
+        assert torch.equal(got[:, :d], dx[:, :d]), what
     # host-side limits and argument checks
     x = torch.zeros((300, 64), device="cuda")
     y = torch.zeros((300, 64), device="cuda")
