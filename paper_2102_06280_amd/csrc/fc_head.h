@@ -40,6 +40,10 @@ struct Args {
     int B, H, C, S;                  // batch, inputs, classes, samples per chunk (16, 32 or 64)
     const float *a;                  // [B][a_ld] per worker (stride a_stride): the head's input
     int64_t a_ld, a_stride;
+    int splits;                      // > 0: the input is still the partial sums of a forward product split along k,
+                                     // a[split][B][H] per worker (a_ld = H): the head's input is
+                                     // relu(sum over splits, in order, + the bias of that layer)
+    int64_t in_bias_off;             // offset of that bias [H] in the worker's parameter row
     const float *params;             // worker rows of stride p_stride; W [C][H] at w_off, bias [C] at b_off
     float *grads;                    // same offsets and stride: receives dW and db
     int64_t p_stride, w_off, b_off;
@@ -73,7 +77,8 @@ __host__ __device__ inline size_t lds_bytes(int H, int C, int S) { return sizeof
 __host__ __device__ inline int64_t partial_floats(int H, int C, bool bprev) { return (int64_t)C * H + C + (bprev ? H : 0) + 1; }
 
 // VEC: the input rows start on 16-byte boundaries and H divides by 4 (128-bit staging loads).
-template <int LOSS, bool VEC>
+// SPLIT: the input arrives as split-k partial sums (Args::splits).
+template <int LOSS, bool VEC, bool SPLIT = false>
 __global__ __launch_bounds__(THREADS) void kernel(Args g)
 {
     extern __shared__ __attribute__((aligned(16))) float sm[];
@@ -107,7 +112,30 @@ __global__ __launch_bounds__(THREADS) void kernel(Args g)
             }
         }
     }
-    if (VEC) {
+    if (SPLIT) {
+        // a = relu(sum of the partial sums + bias): one float4 per thread at a time, all splits in flight
+        const int q4 = HP / 4, total = S * q4;
+        const float *__restrict__ bin = g.params + w * g.p_stride + g.in_bias_off;
+        const int64_t plane = (int64_t)g.B * H;
+        for (int e = tid; e < total; e += THREADS) {
+            const int r = e / q4, k = 4 * (e - r * q4);
+            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (r < ns && k < H) {
+                const float *src = g.a + w * g.a_stride + (int64_t)(s0 + r) * H + k;
+                float4 v[16];
+#pragma unroll
+                for (int q = 0; q < 16; ++q)
+                    if (q < g.splits) v[q] = *(const float4 *)(src + q * plane);
+#pragma unroll
+                for (int q = 0; q < 16; ++q)
+                    if (q < g.splits) { acc.x += v[q].x; acc.y += v[q].y; acc.z += v[q].z; acc.w += v[q].w; }
+                const float4 bv = *(const float4 *)(bin + k);
+                acc.x = fmaxf(acc.x + bv.x, 0.f); acc.y = fmaxf(acc.y + bv.y, 0.f);
+                acc.z = fmaxf(acc.z + bv.z, 0.f); acc.w = fmaxf(acc.w + bv.w, 0.f);
+            }
+            *(float4 *)(al + 4 * e) = acc;
+        }
+    } else if (VEC) {
         const int q4 = HP / 4, total = S * q4;
         for (int e0 = 0; e0 < total; e0 += 8 * THREADS) {
             float4 v[8];

@@ -211,8 +211,9 @@ int64_t dbw_fc_scratch_per_worker(int L, const int32_t *dims, int B)
 {
     int64_t part = 0;
     for (int l = 1; l <= L; ++l) part = std::max<int64_t>(part, (int64_t)MAX_SPLITS * B * dims[l]);
-    if (dims[L] <= fchead::MAX_C)      // partial sums of the fused head, at its smaller chunk size
-        part = std::max(part, (int64_t)((B + 15) / 16) * fchead::partial_floats(dims[L - 1], dims[L], L > 1));
+    part = (part + 3) / 4 * 4;
+    if (dims[L] <= fchead::MAX_C)      // partial sums of the fused head, at its smaller chunk size, behind the split partials
+        part += (int64_t)((B + 15) / 16) * fchead::partial_floats(dims[L - 1], dims[L], L > 1);
     return 2 * act_floats(L, dims, B) + (part + 3) / 4 * 4;
 }
 
@@ -239,6 +240,11 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
 
     const HeadPlan head = head_plan(L, dims, B, N);
     const int L_gemm = head.use ? L - 1 : L;         // layers that go through the GEMM kernels
+    // The output of layer L - 1 feeds nothing but the head.  When its forward product is split along k, the
+    // head sums the partial products itself (same order, then bias and ReLU) and the reduction launch is saved.
+    int head_splits = 0;
+    const bool head_can_sum = head.use && L >= 2 && dims[L - 1] % 4 == 0 && b_off[L - 1] % 4 == 0 && c->ld % 4 == 0 &&
+                              fc32::aligned16(params) && wstride % 4 == 0 && fc32::aligned16(act) && (2 * per) % 4 == 0;
 
     // forward: a_l = relu(a_{l-1} W_l^T + b_l), no ReLU on the logits
     for (int l = 1; l <= L_gemm; ++l) {
@@ -269,6 +275,10 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
                     }
                     DBW_HIP(hipGetLastError());
                 }
+                if (head_can_sum && l == L - 1 && slices <= 16) {
+                    head_splits = slices;
+                    continue;
+                }
                 dbw_timer tm(c, "fc_reduce_kernel", s);
                 hipLaunchKernelGGL(fc_reduce_kernel, dim3((B * dims[l] + 255) / 256, N), dim3(256), 0, s, part, wstride,
                                    slices, B, dims[l], params + b_off[l], c->ld, l < L ? 1 : 0, act + a_off[l],
@@ -292,6 +302,10 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
                 DBW_HIP(bgemm::launch<64>(A, Bm, SplitOut{part, wstride, B, dims[l]}, B, dims[l], dims[l - 1], N, s,
                                           splits));
             }
+            if (head_can_sum && l == L - 1) {
+                head_splits = splits;
+                continue;
+            }
             dbw_timer tm(c, "fc_reduce_kernel", s);
             hipLaunchKernelGGL(fc_reduce_kernel, dim3((B * dims[l] + 255) / 256, N), dim3(256), 0, s, part, wstride,
                                splits, B, dims[l], params + b_off[l], c->ld, l < L ? 1 : 0, act + a_off[l],
@@ -314,13 +328,20 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
             h.bprev_off = -1;
         } else {
             h.a = act + a_off[L - 1]; h.a_ld = dims[L - 1]; h.a_stride = wstride;
+            if (head_splits > 0) {      // partial products [split][B][H] instead of the finished activations
+                h.a = act + 2 * per;
+                h.splits = head_splits;
+                h.in_bias_off = b_off[L - 1];
+            }
             h.da = act + dz_off[L - 1]; h.da_ld = dims[L - 1]; h.da_stride = wstride;
             h.mask = 1;
             h.bprev_off = b_off[L - 1];
         }
         h.params = params; h.grads = grads; h.p_stride = c->ld; h.w_off = w_off[L]; h.b_off = b_off[L];
         h.y = a.y; h.loss = a.loss;
-        h.part = act + 2 * per; h.part_stride = wstride;
+        int64_t split_floats = 0;                        // the split partials of the layers, which the head's own follow
+        for (int q = 1; q <= L; ++q) split_floats = std::max<int64_t>(split_floats, (int64_t)MAX_SPLITS * B * dims[q]);
+        h.part = act + 2 * per + (split_floats + 3) / 4 * 4; h.part_stride = wstride;
         h.err = c->err;
         const dim3 grid(head.chunks, N);
         const size_t lds = fchead::lds_bytes(h.H, h.C, h.S);
@@ -333,7 +354,8 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
             return DBW_OK;
         };
         int rc;
-        if (mse) rc = vec ? go(fchead::kernel<DBW_LOSS_MSE, true>) : go(fchead::kernel<DBW_LOSS_MSE, false>);
+        if (head_splits > 0) rc = mse ? go(fchead::kernel<DBW_LOSS_MSE, true, true>) : go(fchead::kernel<DBW_LOSS_XENT, true, true>);
+        else if (mse) rc = vec ? go(fchead::kernel<DBW_LOSS_MSE, true>) : go(fchead::kernel<DBW_LOSS_MSE, false>);
         else rc = vec ? go(fchead::kernel<DBW_LOSS_XENT, true>) : go(fchead::kernel<DBW_LOSS_XENT, false>);
         if (rc != DBW_OK) return rc;
         if (head.chunks > 1) {
@@ -444,7 +466,9 @@ int dbw_fc_prepare()
     if (done) return DBW_OK;
     const void *kernels[] = {(const void *)fchead::kernel<DBW_LOSS_MSE, true>, (const void *)fchead::kernel<DBW_LOSS_MSE, false>,
                              (const void *)fchead::kernel<DBW_LOSS_XENT, true>,
-                             (const void *)fchead::kernel<DBW_LOSS_XENT, false>};
+                             (const void *)fchead::kernel<DBW_LOSS_XENT, false>,
+                             (const void *)fchead::kernel<DBW_LOSS_MSE, true, true>,
+                             (const void *)fchead::kernel<DBW_LOSS_XENT, true, true>};
     for (const void *k : kernels)
         DBW_HIP(hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)fchead::LDS_LIMIT));
     done = true;
