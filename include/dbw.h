@@ -118,12 +118,26 @@ enum {
                           over classes (the 2NN of Appendix B); fully connected models only */
 };
 
+/* How the gradient of a fully connected model is launched.  The results agree to rounding (the
+ * products are summed in different orders). */
+enum {
+    DBW_GRAD_AUTO = 0,   /* the library picks */
+    DBW_GRAD_LAYERS = 1, /* one batched GEMM launch per layer and pass */
+    DBW_GRAD_CHAIN = 2   /* forward pass, loss and data gradients of all layers in one launch, a
+                            workgroup per block of samples with the activations in LDS; for
+                            DBW_MODEL_MLP with at least two layers, equal hidden widths of 128, 256
+                            or 512, dims[0] a multiple of 16 and at most 16 classes
+                            (DBW_ERR_UNSUPPORTED from dbw_create otherwise, or from dbw_round when
+                            batch_x or the parameter rows do not start on 16-byte boundaries) */
+};
+
 typedef struct {
     int32_t kind;     /* DBW_MODEL_* */
     int32_t batch;    /* samples per worker per round (|C_j(k)| of Section 2.1) */
     int32_t n_layers; /* MLP only */
     int32_t loss;     /* DBW_LOSS_*; the mean over the batch is taken */
     int32_t dims[9];
+    int32_t grad_path; /* DBW_GRAD_*; fully connected models only */
 } dbw_model;
 
 typedef struct {

@@ -23,6 +23,7 @@ MIX_AUTO, MIX_CSR, MIX_DENSE = 0, 1, 2
 MODEL_NONE, MODEL_SOFTMAX, MODEL_MLP, MODEL_CNN = 0, 1, 2, 3
 WARN_THETA_INF = 1
 LOSS_XENT, LOSS_MSE = 0, 1
+GRAD_AUTO, GRAD_LAYERS, GRAD_CHAIN = 0, 1, 2
 CAL_HBM_TRIAD, CAL_MFMA_FP32 = 0, 1
 LAYOUT_ROWS, LAYOUT_TILES = 0, 1
 TILE_COLUMNS = 64
@@ -37,7 +38,7 @@ EXPORTS = ["dbw_create", "dbw_select", "dbw_dtur_b", "dbw_dtur_reset", "dbw_dtur
 
 class dbw_model(C.Structure):
     _fields_ = [("kind", C.c_int32), ("batch", C.c_int32), ("n_layers", C.c_int32), ("loss", C.c_int32),
-                ("dims", C.c_int32 * 9)]
+                ("dims", C.c_int32 * 9), ("grad_path", C.c_int32)]
 
 
 class dbw_opts(C.Structure):
@@ -109,9 +110,10 @@ def _stream():
     return torch.cuda.current_stream().cuda_stream
 
 
-def make_model(kind: int = MODEL_NONE, batch: int = 0, dims=(), loss: int = LOSS_XENT) -> dbw_model:
+def make_model(kind: int = MODEL_NONE, batch: int = 0, dims=(), loss: int = LOSS_XENT,
+               grad_path: int = GRAD_AUTO) -> dbw_model:
     m = dbw_model()
-    m.kind, m.batch, m.loss = kind, batch, loss
+    m.kind, m.batch, m.loss, m.grad_path = kind, batch, loss, grad_path
     dims = list(dims)
     m.n_layers = len(dims) - 1 if kind in (MODEL_MLP, MODEL_SOFTMAX) else 0
     for k, v in enumerate(dims):

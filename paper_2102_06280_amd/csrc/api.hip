@@ -143,6 +143,10 @@ int fill_ctx(dbw_ctx *c, int32_t N, int64_t d, int64_t nnz64, const int32_t *row
         const bool loss_ok = c->model.loss == DBW_LOSS_XENT ||
                              (c->model.loss == DBW_LOSS_MSE && c->model.kind == DBW_MODEL_MLP);
         if (want != d || c->model.batch < 1 || !loss_ok) return DBW_ERR_INVALID;
+        if (c->model.grad_path < DBW_GRAD_AUTO || c->model.grad_path > DBW_GRAD_CHAIN) return DBW_ERR_INVALID;
+        if (c->model.grad_path == DBW_GRAD_CHAIN &&
+            (c->model.kind != DBW_MODEL_MLP || !dbw_fc_chain_shape_ok(c->model.n_layers, c->model.dims, c->model.batch, N)))
+            return DBW_ERR_UNSUPPORTED;
     }
     c->h_rowptr.assign(rowptr, rowptr + N + 1);
     c->h_colidx.assign(colidx, colidx + c->nnz);

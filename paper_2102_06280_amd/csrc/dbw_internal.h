@@ -139,8 +139,10 @@ struct dbw_fc_args {
     int64_t din_ld, din_stride;
     const int32_t *y;
     float *loss;
+    int grad_path;          // DBW_GRAD_*
 };
 int64_t dbw_fc_scratch_per_worker(int L, const int32_t *dims, int B);
+bool dbw_fc_chain_shape_ok(int L, const int32_t *dims, int B, int workers);   // DBW_GRAD_CHAIN can take this model
 int dbw_fc_prepare();   // one-time kernel attributes of the fully connected path
 int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s);
 size_t dbw_mlp_scratch_floats(const dbw_ctx *c);

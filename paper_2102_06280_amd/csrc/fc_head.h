@@ -36,6 +36,18 @@ constexpr int MAX_S = 64;            // samples per workgroup: 16, 32 or 64
 constexpr int MAX_CHUNKS = 256;
 constexpr size_t LDS_LIMIT = 159 * 1024;     // dynamic part; the kernel also has a few bytes of static LDS
 
+// Element i of a small table that sits in the kernel arguments.  Indexing such a table with a run-time value
+// makes the compiler copy the whole argument block into vector registers; a chain of selects over constant
+// indices stays on the scalar unit.
+template <class T, int N>
+__device__ __forceinline__ T pick(const T (&a)[N], int i)
+{
+    T r = a[0];
+#pragma unroll
+    for (int k = 1; k < N; ++k) r = i == k ? a[k] : r;
+    return r;
+}
+
 struct Args {
     int B, H, C, S;                  // batch, inputs, classes, samples per chunk (16, 32 or 64)
     const float *a;                  // [B][a_ld] per worker (stride a_stride): the head's input
@@ -76,6 +88,201 @@ __host__ __device__ inline size_t lds_floats(int H, int C, int S)
 __host__ __device__ inline size_t lds_bytes(int H, int C, int S) { return sizeof(float) * lds_floats(H, C, S); }
 __host__ __device__ inline int64_t partial_floats(int H, int C, bool bprev) { return (int64_t)C * H + C + (bprev ? H : 0) + 1; }
 
+// W [C][H] of worker w -> its LDS image [C + 1][pitch]; row C, the columns >= H and the slack behind are zero.
+__device__ __forceinline__ void stage_w(const Args &g, int w, float *Wl, int tid)
+{
+    const int H = g.H, C = g.C, HP = row_pitch(H);
+    const float *__restrict__ Wg = g.params + w * g.p_stride + g.w_off;
+    const int total = (C + 1) * HP + 16;
+    for (int e0 = 0; e0 < total; e0 += 8 * THREADS) {       // eight loads in flight per thread
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int e = e0 + tid + u * THREADS, r = e / HP, k = e - r * HP;
+            v[u] = (e < total && r < C && k < H) ? Wg[r * H + k] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int e = e0 + tid + u * THREADS;
+            if (e < total) Wl[e] = v[u];
+        }
+    }
+}
+
+// What the body needs from global memory besides the images: the caller fetches it before its own staging, so that
+// the latency passes there and not between two barriers of the body.
+struct Early {
+    float bias;      // b[tid % 16] (0 for the padding classes)
+    int label;       // y of sample s0 + tid of the chunk (threads tid < ns)
+};
+__device__ __forceinline__ Early fetch_early(const Args &g, int w, int s0, int ns, int tid)
+{
+    Early e;
+    const int c = tid & 15;
+    e.bias = c < g.C ? g.params[w * g.p_stride + g.b_off + c] : 0.f;
+    e.label = tid < ns ? g.y[(int64_t)w * g.B + s0 + tid] : 0;
+    return e;
+}
+
+// Everything after the staging: al [S][pitch] holds the chunk's input (rows beyond the batch, the columns >= H and 16
+// floats behind the image zero), Wl the image stage_w makes.  S is a multiple of 16 up to MAX_S.  With da_to_lds the
+// (masked) input gradient replaces the input in al instead of going to g.da.  All THREADS threads call this after a
+// barrier that makes al and Wl visible.
+template <int LOSS>
+__device__ __forceinline__ void body(const Args &g, float *zl, float *zp, float *Wl, float *al, int S, int w, int chunk,
+                                     int chunks, bool da_to_lds, const Early &early)
+{
+    const int H = g.H, C = g.C, HP = row_pitch(H);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, lq = lane >> 4;
+    const int s0 = chunk * S, ns = min(S, g.B - s0);
+
+    // ---- logits z = a W^T: wavefront = (16-sample block, slice of k); partial sums meet in LDS
+    {
+        const int MB = S / 16, KS = WAVES / MB;
+        const int mb = wave % MB, ks = wave / MB;
+        const int quads = HP / 4, per = (quads + KS - 1) / KS;
+        const int q_end = min(quads, (ks + 1) * per);
+        const float *ap = al + (16 * mb + l16) * HP + lq, *wp = Wl + min(l16, C) * HP + lq;
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        for (int q = ks * per; q < q_end; ++q)
+            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ap[4 * q], wp[4 * q], acc, 0, 0, 0);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) zp[(wave * 16 + 4 * lq + v) * 16 + l16] = acc[v];
+        __syncthreads();
+        // sample s, class c: the slices in order, then the bias
+        for (int e = tid; e < S * 16; e += THREADS) {
+            const int s = e >> 4, c = e & 15;
+            float z = 0.f;
+            for (int q = 0; q < KS; ++q) z += zp[((q * MB + (s >> 4)) * 16 + (s & 15)) * 16 + c];
+            zl[e] = c < C ? z + early.bias : 0.f;              // c == tid % 16: the stride of e is a multiple of 16
+        }
+    }
+    __syncthreads();
+
+    // ---- softmax, loss and dz per sample (rows of samples beyond the batch stay zero)
+    float loss_part = 0.f;
+    if (tid < MAX_S) {
+        float *zs = zl + tid * MAX_C;
+        if (tid < ns) {
+            float m = zs[0];
+            for (int c = 1; c < C; ++c) m = fmaxf(m, zs[c]);
+            float sum = 0.f;
+            for (int c = 0; c < C; ++c) sum += expf(zs[c] - m);
+            int label = early.label;
+            if (label < 0 || label >= C) {              // clamped for memory safety, reported by dbw_check
+                *g.err = DBW_ERR_INVALID;
+                label = label < 0 ? 0 : C - 1;
+            }
+            const float inv = 1.0f / sum, inv_b = 1.0f / (float)g.B;
+            if (LOSS == DBW_LOSS_XENT) {
+                loss_part = logf(sum) + m - zs[label];
+                for (int c = 0; c < C; ++c) zs[c] = (expf(zs[c] - m) * inv - (c == label ? 1.f : 0.f)) * inv_b;
+            } else {
+                float f = 0.f, inner = 0.f;
+                for (int c = 0; c < C; ++c) {
+                    const float p = expf(zs[c] - m) * inv, e = p - (c == label ? 1.f : 0.f);
+                    f += e * e;
+                    inner += p * e;
+                }
+                for (int c = 0; c < C; ++c) {
+                    const float p = expf(zs[c] - m) * inv, e = p - (c == label ? 1.f : 0.f);
+                    zs[c] = 2.f * p * (e - inner) * inv_b;
+                }
+                loss_part = f;
+            }
+        } else {
+            for (int c = 0; c < MAX_C; ++c) zs[c] = 0.f;
+        }
+    }
+    __syncthreads();
+
+    float *__restrict__ part = g.part + w * g.part_stride + (int64_t)chunk * partial_floats(H, C, g.bprev_off >= 0);
+    float *__restrict__ out_w = chunks == 1 ? g.grads + w * g.p_stride + g.w_off : part;
+    float *__restrict__ out_b = chunks == 1 ? g.grads + w * g.p_stride + g.b_off : part + (size_t)C * H;
+    float *__restrict__ out_bprev = g.bprev_off < 0 ? nullptr
+                                    : (chunks == 1 ? g.grads + w * g.p_stride + g.bprev_off : part + (size_t)C * H + C);
+    float *__restrict__ da = (g.da && !da_to_lds) ? g.da + w * g.da_stride + (int64_t)s0 * g.da_ld : nullptr;
+    const int NB = (H + 15) / 16;                       // 16-column blocks of the input dimension
+
+    for (int nb = wave; nb < NB; nb += WAVES) {
+        const int col = 16 * nb + l16;
+        // ---- dW[class][col] = sum over samples of dz[sample][class] a[sample][col]
+        {
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+            for (int k0 = 0; k0 < S; k0 += 4)
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(zl[(k0 + lq) * MAX_C + l16], al[(k0 + lq) * HP + col], acc,
+                                                           0, 0, 0);
+            if (col < H) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (4 * lq + v < C) out_w[(4 * lq + v) * H + col] = acc[v];
+            }
+        }
+        // ---- da[sample][col] = sum over classes of dz[sample][class] W[class][col], masked; its column sums
+        if (da || da_to_lds) {
+            float colsum = 0.f;
+            for (int mb = 0; mb < S / 16; ++mb) {
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(zl[(16 * mb + l16) * MAX_C + 4 * j + lq],
+                                                               Wl[min(4 * j + lq, C) * HP + col], acc, 0, 0, 0);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int s = 16 * mb + 4 * lq + v;
+                    float d = acc[v];
+                    if (g.mask && !(al[s * HP + col] > 0.f)) d = 0.f;
+                    if (da_to_lds) al[s * HP + col] = d;       // this wavefront alone reads and writes these columns
+                    else if (s < ns && col < H) da[(int64_t)s * g.da_ld + col] = d;
+                    colsum += d;                        // rows beyond the batch have dz = 0
+                }
+            }
+            colsum += __shfl_xor(colsum, 16, 64);
+            colsum += __shfl_xor(colsum, 32, 64);
+            if (out_bprev && lq == 0 && col < H) out_bprev[col] = colsum;
+        }
+    }
+    if (tid < C) {
+        float sum = 0.f;
+        for (int s = 0; s < ns; ++s) sum += zl[s * MAX_C + tid];
+        out_b[tid] = sum;
+    }
+    // ---- the chunk's loss: its samples in a fixed order (tree in LDS)
+    if (g.loss) {
+        float *red = zp;
+        if (tid < MAX_S) red[tid] = loss_part;
+        __syncthreads();
+        for (int o = MAX_S / 2; o > 0; o >>= 1) {
+            if (tid < o) red[tid] += red[tid + o];
+            __syncthreads();
+        }
+        if (tid == 0) {
+            if (chunks == 1) g.loss[w] = red[0] / (float)g.B;
+            else part[partial_floats(H, C, g.bprev_off >= 0) - 1] = red[0];
+        }
+    }
+}
+
+// Sum of the first `splits` (<= NQ) of the float4s at src + q * plane, in order, all NQ loads in flight.  A slot
+// beyond the splits re-reads the last one and adds zero: loads under a condition each would be merged back into
+// one register array with a move per element.
+template <int NQ>
+__device__ __forceinline__ float4 split_sum(const float *src, int64_t plane, int splits)
+{
+    float4 v[NQ];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) v[q] = *(const float4 *)(src + min(q, splits - 1) * plane);
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+        const bool on = q < splits;
+        acc.x += on ? v[q].x : 0.f; acc.y += on ? v[q].y : 0.f;
+        acc.z += on ? v[q].z : 0.f; acc.w += on ? v[q].w : 0.f;
+    }
+    return acc;
+}
+
 // VEC: the input rows start on 16-byte boundaries and H divides by 4 (128-bit staging loads).
 // SPLIT: the input arrives as split-k partial sums (Args::splits).
 template <int LOSS, bool VEC, bool SPLIT = false>
@@ -87,31 +294,14 @@ __global__ __launch_bounds__(THREADS) void kernel(Args g)
     float *zp = zl + MAX_S * MAX_C;                  // [8][16][16]: partial logits of the wavefronts
     float *Wl = zp + WAVES * 16 * 16;                // [C + 1][HP]: row C and the columns >= H are zero
     float *al = Wl + (C + 1) * HP + 16;              // [S][HP], rows >= ns and columns >= H zero
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int l16 = lane & 15, lq = lane >> 4;
+    const int tid = threadIdx.x;
     const int chunk = blockIdx.x, chunks = gridDim.x, w = blockIdx.y;
     const int s0 = chunk * S, ns = min(S, g.B - s0);
     const float *__restrict__ a = g.a + w * g.a_stride + (int64_t)s0 * g.a_ld;
-    const float *__restrict__ Wg = g.params + w * g.p_stride + g.w_off;
-    const float *__restrict__ bg = g.params + w * g.p_stride + g.b_off;
 
+    const Early early = fetch_early(g, w, s0, ns, tid);
     // ---- stage W and this chunk of a; everything the fragments may touch beyond them is zero
-    {
-        const int total = (C + 1) * HP + 16;
-        for (int e0 = 0; e0 < total; e0 += 8 * THREADS) {       // eight loads in flight per thread
-            float v[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int e = e0 + tid + u * THREADS, r = e / HP, k = e - r * HP;
-                v[u] = (e < total && r < C && k < H) ? Wg[r * H + k] : 0.f;
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int e = e0 + tid + u * THREADS;
-                if (e < total) Wl[e] = v[u];
-            }
-        }
-    }
+    stage_w(g, w, Wl, tid);
     if (SPLIT) {
         // a = relu(sum of the partial sums + bias): one float4 per thread at a time, all splits in flight
         const int q4 = HP / 4, total = S * q4;
@@ -122,13 +312,10 @@ __global__ __launch_bounds__(THREADS) void kernel(Args g)
             float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
             if (r < ns && k < H) {
                 const float *src = g.a + w * g.a_stride + (int64_t)(s0 + r) * H + k;
-                float4 v[16];
-#pragma unroll
-                for (int q = 0; q < 16; ++q)
-                    if (q < g.splits) v[q] = *(const float4 *)(src + q * plane);
-#pragma unroll
-                for (int q = 0; q < 16; ++q)
-                    if (q < g.splits) { acc.x += v[q].x; acc.y += v[q].y; acc.z += v[q].z; acc.w += v[q].w; }
+                if (g.splits <= 2) acc = split_sum<2>(src, plane, g.splits);
+                else if (g.splits <= 4) acc = split_sum<4>(src, plane, g.splits);
+                else if (g.splits <= 8) acc = split_sum<8>(src, plane, g.splits);
+                else acc = split_sum<16>(src, plane, g.splits);
                 const float4 bv = *(const float4 *)(bin + k);
                 acc.x = fmaxf(acc.x + bv.x, 0.f); acc.y = fmaxf(acc.y + bv.y, 0.f);
                 acc.z = fmaxf(acc.z + bv.z, 0.f); acc.w = fmaxf(acc.w + bv.w, 0.f);
@@ -170,140 +357,17 @@ __global__ __launch_bounds__(THREADS) void kernel(Args g)
     if (tid < 16) al[S * HP + tid] = 0.f;
     __syncthreads();
 
-    // ---- logits z = a W^T: wavefront = (16-sample block, slice of k); partial sums meet in LDS
-    {
-        const int MB = S / 16, KS = WAVES / MB;
-        const int mb = wave % MB, ks = wave / MB;
-        const int quads = HP / 4, per = (quads + KS - 1) / KS;
-        const int q_end = min(quads, (ks + 1) * per);
-        const float *ap = al + (16 * mb + l16) * HP + lq, *wp = Wl + min(l16, C) * HP + lq;
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-        for (int q = ks * per; q < q_end; ++q)
-            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ap[4 * q], wp[4 * q], acc, 0, 0, 0);
-#pragma unroll
-        for (int v = 0; v < 4; ++v) zp[(wave * 16 + 4 * lq + v) * 16 + l16] = acc[v];
-        __syncthreads();
-        // sample s, class c: the slices in order, then the bias
-        for (int e = tid; e < S * 16; e += THREADS) {
-            const int s = e >> 4, c = e & 15;
-            float z = 0.f;
-            for (int q = 0; q < KS; ++q) z += zp[((q * MB + (s >> 4)) * 16 + (s & 15)) * 16 + c];
-            zl[e] = c < C ? z + bg[c] : 0.f;
-        }
-    }
-    __syncthreads();
-
-    // ---- softmax, loss and dz per sample (rows of samples beyond the batch stay zero)
-    float loss_part = 0.f;
-    if (tid < MAX_S) {
-        float *zs = zl + tid * MAX_C;
-        if (tid < ns) {
-            float m = zs[0];
-            for (int c = 1; c < C; ++c) m = fmaxf(m, zs[c]);
-            float sum = 0.f;
-            for (int c = 0; c < C; ++c) sum += expf(zs[c] - m);
-            int label = g.y[(int64_t)w * g.B + s0 + tid];
-            if (label < 0 || label >= C) {              // clamped for memory safety, reported by dbw_check
-                *g.err = DBW_ERR_INVALID;
-                label = label < 0 ? 0 : C - 1;
-            }
-            const float inv = 1.0f / sum, inv_b = 1.0f / (float)g.B;
-            if (LOSS == DBW_LOSS_XENT) {
-                loss_part = logf(sum) + m - zs[label];
-                for (int c = 0; c < C; ++c) zs[c] = (expf(zs[c] - m) * inv - (c == label ? 1.f : 0.f)) * inv_b;
-            } else {
-                float f = 0.f, inner = 0.f;
-                for (int c = 0; c < C; ++c) {
-                    const float p = expf(zs[c] - m) * inv, e = p - (c == label ? 1.f : 0.f);
-                    f += e * e;
-                    inner += p * e;
-                }
-                for (int c = 0; c < C; ++c) {
-                    const float p = expf(zs[c] - m) * inv, e = p - (c == label ? 1.f : 0.f);
-                    zs[c] = 2.f * p * (e - inner) * inv_b;
-                }
-                loss_part = f;
-            }
-        } else {
-            for (int c = 0; c < MAX_C; ++c) zs[c] = 0.f;
-        }
-    }
-    __syncthreads();
-
-    float *__restrict__ part = g.part + w * g.part_stride + (int64_t)chunk * partial_floats(H, C, g.bprev_off >= 0);
-    float *__restrict__ out_w = chunks == 1 ? g.grads + w * g.p_stride + g.w_off : part;
-    float *__restrict__ out_b = chunks == 1 ? g.grads + w * g.p_stride + g.b_off : part + (size_t)C * H;
-    float *__restrict__ out_bprev = g.bprev_off < 0 ? nullptr
-                                    : (chunks == 1 ? g.grads + w * g.p_stride + g.bprev_off : part + (size_t)C * H + C);
-    float *__restrict__ da = g.da ? g.da + w * g.da_stride + (int64_t)s0 * g.da_ld : nullptr;
-    const int NB = (H + 15) / 16;                       // 16-column blocks of the input dimension
-
-    for (int nb = wave; nb < NB; nb += WAVES) {
-        const int col = 16 * nb + l16;
-        // ---- dW[class][col] = sum over samples of dz[sample][class] a[sample][col]
-        {
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-            for (int k0 = 0; k0 < S; k0 += 4)
-                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(zl[(k0 + lq) * MAX_C + l16], al[(k0 + lq) * HP + col], acc,
-                                                           0, 0, 0);
-            if (col < H) {
-#pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    if (4 * lq + v < C) out_w[(4 * lq + v) * H + col] = acc[v];
-            }
-        }
-        // ---- da[sample][col] = sum over classes of dz[sample][class] W[class][col], masked; its column sums
-        if (da) {
-            float colsum = 0.f;
-            for (int mb = 0; mb < S / 16; ++mb) {
-                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(zl[(16 * mb + l16) * MAX_C + 4 * j + lq],
-                                                               Wl[min(4 * j + lq, C) * HP + col], acc, 0, 0, 0);
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int s = 16 * mb + 4 * lq + v;
-                    float d = acc[v];
-                    if (g.mask && !(al[s * HP + col] > 0.f)) d = 0.f;
-                    if (s < ns && col < H) da[(int64_t)s * g.da_ld + col] = d;
-                    colsum += d;                        // rows beyond the batch have dz = 0
-                }
-            }
-            colsum += __shfl_xor(colsum, 16, 64);
-            colsum += __shfl_xor(colsum, 32, 64);
-            if (out_bprev && lq == 0 && col < H) out_bprev[col] = colsum;
-        }
-    }
-    if (tid < C) {
-        float sum = 0.f;
-        for (int s = 0; s < ns; ++s) sum += zl[s * MAX_C + tid];
-        out_b[tid] = sum;
-    }
-    // ---- the chunk's loss: its samples in a fixed order (tree in LDS)
-    if (g.loss) {
-        float *red = zp;
-        if (tid < MAX_S) red[tid] = loss_part;
-        __syncthreads();
-        for (int o = MAX_S / 2; o > 0; o >>= 1) {
-            if (tid < o) red[tid] += red[tid + o];
-            __syncthreads();
-        }
-        if (tid == 0) {
-            if (chunks == 1) g.loss[w] = red[0] / (float)g.B;
-            else part[partial_floats(H, C, g.bprev_off >= 0) - 1] = red[0];
-        }
-    }
+    body<LOSS>(g, zl, zp, Wl, al, S, w, chunk, chunks, false, early);
 }
 
 // Sum of the per-chunk partials in chunk order -> dW, db, the bias gradient below, the loss.
-// grid = (ceil(E / 256), workers), E = partial_floats.
-__global__ __launch_bounds__(256) void reduce_kernel(Args g, int chunks)
+// Blocks bx = 0 .. ceil(E / 256) - 1 of 256 threads per worker w, E = partial_floats.
+__device__ __forceinline__ void reduce_body(const Args &g, int chunks, int bx, int w)
 {
-    const int w = blockIdx.y, H = g.H, C = g.C;
+    const int H = g.H, C = g.C;
     const int n_w = C * H, n_b = C, n_p = g.bprev_off >= 0 ? H : 0;
     const int64_t E = partial_floats(H, C, g.bprev_off >= 0);
-    const int e = blockIdx.x * 256 + threadIdx.x;
+    const int e = bx * 256 + threadIdx.x;
     if (e >= E || (e == E - 1 && !g.loss)) return;
     const float *__restrict__ all = g.part + w * g.part_stride;
     float *__restrict__ gw = g.grads + w * g.p_stride;
@@ -320,5 +384,8 @@ __global__ __launch_bounds__(256) void reduce_kernel(Args g, int chunks)
     else if (e < n_w + n_b + n_p) gw[g.bprev_off + (e - n_w - n_b)] = sum;
     else g.loss[w] = sum / (float)g.B;
 }
+
+// grid = (ceil(E / 256), workers)
+__global__ __launch_bounds__(256) void reduce_kernel(Args g, int chunks) { reduce_body(g, chunks, blockIdx.x, blockIdx.y); }
 
 }  // namespace fchead

@@ -11,6 +11,8 @@
 #include "bgemm.h"
 #include "fc_batch32.h"
 #include "fc_head.h"
+#include "mlp_chain.h"
+#include "mlp_wgrad.h"
 #include "dbw_internal.h"
 
 namespace {
@@ -198,11 +200,49 @@ HeadPlan head_plan(int L, const int32_t *dims, int B, int workers)
     return hp;
 }
 
+// The whole chain of layers in one launch (mlp_chain.h) applies to equal hidden widths of 128, 256 or 512, an
+// input width that divides by 16, at most 16 classes, and operands on 16-byte boundaries.  S = samples per
+// workgroup: the one that needs the least time when every CU takes one workgroup at a time (ties: the larger).
+struct ChainPlan {
+    bool use;
+    int S, chunks;
+    size_t lds;
+};
+ChainPlan chain_plan(int L, const int32_t *dims, int B, int workers, int grad_path)
+{
+    ChainPlan cp{false, 0, 0, 0};
+    if (grad_path == DBW_GRAD_LAYERS || L < 2 || L > mlpchain::MAX_L || dims[L] > fchead::MAX_C) return cp;
+    const int H = dims[1];
+    if (H != 128 && H != 256 && H != 512) return cp;
+    for (int l = 2; l < L; ++l)
+        if (dims[l] != H) return cp;
+    if (dims[0] % 16 != 0 || dims[0] <= 0) return cp;
+    int64_t best = 0;
+    for (int S = 64; S >= 16; S -= 16) {
+        if (mlpchain::lds_bytes(dims[0], H, dims[L], S, L) > fchead::LDS_LIMIT) continue;
+        const int chunks = (B + S - 1) / S;
+        if (chunks > fchead::MAX_CHUNKS) continue;
+        const int64_t cost = ((int64_t)chunks * workers + 255) / 256 * S;
+        if (cp.S == 0 || cost < best) {
+            best = cost;
+            cp.S = S;
+            cp.chunks = chunks;
+        }
+    }
+    if (cp.S == 0) return cp;
+    // worth it when the workgroups keep at least half of the chip busy; otherwise the layered path, which
+    // splits its products over all CUs, wins
+    if (grad_path != DBW_GRAD_CHAIN && (int64_t)B * workers * 2 < best * 256) return cp;
+    cp.lds = mlpchain::lds_bytes(dims[0], H, dims[L], cp.S, L);
+    cp.use = true;
+    return cp;
+}
+
 int64_t act_floats(int L, const int32_t *dims, int B)
 {
     int64_t n = 0;
     for (int l = 1; l <= L; ++l) n += (int64_t)B * dims[l];
-    return n;
+    return (n + 3) / 4 * 4;          // the deltas and the partial sums behind them keep the 16-byte alignment
 }
 
 }  // namespace
@@ -215,6 +255,11 @@ int64_t dbw_fc_scratch_per_worker(int L, const int32_t *dims, int B)
     if (dims[L] <= fchead::MAX_C)      // partial sums of the fused head, at its smaller chunk size, behind the split partials
         part += (int64_t)((B + 15) / 16) * fchead::partial_floats(dims[L - 1], dims[L], L > 1);
     return 2 * act_floats(L, dims, B) + (part + 3) / 4 * 4;
+}
+
+bool dbw_fc_chain_shape_ok(int L, const int32_t *dims, int B, int workers)
+{
+    return chain_plan(L, dims, B, workers, DBW_GRAD_CHAIN).use;
 }
 
 // Forward and backward pass of a stack of fully connected layers for all workers.
@@ -238,8 +283,19 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
     const float *params = a.params;
     float *grads = a.grads;
 
-    const HeadPlan head = head_plan(L, dims, B, N);
-    const int L_gemm = head.use ? L - 1 : L;         // layers that go through the GEMM kernels
+    HeadPlan head = head_plan(L, dims, B, N);
+    ChainPlan chain = chain_plan(L, dims, B, N, a.grad_path);
+    if (chain.use && !(a.din == nullptr && a.in_ld % 4 == 0 && a.in_stride % 4 == 0 && fc32::aligned16(a.in) &&
+                       fc32::aligned16(params) && c->ld % 4 == 0 && a.param_off % 4 == 0 && fc32::aligned16(act) &&
+                       wstride % 4 == 0 && per % 4 == 0))
+        chain.use = false;
+    if (a.grad_path == DBW_GRAD_CHAIN && !chain.use) return DBW_ERR_UNSUPPORTED;
+    if (chain.use) {      // the head runs inside the chain, on the chain's chunks
+        head.use = true;
+        head.S = chain.S;
+        head.chunks = chain.chunks;
+    }
+    const int L_gemm = chain.use ? 0 : (head.use ? L - 1 : L);         // layers that go through the forward GEMM kernels
     // The output of layer L - 1 feeds nothing but the head.  When its forward product is split along k, the
     // head sums the partial products itself (same order, then bias and ReLU) and the reduction launch is saved.
     int head_splits = 0;
@@ -318,7 +374,7 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
         DBW_HIP(bgemm::launch<64>(A, Bm, E, B, dims[l], dims[l - 1], N, s));
     }
     if (head.use) {
-        // last layer, loss and its whole backward pass in one launch
+        // last layer, loss and its whole backward pass in one launch (with the chain: the layers below as well)
         fchead::Args h{};
         h.B = B; h.H = dims[L - 1]; h.C = dims[L]; h.S = head.S;
         if (L == 1) {
@@ -343,6 +399,88 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
         for (int q = 1; q <= L; ++q) split_floats = std::max<int64_t>(split_floats, (int64_t)MAX_SPLITS * B * dims[q]);
         h.part = act + 2 * per + (split_floats + 3) / 4 * 4; h.part_stride = wstride;
         h.err = c->err;
+        if (chain.use) {
+            mlpchain::Args g{};
+            g.B = B; g.L = L; g.K0 = dims[0]; g.H = dims[1]; g.C = dims[L];
+            g.chunks = chain.chunks; g.workers = N; g.loss_kind = a.loss_kind;
+            g.x = a.in; g.x_ld = a.in_ld; g.x_stride = a.in_stride;
+            g.params = params; g.p_stride = c->ld;
+            g.act = act; g.act_stride = wstride;
+            for (int l = 1; l <= L; ++l) {
+                g.w_off[l] = w_off[l]; g.b_off[l] = b_off[l]; g.a_off[l] = a_off[l]; g.dz_off[l] = dz_off[l];
+            }
+            h.a = nullptr; h.da = nullptr;
+            g.head = h;
+            const int total = chain.chunks * N;
+            const dim3 grid((total + mlpchain::XCDS - 1) / mlpchain::XCDS * mlpchain::XCDS);
+            auto go = [&](auto kern) -> int {
+                dbw_timer tm(c, "mlp_chain_kernel", s);
+                hipLaunchKernelGGL(kern, grid, dim3(mlpchain::THREADS), chain.lds, s, g);
+                DBW_HIP(hipGetLastError());
+                return DBW_OK;
+            };
+            const int rb = chain.S / 16, cb = dims[1] / 128;
+            int rc = DBW_ERR_UNSUPPORTED;
+            switch (rb * 8 + cb) {
+            case 1 * 8 + 1: rc = go(mlpchain::kernel<1, 1>); break;
+            case 1 * 8 + 2: rc = go(mlpchain::kernel<1, 2>); break;
+            case 1 * 8 + 4: rc = go(mlpchain::kernel<1, 4>); break;
+            case 2 * 8 + 1: rc = go(mlpchain::kernel<2, 1>); break;
+            case 2 * 8 + 2: rc = go(mlpchain::kernel<2, 2>); break;
+            case 2 * 8 + 4: rc = go(mlpchain::kernel<2, 4>); break;
+            case 3 * 8 + 1: rc = go(mlpchain::kernel<3, 1>); break;
+            case 3 * 8 + 2: rc = go(mlpchain::kernel<3, 2>); break;
+            case 3 * 8 + 4: rc = go(mlpchain::kernel<3, 4>); break;
+            case 4 * 8 + 1: rc = go(mlpchain::kernel<4, 1>); break;
+            case 4 * 8 + 2: rc = go(mlpchain::kernel<4, 2>); break;
+            case 4 * 8 + 4: rc = go(mlpchain::kernel<4, 4>); break;
+            }
+            if (rc != DBW_OK) return rc;
+
+            // weight and bias gradients of the layers below the head: one launch, and one more that adds its
+            // split sums and the head's per-chunk sums
+            mlpwgrad::Args q{};
+            q.B = B; q.H = dims[1]; q.layers = L - 1; q.workers = N;
+            int tiles = 0;
+            for (int l = 1; l < L; ++l) {
+                q.n_cols[l] = dims[l - 1];
+                q.tile_begin[l] = tiles;
+                tiles += (dims[1] / 64) * ((dims[l - 1] + 63) / 64);
+                q.want_db[l] = l < L - 1;                 // the head has the bias gradient of the layer below it
+                q.dz_off[l] = dz_off[l];
+                q.a[l] = l == 1 ? a.in : act + a_off[l - 1];
+                q.a_ld[l] = l == 1 ? a.in_ld : dims[l - 1];
+                q.a_stride[l] = l == 1 ? a.in_stride : wstride;
+                q.w_off[l] = w_off[l];
+            }
+            q.tile_begin[L] = tiles;
+            q.w_off[L] = w_off[L];
+            q.dz = act; q.dz_stride = wstride;
+            q.grads = grads; q.g_stride = c->ld;
+            q.part = act + 2 * per; q.part_stride = wstride;
+            const int64_t len = w_off[L] - w_off[1];
+            int splits = (int)std::min<int64_t>(8, std::max<int64_t>(1, (1280 + (int64_t)tiles * N / 2) / ((int64_t)tiles * N)));
+            splits = std::min(splits, (B + 15) / 16);
+            splits = (int)std::min<int64_t>(splits, std::max<int64_t>(1, split_floats / len));
+            q.splits = splits;
+            q.kper = ((B + splits - 1) / splits + 15) / 16 * 16;
+            {
+                dbw_timer tm(c, "mlp_wgrad_kernel", s);
+                const int wgs = tiles * N * splits;
+                hipLaunchKernelGGL(mlpwgrad::kernel, dim3((wgs + mlpwgrad::XCDS - 1) / mlpwgrad::XCDS * mlpwgrad::XCDS),
+                                   dim3(mlpwgrad::THREADS), 0, s, q);
+                DBW_HIP(hipGetLastError());
+            }
+            const int wgrad_blocks = splits > 1 ? (int)((len / 4 + 255) / 256) : 0;
+            const int head_blocks = head.chunks > 1 ? (int)((fchead::partial_floats(h.H, h.C, true) + 255) / 256) : 0;
+            if (wgrad_blocks + head_blocks > 0) {
+                dbw_timer tm(c, "mlp_reduce_kernel", s);
+                hipLaunchKernelGGL(mlpwgrad::reduce_kernel, dim3(wgrad_blocks + head_blocks, N), dim3(256), 0, s, q,
+                                   wgrad_blocks, h, head.chunks);
+                DBW_HIP(hipGetLastError());
+            }
+            return DBW_OK;
+        } else {
         const dim3 grid(head.chunks, N);
         const size_t lds = fchead::lds_bytes(h.H, h.C, h.S);
         const bool vec = h.H % 4 == 0 && h.a_ld % 4 == 0 && h.a_stride % 4 == 0 && (uintptr_t)h.a % 16 == 0;
@@ -358,6 +496,7 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
         else if (mse) rc = vec ? go(fchead::kernel<DBW_LOSS_MSE, true>) : go(fchead::kernel<DBW_LOSS_MSE, false>);
         else rc = vec ? go(fchead::kernel<DBW_LOSS_XENT, true>) : go(fchead::kernel<DBW_LOSS_XENT, false>);
         if (rc != DBW_OK) return rc;
+        }
         if (head.chunks > 1) {
             const int64_t E = fchead::partial_floats(h.H, h.C, L > 1);
             dbw_timer tm(c, "fc_head_reduce", s);
@@ -377,7 +516,7 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
         DBW_HIP(hipGetLastError());
     }
     // backward
-    for (int l = L_gemm; l >= 1; --l) {
+    for (int l = head.use ? L - 1 : L; l >= 1; --l) {
         const bool fast = batch32_layer(B, dims[l - 1], dims[l], c->ld, w_off[l], params, grads) && wstride % 4 == 0 &&
                           dz_off[l] % 4 == 0 && fc32::aligned16(act);
         {   // dW_l = dz_l^T a_{l-1}
@@ -468,7 +607,13 @@ int dbw_fc_prepare()
                              (const void *)fchead::kernel<DBW_LOSS_XENT, true>,
                              (const void *)fchead::kernel<DBW_LOSS_XENT, false>,
                              (const void *)fchead::kernel<DBW_LOSS_MSE, true, true>,
-                             (const void *)fchead::kernel<DBW_LOSS_XENT, true, true>};
+                             (const void *)fchead::kernel<DBW_LOSS_XENT, true, true>,
+                             (const void *)mlpchain::kernel<1, 1>, (const void *)mlpchain::kernel<1, 2>,
+                             (const void *)mlpchain::kernel<1, 4>, (const void *)mlpchain::kernel<2, 1>,
+                             (const void *)mlpchain::kernel<2, 2>, (const void *)mlpchain::kernel<2, 4>,
+                             (const void *)mlpchain::kernel<3, 1>, (const void *)mlpchain::kernel<3, 2>,
+                             (const void *)mlpchain::kernel<3, 4>, (const void *)mlpchain::kernel<4, 1>,
+                             (const void *)mlpchain::kernel<4, 2>, (const void *)mlpchain::kernel<4, 4>};
     for (const void *k : kernels)
         DBW_HIP(hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)fchead::LDS_LIMIT));
     done = true;
@@ -499,5 +644,6 @@ int dbw_launch_grad_mlp(dbw_ctx *c, const float *params, const float *bx, const 
     a.act_stride = dbw_fc_scratch_per_worker(m.n_layers, m.dims, m.batch);
     a.y = by;
     a.loss = loss;
+    a.grad_path = m.grad_path;
     return dbw_fc_forward_backward(c, a, s);
 }

@@ -1,0 +1,344 @@
+// Forward pass, loss and the data-gradient half of the backward pass of a small multilayer
+// perceptron in one launch (Section 2.1, stochastic gradient of the local loss; the 2NN of
+// Appendix B: equal hidden widths, batch 1 024 per worker).
+//
+// As one GEMM launch per layer these products are short (1.3 GFLOP each for the 2NN on 10 workers):
+// every launch pays its own ramp-up, first-tile latency and tail, and the matrix cores sit idle for a
+// third of it.  Nothing but the weight gradients needs more than one sample at a time, so a workgroup
+// here takes S = 16 RB samples of one worker through the whole chain with the activations in LDS:
+//   a_l = relu(a_{l-1} W_l^T + b_l), l = 1 .. L - 1     (a_0 = the batch)
+//   head (fc_head.h): logits, loss, dz_L, dW_L, db_L, dz_{L-1} = (dz_L W_L) masked by a_{L-1} > 0, db_{L-1}
+//   dz_{l-1} = (dz_l W_l) masked by a_{l-1} > 0, l = L - 1 .. 2, in place over a_{l-1}
+// and writes a_1 .. a_{L-2} and dz_1 .. dz_{L-1} to the worker's scratch block, from where the weight
+// gradients dW_l = dz_l^T a_{l-1} (sums over the whole batch) are taken by the GEMM kernels.
+//
+// Products run on v_mfma_f32_16x16x4_f32 (true fp32).  A wavefront owns 16 CB output columns of all
+// S rows: RB x CB accumulator tiles.  Its A fragments come from the LDS image of the layer's input
+// (one 128-bit read per 16 rows and 16 k), its B fragments straight from the weights in global
+// memory (L2), since no other wavefront of the workgroup wants the same ones; they are fetched one
+// 64-wide k-chunk ahead.  The matrix instruction only asks that lane group q of A and of B carry the
+// same k, not which one, so a lane's four values of a 128-bit read serve four instructions:
+//   forward, W_l [out][in], a lane reads W[n][k0 + 4 q .. + 4]: instruction e takes k = k0 + 4 q + e;
+//   backward, a lane reads the CB consecutive columns W[k0 + 4 q + j][n0 + CB c .. + CB] for
+//   j = 0 .. 3: instruction (j, cb) takes k = k0 + 4 q + j and output column n0 + CB c + cb.
+// Workgroup ids are renumbered so that the ids one XCD receives cover consecutive chunks of few
+// workers, whose weights then stay in that XCD's L2.
+#pragma once
+
+#include "fc_head.h"
+
+namespace mlpchain {
+
+using fchead::f32x4;
+using fchead::pick;
+constexpr int THREADS = fchead::THREADS, WAVES = THREADS / 64;
+constexpr int XCDS = 8;
+constexpr int MAX_L = 8;
+
+struct Args {
+    int B, L, K0, H, C;              // batch, layers (the head is layer L), input width, hidden width, classes
+    int chunks, workers, loss_kind;
+    const float *x;                  // [B][x_ld] per worker (stride x_stride)
+    int64_t x_ld, x_stride;
+    const float *params;             // worker rows of stride p_stride; W_l [out][in] at w_off[l], b_l at b_off[l]
+    int64_t p_stride;
+    int64_t w_off[MAX_L + 1], b_off[MAX_L + 1];
+    float *act;                      // per-worker scratch (stride act_stride): a_l [B][H] at a_off[l], dz_l at dz_off[l]
+    int64_t act_stride;
+    int64_t a_off[MAX_L + 1], dz_off[MAX_L + 1];
+    fchead::Args head;               // the head's arguments; its a and da are not used (both stay in LDS)
+};
+
+// LDS: the head's logits, partial logits and W_L image, then max(L - 1, 2) activation slots of
+// S x max(pitch(H), pitch(K0)) floats (+ 16 of slack): a_l in slot l - 1, the batch chunk in slot 1
+// (a_2 replaces it once layer 1 is done).
+__host__ __device__ inline int64_t slot_floats(int K0, int H, int S)
+{
+    const int hp = fchead::row_pitch(H), p0 = fchead::row_pitch(K0);
+    return (int64_t)S * (hp > p0 ? hp : p0) + 16;
+}
+__host__ __device__ inline size_t lds_bytes(int K0, int H, int C, int S, int L)
+{
+    const int slots = L - 1 > 2 ? L - 1 : 2;
+    return sizeof(float) * ((size_t)fchead::MAX_S * fchead::MAX_C + (size_t)WAVES * 256 +
+                            (size_t)(C + 1) * fchead::row_pitch(H) + 16 + (size_t)slots * slot_floats(K0, H, S));
+}
+
+template <int N>
+struct alignas(4 * N) Vec {
+    float v[N];
+};
+
+// The B values of one 64-wide k-chunk for a wavefront: 16 CB floats per lane.
+//   forward:  v[u][4 cb + e] = W[n0 + 16 cb + l16][k0 + 16 u + 4 lq + e]
+//   backward: v[u][CB j + cb] = W[k0 + 16 u + 4 lq + j][n0 + CB l16 + cb]
+template <int CB>
+struct BRegs {
+    float v[4][4 * CB];
+};
+
+template <int CB>
+__device__ __forceinline__ void load_fwd(BRegs<CB> &b, const float *__restrict__ Wg, int K, int k0, int n0, int lane)
+{
+    const int l16 = lane & 15, lq = lane >> 4;
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) {
+        const float *p = Wg + (int64_t)(n0 + 16 * cb + l16) * K + k0 + 4 * lq;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const f32x4 q = *(const f32x4 *)(p + 16 * u);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) b.v[u][4 * cb + e] = q[e];
+        }
+    }
+}
+
+template <int CB>
+__device__ __forceinline__ void load_bwd(BRegs<CB> &b, const float *__restrict__ Wg, int ldw, int k0, int n0, int lane)
+{
+    const int l16 = lane & 15, lq = lane >> 4;
+    const float *p = Wg + (int64_t)(k0 + 4 * lq) * ldw + n0 + CB * l16;
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const Vec<CB> q = *(const Vec<CB> *)(p + (int64_t)(16 * u + j) * ldw);
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) b.v[u][CB * j + cb] = q.v[cb];
+        }
+}
+
+// acc += A(rows of `in`, k0 .. k0 + 63) x (the chunk in b); FWD tells which of the two layouts b has.
+template <int RB, int CB, bool FWD>
+__device__ __forceinline__ void chunk_mfma(f32x4 (&acc)[RB][CB], const float *ap, int pitch, int k0, const BRegs<CB> &b)
+{
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        f32x4 av[RB];
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) av[rb] = *(const f32x4 *)(ap + 16 * rb * pitch + k0 + 16 * u);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+                    acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[rb][e], FWD ? b.v[u][4 * cb + e] : b.v[u][CB * e + cb],
+                                                                       acc[rb][cb], 0, 0, 0);
+    }
+}
+
+// The k loop of one product.  b0 holds chunk 0 on entry (when K >= 64); the chunks alternate between b0 and a
+// second set, each fetched while the other is multiplied, so that a fetch has a whole chunk of matrix
+// instructions (of both wavefronts of the SIMD) to arrive.  K is a multiple of 16; the 16-wide groups behind the
+// last whole chunk are fetched and multiplied one by one.
+template <int RB, int CB, bool FWD>
+__device__ __forceinline__ void product(f32x4 (&acc)[RB][CB], const float *in, int pitch, int K, const float *__restrict__ Wg,
+                                        int ldw, int n0, int lane, BRegs<CB> &b0)
+{
+    const int l16 = lane & 15, lq = lane >> 4;
+    const float *ap = in + l16 * pitch + 4 * lq;
+    const int nch = K / 64;
+    BRegs<CB> b1;
+    auto load = [&](BRegs<CB> &b, int kc) {
+        if (FWD) load_fwd<CB>(b, Wg, ldw, 64 * kc, n0, lane);
+        else load_bwd<CB>(b, Wg, ldw, 64 * kc, n0, lane);
+    };
+    for (int kc = 0; kc < nch; kc += 2) {
+        const bool two = kc + 1 < nch;
+        if (two) load(b1, kc + 1);
+        __builtin_amdgcn_sched_barrier(0);               // the fetch is issued before the multiplies, not after
+        chunk_mfma<RB, CB, FWD>(acc, ap, pitch, 64 * kc, b0);
+        if (two) {
+            if (kc + 2 < nch) load(b0, kc + 2);
+            __builtin_amdgcn_sched_barrier(0);
+            chunk_mfma<RB, CB, FWD>(acc, ap, pitch, 64 * (kc + 1), b1);
+        }
+    }
+    for (int k = 64 * nch; k < K; k += 16) {
+        f32x4 av[RB];
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) av[rb] = *(const f32x4 *)(ap + 16 * rb * pitch + k);
+        if (FWD) {
+            f32x4 bv[CB];
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) bv[cb] = *(const f32x4 *)(Wg + (int64_t)(n0 + 16 * cb + l16) * ldw + k + 4 * lq);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                    for (int cb = 0; cb < CB; ++cb)
+                        acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[rb][e], bv[cb][e], acc[rb][cb], 0, 0, 0);
+        } else {
+            Vec<CB> bv[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) bv[j] = *(const Vec<CB> *)(Wg + (int64_t)(k + 4 * lq + j) * ldw + n0 + CB * l16);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                    for (int cb = 0; cb < CB; ++cb)
+                        acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[rb][j], bv[j].v[cb], acc[rb][cb], 0, 0, 0);
+        }
+    }
+}
+
+template <int RB, int CB>
+__device__ __forceinline__ void zero(f32x4 (&acc)[RB][CB])
+{
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) acc[rb][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+}
+
+// Forward epilogue: out[s][n] = relu(acc + bias[n]) for this wavefront's columns n = n0 + 16 cb + l16.
+// D: register r of lane (l16, lq) is row 4 lq + r, column l16 of the 16 x 16 tile.
+template <int RB, int CB>
+__device__ __forceinline__ void store_forward(const f32x4 (&acc)[RB][CB], const float (&bcol)[CB], float *out, int HP, int n0,
+                                              int lane)
+{
+    const int l16 = lane & 15, lq = lane >> 4;
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) {
+        const int col = n0 + 16 * cb + l16;
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float v = acc[rb][cb][r] + bcol[cb];
+                out[(16 * rb + 4 * lq + r) * HP + col] = v > 0.f ? v : 0.f;
+            }
+    }
+}
+
+// Backward epilogue: prev[s][n] = acc where prev[s][n] > 0, else 0, columns n = n0 + CB l16 + cb.
+template <int RB, int CB>
+__device__ __forceinline__ void store_backward(const f32x4 (&acc)[RB][CB], float *prev, int HP, int n0, int lane)
+{
+    typedef Vec<CB> vec;
+    const int l16 = lane & 15, lq = lane >> 4;
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            vec *p = (vec *)(prev + (16 * rb + 4 * lq + r) * HP + n0 + CB * l16);
+            const vec a = *p;
+            vec d;
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) d.v[cb] = a.v[cb] > 0.f ? acc[rb][cb][r] : 0.f;
+            *p = d;
+        }
+}
+
+// rows x H floats from an LDS image to global rows of H floats, 128 bits per thread and step.
+__device__ __forceinline__ void copy_out(const float *src, int pitch, float *__restrict__ dst, int H, int rows, int tid)
+{
+    const int q4 = H / 4, total = rows * q4;
+    for (int e0 = 0; e0 < total; e0 += 4 * THREADS) {       // four LDS reads in flight, then their stores
+        float4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int e = min(e0 + tid + u * THREADS, total - 1), r = e / q4;
+            v[u] = *(const float4 *)(src + r * pitch + 4 * (e - r * q4));
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int e = e0 + tid + u * THREADS, r = e / q4;
+            if (e < total) *(float4 *)(dst + (int64_t)r * H + 4 * (e - r * q4)) = v[u];
+        }
+    }
+}
+
+// grid = workers x chunks rounded up to a multiple of XCDS; dynamic LDS = lds_bytes(...).
+template <int RB, int CB>
+__global__ __launch_bounds__(THREADS) void kernel(Args g)
+{
+    extern __shared__ __attribute__((aligned(16))) float sm[];
+    constexpr int S = 16 * RB;
+    const int H = g.H, C = g.C, K0 = g.K0, HP = fchead::row_pitch(H), P0 = fchead::row_pitch(K0), Lh = g.L - 1;
+    const int per = gridDim.x / XCDS, id = (blockIdx.x % XCDS) * per + blockIdx.x / XCDS;
+    if (id >= g.workers * g.chunks) return;                // the whole workgroup: no barrier is left waiting
+    const int w = id / g.chunks, chunk = id - w * g.chunks;
+    const int s0 = chunk * S, ns = min(S, g.B - s0);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    float *zl = sm;
+    float *zp = zl + fchead::MAX_S * fchead::MAX_C;
+    float *Wl = zp + WAVES * 256;
+    float *slots = Wl + (C + 1) * HP + 16;
+    const int64_t Z = slot_floats(K0, H, S);
+    float *xl = slots + Z;
+    const float *__restrict__ pw = g.params + w * g.p_stride;
+    float *__restrict__ sw = g.act + w * g.act_stride;
+
+    // the first chunk of W_1 is on its way while the batch is staged; likewise every later product's first chunk
+    // is requested before the epilogue of the product before it
+    const int n0 = wave * 16 * CB;
+    BRegs<CB> b0;
+    if (K0 >= 64) load_fwd<CB>(b0, pw + pick(g.w_off, 1), K0, 0, n0, lane);
+    const fchead::Early early = fchead::fetch_early(g.head, w, s0, ns, tid);
+    fchead::stage_w(g.head, w, Wl, tid);
+    {   // the chunk of the batch, rows beyond it zero
+        const float *__restrict__ x = g.x + w * g.x_stride + (int64_t)s0 * g.x_ld;
+        const int q4 = K0 / 4, total = S * q4;
+        for (int e0 = 0; e0 < total; e0 += 8 * THREADS) {
+            float4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int e = e0 + tid + u * THREADS, r = e / q4, k = 4 * (e - r * q4);
+                v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (e < total && r < ns) v[u] = *(const float4 *)(x + (int64_t)r * g.x_ld + k);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int e = e0 + tid + u * THREADS, r = e / q4, k = 4 * (e - r * q4);
+                if (e < total) *(float4 *)(xl + r * P0 + k) = v[u];
+            }
+        }
+    }
+    __syncthreads();
+
+    f32x4 acc[RB][CB];
+    for (int l = 1; l <= Lh; ++l) {
+        const float *in = l == 1 ? xl : slots + (l - 2) * Z;
+        float *out = slots + (l - 1) * Z;
+        // what the head reads beyond the H columns of a row and behind the image must be zero (nobody reads this
+        // slot during this layer; the batch chunk that lay in slot 1 is dead from layer 2 on)
+        for (int e = tid; e < S * (HP - H); e += THREADS) out[(e / (HP - H)) * HP + H + e % (HP - H)] = 0.f;
+        if (tid < 16) out[S * HP + tid] = 0.f;
+        float bcol[CB];
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) bcol[cb] = pw[pick(g.b_off, l) + n0 + 16 * cb + (lane & 15)];
+        zero<RB, CB>(acc);
+        const int K = l == 1 ? K0 : H;
+        product<RB, CB, true>(acc, in, l == 1 ? P0 : HP, K, pw + pick(g.w_off, l), K, n0, lane, b0);
+        if (l < Lh) load_fwd<CB>(b0, pw + pick(g.w_off, l + 1), H, 0, n0, lane);
+        else if (Lh >= 2) load_bwd<CB>(b0, pw + pick(g.w_off, Lh), H, 0, n0, lane);     // waits in registers through the head
+        store_forward<RB, CB>(acc, bcol, out, HP, n0, lane);
+        __syncthreads();
+        if (l < Lh) copy_out(out, HP, sw + pick(g.a_off, l) + (int64_t)s0 * H, H, ns, tid);
+    }
+
+    float *top = slots + (Lh - 1) * Z;                     // a_{L-1}, then dz_{L-1}
+    if (g.loss_kind == DBW_LOSS_MSE)
+        fchead::body<DBW_LOSS_MSE>(g.head, zl, zp, Wl, top, S, w, chunk, g.chunks, true, early);
+    else
+        fchead::body<DBW_LOSS_XENT>(g.head, zl, zp, Wl, top, S, w, chunk, g.chunks, true, early);
+    __syncthreads();
+    copy_out(top, HP, sw + pick(g.dz_off, Lh) + (int64_t)s0 * H, H, ns, tid);
+
+    for (int l = Lh; l >= 2; --l) {
+        float *prev = slots + (l - 2) * Z;
+        zero<RB, CB>(acc);
+        product<RB, CB, false>(acc, slots + (l - 1) * Z, HP, H, pw + pick(g.w_off, l), H, n0, lane, b0);
+        if (l > 2) load_bwd<CB>(b0, pw + pick(g.w_off, l - 1), H, 0, n0, lane);
+        store_backward<RB, CB>(acc, prev, HP, n0, lane);
+        __syncthreads();
+        copy_out(prev, HP, sw + pick(g.dz_off, l - 1) + (int64_t)s0 * H, H, ns, tid);
+    }
+}
+
+}  // namespace mlpchain

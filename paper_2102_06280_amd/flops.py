@@ -23,6 +23,9 @@ def _mlp(cfg, dims):
         table.update({"mlp_forward_gemm": n * sum(fwd) / len(fwd), "mlp_wgrad_gemm": n * sum(fwd) / len(fwd)})
     if dgrad:
         table["mlp_dgrad_gemm"] = n * sum(dgrad) / len(dgrad)
+    # the same products when the whole chain of layers runs in one launch and the weight gradients in another
+    table["mlp_chain_kernel"] = n * (sum(fwd) + sum(dgrad)) + table["fc_head_kernel"]
+    table["mlp_wgrad_kernel"] = n * sum(fwd)
     return table
 
 

@@ -67,15 +67,16 @@ def test_binding_structs_match_the_header(tmp_path):
     from paper_2102_06280_amd import binding as B
     src = tmp_path / "layout.c"
     src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "dbw_measure.h"\n'
-                   'int main(void) { printf("%zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu\\n", sizeof(dbw_model), '
-                   'offsetof(dbw_model, loss), offsetof(dbw_model, dims), sizeof(dbw_opts), offsetof(dbw_opts, order), '
+                   'int main(void) { printf("%zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu\\n", sizeof(dbw_model), '
+                   'offsetof(dbw_model, loss), offsetof(dbw_model, dims), offsetof(dbw_model, grad_path), sizeof(dbw_opts), offsetof(dbw_opts, order), '
                    'offsetof(dbw_opts, mix_path), offsetof(dbw_opts, layout), offsetof(dbw_opts, model), '
                    'sizeof(dbw_kernel_time), offsetof(dbw_kernel_time, ms_total), offsetof(dbw_kernel_time, launches)); '
                    'return 0; }\n')
     exe = tmp_path / "layout"
     subprocess.run(["gcc", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
     got = [int(v) for v in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
-    want = [C.sizeof(B.dbw_model), B.dbw_model.loss.offset, B.dbw_model.dims.offset, C.sizeof(B.dbw_opts),
+    want = [C.sizeof(B.dbw_model), B.dbw_model.loss.offset, B.dbw_model.dims.offset, B.dbw_model.grad_path.offset,
+            C.sizeof(B.dbw_opts),
             B.dbw_opts.order.offset, B.dbw_opts.mix_path.offset, B.dbw_opts.layout.offset, B.dbw_opts.model.offset,
             C.sizeof(B.dbw_kernel_time), B.dbw_kernel_time.ms_total.offset, B.dbw_kernel_time.launches.offset]
     assert got == want

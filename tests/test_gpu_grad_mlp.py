@@ -49,9 +49,7 @@ SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("dims,batch,n,loss_kind", SHAPES,
-                         ids=[f"{'-'.join(map(str, s[0]))}-B{s[1]}-N{s[2]}-{s[3]}" for s in SHAPES])
-def test_mlp_gradients_match_oracle(B, orc, dims, batch, n, loss_kind):
+def check_gradients(B, orc, dims, batch, n, loss_kind, grad_path=0, expect=None):
     g = np.random.default_rng(401)
     desc = {"kind": "mlp", "dims": dims, "loss": loss_kind}
     d = inputs.param_count(desc)
@@ -63,7 +61,8 @@ def test_mlp_gradients_match_oracle(B, orc, dims, batch, n, loss_kind):
     x = g.standard_normal((n, batch, dims[0])).astype(np.float32)
     y = g.integers(0, dims[-1], (n, batch)).astype(np.int32)
     h = B.dbw_create(rowptr, colidx, n, d, ld=ld,
-                     model=B.make_model(B.MODEL_MLP, batch, dims, B.LOSS_MSE if loss_kind == "mse" else B.LOSS_XENT))
+                     model=B.make_model(B.MODEL_MLP, batch, dims, B.LOSS_MSE if loss_kind == "mse" else B.LOSS_XENT,
+                                        grad_path=grad_path))
     try:
         grads = torch.full((n, ld), 7.0, dtype=torch.float32, device="cuda")
         loss = torch.zeros(n, dtype=torch.float32, device="cuda")
@@ -71,7 +70,9 @@ def test_mlp_gradients_match_oracle(B, orc, dims, batch, n, loss_kind):
         B.dbw_grad(h, dev(params), dev(x), dev(y), grads, loss)
         kernels = set(B.dbw_get_timing(h))
         B.dbw_set_timing(h, False)
-        if batch == 32 and any(a % 512 == 0 and b % 32 == 0 for a, b in zip(dims[:-1], dims[1:])):
+        if expect is not None:
+            assert expect <= kernels, kernels
+        elif batch == 32 and any(a % 512 == 0 and b % 32 == 0 for a, b in zip(dims[:-1], dims[1:])):
             assert {"fc32_forward", "fc32_wgrad"} <= kernels, kernels       # the streaming kernels really ran
             if any(a % 512 == 0 and b % 32 == 0 for a, b in zip(dims[1:-1], dims[2:])):
                 assert "fc32_dgrad" in kernels, kernels
@@ -97,6 +98,63 @@ def test_mlp_gradients_match_oracle(B, orc, dims, batch, n, loss_kind):
         print(res.summary())
     finally:
         B.dbw_destroy(h)
+
+
+@pytest.mark.parametrize("dims,batch,n,loss_kind", SHAPES,
+                         ids=[f"{'-'.join(map(str, s[0]))}-B{s[1]}-N{s[2]}-{s[3]}" for s in SHAPES])
+def test_mlp_gradients_match_oracle(B, orc, dims, batch, n, loss_kind):
+    check_gradients(B, orc, dims, batch, n, loss_kind)
+
+
+# The chain of layers in one launch (equal hidden widths of 128, 256, 512): one, two and three hidden layers,
+# input widths with and without a whole 64-wide k-chunk, ragged last blocks of samples, both losses; batch and
+# worker counts chosen so that blocks of 16, 32, 48 and 64 samples are taken ("blocks" below).
+CHAIN_SHAPES = [
+    # dims, batch, workers, loss, blocks of
+    ([64, 128, 10], 50, 3, "xent", 16),
+    ([48, 128, 128, 128, 5], 100, 4, "mse", 16),
+    ([80, 512, 512, 16], 37, 2, "xent", 16),
+    ([784, 256, 256, 10], 70, 5, "xent", 16),
+    ([256, 256, 10], 1037, 3, "xent", 16),
+    ([128, 128, 128, 10], 509, 10, "mse", 32),
+    ([256, 256, 256, 10], 1024, 10, "xent", 48),
+    ([64, 512, 512, 10], 1500, 10, "xent", 64),
+]
+
+
+@pytest.mark.parametrize("dims,batch,n,loss_kind,blocks", CHAIN_SHAPES,
+                         ids=[f"{'-'.join(map(str, s[0]))}-B{s[1]}-N{s[2]}-{s[3]}" for s in CHAIN_SHAPES])
+def test_chain_gradients_match_oracle(B, orc, dims, batch, n, loss_kind, blocks):
+    check_gradients(B, orc, dims, batch, n, loss_kind, grad_path=B.GRAD_CHAIN, expect={"mlp_chain_kernel"})
+
+
+def test_chain_is_picked_for_the_2nn_and_refused_where_it_cannot_run(B):
+    rowptr, colidx = inputs.graph_ring(10)
+
+    def kernels_of(dims, batch, grad_path):
+        desc = {"kind": "mlp", "dims": dims, "loss": "mse"}
+        d = inputs.param_count(desc)
+        ld = inputs.pad_ld(d)
+        h = B.dbw_create(rowptr, colidx, 10, d, ld=ld, model=B.make_model(B.MODEL_MLP, batch, dims, B.LOSS_MSE,
+                                                                           grad_path=grad_path))
+        try:
+            B.dbw_set_timing(h, True)
+            B.dbw_grad(h, torch.zeros((10, ld), device="cuda"), torch.zeros((10, batch, dims[0]), device="cuda"),
+                       torch.zeros((10, batch), dtype=torch.int32, device="cuda"),
+                       torch.zeros((10, ld), device="cuda"), torch.zeros(10, device="cuda"))
+            return set(B.dbw_get_timing(h))
+        finally:
+            B.dbw_destroy(h)
+    assert "mlp_chain_kernel" in kernels_of([256, 256, 256, 10], 1024, B.GRAD_AUTO)
+    assert "mlp_chain_kernel" not in kernels_of([256, 256, 256, 10], 1024, B.GRAD_LAYERS)
+    assert "mlp_chain_kernel" not in kernels_of([256, 256, 256, 10], 16, B.GRAD_AUTO)       # too few blocks to fill the chip
+    for dims in ([256, 200, 10], [250, 256, 10], [256, 256, 128, 10], [256, 256, 20], [256, 10]):
+        desc = {"kind": "mlp", "dims": dims, "loss": "mse"}
+        d = inputs.param_count(desc)
+        with pytest.raises(B.DbwError) as e:
+            B.dbw_create(rowptr, colidx, 10, d, ld=inputs.pad_ld(d),
+                         model=B.make_model(B.MODEL_MLP, 64, dims, B.LOSS_MSE, grad_path=B.GRAD_CHAIN))
+        assert e.value.code == B.ERR_UNSUPPORTED, dims
 
 
 def test_softmax_zero_init_round_one(B, orc):
