@@ -113,14 +113,16 @@ __device__ __forceinline__ void stage_w(const Args &g, int w, float *Wl, int tid
 // the latency passes there and not between two barriers of the body.
 struct Early {
     float bias;      // b[tid % 16] (0 for the padding classes)
-    int label;       // y of sample s0 + tid of the chunk (threads tid < ns)
+    int label[2];    // y of samples tid / 16 and 32 + tid / 16 of the chunk (0 beyond it)
 };
 __device__ __forceinline__ Early fetch_early(const Args &g, int w, int s0, int ns, int tid)
 {
     Early e;
-    const int c = tid & 15;
+    const int c = tid & 15, s = tid >> 4;
     e.bias = c < g.C ? g.params[w * g.p_stride + g.b_off + c] : 0.f;
-    e.label = tid < ns ? g.y[(int64_t)w * g.B + s0 + tid] : 0;
+    const int32_t *__restrict__ y = g.y + (int64_t)w * g.B + s0;
+    e.label[0] = s < ns ? y[s] : 0;
+    e.label[1] = s + 32 < ns ? y[s + 32] : 0;
     return e;
 }
 
@@ -137,18 +139,33 @@ __device__ __forceinline__ void body(const Args &g, float *zl, float *zp, float 
     const int l16 = lane & 15, lq = lane >> 4;
     const int s0 = chunk * S, ns = min(S, g.B - s0);
 
-    // ---- logits z = a W^T: wavefront = (16-sample block, slice of k); partial sums meet in LDS
+    // ---- logits z = a W^T: wavefront = (16-sample block, slice of k); partial sums meet in LDS.
+    // A lane reads four consecutive k of its row with one 128-bit LDS read; lane group q of both operands then
+    // carries k = 16 g + 4 q + e in instruction e, which is all the matrix instruction asks for.  Two
+    // accumulators halve the chain of dependent instructions.
     {
         const int MB = S / 16, KS = WAVES / MB;
         const int mb = wave % MB, ks = wave / MB;
-        const int quads = HP / 4, per = (quads + KS - 1) / KS;
-        const int q_end = min(quads, (ks + 1) * per);
-        const float *ap = al + (16 * mb + l16) * HP + lq, *wp = Wl + min(l16, C) * HP + lq;
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-        for (int q = ks * per; q < q_end; ++q)
-            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ap[4 * q], wp[4 * q], acc, 0, 0, 0);
+        f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = acc0;
+        if (ks < KS) {
+            const int G = HP / 16, per = (G + KS - 1) / KS, g_end = min(G, (ks + 1) * per);
+            const float *ap = al + (16 * mb + l16) * HP + 4 * lq, *wp = Wl + min(l16, C) * HP + 4 * lq;
+#pragma unroll 2
+            for (int gk = ks * per; gk < g_end; ++gk) {
+                const f32x4 a4 = *(const f32x4 *)(ap + 16 * gk), w4 = *(const f32x4 *)(wp + 16 * gk);
+                acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[0], w4[0], acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[1], w4[1], acc1, 0, 0, 0);
+                acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[2], w4[2], acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[3], w4[3], acc1, 0, 0, 0);
+            }
+            if (ks == KS - 1) {     // the columns behind the last whole group of 16
+                const float *a1 = al + (16 * mb + l16) * HP + lq, *w1 = Wl + min(l16, C) * HP + lq;
+                for (int q = 4 * G; q < HP / 4; ++q)
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a1[4 * q], w1[4 * q], acc0, 0, 0, 0);
+            }
+        }
 #pragma unroll
-        for (int v = 0; v < 4; ++v) zp[(wave * 16 + 4 * lq + v) * 16 + l16] = acc[v];
+        for (int v = 0; v < 4; ++v) zp[(wave * 16 + 4 * lq + v) * 16 + l16] = acc0[v] + acc1[v];
         __syncthreads();
         // sample s, class c: the slices in order, then the bias
         for (int e = tid; e < S * 16; e += THREADS) {
@@ -160,39 +177,53 @@ __device__ __forceinline__ void body(const Args &g, float *zl, float *zp, float 
     }
     __syncthreads();
 
-    // ---- softmax, loss and dz per sample (rows of samples beyond the batch stay zero)
-    float loss_part = 0.f;
-    if (tid < MAX_S) {
-        float *zs = zl + tid * MAX_C;
-        if (tid < ns) {
-            float m = zs[0];
-            for (int c = 1; c < C; ++c) m = fmaxf(m, zs[c]);
-            float sum = 0.f;
-            for (int c = 0; c < C; ++c) sum += expf(zs[c] - m);
-            int label = early.label;
-            if (label < 0 || label >= C) {              // clamped for memory safety, reported by dbw_check
-                *g.err = DBW_ERR_INVALID;
-                label = label < 0 ? 0 : C - 1;
-            }
-            const float inv = 1.0f / sum, inv_b = 1.0f / (float)g.B;
-            if (LOSS == DBW_LOSS_XENT) {
-                loss_part = logf(sum) + m - zs[label];
-                for (int c = 0; c < C; ++c) zs[c] = (expf(zs[c] - m) * inv - (c == label ? 1.f : 0.f)) * inv_b;
-            } else {
-                float f = 0.f, inner = 0.f;
-                for (int c = 0; c < C; ++c) {
-                    const float p = expf(zs[c] - m) * inv, e = p - (c == label ? 1.f : 0.f);
-                    f += e * e;
-                    inner += p * e;
+    // ---- softmax, loss and dz: 16 lanes per sample, one class each; maxima and sums by butterflies over the 16
+    // lanes, so that every lane holds them.  Rows of samples beyond the batch become zero.  The per-sample losses
+    // go to red[0 .. 63] (the partial logits are dead) for the tree at the end.
+    float *red = zp;
+    {
+        const float inv_b = 1.0f / (float)g.B;
+#pragma unroll
+        for (int pass = 0; pass < 2; ++pass) {
+            const int s = (tid >> 4) + 32 * pass, c = tid & 15;
+            float *zs = zl + s * MAX_C;
+            float dzv = 0.f, lossv = 0.f;
+            if (s < ns) {                                       // the same for the 16 lanes of a sample
+                const bool real = c < C;
+                const float z = real ? zs[c] : -INFINITY;
+                float m = z;
+#pragma unroll
+                for (int o = 1; o < 16; o <<= 1) m = fmaxf(m, __shfl_xor(m, o, 16));
+                const float ex = real ? expf(z - m) : 0.f;
+                float sum = ex;
+#pragma unroll
+                for (int o = 1; o < 16; o <<= 1) sum += __shfl_xor(sum, o, 16);
+                int label = early.label[pass];
+                if (label < 0 || label >= C) {              // clamped for memory safety, reported by dbw_check
+                    *g.err = DBW_ERR_INVALID;
+                    label = label < 0 ? 0 : C - 1;
                 }
-                for (int c = 0; c < C; ++c) {
-                    const float p = expf(zs[c] - m) * inv, e = p - (c == label ? 1.f : 0.f);
-                    zs[c] = 2.f * p * (e - inner) * inv_b;
+                const float pr = ex * (1.0f / sum), hot = c == label ? 1.f : 0.f;
+                if (LOSS == DBW_LOSS_XENT) {
+                    float zl_ = c == label ? z : 0.f;           // z of the label's class, to every lane
+#pragma unroll
+                    for (int o = 1; o < 16; o <<= 1) zl_ += __shfl_xor(zl_, o, 16);
+                    lossv = logf(sum) + m - zl_;
+                    dzv = real ? (pr - hot) * inv_b : 0.f;
+                } else {
+                    const float er = real ? pr - hot : 0.f;
+                    float f = er * er, inner = pr * er;
+#pragma unroll
+                    for (int o = 1; o < 16; o <<= 1) {
+                        f += __shfl_xor(f, o, 16);
+                        inner += __shfl_xor(inner, o, 16);
+                    }
+                    lossv = f;
+                    dzv = 2.f * pr * (er - inner) * inv_b;
                 }
-                loss_part = f;
             }
-        } else {
-            for (int c = 0; c < MAX_C; ++c) zs[c] = 0.f;
+            zs[c] = dzv;
+            if (c == 0) red[s] = lossv;
         }
     }
     __syncthreads();
@@ -207,32 +238,48 @@ __device__ __forceinline__ void body(const Args &g, float *zl, float *zp, float 
 
     for (int nb = wave; nb < NB; nb += WAVES) {
         const int col = 16 * nb + l16;
-        // ---- dW[class][col] = sum over samples of dz[sample][class] a[sample][col]
+        // ---- dW[class][col] = sum over samples of dz[sample][class] a[sample][col]: the operands of 16 samples are
+        // read before their four instructions, two accumulators
         {
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-            for (int k0 = 0; k0 < S; k0 += 4)
-                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(zl[(k0 + lq) * MAX_C + l16], al[(k0 + lq) * HP + col], acc,
-                                                           0, 0, 0);
+            f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = acc0;
+            for (int k0 = 0; k0 < S; k0 += 16) {
+                float zv[4], av[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    zv[u] = zl[(k0 + 4 * u + lq) * MAX_C + l16];
+                    av[u] = al[(k0 + 4 * u + lq) * HP + col];
+                }
+                acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(zv[0], av[0], acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(zv[1], av[1], acc1, 0, 0, 0);
+                acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(zv[2], av[2], acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(zv[3], av[3], acc1, 0, 0, 0);
+            }
             if (col < H) {
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
-                    if (4 * lq + v < C) out_w[(4 * lq + v) * H + col] = acc[v];
+                    if (4 * lq + v < C) out_w[(4 * lq + v) * H + col] = acc0[v] + acc1[v];
             }
         }
-        // ---- da[sample][col] = sum over classes of dz[sample][class] W[class][col], masked; its column sums
+        // ---- da[sample][col] = sum over classes of dz[sample][class] W[class][col], masked; its column sums.
+        // Lane group q carries the classes 4 q + j in instruction j: one 128-bit read of dz per 16 samples.
         if (da || da_to_lds) {
+            float wv[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) wv[j] = Wl[min(4 * lq + j, C) * HP + col];
             float colsum = 0.f;
             for (int mb = 0; mb < S / 16; ++mb) {
+                const f32x4 zq = *(const f32x4 *)(zl + (16 * mb + l16) * MAX_C + 4 * lq);
+                float keep[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) keep[v] = al[(16 * mb + 4 * lq + v) * HP + col];
                 f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(zl[(16 * mb + l16) * MAX_C + 4 * j + lq],
-                                                               Wl[min(4 * j + lq, C) * HP + col], acc, 0, 0, 0);
+                for (int j = 0; j < 4; ++j) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(zq[j], wv[j], acc, 0, 0, 0);
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     const int s = 16 * mb + 4 * lq + v;
                     float d = acc[v];
-                    if (g.mask && !(al[s * HP + col] > 0.f)) d = 0.f;
+                    if (g.mask && !(keep[v] > 0.f)) d = 0.f;
                     if (da_to_lds) al[s * HP + col] = d;       // this wavefront alone reads and writes these columns
                     else if (s < ns && col < H) da[(int64_t)s * g.da_ld + col] = d;
                     colsum += d;                        // rows beyond the batch have dz = 0
@@ -250,9 +297,6 @@ __device__ __forceinline__ void body(const Args &g, float *zl, float *zp, float 
     }
     // ---- the chunk's loss: its samples in a fixed order (tree in LDS)
     if (g.loss) {
-        float *red = zp;
-        if (tid < MAX_S) red[tid] = loss_part;
-        __syncthreads();
         for (int o = MAX_S / 2; o > 0; o >>= 1) {
             if (tid < o) red[tid] += red[tid + o];
             __syncthreads();
