@@ -135,7 +135,8 @@ __device__ __forceinline__ void body(const Args &g, float *zl, float *zp, float 
                                      int chunks, bool da_to_lds, const Early &early)
 {
     const int H = g.H, C = g.C, HP = row_pitch(H);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);       // on the scalar unit: loops and branches on it are uniform
     const int l16 = lane & 15, lq = lane >> 4;
     const int s0 = chunk * S, ns = min(S, g.B - s0);
 

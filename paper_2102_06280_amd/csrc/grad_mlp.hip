@@ -441,11 +441,21 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
             // split sums and the head's per-chunk sums
             mlpwgrad::Args q{};
             q.B = B; q.H = dims[1]; q.layers = L - 1; q.workers = N;
-            int tiles = 0;
+            // 64 x 64 tiles when they alone give every CU two workgroups, else 64 x 32; if that still leaves CUs
+            // idle, the batch is split as well (partial tiles to scratch, one more launch to add them)
+            auto count_tiles = [&](int tn, int *begin) {
+                int t = 0;
+                for (int l = 1; l < L; ++l) {
+                    if (begin) begin[l] = t;
+                    t += (dims[1] / 64) * ((dims[l - 1] + tn - 1) / tn);
+                }
+                if (begin) begin[L] = t;
+                return t;
+            };
+            const int tn = (int64_t)count_tiles(64, nullptr) * N >= 512 ? 64 : 32;
+            const int tiles = count_tiles(tn, q.tile_begin);
             for (int l = 1; l < L; ++l) {
                 q.n_cols[l] = dims[l - 1];
-                q.tile_begin[l] = tiles;
-                tiles += (dims[1] / 64) * ((dims[l - 1] + 63) / 64);
                 q.want_db[l] = l < L - 1;                 // the head has the bias gradient of the layer below it
                 q.dz_off[l] = dz_off[l];
                 q.a[l] = l == 1 ? a.in : act + a_off[l - 1];
@@ -453,30 +463,30 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
                 q.a_stride[l] = l == 1 ? a.in_stride : wstride;
                 q.w_off[l] = w_off[l];
             }
-            q.tile_begin[L] = tiles;
             q.w_off[L] = w_off[L];
             q.dz = act; q.dz_stride = wstride;
             q.grads = grads; q.g_stride = c->ld;
             q.part = act + 2 * per; q.part_stride = wstride;
             const int64_t len = w_off[L] - w_off[1];
-            int splits = (int)std::min<int64_t>(8, std::max<int64_t>(1, (1280 + (int64_t)tiles * N / 2) / ((int64_t)tiles * N)));
-            splits = std::min(splits, (B + 15) / 16);
+            int splits = (int)std::min<int64_t>(8, std::max<int64_t>(1, 512 / ((int64_t)tiles * N)));
+            splits = std::min(splits, (B + 63) / 64);
             splits = (int)std::min<int64_t>(splits, std::max<int64_t>(1, split_floats / len));
             q.splits = splits;
             q.kper = ((B + splits - 1) / splits + 15) / 16 * 16;
+            const int head_blocks = head.chunks > 1 ? (int)((fchead::partial_floats(h.H, h.C, true) + 255) / 256) : 0;
             {
                 dbw_timer tm(c, "mlp_wgrad_kernel", s);
-                const int wgs = tiles * N * splits;
-                hipLaunchKernelGGL(mlpwgrad::kernel, dim3((wgs + mlpwgrad::XCDS - 1) / mlpwgrad::XCDS * mlpwgrad::XCDS),
-                                   dim3(mlpwgrad::THREADS), 0, s, q);
+                const int wgs = tiles * N * splits + head_blocks * N;
+                const dim3 grid((wgs + mlpwgrad::XCDS - 1) / mlpwgrad::XCDS * mlpwgrad::XCDS);
+                if (tn == 64)
+                    hipLaunchKernelGGL(mlpwgrad::kernel<4>, grid, dim3(mlpwgrad::THREADS), 0, s, q, h, head.chunks, head_blocks);
+                else
+                    hipLaunchKernelGGL(mlpwgrad::kernel<2>, grid, dim3(mlpwgrad::THREADS), 0, s, q, h, head.chunks, head_blocks);
                 DBW_HIP(hipGetLastError());
             }
-            const int wgrad_blocks = splits > 1 ? (int)((len / 4 + 255) / 256) : 0;
-            const int head_blocks = head.chunks > 1 ? (int)((fchead::partial_floats(h.H, h.C, true) + 255) / 256) : 0;
-            if (wgrad_blocks + head_blocks > 0) {
+            if (splits > 1) {
                 dbw_timer tm(c, "mlp_reduce_kernel", s);
-                hipLaunchKernelGGL(mlpwgrad::reduce_kernel, dim3(wgrad_blocks + head_blocks, N), dim3(256), 0, s, q,
-                                   wgrad_blocks, h, head.chunks);
+                hipLaunchKernelGGL(mlpwgrad::reduce_kernel, dim3((unsigned)((len / 4 + 255) / 256), N), dim3(256), 0, s, q);
                 DBW_HIP(hipGetLastError());
             }
             return DBW_OK;

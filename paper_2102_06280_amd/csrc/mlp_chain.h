@@ -263,7 +263,8 @@ __global__ __launch_bounds__(THREADS) void kernel(Args g)
     if (id >= g.workers * g.chunks) return;                // the whole workgroup: no barrier is left waiting
     const int w = id / g.chunks, chunk = id - w * g.chunks;
     const int s0 = chunk * S, ns = min(S, g.B - s0);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);       // on the scalar unit
 
     float *zl = sm;
     float *zp = zl + fchead::MAX_S * fchead::MAX_C;

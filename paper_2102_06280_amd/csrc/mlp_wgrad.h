@@ -29,7 +29,11 @@ using fchead::f32x4;
 using fchead::pick;
 constexpr int THREADS = 256, WAVES = 4, MAX_L = 8, XCDS = 8;
 constexpr int PF = 8;                 // groups of four samples a wavefront keeps in flight
-constexpr int TP = 68;                // row pitch of the 64 x 64 tiles in LDS
+
+template <int N>
+struct alignas(4 * N) Vec {
+    float v[N];
+};
 
 struct Args {
     int B, H, layers, workers;               // batch, rows of every dW_l (the hidden width), l = 1 .. layers
@@ -47,79 +51,116 @@ struct Args {
     int splits, kper;                        // samples per split, a multiple of 4
 };
 
-// grid = tiles of all layers x workers x splits, rounded up to a multiple of XCDS.  Workgroup ids are renumbered
-// so that the ids one XCD receives are consecutive tiles: the 16 or so tiles that read the same samples of the
-// same worker and layer then share that XCD's L2 instead of fetching them into all eight.
-__global__ __launch_bounds__(THREADS, 2) void kernel(Args g)
+// grid = (tiles of all layers x workers x splits) + (head_blocks x workers), rounded up to a multiple of XCDS.
+// Workgroup ids are renumbered so that the ids one XCD receives are consecutive tiles: the tiles that read the same
+// samples of the same worker and layer then share that XCD's L2 instead of fetching them into all eight.
+// CBK = column blocks of a tile: 64 x 64 tiles (4) or 64 x 32 (2, twice as many workgroups, for launches that
+// would otherwise have to split the batch to fill the chip).  The workgroups behind the tiles add the per-chunk
+// sums of the head (fc_head.h), which the chain kernel left before this launch: head_blocks of them per worker.
+template <int CBK>
+__global__ __launch_bounds__(THREADS, 2) void kernel(Args g, fchead::Args h, int chunks, int head_blocks)
 {
+    constexpr int TN = 16 * CBK, TP = TN + 4;
+    typedef Vec<CBK> vec;
     __shared__ __attribute__((aligned(16))) float red[WAVES - 1][64 * TP];
     __shared__ __attribute__((aligned(16))) float bred[WAVES][64];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l16 = lane & 15, lq = lane >> 4;
+    const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, lq = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);       // on the scalar unit: the loops below branch on it
     const int tiles = pick(g.tile_begin, g.layers + 1);
     const int per = gridDim.x / XCDS, id = (blockIdx.x % XCDS) * per + blockIdx.x / XCDS;
-    if (id >= tiles * g.workers * g.splits) return;             // the whole workgroup, before any barrier
+    const int tile_wgs = tiles * g.workers * g.splits;
+    if (id >= tile_wgs) {                                       // the whole workgroup, before any barrier
+        const int hid = id - tile_wgs;
+        if (hid < head_blocks * g.workers) fchead::reduce_body(h, chunks, hid % head_blocks, hid / head_blocks);
+        return;
+    }
     const int bx = id % tiles, w = (id / tiles) % g.workers, split = id / (tiles * g.workers);
     int l = 1;
     while (l < g.layers && bx >= pick(g.tile_begin, l + 1)) ++l;
-    const int N = pick(g.n_cols, l), H = g.H, ntn = (N + 63) / 64;
-    const int t = bx - pick(g.tile_begin, l), m0 = 64 * (t / ntn), n0 = 64 * (t % ntn);
+    const int N = pick(g.n_cols, l), H = g.H, ntn = (N + TN - 1) / TN;
+    const int t = bx - pick(g.tile_begin, l), m0 = 64 * (t / ntn), n0 = TN * (t % ntn);
     const int s_begin = split * g.kper, s_end = min(g.B, s_begin + g.kper);
     const bool bias = pick(g.want_db, l) && n0 == 0;
 
     const float *__restrict__ dz = g.dz + w * g.dz_stride + pick(g.dz_off, l) + m0 + 4 * l16;
-    const int ncol = n0 + 4 * l16 < N ? n0 + 4 * l16 : 0;        // a column group beyond N: any valid one, never stored
+    const bool cols_ok = n0 + CBK * l16 < N;                  // N divides by 4, so by CBK
+    const int ncol = cols_ok ? n0 + CBK * l16 : 0;            // a column group beyond N: any valid one, never stored
     const float *__restrict__ av = pick(g.a, l) + w * pick(g.a_stride, l) + ncol;
     const int64_t a_ld = pick(g.a_ld, l);
 
-    f32x4 acc[4][4];
+    f32x4 acc[4][CBK];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < CBK; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
     f32x4 dsum = {0.f, 0.f, 0.f, 0.f};
 
-    // this wavefront's groups of four samples: number wave, wave + 4, ... of the split
-    const int groups = (s_end - s_begin + 3) / 4, mine = groups > wave ? (groups - wave + WAVES - 1) / WAVES : 0;
-    auto sample = [&](int i) { return s_begin + 4 * (wave + WAVES * i) + lq; };
-    f32x4 ra[PF], rb[PF];
-    auto fetch = [&](int i, f32x4 &x, f32x4 &y) {
-        const int s = min(sample(i), s_end - 1);                   // beyond the batch: a valid row, zeroed at use
-        x = *(const f32x4 *)(dz + (int64_t)s * H);
-        y = *(const f32x4 *)(av + (int64_t)s * a_ld);
+    // This wavefront's groups of four samples: number wave, wave + 4, ... of the split; lane group lq takes sample lq
+    // of a group.  Whole groups run in the main loop, PF of them in flight; the split's last, partial group (if any)
+    // belongs to one wavefront and is masked per lane.
+    const int len = max(s_end - s_begin, 0), whole = len / 4;
+    const int mine = whole > wave ? (whole - wave + WAVES - 1) / WAVES : 0;
+    const float *pa = dz + (int64_t)(s_begin + 4 * wave + lq) * H;
+    const float *pb = av + (int64_t)(s_begin + 4 * wave + lq) * a_ld;
+    const int64_t step_a = (int64_t)4 * WAVES * H, step_b = (int64_t)4 * WAVES * a_ld;
+    auto multiply = [&](const f32x4 &x, const vec &y) {
+        dsum += x;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < CBK; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[i], y.v[j], acc[i][j], 0, 0, 0);
+    };
+    f32x4 ra[PF];
+    vec rb[PF];
+    auto fetch = [&](int u) {
+        ra[u] = *(const f32x4 *)(pa + u * step_a);
+        rb[u] = *(const vec *)(pb + u * step_b);
     };
 #pragma unroll
     for (int u = 0; u < PF; ++u)
-        if (u < mine) fetch(u, ra[u], rb[u]);
+        if (u < mine) fetch(u);
+    pa += PF * step_a;
+    pb += PF * step_b;
+    // (a copy of this loop without the two conditions for the stretch where they always hold was measured slower,
+    // 46 against 41 us for the 2NN: the scalar branches keep each group's loads next to its multiplies)
     for (int it = 0; it < mine; it += PF) {
 #pragma unroll
         for (int u = 0; u < PF; ++u) {
             if (it + u < mine) {
-                f32x4 x = ra[u], y = rb[u];
-                if (it + u + PF < mine) fetch(it + u + PF, ra[u], rb[u]);
-                if (sample(it + u) >= s_end) {
-                    x = f32x4{0.f, 0.f, 0.f, 0.f};
-                    y = x;
-                }
-                dsum += x;
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[i], y[j], acc[i][j], 0, 0, 0);
+                const f32x4 x = ra[u];
+                const vec y = rb[u];
+                if (it + u + PF < mine) fetch(u);
+                multiply(x, y);
             }
         }
+        pa += PF * step_a;
+        pb += PF * step_b;
+    }
+    if (len % 4 != 0 && whole % WAVES == wave) {
+        const bool ok = lq < len % 4;
+        const int64_t sl = s_begin + 4 * whole + (ok ? lq : 0);      // a lane beyond the batch: a valid row, zeroed
+        f32x4 x = *(const f32x4 *)(dz + sl * H);
+        vec y = *(const vec *)(av + sl * a_ld);
+        if (!ok) {
+            x = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < CBK; ++j) y.v[j] = 0.f;
+        }
+        multiply(x, y);
     }
 
     // ---- the four wavefronts' tiles: 1, 2, 3 through LDS, added to wavefront 0's in that order.
-    // Register r of row block i, lane (l16, lq): output row 4 (4 lq + r) + i, columns 4 l16 .. 4 l16 + 3.
+    // Register r of row block i, lane (l16, lq): output row 4 (4 lq + r) + i, columns CBK l16 .. CBK l16 + CBK - 1.
     if (wave > 0) {
         float *mine_t = red[wave - 1];
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const f32x4 v = {acc[i][0][r], acc[i][1][r], acc[i][2][r], acc[i][3][r]};
-                *(f32x4 *)&mine_t[(4 * (4 * lq + r) + i) * TP + 4 * l16] = v;
+                vec v;
+#pragma unroll
+                for (int j = 0; j < CBK; ++j) v.v[j] = acc[i][j][r];
+                *(vec *)&mine_t[(4 * (4 * lq + r) + i) * TP + CBK * l16] = v;
             }
     }
     if (bias) {     // sums over this wavefront's samples: lane groups first
@@ -136,16 +177,21 @@ __global__ __launch_bounds__(THREADS, 2) void kernel(Args g)
                                             : g.part + w * g.part_stride +
                                                   (int64_t)split * (pick(g.w_off, g.layers + 1) - pick(g.w_off, 1)) + (pick(g.w_off, l) - pick(g.w_off, 1));
     if (wave == 0) {
-        const bool cols_ok = n0 + 4 * l16 < N;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int row = 4 * (4 * lq + r) + i;
-                f32x4 v = {acc[i][0][r], acc[i][1][r], acc[i][2][r], acc[i][3][r]};
+                vec v;
 #pragma unroll
-                for (int q = 0; q < WAVES - 1; ++q) v += *(const f32x4 *)&red[q][row * TP + 4 * l16];
-                if (cols_ok) *(f32x4 *)(out + (int64_t)(m0 + row) * N + n0 + 4 * l16) = v;
+                for (int j = 0; j < CBK; ++j) v.v[j] = acc[i][j][r];
+#pragma unroll
+                for (int q = 0; q < WAVES - 1; ++q) {
+                    const vec o = *(const vec *)&red[q][row * TP + CBK * l16];
+#pragma unroll
+                    for (int j = 0; j < CBK; ++j) v.v[j] += o.v[j];
+                }
+                if (cols_ok) *(vec *)(out + (int64_t)(m0 + row) * N + n0 + CBK * l16) = v;
             }
     } else if (wave == 1 && bias && lane < 16) {
         f32x4 v = *(const f32x4 *)&bred[0][4 * lane];
@@ -187,13 +233,7 @@ __device__ __forceinline__ void reduce_body(const Args &g, int bx, int w)
     if (keep) *(f32x4 *)(g.grads + w * g.g_stride + pos) = sum;
 }
 
-// The split sums above and the per-chunk sums of the head (fc_head.h) in one launch:
-// blockIdx.x < wgrad_blocks belongs to the former.
-__global__ __launch_bounds__(256) void reduce_kernel(Args g, int wgrad_blocks, fchead::Args h, int chunks)
-{
-    const int w = blockIdx.y;
-    if ((int)blockIdx.x < wgrad_blocks) reduce_body(g, blockIdx.x, w);
-    else fchead::reduce_body(h, chunks, blockIdx.x - wgrad_blocks, w);
-}
+// grid = (ceil(length / 4 / 256), workers)
+__global__ __launch_bounds__(256) void reduce_kernel(Args g) { reduce_body(g, blockIdx.x, blockIdx.y); }
 
 }  // namespace mlpwgrad
