@@ -178,6 +178,13 @@ int dbw_select(dbw_ctx *ctx, const float *resp_times, const int32_t *b, void *st
  * dbw_select.  The epoch state lives in the context (dbw_dtur_reset empties it).
  * resp_times [dev, N], b_out [dev, N], theta_out [dev, 1] or NULL.  Asynchronous. */
 int dbw_dtur_b(dbw_ctx *ctx, const float *resp_times, int32_t *b_out, float *theta_out, void *stream);
+
+/* dbw_dtur_b followed by dbw_select with the backup counts it wrote (Algorithm 2, then
+ * Section 2.2), as one call: the same state change, the same outputs.  For graphs of up to
+ * 256 workers whose rows have at most 64 neighbours it is a single launch; otherwise the two
+ * launches of the separate calls.  resp_times [dev, N], b_out [dev, N] (required),
+ * theta_out [dev, 1] or NULL.  Asynchronous. */
+int dbw_dtur_select(dbw_ctx *ctx, const float *resp_times, int32_t *b_out, float *theta_out, void *stream);
 /* Empty the visited set: the next dbw_dtur_b starts a fresh epoch.  Asynchronous on `stream`. */
 int dbw_dtur_reset(dbw_ctx *ctx, void *stream);
 /* The epoch state of the threshold rule, for checkpoint and resume (everything else a run needs

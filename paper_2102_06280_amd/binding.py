@@ -28,7 +28,7 @@ CAL_HBM_TRIAD, CAL_MFMA_FP32 = 0, 1
 LAYOUT_ROWS, LAYOUT_TILES = 0, 1
 TILE_COLUMNS = 64
 
-EXPORTS = ["dbw_create", "dbw_select", "dbw_dtur_b", "dbw_dtur_reset", "dbw_dtur_get_state", "dbw_dtur_set_state",
+EXPORTS = ["dbw_create", "dbw_select", "dbw_dtur_b", "dbw_dtur_select", "dbw_dtur_reset", "dbw_dtur_get_state", "dbw_dtur_set_state",
            "dbw_get_selection",
            "dbw_get_weights", "dbw_round_time", "dbw_round", "dbw_round_eta", "dbw_consensus_rounds",
            "dbw_consensus_rounds_static",
@@ -60,6 +60,7 @@ _vp, _i32, _i64, _f = C.c_void_p, C.c_int32, C.c_int64, C.c_float
 _lib.dbw_create.argtypes = [C.POINTER(_vp), _i32, _i64, _vp, _vp, C.POINTER(dbw_opts)]
 _lib.dbw_select.argtypes = [_vp, _vp, _vp, _vp]
 _lib.dbw_dtur_b.argtypes = [_vp, _vp, _vp, _vp, _vp]
+_lib.dbw_dtur_select.argtypes = [_vp, _vp, _vp, _vp, _vp]
 _lib.dbw_dtur_reset.argtypes = [_vp, _vp]
 _lib.dbw_dtur_get_state.argtypes = [_vp, _vp, _vp, _vp]
 _lib.dbw_dtur_set_state.argtypes = [_vp, _vp, _i32, _vp]
@@ -141,6 +142,10 @@ def dbw_select(h, resp_times, b):
 
 def dbw_dtur_b(h, resp_times, b_out, theta_out=None):
     return _chk(_lib.dbw_dtur_b(h, _ptr(resp_times), _ptr(b_out), _ptr(theta_out), _stream()), "dbw_dtur_b")
+
+
+def dbw_dtur_select(h, resp_times, b_out, theta_out=None):
+    return _chk(_lib.dbw_dtur_select(h, _ptr(resp_times), _ptr(b_out), _ptr(theta_out), _stream()), "dbw_dtur_select")
 
 
 def dbw_dtur_reset(h):

@@ -274,6 +274,21 @@ int dbw_dtur_b(dbw_ctx *c, const float *resp_times, int32_t *b_out, float *theta
     return dbw_launch_dtur(c, resp_times, b_out, theta_out, (hipStream_t)stream);
 }
 
+int dbw_dtur_select(dbw_ctx *c, const float *resp_times, int32_t *b_out, float *theta_out, void *stream)
+{
+    if (!c || !resp_times || !b_out) return DBW_ERR_NULL;
+    hipStream_t s = (hipStream_t)stream;
+    int rc;
+    if (dbw_fused_dtur_select_fits(c)) {
+        rc = dbw_launch_dtur_select(c, resp_times, b_out, theta_out, s);
+    } else {
+        rc = dbw_launch_dtur(c, resp_times, b_out, theta_out, s);
+        if (rc == DBW_OK) rc = dbw_launch_select(c, resp_times, b_out, s);
+    }
+    if (rc == DBW_OK) c->selected = true;
+    return rc;
+}
+
 int dbw_dtur_reset(dbw_ctx *c, void *stream)
 {
     if (!c) return DBW_ERR_NULL;

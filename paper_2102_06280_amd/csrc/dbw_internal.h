@@ -20,6 +20,7 @@ constexpr int DBW_DENSE_MAX_N = 256;   // the dense mixing kernel keeps all of P
 // the dense mixing kernel adds 32-bit per-lane byte offsets of up to 40 rows to 64-bit uniform bases
 constexpr int64_t DBW_DENSE_MAX_LD = (int64_t)UINT32_MAX / (40 * 4);
 constexpr int DBW_SELECT_LDS_KEYS = 2048;
+constexpr int DBW_FUSED_SELECT_MAX_N = 256;   // threshold rule + selection in one workgroup up to this many workers
 constexpr int DBW_LOSS_CHUNKS = 16;     // workgroups per worker in the loss kernel, at most
 constexpr int DBW_TILES_MAX_N = 256;   // the tile-major mixing kernel holds one 256-byte piece per worker in LDS
 
@@ -87,6 +88,8 @@ int dbw_validate_graph(int32_t N, const int32_t *rowptr, const int32_t *colidx);
 int dbw_launch_select(dbw_ctx *c, const float *t, const int32_t *b, hipStream_t s);
 int dbw_launch_round_time(dbw_ctx *c, float *out, hipStream_t s);
 int dbw_launch_dtur(dbw_ctx *c, const float *t, int32_t *b_out, float *theta_out, hipStream_t s);
+bool dbw_fused_dtur_select_fits(const dbw_ctx *c);
+int dbw_launch_dtur_select(dbw_ctx *c, const float *t, int32_t *b_out, float *theta_out, hipStream_t s);
 int dbw_launch_dtur_reset(dbw_ctx *c, hipStream_t s);
 int dbw_launch_dense_weights(dbw_ctx *c, float *P, hipStream_t s);
 // mix_csr.hip

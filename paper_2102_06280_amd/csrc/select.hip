@@ -44,27 +44,49 @@ __device__ __forceinline__ float wave_max(float v)
     return v;
 }
 
-// grid = N blocks of WAVES wavefronts: one block per worker.  Each wave ranks one 64-wide slice
-// of the row at a time; slices are compacted in ascending order through per-wave counts.
+// A row group = WAVES wavefronts that share one worker's row.  With one wavefront the group needs no
+// workgroup barrier: LDS operations of one wavefront complete in order, only the compiler has to keep them
+// in order too.
 template <int WAVES>
-__global__ __launch_bounds__(64 * WAVES) void select_kernel(
-    int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
-    const float *__restrict__ t, const int32_t *__restrict__ b, int32_t *__restrict__ p_out,
-    uint8_t *__restrict__ mask, float *__restrict__ wait, int32_t *__restrict__ sel_idx,
-    float *__restrict__ sel_w, float *__restrict__ self_w, float *__restrict__ Wdense, int Npad,
-    int32_t *__restrict__ err)
+__device__ __forceinline__ void group_sync()
+{
+    if (WAVES > 1) {
+        __syncthreads();
+    } else {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+}
+
+// LDS of one row group.
+template <int WAVES, int KEYS>
+struct SelectLds {
+    uint64_t keys[KEYS];
+    float wrow[DBW_DENSE_MAX_N];
+    int slice_cnt[WAVES];
+    float red[2][WAVES];
+};
+
+// Selection, weights and wait time of worker i by a row group of WAVES wavefronts (tid = thread index inside
+// the group).  Each wave ranks one 64-wide slice of the row at a time; slices are compacted in ascending order
+// through per-wave counts.  b may point to global memory or to LDS.
+template <int WAVES, int KEYS>
+__device__ __forceinline__ void select_row(
+    int i, int tid, SelectLds<WAVES, KEYS> &L, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
+    const float *__restrict__ t, const int32_t *b, int32_t *__restrict__ p_out, uint8_t *__restrict__ mask,
+    float *__restrict__ wait, int32_t *__restrict__ sel_idx, float *__restrict__ sel_w, float *__restrict__ self_w,
+    float *__restrict__ Wdense, int Npad, int32_t *__restrict__ err)
 {
     constexpr int T = 64 * WAVES;
-    __shared__ uint64_t keys[DBW_SELECT_LDS_KEYS];
-    __shared__ float wrow[DBW_DENSE_MAX_N];
-    __shared__ int slice_cnt[WAVES];
-    __shared__ float red[2][WAVES];
-    const int i = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint64_t *keys = L.keys;
+    float *wrow = L.wrow;
+    const int lane = tid & 63, wave = tid >> 6;
     const int beg = rowptr[i], deg = rowptr[i + 1] - beg;
     const int bi_raw = b[i];
     if ((bi_raw < 0 || bi_raw > deg) && tid == 0) *err = DBW_ERR_INVALID;
     const int pi = deg - clamp_b(bi_raw, deg);
-    const bool in_lds = deg <= DBW_SELECT_LDS_KEYS;
+    const bool in_lds = deg <= KEYS;
 
     if (in_lds)
         for (int k = tid; k < deg; k += T) {
@@ -73,7 +95,7 @@ __global__ __launch_bounds__(64 * WAVES) void select_kernel(
         }
     if (Wdense)
         for (int c = tid; c < Npad; c += T) wrow[c] = 0.0f;
-    __syncthreads();
+    group_sync<WAVES>();
 
     float wsum = 0.0f, tmax = canon_time(t[i]);
     int base = 0;
@@ -109,13 +131,13 @@ __global__ __launch_bounds__(64 * WAVES) void select_kernel(
         const uint64_t ballot = __ballot(sel);
         int before = 0, total = __popcll(ballot);
         if (WAVES > 1) {
-            if (lane == 0) slice_cnt[wave] = total;
+            if (lane == 0) L.slice_cnt[wave] = total;
             __syncthreads();
             total = 0;
 #pragma unroll
             for (int q = 0; q < WAVES; ++q) {
-                before += q < wave ? slice_cnt[q] : 0;
-                total += slice_cnt[q];
+                before += q < wave ? L.slice_cnt[q] : 0;
+                total += L.slice_cnt[q];
             }
             __syncthreads();                          // slice_cnt is rewritten in the next pass
         }
@@ -131,15 +153,15 @@ __global__ __launch_bounds__(64 * WAVES) void select_kernel(
     tmax = wave_max(tmax);
     if (WAVES > 1) {
         if (lane == 0) {
-            red[0][wave] = wsum;
-            red[1][wave] = tmax;
+            L.red[0][wave] = wsum;
+            L.red[1][wave] = tmax;
         }
         __syncthreads();
         wsum = 0.0f;
 #pragma unroll
         for (int q = 0; q < WAVES; ++q) {
-            wsum += red[0][q];
-            tmax = fmaxf(tmax, red[1][q]);
+            wsum += L.red[0][q];
+            tmax = fmaxf(tmax, L.red[1][q]);
         }
     }
     const float ws = 1.0f - wsum;
@@ -149,9 +171,9 @@ __global__ __launch_bounds__(64 * WAVES) void select_kernel(
         self_w[i] = ws;
     }
     if (Wdense) {
-        __syncthreads();
+        group_sync<WAVES>();
         if (tid == 0) wrow[i] = ws;
-        __syncthreads();
+        group_sync<WAVES>();
         // A-operand fragment order of the dense kernel: [row block][k-step][lane], with
         // lane = (k % 2) * 32 + row % 32 holding P[row][k]
         const int KB = Npad / 2;
@@ -160,22 +182,37 @@ __global__ __launch_bounds__(64 * WAVES) void select_kernel(
     }
 }
 
-// Rows [N, Npad) of the padded dense matrix stay zero: cleared once at create.
-
-// Threshold rule and the d-iteration procedure (Section 4.1, Algorithm 2); one block.
-// A link (u, v) is established at max(t_u, t_v).  theta = the smallest establishment
-// time over links not yet visited in this epoch, lowest link id on ties.
-__global__ __launch_bounds__(256) void dtur_kernel(
-    int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx, int n_links,
-    const int32_t *__restrict__ links, uint8_t *__restrict__ visited, int32_t *__restrict__ n_visited,
-    const float *__restrict__ t, int32_t *__restrict__ b_out, float *__restrict__ theta_out,
+// grid = N blocks of WAVES wavefronts: one block per worker.
+template <int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void select_kernel(
+    int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
+    const float *__restrict__ t, const int32_t *__restrict__ b, int32_t *__restrict__ p_out,
+    uint8_t *__restrict__ mask, float *__restrict__ wait, int32_t *__restrict__ sel_idx,
+    float *__restrict__ sel_w, float *__restrict__ self_w, float *__restrict__ Wdense, int Npad,
     int32_t *__restrict__ err)
 {
-    __shared__ uint64_t red[256];
+    __shared__ SelectLds<WAVES, DBW_SELECT_LDS_KEYS> L;
+    select_row<WAVES, DBW_SELECT_LDS_KEYS>(blockIdx.x, threadIdx.x, L, rowptr, colidx, t, b, p_out, mask, wait, sel_idx,
+                                           sel_w, self_w, Wdense, Npad, err);
+}
+
+// Rows [N, Npad) of the padded dense matrix stay zero: cleared once at create.
+
+// Threshold rule and the d-iteration procedure (Section 4.1, Algorithm 2); one block of T threads.
+// A link (u, v) is established at max(t_u, t_v).  theta = the smallest establishment
+// time over links not yet visited in this epoch, lowest link id on ties.  b_lds (nullable) receives a
+// copy of the backup counts in LDS.
+template <int T>
+__device__ __forceinline__ void dtur_body(
+    uint64_t *red /* LDS [T] */, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
+    int n_links, const int32_t *__restrict__ links, uint8_t *__restrict__ visited, int32_t *__restrict__ n_visited,
+    const float *__restrict__ t, int32_t *__restrict__ b_out, int32_t *b_lds, float *__restrict__ theta_out,
+    int32_t *__restrict__ err)
+{
     const int tid = threadIdx.x;
     const bool fresh = *n_visited >= n_links;   // previous epoch complete: P' starts empty
     uint64_t best = ~0ull;
-    for (int e = tid; e < n_links; e += 256) {
+    for (int e = tid; e < n_links; e += T) {
         if (!fresh && visited[e]) continue;
         const float est = fmaxf(canon_time(t[links[2 * e]]), canon_time(t[links[2 * e + 1]]));
         const uint64_t key = make_key(est, e);
@@ -183,7 +220,7 @@ __global__ __launch_bounds__(256) void dtur_kernel(
     }
     red[tid] = best;
     __syncthreads();
-    for (int o = 128; o > 0; o >>= 1) {
+    for (int o = T / 2; o > 0; o >>= 1) {
         if (tid < o) red[tid] = red[tid + o] < red[tid] ? red[tid + o] : red[tid];
         __syncthreads();
     }
@@ -196,7 +233,7 @@ __global__ __launch_bounds__(256) void dtur_kernel(
     }
     __syncthreads();    // every thread has read n_visited / visited before they change
     if (fresh)
-        for (int e = tid; e < n_links; e += 256) visited[e] = 0;
+        for (int e = tid; e < n_links; e += T) visited[e] = 0;
     __syncthreads();
     if (tid == 0) {
         if (chosen >= 0) visited[chosen] = 1;
@@ -206,7 +243,7 @@ __global__ __launch_bounds__(256) void dtur_kernel(
         // worker keeps to itself this round.  Recorded as a warning unless an error is pending.
         if (n_links > 0 && theta == __builtin_inff() && *err == 0) *err = DBW_WARN_THETA_INF;
     }
-    for (int j = tid; j < N; j += 256) {
+    for (int j = tid; j < N; j += T) {
         const int beg = rowptr[j], end = rowptr[j + 1];
         int bj = end - beg;
         if (canon_time(t[j]) <= theta) {
@@ -215,7 +252,41 @@ __global__ __launch_bounds__(256) void dtur_kernel(
             bj -= cnt;
         }
         b_out[j] = bj;
+        if (b_lds) b_lds[j] = bj;
     }
+}
+
+__global__ __launch_bounds__(256) void dtur_kernel(
+    int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx, int n_links,
+    const int32_t *__restrict__ links, uint8_t *__restrict__ visited, int32_t *__restrict__ n_visited,
+    const float *__restrict__ t, int32_t *__restrict__ b_out, float *__restrict__ theta_out,
+    int32_t *__restrict__ err)
+{
+    __shared__ uint64_t red[256];
+    dtur_body<256>(red, N, rowptr, colidx, n_links, links, visited, n_visited, t, b_out, nullptr, theta_out, err);
+}
+
+// The threshold rule and the selection it leads to in one launch, for graphs of up to DBW_FUSED_SELECT_MAX_N
+// workers with rows of at most 64 neighbours: one workgroup of 16 wavefronts runs the rule, then every
+// wavefront takes workers i = wave, wave + 16, ... through select_row.  Two launches of 4-8 us each become one;
+// the selection is the same code, so the results are identical.
+constexpr int FUSED_WAVES = 16;
+__global__ __launch_bounds__(64 * FUSED_WAVES) void dtur_select_kernel(
+    int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx, int n_links,
+    const int32_t *__restrict__ links, uint8_t *__restrict__ visited, int32_t *__restrict__ n_visited,
+    const float *__restrict__ t, int32_t *__restrict__ b_out, float *__restrict__ theta_out,
+    int32_t *__restrict__ p_out, uint8_t *__restrict__ mask, float *__restrict__ wait, int32_t *__restrict__ sel_idx,
+    float *__restrict__ sel_w, float *__restrict__ self_w, float *__restrict__ Wdense, int Npad, int32_t *__restrict__ err)
+{
+    __shared__ uint64_t red[64 * FUSED_WAVES];
+    __shared__ int32_t b_lds[DBW_FUSED_SELECT_MAX_N];
+    __shared__ SelectLds<1, 64> L[FUSED_WAVES];
+    dtur_body<64 * FUSED_WAVES>(red, N, rowptr, colidx, n_links, links, visited, n_visited, t, b_out, b_lds, theta_out, err);
+    __syncthreads();
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    for (int i = wave; i < N; i += FUSED_WAVES)
+        select_row<1, 64>(i, lane, L[wave], rowptr, colidx, t, b_lds, p_out, mask, wait, sel_idx, sel_w, self_w, Wdense,
+                          Npad, err);
 }
 
 // The next call of the threshold rule starts a fresh epoch.
@@ -313,6 +384,18 @@ int dbw_launch_dtur(dbw_ctx *c, const float *t, int32_t *b_out, float *theta_out
     dbw_timer tm(c, "dtur_kernel", s);
     hipLaunchKernelGGL(dtur_kernel, dim3(1), dim3(256), 0, s, c->N, c->rowptr, c->colidx, c->N - 1, c->links,
                        c->visited, c->n_visited, t, b_out, theta_out, c->err);
+    DBW_HIP(hipGetLastError());
+    return DBW_OK;
+}
+
+bool dbw_fused_dtur_select_fits(const dbw_ctx *c) { return c->N <= DBW_FUSED_SELECT_MAX_N && c->max_deg <= 64; }
+
+int dbw_launch_dtur_select(dbw_ctx *c, const float *t, int32_t *b_out, float *theta_out, hipStream_t s)
+{
+    dbw_timer tm(c, "dtur_select_kernel", s);
+    hipLaunchKernelGGL(dtur_select_kernel, dim3(1), dim3(64 * FUSED_WAVES), 0, s, c->N, c->rowptr, c->colidx, c->N - 1,
+                       c->links, c->visited, c->n_visited, t, b_out, theta_out, c->p, c->mask, c->wait, c->sel_idx, c->sel_w,
+                       c->self_w, c->Wdense, c->Npad, c->err);
     DBW_HIP(hipGetLastError());
     return DBW_OK;
 }

@@ -49,8 +49,9 @@ def run(cid: int, rounds: int, policy: str, order: int = B.ORDER_CTA, pool: int 
         cur = 0
         for k in range(rounds):
             if policy == "dybw" and threshold_rule and k > 0:
-                B.dbw_dtur_b(wl.h, t[k], b[k])
-            B.dbw_select(wl.h, t[k], b[k])
+                B.dbw_dtur_select(wl.h, t[k], b[k])
+            else:
+                B.dbw_select(wl.h, t[k], b[k])
             B.dbw_round(wl.h, wl.x[cur], wl.x[cur ^ 1], inputs.learning_rate(cfg, k),
                         batch_x=wl.bx[k % pool], batch_y=wl.by[k % pool], loss_out=loss[k])
             B.dbw_round_time(wl.h, T[k])

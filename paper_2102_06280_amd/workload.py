@@ -86,8 +86,9 @@ class Workload:
         """One round: (threshold rule,) selection, gradient, masked average, SGD step."""
         r = self.k % self.rounds
         if self.dynamic_b and r > 0:
-            B.dbw_dtur_b(self.h, self.t[r], self.b[r])
-        B.dbw_select(self.h, self.t[r], self.b[r])
+            B.dbw_dtur_select(self.h, self.t[r], self.b[r])     # threshold rule + selection, one launch for small graphs
+        else:
+            B.dbw_select(self.h, self.t[r], self.b[r])
         src, dst = self.x[self.cur], self.x[self.cur ^ 1]
         if self.desc is None:
             B.dbw_round(self.h, src, dst, self.cfg.lr, ext_grads=self.g)

@@ -184,3 +184,75 @@ def test_isolated_and_dead_workers(B, orc):
         assert_params_close(got, orc.round_(rowptr, colidx, om, op, x, gr, 0.5, 0))
     finally:
         B.dbw_destroy(h)
+
+
+def dtur_graphs():
+    g = np.random.default_rng(131)
+    return [("ring8", inputs.graph_ring(8)), ("complete10", inputs.graph_complete(10)),
+            ("er40", inputs.graph_er(40, 0.2, g)), ("reg8x128", inputs.graph_regular(128, 8, g)),
+            ("complete65", inputs.graph_complete(65)),         # 64 neighbours per row: the largest the one-launch form takes
+            ("complete100", inputs.graph_complete(100)),       # rows of 99 neighbours: two launches
+            ("reg4x300", inputs.graph_regular(300, 4, g))]     # more than 256 workers: two launches
+
+
+@pytest.mark.parametrize("name,graph", dtur_graphs(), ids=[n for n, _ in dtur_graphs()])
+def test_dtur_select_equals_the_two_calls(B, orc, name, graph):
+    """dbw_dtur_select against dbw_dtur_b + dbw_select on a second context and against the oracle: backup counts,
+    theta, selection, wait times, weights, epoch state, and one gradient-free round through whichever mixing path
+    the context picked, bit for bit, over more than one epoch with ties and dead workers."""
+    rowptr, colidx = graph
+    n, nnz, d = rowptr.size - 1, colidx.size, 192
+    g = np.random.default_rng(137)
+    x = dev(g.standard_normal((n, d)).astype(np.float32))
+    h1 = B.dbw_create(rowptr, colidx, n, d)
+    h2 = B.dbw_create(rowptr, colidx, n, d)
+    try:
+        dt = orc.Dtur(rowptr, colidx)
+        b1 = torch.zeros(n, dtype=torch.int32, device="cuda")
+        b2 = torch.full((n,), -7, dtype=torch.int32, device="cuda")
+        th1 = torch.zeros(1, device="cuda")
+        th2 = torch.zeros(1, device="cuda")
+        B.dbw_set_timing(h2, True)
+        rounds = min(n + 6, 48)
+        for k in range(rounds):
+            t = g.standard_exponential(n).astype(np.float32)
+            if k % 3 == 1:
+                t = (np.ceil(t * 2) / 2).astype(np.float32)
+            if k % 5 == 3:
+                t[g.integers(0, n)] = np.inf
+            td = dev(t)
+            B.dbw_dtur_b(h1, td, b1, th1)
+            B.dbw_select(h1, td, b1)
+            B.dbw_dtur_select(h2, td, b2, th2)
+            ob, otheta = dt.step(t)
+            assert np.array_equal(b2.cpu().numpy(), ob), k
+            assert np.array_equal(b1.cpu().numpy(), ob), k
+            assert th2.item() == np.float32(otheta) and th1.item() == th2.item(), k
+            sel = []
+            for h in (h1, h2):
+                p = torch.empty(n, dtype=torch.int32, device="cuda")
+                mask = torch.empty(nnz, dtype=torch.uint8, device="cuda")
+                wait = torch.empty(n, dtype=torch.float32, device="cuda")
+                try:
+                    B.dbw_get_selection(h, p, mask, wait)
+                except B.DbwError as e:                       # theta = +inf is reported as a warning code
+                    assert e.code == B.WARN_THETA_INF, e
+                P = torch.empty((n, n), device="cuda")
+                B.dbw_get_weights(h, P)
+                out = torch.empty((n, d), device="cuda")
+                B.dbw_round(h, x, out, 0.0)
+                sel.append([v.cpu().numpy() for v in (p, mask, wait, P, out)])
+            omask, op, owait = orc.select(rowptr, colidx, t, ob)
+            for got, want in zip(sel[1][:3], (op, omask, owait)):
+                assert np.array_equal(got, want), k
+            for a, c in zip(sel[0], sel[1]):
+                assert np.array_equal(a, c), k
+            assert B.dbw_dtur_get_state(h1, n)[1] == B.dbw_dtur_get_state(h2, n)[1]
+            assert np.array_equal(B.dbw_dtur_get_state(h1, n)[0], B.dbw_dtur_get_state(h2, n)[0])
+        kernels = set(B.dbw_get_timing(h2))
+        one_launch = n <= 256 and np.diff(rowptr).max() <= 64
+        assert ("dtur_select_kernel" in kernels) == one_launch, kernels
+        assert ("dtur_kernel" in kernels) == (not one_launch), kernels
+    finally:
+        B.dbw_destroy(h1)
+        B.dbw_destroy(h2)
