@@ -48,6 +48,19 @@ __device__ __forceinline__ T pick(const T (&a)[N], int i)
     return r;
 }
 
+// A wave-uniform address, pinned to scalar registers: global loads then take this base plus a 32-bit lane
+// offset.  Without the pin the compiler folds the lane offset into one loop-invariant 64-bit vector address per
+// load, and dozens of such register pairs crowd out the accumulators.
+__device__ __forceinline__ const char *uniform_base(const void *p)
+{
+    const uint64_t a = (uint64_t)p;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+    uint64_t v = ((uint64_t)hi << 32) | lo;
+    asm volatile("" : "+s"(v));
+    return (const char *)v;
+}
+
 struct Args {
     int B, H, C, S;                  // batch, inputs, classes, samples per chunk (16, 32 or 64)
     const float *a;                  // [B][a_ld] per worker (stride a_stride): the head's input

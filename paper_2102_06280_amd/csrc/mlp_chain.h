@@ -13,7 +13,7 @@
 // gradients dW_l = dz_l^T a_{l-1} (sums over the whole batch) are taken by the GEMM kernels.
 //
 // Products run on v_mfma_f32_16x16x4_f32 (true fp32).  A wavefront owns 16 CB output columns of all
-// S rows: RB x CB accumulator tiles.  Its A fragments come from the LDS image of the layer's input
+// S rows, worked off 32 columns at a time: RB x min(CB, 2) accumulator tiles.  Its A fragments come from the LDS image of the layer's input
 // (one 128-bit read per 16 rows and 16 k), its B fragments straight from the weights in global
 // memory (L2), since no other wavefront of the workgroup wants the same ones; they are fetched one
 // 64-wide k-chunk ahead.  The matrix instruction only asks that lane group q of A and of B carry the
@@ -31,6 +31,7 @@ namespace mlpchain {
 
 using fchead::f32x4;
 using fchead::pick;
+using fchead::uniform_base;
 constexpr int THREADS = fchead::THREADS, WAVES = THREADS / 64;
 constexpr int XCDS = 8;
 constexpr int MAX_L = 8;
@@ -77,16 +78,18 @@ struct BRegs {
     float v[4][4 * CB];
 };
 
+// Both loaders split an address into a wave-uniform base (scalar registers) and one 32-bit lane offset that is
+// the same for every load of the product.
 template <int CB>
 __device__ __forceinline__ void load_fwd(BRegs<CB> &b, const float *__restrict__ Wg, int K, int k0, int n0, int lane)
 {
-    const int l16 = lane & 15, lq = lane >> 4;
+    const uint32_t lane_off = 4u * ((uint32_t)(lane & 15) * (uint32_t)K + 4u * (uint32_t)(lane >> 4));
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb) {
-        const float *p = Wg + (int64_t)(n0 + 16 * cb + l16) * K + k0 + 4 * lq;
+        const char *base = uniform_base(Wg + (int64_t)(n0 + 16 * cb) * K + k0);
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const f32x4 q = *(const f32x4 *)(p + 16 * u);
+            const f32x4 q = *(const f32x4 *)(base + 64 * u + lane_off);
 #pragma unroll
             for (int e = 0; e < 4; ++e) b.v[u][4 * cb + e] = q[e];
         }
@@ -96,13 +99,13 @@ __device__ __forceinline__ void load_fwd(BRegs<CB> &b, const float *__restrict__
 template <int CB>
 __device__ __forceinline__ void load_bwd(BRegs<CB> &b, const float *__restrict__ Wg, int ldw, int k0, int n0, int lane)
 {
-    const int l16 = lane & 15, lq = lane >> 4;
-    const float *p = Wg + (int64_t)(k0 + 4 * lq) * ldw + n0 + CB * l16;
+    const uint32_t lane_off = 4u * (4u * (uint32_t)(lane >> 4) * (uint32_t)ldw + (uint32_t)CB * (uint32_t)(lane & 15));
 #pragma unroll
     for (int u = 0; u < 4; ++u)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const Vec<CB> q = *(const Vec<CB> *)(p + (int64_t)(16 * u + j) * ldw);
+            const char *base = uniform_base(Wg + (int64_t)(k0 + 16 * u + j) * ldw + n0);
+            const Vec<CB> q = *(const Vec<CB> *)(base + lane_off);
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb) b.v[u][CB * j + cb] = q.v[cb];
         }
@@ -112,18 +115,23 @@ __device__ __forceinline__ void load_bwd(BRegs<CB> &b, const float *__restrict__
 template <int RB, int CB, bool FWD>
 __device__ __forceinline__ void chunk_mfma(f32x4 (&acc)[RB][CB], const float *ap, int pitch, int k0, const BRegs<CB> &b)
 {
+    // the A fragments of the next 16 k are requested before the multiplies of the current ones
+    f32x4 av[2][RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) av[0][rb] = *(const f32x4 *)(ap + 16 * rb * pitch + k0);
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-        f32x4 av[RB];
+        if (u + 1 < 4) {
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb) av[rb] = *(const f32x4 *)(ap + 16 * rb * pitch + k0 + 16 * u);
+            for (int rb = 0; rb < RB; ++rb) av[(u + 1) & 1][rb] = *(const f32x4 *)(ap + 16 * rb * pitch + k0 + 16 * (u + 1));
+        }
 #pragma unroll
         for (int e = 0; e < 4; ++e)
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb)
-                    acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[rb][e], FWD ? b.v[u][4 * cb + e] : b.v[u][CB * e + cb],
+                    acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u & 1][rb][e], FWD ? b.v[u][4 * cb + e] : b.v[u][CB * e + cb],
                                                                        acc[rb][cb], 0, 0, 0);
     }
 }
@@ -162,7 +170,8 @@ __device__ __forceinline__ void product(f32x4 (&acc)[RB][CB], const float *in, i
         if (FWD) {
             f32x4 bv[CB];
 #pragma unroll
-            for (int cb = 0; cb < CB; ++cb) bv[cb] = *(const f32x4 *)(Wg + (int64_t)(n0 + 16 * cb + l16) * ldw + k + 4 * lq);
+            for (int cb = 0; cb < CB; ++cb)
+                bv[cb] = *(const f32x4 *)(uniform_base(Wg + (int64_t)(n0 + 16 * cb) * ldw + k) + 4u * ((uint32_t)l16 * (uint32_t)ldw + 4u * (uint32_t)lq));
 #pragma unroll
             for (int e = 0; e < 4; ++e)
 #pragma unroll
@@ -173,7 +182,8 @@ __device__ __forceinline__ void product(f32x4 (&acc)[RB][CB], const float *in, i
         } else {
             Vec<CB> bv[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) bv[j] = *(const Vec<CB> *)(Wg + (int64_t)(k + 4 * lq + j) * ldw + n0 + CB * l16);
+            for (int j = 0; j < 4; ++j)
+                bv[j] = *(const Vec<CB> *)(uniform_base(Wg + (int64_t)(k + j) * ldw + n0) + 4u * (4u * (uint32_t)lq * (uint32_t)ldw + (uint32_t)CB * (uint32_t)l16));
 #pragma unroll
             for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -275,11 +285,14 @@ __global__ __launch_bounds__(THREADS) void kernel(Args g)
     const float *__restrict__ pw = g.params + w * g.p_stride;
     float *__restrict__ sw = g.act + w * g.act_stride;
 
-    // the first chunk of W_1 is on its way while the batch is staged; likewise every later product's first chunk
-    // is requested before the epilogue of the product before it
+    // A wavefront's 16 CB columns are worked off in blocks of 16 CBI: with four 16-column blocks at once the
+    // accumulators and the two sets of weight registers no longer fit the register file.
+    // The first chunk of W_1 is on its way while the batch is staged; likewise every later product's first chunk
+    // is requested before the epilogue of the product before it.
+    constexpr int CBI = CB > 2 ? 2 : CB, NSUB = CB / CBI;
     const int n0 = wave * 16 * CB;
-    BRegs<CB> b0;
-    if (K0 >= 64) load_fwd<CB>(b0, pw + pick(g.w_off, 1), K0, 0, n0, lane);
+    BRegs<CBI> b0;
+    if (K0 >= 64) load_fwd<CBI>(b0, pw + pick(g.w_off, 1), K0, 0, n0, lane);
     const fchead::Early early = fchead::fetch_early(g.head, w, s0, ns, tid);
     fchead::stage_w(g.head, w, Wl, tid);
     {   // the chunk of the batch, rows beyond it zero
@@ -302,7 +315,7 @@ __global__ __launch_bounds__(THREADS) void kernel(Args g)
     }
     __syncthreads();
 
-    f32x4 acc[RB][CB];
+    f32x4 acc[RB][CBI];
     for (int l = 1; l <= Lh; ++l) {
         const float *in = l == 1 ? xl : slots + (l - 2) * Z;
         float *out = slots + (l - 1) * Z;
@@ -310,15 +323,24 @@ __global__ __launch_bounds__(THREADS) void kernel(Args g)
         // slot during this layer; the batch chunk that lay in slot 1 is dead from layer 2 on)
         for (int e = tid; e < S * (HP - H); e += THREADS) out[(e / (HP - H)) * HP + H + e % (HP - H)] = 0.f;
         if (tid < 16) out[S * HP + tid] = 0.f;
-        float bcol[CB];
-#pragma unroll
-        for (int cb = 0; cb < CB; ++cb) bcol[cb] = pw[pick(g.b_off, l) + n0 + 16 * cb + (lane & 15)];
-        zero<RB, CB>(acc);
         const int K = l == 1 ? K0 : H;
-        product<RB, CB, true>(acc, in, l == 1 ? P0 : HP, K, pw + pick(g.w_off, l), K, n0, lane, b0);
-        if (l < Lh) load_fwd<CB>(b0, pw + pick(g.w_off, l + 1), H, 0, n0, lane);
-        else if (Lh >= 2) load_bwd<CB>(b0, pw + pick(g.w_off, Lh), H, 0, n0, lane);     // waits in registers through the head
-        store_forward<RB, CB>(acc, bcol, out, HP, n0, lane);
+        const float *__restrict__ Wl_ = pw + pick(g.w_off, l);
+        for (int sub = 0; sub < NSUB; ++sub) {
+            const int n0s = n0 + 16 * CBI * sub;
+            float bcol[CBI];
+#pragma unroll
+            for (int cb = 0; cb < CBI; ++cb) bcol[cb] = pw[pick(g.b_off, l) + n0s + 16 * cb + (lane & 15)];
+            zero<RB, CBI>(acc);
+            product<RB, CBI, true>(acc, in, l == 1 ? P0 : HP, K, Wl_, K, n0s, lane, b0);
+            if (sub + 1 < NSUB) {
+                if (K >= 64) load_fwd<CBI>(b0, Wl_, K, 0, n0s + 16 * CBI, lane);
+            } else if (l < Lh) {
+                load_fwd<CBI>(b0, pw + pick(g.w_off, l + 1), H, 0, n0, lane);
+            } else if (Lh >= 2) {
+                load_bwd<CBI>(b0, pw + pick(g.w_off, Lh), H, 0, n0, lane);     // waits in registers through the head
+            }
+            store_forward<RB, CBI>(acc, bcol, out, HP, n0s, lane);
+        }
         __syncthreads();
         if (l < Lh) copy_out(out, HP, sw + pick(g.a_off, l) + (int64_t)s0 * H, H, ns, tid);
     }
@@ -333,10 +355,15 @@ __global__ __launch_bounds__(THREADS) void kernel(Args g)
 
     for (int l = Lh; l >= 2; --l) {
         float *prev = slots + (l - 2) * Z;
-        zero<RB, CB>(acc);
-        product<RB, CB, false>(acc, slots + (l - 1) * Z, HP, H, pw + pick(g.w_off, l), H, n0, lane, b0);
-        if (l > 2) load_bwd<CB>(b0, pw + pick(g.w_off, l - 1), H, 0, n0, lane);
-        store_backward<RB, CB>(acc, prev, HP, n0, lane);
+        const float *__restrict__ Wl_ = pw + pick(g.w_off, l);
+        for (int sub = 0; sub < NSUB; ++sub) {
+            const int n0s = n0 + 16 * CBI * sub;
+            zero<RB, CBI>(acc);
+            product<RB, CBI, false>(acc, slots + (l - 1) * Z, HP, H, Wl_, H, n0s, lane, b0);
+            if (sub + 1 < NSUB) load_bwd<CBI>(b0, Wl_, H, 0, n0s + 16 * CBI, lane);
+            else if (l > 2) load_bwd<CBI>(b0, pw + pick(g.w_off, l - 1), H, 0, n0, lane);
+            store_backward<RB, CBI>(acc, prev, HP, n0s, lane);
+        }
         __syncthreads();
         copy_out(prev, HP, sw + pick(g.dz_off, l - 1) + (int64_t)s0 * H, H, ns, tid);
     }

@@ -121,9 +121,25 @@ __global__ __launch_bounds__(THREADS, 2) void kernel(Args g, fchead::Args h, int
         if (u < mine) fetch(u);
     pa += PF * step_a;
     pb += PF * step_b;
-    // (a copy of this loop without the two conditions for the stretch where they always hold was measured slower,
-    // 46 against 41 us for the 2NN: the scalar branches keep each group's loads next to its multiplies)
-    for (int it = 0; it < mine; it += PF) {
+    // A taken branch costs a stream of matrix instructions about 40 idle cycles (a register-resident loop of 6
+    // instructions per iteration runs at 83 % of the rate of the same loop unrolled), so the stretch where all PF
+    // groups and their successors exist runs without conditions; the scheduling barriers keep each group's loads next
+    // to its multiplies (without them the compiler gathers the loads at the top and the wave waits there).
+    int it = 0;
+    for (; it + 2 * PF <= mine; it += PF) {
+#pragma unroll
+        for (int u = 0; u < PF; ++u) {
+            const f32x4 x = ra[u];
+            const vec y = rb[u];
+            fetch(u);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(x, y);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        pa += PF * step_a;
+        pb += PF * step_b;
+    }
+    for (; it < mine; it += PF) {
 #pragma unroll
         for (int u = 0; u < PF; ++u) {
             if (it + u < mine) {
