@@ -128,6 +128,48 @@ def test_chain_gradients_match_oracle(B, orc, dims, batch, n, loss_kind, blocks)
     check_gradients(B, orc, dims, batch, n, loss_kind, grad_path=B.GRAD_CHAIN, expect={"mlp_chain_kernel"})
 
 
+def test_chain_falls_back_when_the_batch_is_not_16_byte_aligned(B, orc):
+    """The chain kernel fetches the batch with 128-bit loads.  A batch that starts 4 bytes into an allocation takes
+    the layered path under DBW_GRAD_AUTO (same gradients), and is refused under DBW_GRAD_CHAIN."""
+    dims, batch, n = [256, 256, 256, 10], 1024, 10
+    desc = {"kind": "mlp", "dims": dims, "loss": "mse"}
+    d = inputs.param_count(desc)
+    ld = inputs.pad_ld(d)
+    rowptr, colidx = inputs.graph_ring(n)
+    g = np.random.default_rng(409)
+    params = dev(inputs.init_params(desc, n, ld, g))
+    x = g.standard_normal((n, batch, dims[0])).astype(np.float32)
+    y = dev(g.integers(0, 10, (n, batch)).astype(np.int32))
+    store = torch.zeros(x.size + 1, dtype=torch.float32, device="cuda")
+    store[1:] = torch.from_numpy(x.ravel()).cuda()
+    shifted = store[1:].view(n, batch, dims[0])
+    assert shifted.data_ptr() % 16 == 4
+    out = {}
+    for name, path, bx in (("aligned", B.GRAD_AUTO, dev(x)), ("shifted", B.GRAD_AUTO, shifted)):
+        h = B.dbw_create(rowptr, colidx, n, d, ld=ld, model=B.make_model(B.MODEL_MLP, batch, dims, B.LOSS_MSE, grad_path=path))
+        try:
+            grads = torch.zeros((n, ld), device="cuda")
+            loss = torch.zeros(n, device="cuda")
+            B.dbw_set_timing(h, True)
+            B.dbw_grad(h, params, bx, y, grads, loss)
+            out[name] = (grads.cpu().numpy(), loss.cpu().numpy(), set(B.dbw_get_timing(h)))
+        finally:
+            B.dbw_destroy(h)
+    assert "mlp_chain_kernel" in out["aligned"][2] and "mlp_chain_kernel" not in out["shifted"][2]
+    scale = np.abs(out["aligned"][0]).max()
+    # two summation orders, and a ReLU unit within rounding of zero may fall either way: a loose bound, the strict
+    # comparison with the oracle is test_chain_gradients_match_oracle and test_mlp_gradients_match_oracle
+    assert np.abs(out["aligned"][0] - out["shifted"][0]).max() <= 1e-4 * scale
+    assert np.allclose(out["aligned"][1], out["shifted"][1], rtol=2e-6)
+    h = B.dbw_create(rowptr, colidx, n, d, ld=ld, model=B.make_model(B.MODEL_MLP, batch, dims, B.LOSS_MSE, grad_path=B.GRAD_CHAIN))
+    try:
+        with pytest.raises(B.DbwError) as e:
+            B.dbw_grad(h, params, shifted, y, torch.zeros((n, ld), device="cuda"), torch.zeros(n, device="cuda"))
+        assert e.value.code == B.ERR_UNSUPPORTED
+    finally:
+        B.dbw_destroy(h)
+
+
 def test_chain_is_picked_for_the_2nn_and_refused_where_it_cannot_run(B):
     rowptr, colidx = inputs.graph_ring(10)
 
@@ -146,6 +188,7 @@ def test_chain_is_picked_for_the_2nn_and_refused_where_it_cannot_run(B):
         finally:
             B.dbw_destroy(h)
     assert "mlp_chain_kernel" in kernels_of([256, 256, 256, 10], 1024, B.GRAD_AUTO)
+    assert "mlp_wgrad_kernel" in kernels_of([256, 256, 256, 10], 1024, B.GRAD_AUTO)
     assert "mlp_chain_kernel" not in kernels_of([256, 256, 256, 10], 1024, B.GRAD_LAYERS)
     assert "mlp_chain_kernel" not in kernels_of([256, 256, 256, 10], 16, B.GRAD_AUTO)       # too few blocks to fill the chip
     for dims in ([256, 200, 10], [250, 256, 10], [256, 256, 128, 10], [256, 256, 20], [256, 10]):
