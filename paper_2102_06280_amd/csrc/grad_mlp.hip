@@ -238,6 +238,75 @@ ChainPlan chain_plan(int L, const int32_t *dims, int B, int workers, int grad_pa
     return cp;
 }
 
+// Weight and bias gradients of layers 1 .. layers in one launch (mlp_wgrad.h), from the deltas and activations
+// in the workers' scratch blocks; extra workgroups add the head's per-chunk sums when it has any.
+struct WgradPlan {
+    int layers;                 // dW_l and db_l for l = 1 .. layers
+    bool last_db;               // false: somebody else (the head) computes db of layer `layers`
+    const int64_t *a_off, *dz_off, *w_off;
+    int64_t w_end;              // end of b_layers in the parameter row
+    int64_t per, split_floats;
+};
+int launch_grouped_wgrad(dbw_ctx *c, const dbw_fc_args &a, const WgradPlan &wp, const fchead::Args &h, int head_chunks,
+                         hipStream_t s)
+{
+    const int B = a.B, N = c->N;
+    const int32_t *dims = a.dims;
+    const int64_t wstride = a.act_stride;
+    mlpwgrad::Args q{};
+    q.B = B; q.layers = wp.layers; q.workers = N;
+    // 64 x 64 tiles when they alone give every CU two workgroups, else 64 x 32; if that still leaves CUs idle, the
+    // batch is split as well (partial tiles to scratch, one more launch to add them)
+    auto count_tiles = [&](int tn, int *begin) {
+        int t = 0;
+        for (int l = 1; l <= wp.layers; ++l) {
+            if (begin) begin[l] = t;
+            t += ((dims[l] + 63) / 64) * ((dims[l - 1] + tn - 1) / tn);
+        }
+        if (begin) begin[wp.layers + 1] = t;
+        return t;
+    };
+    const int tn = (int64_t)count_tiles(64, nullptr) * N >= 512 ? 64 : 32;
+    const int tiles = count_tiles(tn, q.tile_begin);
+    for (int l = 1; l <= wp.layers; ++l) {
+        q.n_rows[l] = dims[l];
+        q.n_cols[l] = dims[l - 1];
+        q.want_db[l] = l < wp.layers || wp.last_db;
+        q.dz_off[l] = wp.dz_off[l];
+        q.a[l] = l == 1 ? a.in : a.act + wp.a_off[l - 1];
+        q.a_ld[l] = l == 1 ? a.in_ld : dims[l - 1];
+        q.a_stride[l] = l == 1 ? a.in_stride : wstride;
+        q.w_off[l] = wp.w_off[l];
+    }
+    q.w_off[wp.layers + 1] = wp.w_end;
+    q.dz = a.act; q.dz_stride = wstride;
+    q.grads = a.grads; q.g_stride = c->ld;
+    q.part = a.act + 2 * wp.per; q.part_stride = wstride;
+    const int64_t len = wp.w_end - wp.w_off[1];
+    int splits = (int)std::min<int64_t>(8, std::max<int64_t>(1, 512 / ((int64_t)tiles * N)));
+    splits = std::min(splits, (B + 63) / 64);
+    splits = (int)std::min<int64_t>(splits, std::max<int64_t>(1, wp.split_floats / len));
+    q.splits = splits;
+    q.kper = ((B + splits - 1) / splits + 15) / 16 * 16;
+    const int head_blocks = head_chunks > 1 ? (int)((fchead::partial_floats(h.H, h.C, h.bprev_off >= 0) + 255) / 256) : 0;
+    {
+        dbw_timer tm(c, "mlp_wgrad_kernel", s);
+        const int wgs = tiles * N * splits + head_blocks * N;
+        const dim3 grid((wgs + mlpwgrad::XCDS - 1) / mlpwgrad::XCDS * mlpwgrad::XCDS);
+        if (tn == 64)
+            hipLaunchKernelGGL(mlpwgrad::kernel<4>, grid, dim3(mlpwgrad::THREADS), 0, s, q, h, head_chunks, head_blocks);
+        else
+            hipLaunchKernelGGL(mlpwgrad::kernel<2>, grid, dim3(mlpwgrad::THREADS), 0, s, q, h, head_chunks, head_blocks);
+        DBW_HIP(hipGetLastError());
+    }
+    if (splits > 1) {
+        dbw_timer tm(c, "mlp_reduce_kernel", s);
+        hipLaunchKernelGGL(mlpwgrad::reduce_kernel, dim3((unsigned)((len / 4 + 255) / 256), N), dim3(256), 0, s, q);
+        DBW_HIP(hipGetLastError());
+    }
+    return DBW_OK;
+}
+
 int64_t act_floats(int L, const int32_t *dims, int B)
 {
     int64_t n = 0;
@@ -373,9 +442,23 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
         dbw_timer tm(c, "mlp_forward_gemm", s);
         DBW_HIP(bgemm::launch<64>(A, Bm, E, B, dims[l], dims[l - 1], N, s));
     }
+    // Weight gradients of the layers the GEMM kernels would take: all of them in one launch (mlp_wgrad.h) when the
+    // library may choose, every operand allows 128-bit accesses and the batch is long enough for that kernel's four
+    // wavefronts per tile, which share the samples (measured on 784-200-10 with 64 samples on 32 workers: 26 us
+    // against 21 us for the GEMM kernel, whose wavefronts share the tile instead).  The batch-32 streaming kernels
+    // keep their layers.
+    const int Lw = head.use ? L - 1 : L;
+    bool grouped = !chain.use && a.grad_path == DBW_GRAD_AUTO && Lw >= 1 && B >= 256 && a.in_ld % 4 == 0 && a.in_stride % 4 == 0 &&
+                   fc32::aligned16(a.in) && fc32::aligned16(grads) && c->ld % 4 == 0 && a.param_off % 4 == 0 &&
+                   fc32::aligned16(act) && wstride % 4 == 0;
+    for (int l = 0; l <= Lw && grouped; ++l) grouped = dims[l] % 4 == 0;
+    for (int l = 1; l <= Lw && grouped; ++l)
+        grouped = !batch32_layer(B, dims[l - 1], dims[l], c->ld, w_off[l], params, grads);
+    int64_t split_floats = 0;                            // the split partials of the layers, which the head's own follow
+    for (int q = 1; q <= L; ++q) split_floats = std::max<int64_t>(split_floats, (int64_t)MAX_SPLITS * B * dims[q]);
+    fchead::Args h{};
     if (head.use) {
         // last layer, loss and its whole backward pass in one launch (with the chain: the layers below as well)
-        fchead::Args h{};
         h.B = B; h.H = dims[L - 1]; h.C = dims[L]; h.S = head.S;
         if (L == 1) {
             h.a = a.in; h.a_ld = a.in_ld; h.a_stride = a.in_stride;
@@ -395,8 +478,6 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
         }
         h.params = params; h.grads = grads; h.p_stride = c->ld; h.w_off = w_off[L]; h.b_off = b_off[L];
         h.y = a.y; h.loss = a.loss;
-        int64_t split_floats = 0;                        // the split partials of the layers, which the head's own follow
-        for (int q = 1; q <= L; ++q) split_floats = std::max<int64_t>(split_floats, (int64_t)MAX_SPLITS * B * dims[q]);
         h.part = act + 2 * per + (split_floats + 3) / 4 * 4; h.part_stride = wstride;
         h.err = c->err;
         if (chain.use) {
@@ -437,58 +518,10 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
             }
             if (rc != DBW_OK) return rc;
 
-            // weight and bias gradients of the layers below the head: one launch, and one more that adds its
-            // split sums and the head's per-chunk sums
-            mlpwgrad::Args q{};
-            q.B = B; q.H = dims[1]; q.layers = L - 1; q.workers = N;
-            // 64 x 64 tiles when they alone give every CU two workgroups, else 64 x 32; if that still leaves CUs
-            // idle, the batch is split as well (partial tiles to scratch, one more launch to add them)
-            auto count_tiles = [&](int tn, int *begin) {
-                int t = 0;
-                for (int l = 1; l < L; ++l) {
-                    if (begin) begin[l] = t;
-                    t += (dims[1] / 64) * ((dims[l - 1] + tn - 1) / tn);
-                }
-                if (begin) begin[L] = t;
-                return t;
-            };
-            const int tn = (int64_t)count_tiles(64, nullptr) * N >= 512 ? 64 : 32;
-            const int tiles = count_tiles(tn, q.tile_begin);
-            for (int l = 1; l < L; ++l) {
-                q.n_cols[l] = dims[l - 1];
-                q.want_db[l] = l < L - 1;                 // the head has the bias gradient of the layer below it
-                q.dz_off[l] = dz_off[l];
-                q.a[l] = l == 1 ? a.in : act + a_off[l - 1];
-                q.a_ld[l] = l == 1 ? a.in_ld : dims[l - 1];
-                q.a_stride[l] = l == 1 ? a.in_stride : wstride;
-                q.w_off[l] = w_off[l];
-            }
-            q.w_off[L] = w_off[L];
-            q.dz = act; q.dz_stride = wstride;
-            q.grads = grads; q.g_stride = c->ld;
-            q.part = act + 2 * per; q.part_stride = wstride;
-            const int64_t len = w_off[L] - w_off[1];
-            int splits = (int)std::min<int64_t>(8, std::max<int64_t>(1, 512 / ((int64_t)tiles * N)));
-            splits = std::min(splits, (B + 63) / 64);
-            splits = (int)std::min<int64_t>(splits, std::max<int64_t>(1, split_floats / len));
-            q.splits = splits;
-            q.kper = ((B + splits - 1) / splits + 15) / 16 * 16;
-            const int head_blocks = head.chunks > 1 ? (int)((fchead::partial_floats(h.H, h.C, true) + 255) / 256) : 0;
-            {
-                dbw_timer tm(c, "mlp_wgrad_kernel", s);
-                const int wgs = tiles * N * splits + head_blocks * N;
-                const dim3 grid((wgs + mlpwgrad::XCDS - 1) / mlpwgrad::XCDS * mlpwgrad::XCDS);
-                if (tn == 64)
-                    hipLaunchKernelGGL(mlpwgrad::kernel<4>, grid, dim3(mlpwgrad::THREADS), 0, s, q, h, head.chunks, head_blocks);
-                else
-                    hipLaunchKernelGGL(mlpwgrad::kernel<2>, grid, dim3(mlpwgrad::THREADS), 0, s, q, h, head.chunks, head_blocks);
-                DBW_HIP(hipGetLastError());
-            }
-            if (splits > 1) {
-                dbw_timer tm(c, "mlp_reduce_kernel", s);
-                hipLaunchKernelGGL(mlpwgrad::reduce_kernel, dim3((unsigned)((len / 4 + 255) / 256), N), dim3(256), 0, s, q);
-                DBW_HIP(hipGetLastError());
-            }
+            // weight and bias gradients of the layers below the head, and the head's per-chunk sums
+            const WgradPlan wp{L - 1, false, a_off, dz_off, w_off, w_off[L], per, split_floats};
+            const int rc2 = launch_grouped_wgrad(c, a, wp, h, head.chunks, s);
+            if (rc2 != DBW_OK) return rc2;
             return DBW_OK;
         } else {
         const dim3 grid(head.chunks, N);
@@ -507,7 +540,7 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
         else rc = vec ? go(fchead::kernel<DBW_LOSS_XENT, true>) : go(fchead::kernel<DBW_LOSS_XENT, false>);
         if (rc != DBW_OK) return rc;
         }
-        if (head.chunks > 1) {
+        if (head.chunks > 1 && !grouped) {          // (the grouped weight-gradient launch adds them otherwise)
             const int64_t E = fchead::partial_floats(h.H, h.C, L > 1);
             dbw_timer tm(c, "fc_head_reduce", s);
             hipLaunchKernelGGL(fchead::reduce_kernel, dim3((unsigned)((E + 255) / 256), N), dim3(256), 0, s, h, head.chunks);
@@ -526,10 +559,10 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
         DBW_HIP(hipGetLastError());
     }
     // backward
-    for (int l = head.use ? L - 1 : L; l >= 1; --l) {
+    for (int l = Lw; l >= 1; --l) {
         const bool fast = batch32_layer(B, dims[l - 1], dims[l], c->ld, w_off[l], params, grads) && wstride % 4 == 0 &&
                           dz_off[l] % 4 == 0 && fc32::aligned16(act);
-        {   // dW_l = dz_l^T a_{l-1}
+        if (!grouped) {   // dW_l = dz_l^T a_{l-1}
             Dense<false> A{act + dz_off[l], dims[l], wstride}, Bm;
             if (l == 1)
                 Bm = {a.in, a.in_ld, a.in_stride};
@@ -566,7 +599,7 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
                 }
             }
         }
-        if (!(head.use && l == L - 1)) {       // the head has written the bias gradient of the layer below it
+        if (!grouped && !(head.use && l == L - 1)) {       // the head has written the bias gradient of the layer below it
             dbw_timer tm(c, "colsum_kernel", s);
             if (B >= 512)    // long batches: 32 row groups per workgroup
                 hipLaunchKernelGGL(colsum_kernel<32>, dim3((dims[l] + 31) / 32, N), dim3(1024), 0, s, B, dims[l],
@@ -603,6 +636,10 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
             dbw_timer tm(c, "mlp_dgrad_gemm", s);
             DBW_HIP(bgemm::launch<64>(A, Bm, E, B, dims[0], dims[1], N, s));
         }
+    }
+    if (grouped) {
+        const WgradPlan wp{Lw, !head.use, a_off, dz_off, w_off, b_off[Lw] + dims[Lw], per, split_floats};
+        return launch_grouped_wgrad(c, a, wp, h, head.use ? head.chunks : 1, s);
     }
     return DBW_OK;
 }

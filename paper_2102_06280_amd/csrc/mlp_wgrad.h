@@ -1,8 +1,10 @@
 // Weight and bias gradients of all hidden layers of a multilayer perceptron, all workers, in
 // one launch (Section 2.1, stochastic gradient of the local loss):
 //   dW_l[m][n] = sum over the batch of dz_l[s][m] a_{l-1}[s][n],   db_l[m] = sum over the batch of dz_l[s][m]
-// for l = 1 .. L - 1, reading the deltas and activations that the chain kernel (mlp_chain.h) left
-// in the worker's scratch block (a_0 = the batch itself).
+// for the layers below the head (or all layers, when the model has no fused head), reading the deltas
+// and activations that the chain kernel (mlp_chain.h) or the per-layer kernels left in the worker's
+// scratch block (a_0 = the batch itself).  Widths must divide by 4; tiles of rows or columns that
+// stick out over a matrix are computed on any valid data and not stored.
 //
 // Both operands are stored sample-major, i.e. contiguous along their output index, and the matrix
 // instruction v_mfma_f32_16x16x4_f32 leaves open which 16 outputs a tile's rows stand for.  So a lane
@@ -36,15 +38,16 @@ struct alignas(4 * N) Vec {
 };
 
 struct Args {
-    int B, H, layers, workers;               // batch, rows of every dW_l (the hidden width), l = 1 .. layers
+    int B, layers, workers;                  // batch; l = 1 .. layers
+    int n_rows[MAX_L + 1];                   // rows of dW_l = width of layer l, a multiple of 4
     int n_cols[MAX_L + 1];                   // columns of dW_l = width of a_{l-1}, a multiple of 4
     int tile_begin[MAX_L + 2];               // blockIdx.x of layer l's first tile
     int want_db[MAX_L + 1];                  // 0: somebody else computes db_l
-    const float *dz;                         // dz_l [B][H] at dz + w * dz_stride + dz_off[l]
+    const float *dz;                         // dz_l [B][n_rows] at dz + w * dz_stride + dz_off[l]
     int64_t dz_off[MAX_L + 1], dz_stride;
     const float *a[MAX_L + 1];               // a_{l-1} [B][a_ld] at a[l] + w * a_stride[l]
     int64_t a_ld[MAX_L + 1], a_stride[MAX_L + 1];
-    float *grads;                            // worker rows of stride g_stride; W_l [H][n_cols] at w_off[l], then b_l [H]
+    float *grads;                            // worker rows of stride g_stride; W_l [n_rows][n_cols] at w_off[l], then b_l
     int64_t g_stride, w_off[MAX_L + 2];      // w_off[layers + 1] = end of b_layers
     float *part;                             // [worker][split][w_off[layers + 1] - w_off[1]] when splits > 1
     int64_t part_stride;
@@ -77,14 +80,15 @@ __global__ __launch_bounds__(THREADS, 2) void kernel(Args g, fchead::Args h, int
     const int bx = id % tiles, w = (id / tiles) % g.workers, split = id / (tiles * g.workers);
     int l = 1;
     while (l < g.layers && bx >= pick(g.tile_begin, l + 1)) ++l;
-    const int N = pick(g.n_cols, l), H = g.H, ntn = (N + TN - 1) / TN;
+    const int N = pick(g.n_cols, l), H = pick(g.n_rows, l), ntn = (N + TN - 1) / TN;
     const int t = bx - pick(g.tile_begin, l), m0 = 64 * (t / ntn), n0 = TN * (t % ntn);
     const int s_begin = split * g.kper, s_end = min(g.B, s_begin + g.kper);
     const bool bias = pick(g.want_db, l) && n0 == 0;
 
-    const float *__restrict__ dz = g.dz + w * g.dz_stride + pick(g.dz_off, l) + m0 + 4 * l16;
-    const bool cols_ok = n0 + CBK * l16 < N;                  // N divides by 4, so by CBK
-    const int ncol = cols_ok ? n0 + CBK * l16 : 0;            // a column group beyond N: any valid one, never stored
+    // a row or column group beyond the matrix (H and N divide by 4): any valid one instead, never stored
+    const bool rows_ok = m0 + 4 * l16 < H, cols_ok = n0 + CBK * l16 < N;
+    const float *__restrict__ dz = g.dz + w * g.dz_stride + pick(g.dz_off, l) + (rows_ok ? m0 + 4 * l16 : 0);
+    const int ncol = cols_ok ? n0 + CBK * l16 : 0;
     const float *__restrict__ av = pick(g.a, l) + w * pick(g.a_stride, l) + ncol;
     const int64_t a_ld = pick(g.a_ld, l);
 
@@ -207,9 +211,9 @@ __global__ __launch_bounds__(THREADS, 2) void kernel(Args g, fchead::Args h, int
 #pragma unroll
                     for (int j = 0; j < CBK; ++j) v.v[j] += o.v[j];
                 }
-                if (cols_ok) *(vec *)(out + (int64_t)(m0 + row) * N + n0 + CBK * l16) = v;
+                if (cols_ok && m0 + row < H) *(vec *)(out + (int64_t)(m0 + row) * N + n0 + CBK * l16) = v;
             }
-    } else if (wave == 1 && bias && lane < 16) {
+    } else if (wave == 1 && bias && lane < 16 && m0 + 4 * lane < H) {
         f32x4 v = *(const f32x4 *)&bred[0][4 * lane];
 #pragma unroll
         for (int q = 1; q < WAVES; ++q) v += *(const f32x4 *)&bred[q][4 * lane];
@@ -244,7 +248,7 @@ __device__ __forceinline__ void reduce_body(const Args &g, int bx, int w)
     bool keep = true;
 #pragma unroll
     for (int l = 1; l <= MAX_L; ++l)
-        if (l <= g.layers && !pick(g.want_db, l) && pos >= pick(g.w_off, l) + (int64_t)g.H * pick(g.n_cols, l) && pos < pick(g.w_off, l + 1))
+        if (l <= g.layers && !pick(g.want_db, l) && pos >= pick(g.w_off, l) + (int64_t)pick(g.n_rows, l) * pick(g.n_cols, l) && pos < pick(g.w_off, l + 1))
             keep = false;
     if (keep) *(f32x4 *)(g.grads + w * g.g_stride + pos) = sum;
 }

@@ -128,6 +128,24 @@ def test_chain_gradients_match_oracle(B, orc, dims, batch, n, loss_kind, blocks)
     check_gradients(B, orc, dims, batch, n, loss_kind, grad_path=B.GRAD_CHAIN, expect={"mlp_chain_kernel"})
 
 
+# Layered path with the weight gradients of all layers in one launch (long batches, widths that divide by 4):
+# unequal hidden widths and a head with per-chunk sums; more than 16 classes (no head, every bias sum from the
+# weight-gradient kernel); one wide layer with 12 outputs (a partial tile of rows), split over the batch.
+GROUPED_SHAPES = [
+    ([64, 96, 40, 12], 300, 5, "xent"),
+    ([64, 40, 20], 260, 3, "xent"),
+    ([2000, 12], 256, 2, "mse"),
+    ([128, 72, 8], 1000, 2, "mse"),
+]
+
+
+@pytest.mark.parametrize("dims,batch,n,loss_kind", GROUPED_SHAPES,
+                         ids=[f"{'-'.join(map(str, s[0]))}-B{s[1]}-N{s[2]}-{s[3]}" for s in GROUPED_SHAPES])
+def test_grouped_weight_gradients_match_oracle(B, orc, dims, batch, n, loss_kind):
+    check_gradients(B, orc, dims, batch, n, loss_kind, expect={"mlp_wgrad_kernel"})
+    check_gradients(B, orc, dims, batch, n, loss_kind, grad_path=B.GRAD_LAYERS, expect={"mlp_wgrad_gemm"})
+
+
 def test_chain_falls_back_when_the_batch_is_not_16_byte_aligned(B, orc):
     """The chain kernel fetches the batch with 128-bit loads.  A batch that starts 4 bytes into an allocation takes
     the layered path under DBW_GRAD_AUTO (same gradients), and is refused under DBW_GRAD_CHAIN."""
