@@ -298,10 +298,25 @@ int launch(dbw_ctx *c, const float *x, const float *g, float *out, LR lr, hipStr
                          (!HAS_G || (uintptr_t)g % 16 == 0);
     int64_t n_vec = aligned ? c->d / 4 : 0;
     if (n_vec > 0) {
-        // widest tile (power of two float4 columns, 8..256) that holds all N rows in 64 KB
-        int tc4 = 256;
-        while (tc4 >= 8 && (int64_t)c->N * tc4 > LDS_TILE) tc4 /= 2;
-        const bool use_lds = tc4 >= 8 && c->nnz <= LDS_MAX_EDGES && (n_vec + tc4 - 1) / tc4 >= device_cus() / 2;
+        // Tile width: a power of two of float4 columns, 8..256, that holds all N rows in 64 KB.  The widest one
+        // moves the longest pieces of a row (2 KB pieces run at about 70 % of the HBM peak, 1 KB 68 %, 512 B 62 %,
+        // 256 B 54 %), but a short parameter vector then gives the CUs unequal numbers of tiles (d = 159 010 on 32
+        // workers: 311 tiles of 128 columns on 256 CUs, two rounds for 55 of them), so the width that minimises
+        // rounds x width / efficiency is taken.
+        const int64_t vec_cols = (c->d + 3) / 4;
+        int tc4 = 0;
+        double best = 0.0;
+        for (int cand = 256; cand >= 8; cand /= 2) {
+            if ((int64_t)c->N * cand > LDS_TILE) continue;
+            const int64_t tiles = (vec_cols + cand - 1) / cand, rounds = (tiles + device_cus() - 1) / device_cus();
+            const double eff = cand >= 128 ? 0.70 : (cand == 64 ? 0.68 : (cand == 32 ? 0.62 : (cand == 16 ? 0.54 : 0.40)));
+            const double cost = (double)rounds * cand / eff;
+            if (tc4 == 0 || cost < best) {
+                best = cost;
+                tc4 = cand;
+            }
+        }
+        const bool use_lds = tc4 >= 8 && c->nnz <= LDS_MAX_EDGES && (vec_cols + tc4 - 1) / tc4 >= device_cus() / 2;
         int rc = DBW_OK;
         if (use_lds) {
             // the LDS kernel also takes the float4 that straddles column d (rows are aligned and
