@@ -332,12 +332,14 @@ def test_paper_models_lock_step(B, orc, cid, order):
         wl.close()
 
 
-def test_graph_replay_matches_eager(B):
+@pytest.mark.parametrize("cid", [2, 7], ids=["config2", "config7-chain-and-threshold-rule"])
+def test_graph_replay_matches_eager(B, cid):
     """Rounds captured as HIP graphs (one per round) give the same bits as eager rounds, on
-    every replay, with eager work and synchronisations between replays."""
+    every replay, with eager work and synchronisations between replays.  Configuration 7 runs the chain kernels
+    and the one-launch threshold rule + selection, whose epoch state is put back before every replay."""
     from paper_2102_06280_amd.workload import Workload
-    eager = Workload(2, rounds=6)
-    graphed = Workload(2, rounds=6)
+    eager = Workload(cid, rounds=6)
+    graphed = Workload(cid, rounds=6)
     try:
         for _ in range(6):
             eager.step()
@@ -348,6 +350,8 @@ def test_graph_replay_matches_eager(B):
         for rep in range(3):
             graphed.x[0].copy_(start)
             graphed.cur, graphed.k = 0, 0
+            if graphed.dynamic_b:
+                B.dbw_dtur_reset(graphed.h)
             torch.cuda.synchronize()
             graphed.replay(graphs[:3])
             torch.cuda.synchronize()
