@@ -101,18 +101,62 @@ __host__ __device__ inline size_t lds_floats(int H, int C, int S)
 __host__ __device__ inline size_t lds_bytes(int H, int C, int S) { return sizeof(float) * lds_floats(H, C, S); }
 __host__ __device__ inline int64_t partial_floats(int H, int C, bool bprev) { return (int64_t)C * H + C + (bprev ? H : 0) + 1; }
 
+// (row, column) of the flat index e in rows of P elements, for e = tid, tid + THREADS, ...: one division per thread,
+// then additions.  With a division per element the staging loops below spent more time on them than on their loads.
+struct RowWalk {
+    int r, k, dr, dk, P;
+    __device__ __forceinline__ RowWalk(int tid, int P_) : P(P_)
+    {
+        r = tid / P_;
+        k = tid - r * P_;
+        dr = THREADS / P_;
+        dk = THREADS - dr * P_;
+    }
+    __device__ __forceinline__ void next()
+    {
+        r += dr;
+        k += dk;
+        if (k >= P) {
+            k -= P;
+            ++r;
+        }
+    }
+};
+
 // W [C][H] of worker w -> its LDS image [C + 1][pitch]; row C, the columns >= H and the slack behind are zero.
 __device__ __forceinline__ void stage_w(const Args &g, int w, float *Wl, int tid)
 {
     const int H = g.H, C = g.C, HP = row_pitch(H);
     const float *__restrict__ Wg = g.params + w * g.p_stride + g.w_off;
+    if (H % 4 == 0 && g.w_off % 4 == 0 && g.p_stride % 4 == 0 && (uintptr_t)g.params % 16 == 0) {
+        // rows of W start on 16-byte boundaries: 128-bit loads, a quarter of the instructions
+        const int q4 = HP / 4, total = (C + 1) * q4 + 4;
+        RowWalk rw(tid, q4);
+        for (int e0 = 0; e0 < total; e0 += 4 * THREADS) {
+            float4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const bool ok = e0 + tid + u * THREADS < total && rw.r < C && 4 * rw.k < H;
+                v[u] = *(const float4 *)(Wg + (ok ? rw.r * H + 4 * rw.k : 0));
+                if (!ok) v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                rw.next();
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int e = e0 + tid + u * THREADS;
+                if (e < total) *(float4 *)(Wl + 4 * e) = v[u];
+            }
+        }
+        return;
+    }
     const int total = (C + 1) * HP + 16;
+    RowWalk rw(tid, HP);
     for (int e0 = 0; e0 < total; e0 += 8 * THREADS) {       // eight loads in flight per thread
         float v[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            const int e = e0 + tid + u * THREADS, r = e / HP, k = e - r * HP;
-            v[u] = (e < total && r < C && k < H) ? Wg[r * H + k] : 0.f;
+            v[u] = (e0 + tid + u * THREADS < total && rw.r < C && rw.k < H) ? Wg[rw.r * H + rw.k] : 0.f;
+            rw.next();
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
@@ -250,58 +294,82 @@ __device__ __forceinline__ void body(const Args &g, float *zl, float *zp, float 
     float *__restrict__ da = (g.da && !da_to_lds) ? g.da + w * g.da_stride + (int64_t)s0 * g.da_ld : nullptr;
     const int NB = (H + 15) / 16;                       // 16-column blocks of the input dimension
 
-    for (int nb = wave; nb < NB; nb += WAVES) {
-        const int col = 16 * nb + l16;
+    // Two 16-column blocks per pass (nb and nb + WAVES): their chains of dependent instructions and LDS reads overlap.
+    // A pass whose second block does not exist computes it on the first one's columns and stores nothing for it.
+    for (int nb0 = wave; nb0 < NB; nb0 += 2 * WAVES) {
+        const bool two = nb0 + WAVES < NB;
+        int col[2];
+        col[0] = 16 * nb0 + l16;
+        col[1] = two ? col[0] + 16 * WAVES : col[0];
         // ---- dW[class][col] = sum over samples of dz[sample][class] a[sample][col]: the operands of 16 samples are
-        // read before their four instructions, two accumulators
+        // read before their instructions, two accumulators per block
         {
-            f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = acc0;
+            f32x4 acc[2][2];
+#pragma unroll
+            for (int p = 0; p < 2; ++p) acc[p][0] = acc[p][1] = f32x4{0.f, 0.f, 0.f, 0.f};
             for (int k0 = 0; k0 < S; k0 += 16) {
-                float zv[4], av[4];
+                float zv[4], av[2][4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     zv[u] = zl[(k0 + 4 * u + lq) * MAX_C + l16];
-                    av[u] = al[(k0 + 4 * u + lq) * HP + col];
-                }
-                acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(zv[0], av[0], acc0, 0, 0, 0);
-                acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(zv[1], av[1], acc1, 0, 0, 0);
-                acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(zv[2], av[2], acc0, 0, 0, 0);
-                acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(zv[3], av[3], acc1, 0, 0, 0);
-            }
-            if (col < H) {
 #pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    if (4 * lq + v < C) out_w[(4 * lq + v) * H + col] = acc0[v] + acc1[v];
+                    for (int p = 0; p < 2; ++p) av[p][u] = al[(k0 + 4 * u + lq) * HP + col[p]];
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int p = 0; p < 2; ++p)
+                        acc[p][u & 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(zv[u], av[p][u], acc[p][u & 1], 0, 0, 0);
             }
+#pragma unroll
+            for (int p = 0; p < 2; ++p)
+                if (col[p] < H && (p == 0 || two)) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        if (4 * lq + v < C) out_w[(4 * lq + v) * H + col[p]] = acc[p][0][v] + acc[p][1][v];
+                }
         }
         // ---- da[sample][col] = sum over classes of dz[sample][class] W[class][col], masked; its column sums.
         // Lane group q carries the classes 4 q + j in instruction j: one 128-bit read of dz per 16 samples.
         if (da || da_to_lds) {
-            float wv[4];
+            float wv[2][4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) wv[j] = Wl[min(4 * lq + j, C) * HP + col];
-            float colsum = 0.f;
+            for (int p = 0; p < 2; ++p)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) wv[p][j] = Wl[min(4 * lq + j, C) * HP + col[p]];
+            float colsum[2] = {0.f, 0.f};
             for (int mb = 0; mb < S / 16; ++mb) {
                 const f32x4 zq = *(const f32x4 *)(zl + (16 * mb + l16) * MAX_C + 4 * lq);
-                float keep[4];
+                float keep[2][4];
 #pragma unroll
-                for (int v = 0; v < 4; ++v) keep[v] = al[(16 * mb + 4 * lq + v) * HP + col];
-                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+                for (int p = 0; p < 2; ++p)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(zq[j], wv[j], acc, 0, 0, 0);
+                    for (int v = 0; v < 4; ++v) keep[p][v] = al[(16 * mb + 4 * lq + v) * HP + col[p]];
+                f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int s = 16 * mb + 4 * lq + v;
-                    float d = acc[v];
-                    if (g.mask && !(keep[v] > 0.f)) d = 0.f;
-                    if (da_to_lds) al[s * HP + col] = d;       // this wavefront alone reads and writes these columns
-                    else if (s < ns && col < H) da[(int64_t)s * g.da_ld + col] = d;
-                    colsum += d;                        // rows beyond the batch have dz = 0
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int p = 0; p < 2; ++p) acc[p] = __builtin_amdgcn_mfma_f32_16x16x4f32(zq[j], wv[p][j], acc[p], 0, 0, 0);
+#pragma unroll
+                for (int p = 0; p < 2; ++p) {
+                    if (p == 1 && !two) continue;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int s = 16 * mb + 4 * lq + v;
+                        float d = acc[p][v];
+                        if (g.mask && !(keep[p][v] > 0.f)) d = 0.f;
+                        if (da_to_lds) al[s * HP + col[p]] = d;       // this wavefront alone reads and writes these columns
+                        else if (s < ns && col[p] < H) da[(int64_t)s * g.da_ld + col[p]] = d;
+                        colsum[p] += d;                        // rows beyond the batch have dz = 0
+                    }
                 }
             }
-            colsum += __shfl_xor(colsum, 16, 64);
-            colsum += __shfl_xor(colsum, 32, 64);
-            if (out_bprev && lq == 0 && col < H) out_bprev[col] = colsum;
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                colsum[p] += __shfl_xor(colsum[p], 16, 64);
+                colsum[p] += __shfl_xor(colsum[p], 32, 64);
+                if (out_bprev && lq == 0 && col[p] < H && (p == 0 || two)) out_bprev[col[p]] = colsum[p];
+            }
         }
     }
     if (tid < C) {
@@ -365,8 +433,9 @@ __global__ __launch_bounds__(THREADS) void kernel(Args g)
         const int q4 = HP / 4, total = S * q4;
         const float *__restrict__ bin = g.params + w * g.p_stride + g.in_bias_off;
         const int64_t plane = (int64_t)g.B * H;
-        for (int e = tid; e < total; e += THREADS) {
-            const int r = e / q4, k = 4 * (e - r * q4);
+        RowWalk rw(tid, q4);
+        for (int e = tid; e < total; e += THREADS, rw.next()) {
+            const int r = rw.r, k = 4 * rw.k;
             float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
             if (r < ns && k < H) {
                 const float *src = g.a + w * g.a_stride + (int64_t)(s0 + r) * H + k;
@@ -382,13 +451,15 @@ __global__ __launch_bounds__(THREADS) void kernel(Args g)
         }
     } else if (VEC) {
         const int q4 = HP / 4, total = S * q4;
+        RowWalk rw(tid, q4);
         for (int e0 = 0; e0 < total; e0 += 8 * THREADS) {
             float4 v[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
-                const int e = e0 + tid + u * THREADS, r = e / q4, k = 4 * (e - r * q4);
                 v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (e < total && r < ns && k < H) v[u] = *(const float4 *)(a + (int64_t)r * g.a_ld + k);
+                if (e0 + tid + u * THREADS < total && rw.r < ns && 4 * rw.k < H)
+                    v[u] = *(const float4 *)(a + (int64_t)rw.r * g.a_ld + 4 * rw.k);
+                rw.next();
             }
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
@@ -398,12 +469,13 @@ __global__ __launch_bounds__(THREADS) void kernel(Args g)
         }
     } else {
         const int total = S * HP;
+        RowWalk rw(tid, HP);
         for (int e0 = 0; e0 < total; e0 += 8 * THREADS) {
             float v[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
-                const int e = e0 + tid + u * THREADS, r = e / HP, k = e - r * HP;
-                v[u] = (e < total && r < ns && k < H) ? a[(int64_t)r * g.a_ld + k] : 0.f;
+                v[u] = (e0 + tid + u * THREADS < total && rw.r < ns && rw.k < H) ? a[(int64_t)rw.r * g.a_ld + rw.k] : 0.f;
+                rw.next();
             }
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
