@@ -259,25 +259,27 @@ __device__ __forceinline__ void store_backward(const f32x4 (&acc)[RB][CB], float
         }
 }
 
-// rows x H floats from an LDS image to global rows of H floats, 128 bits per thread and step.
-__device__ __forceinline__ void copy_out(const float *src, int pitch, float *__restrict__ dst, int H, int rows, int tid)
+// rows x 4 Q4 floats from an LDS image to global rows of 4 Q4 floats, 128 bits per thread and step (Q4 is a
+// compile-time constant: the index arithmetic is shifts, not divisions).
+template <int Q4>
+__device__ __forceinline__ void copy_out(const float *src, int pitch, float *__restrict__ dst, int rows, int tid)
 {
-    const int q4 = H / 4, total = rows * q4;
+    const int total = rows * Q4;
     for (int e0 = 0; e0 < total; e0 += 4 * THREADS) {       // four LDS reads in flight, then their stores
         float4 v[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const int e = min(e0 + tid + u * THREADS, total - 1), r = e / q4;
-            v[u] = *(const float4 *)(src + r * pitch + 4 * (e - r * q4));
+            const int e = min(e0 + tid + u * THREADS, total - 1), r = e / Q4;
+            v[u] = *(const float4 *)(src + r * pitch + 4 * (e - r * Q4));
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const int e = e0 + tid + u * THREADS, r = e / q4;
+            const int e = e0 + tid + u * THREADS, r = e / Q4;
             // streaming stores: 30 MB of copies per launch must not push the 8 MB of weights, which every workgroup
             // reads over and over, out of the L2
             if (e < total) {
                 const f32x4 t = {v[u].x, v[u].y, v[u].z, v[u].w};
-                __builtin_nontemporal_store(t, (f32x4 *)(dst + (int64_t)r * H + 4 * (e - r * q4)));
+                __builtin_nontemporal_store(t, (f32x4 *)(dst + (int64_t)r * (4 * Q4) + 4 * (e - r * Q4)));
             }
         }
     }
@@ -319,19 +321,20 @@ __global__ __launch_bounds__(THREADS) void kernel(Args g)
     {   // the chunk of the batch, rows beyond it zero
         const float *__restrict__ x = g.x + w * g.x_stride + (int64_t)s0 * g.x_ld;
         const int q4 = K0 / 4, total = S * q4;
+        fchead::RowWalk rw(tid, q4);
         for (int e0 = 0; e0 < total; e0 += 8 * THREADS) {
             float4 v[8];
+            int at[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
-                const int e = e0 + tid + u * THREADS, r = e / q4, k = 4 * (e - r * q4);
                 v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (e < total && r < ns) v[u] = *(const float4 *)(x + (int64_t)r * g.x_ld + k);
+                if (e0 + tid + u * THREADS < total && rw.r < ns) v[u] = *(const float4 *)(x + (int64_t)rw.r * g.x_ld + 4 * rw.k);
+                at[u] = rw.r * P0 + 4 * rw.k;
+                rw.next();
             }
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int e = e0 + tid + u * THREADS, r = e / q4, k = 4 * (e - r * q4);
-                if (e < total) *(float4 *)(xl + r * P0 + k) = v[u];
-            }
+            for (int u = 0; u < 8; ++u)
+                if (e0 + tid + u * THREADS < total) *(float4 *)(xl + at[u]) = v[u];
         }
     }
     __syncthreads();
@@ -342,7 +345,7 @@ __global__ __launch_bounds__(THREADS) void kernel(Args g)
         float *out = slots + (l - 1) * Z;
         // what the head reads beyond the H columns of a row and behind the image must be zero (nobody reads this
         // slot during this layer; the batch chunk that lay in slot 1 is dead from layer 2 on)
-        for (int e = tid; e < S * (HP - H); e += THREADS) out[(e / (HP - H)) * HP + H + e % (HP - H)] = 0.f;
+        for (int e = tid; e < S * 4; e += THREADS) out[(e >> 2) * HP + H + (e & 3)] = 0.f;     // HP = H + 4 for these widths
         if (tid < 16) out[S * HP + tid] = 0.f;
         const int K = l == 1 ? K0 : H;
         const float *__restrict__ Wl_ = pw + pick(g.w_off, l);
@@ -363,7 +366,7 @@ __global__ __launch_bounds__(THREADS) void kernel(Args g)
             // a_{l-1} goes to scratch here, behind this product's last loads: a wavefront's loads and stores complete
             // in order, so stores issued before a product hold up the wait for its second chunk until they are
             // acknowledged (this product's phase was 1.4 us longer with the copy in front of it)
-            if (sub + 1 == NSUB && l >= 2) copy_out(in, HP, sw + pick(g.a_off, l - 1) + (int64_t)s0 * H, H, ns, tid);
+            if (sub + 1 == NSUB && l >= 2) copy_out<32 * CB>(in, HP, sw + pick(g.a_off, l - 1) + (int64_t)s0 * H, ns, tid);
             store_forward<RB, CBI>(acc, bcol, out, HP, n0s, lane);
         }
         __syncthreads();
@@ -385,12 +388,12 @@ __global__ __launch_bounds__(THREADS) void kernel(Args g)
             product<RB, CBI, false>(acc, slots + (l - 1) * Z, HP, H, Wl_, H, n0s, lane, b0);
             if (sub + 1 < NSUB) load_bwd<CBI>(b0, Wl_, H, 0, n0s + 16 * CBI, lane);
             else if (l > 2) load_bwd<CBI>(b0, pw + pick(g.w_off, l - 1), H, 0, n0, lane);
-            if (sub + 1 == NSUB) copy_out(slots + (l - 1) * Z, HP, sw + pick(g.dz_off, l) + (int64_t)s0 * H, H, ns, tid);
+            if (sub + 1 == NSUB) copy_out<32 * CB>(slots + (l - 1) * Z, HP, sw + pick(g.dz_off, l) + (int64_t)s0 * H, ns, tid);
             store_backward<RB, CBI>(acc, prev, HP, n0s, lane);
         }
         __syncthreads();
     }
-    copy_out(slots, HP, sw + pick(g.dz_off, 1) + (int64_t)s0 * H, H, ns, tid);      // dz_1 (with one hidden layer: the head's)
+    copy_out<32 * CB>(slots, HP, sw + pick(g.dz_off, 1) + (int64_t)s0 * H, ns, tid);      // dz_1 (with one hidden layer: the head's)
 }
 
 }  // namespace mlpchain
