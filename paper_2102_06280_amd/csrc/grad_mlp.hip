@@ -12,6 +12,7 @@
 #include "fc_batch32.h"
 #include "fc_head.h"
 #include "mlp_chain.h"
+#include "mlp_thin.h"
 #include "mlp_wgrad.h"
 #include "dbw_internal.h"
 
@@ -266,7 +267,8 @@ int launch_grouped_wgrad(dbw_ctx *c, const dbw_fc_args &a, const WgradPlan &wp, 
         if (begin) begin[wp.layers + 1] = t;
         return t;
     };
-    const int tn = (int64_t)count_tiles(64, nullptr) * N >= 512 ? 64 : 32;
+    const bool thin = B <= mlpthin::MAX_B;        // one wavefront per 64 x 32 tile, no split (mlp_thin.h)
+    const int tn = !thin && (int64_t)count_tiles(64, nullptr) * N >= 512 ? 64 : 32;
     const int tiles = count_tiles(tn, q.tile_begin);
     for (int l = 1; l <= wp.layers; ++l) {
         q.n_rows[l] = dims[l];
@@ -286,14 +288,21 @@ int launch_grouped_wgrad(dbw_ctx *c, const dbw_fc_args &a, const WgradPlan &wp, 
     int splits = (int)std::min<int64_t>(8, std::max<int64_t>(1, 512 / ((int64_t)tiles * N)));
     splits = std::min(splits, (B + 63) / 64);
     splits = (int)std::min<int64_t>(splits, std::max<int64_t>(1, wp.split_floats / len));
+    if (thin) splits = 1;
     q.splits = splits;
     q.kper = ((B + splits - 1) / splits + 15) / 16 * 16;
     const int head_blocks = head_chunks > 1 ? (int)((fchead::partial_floats(h.H, h.C, h.bprev_off >= 0) + 255) / 256) : 0;
     {
         dbw_timer tm(c, "mlp_wgrad_kernel", s);
-        const int wgs = tiles * N * splits + head_blocks * N;
+        const int wgs = (thin ? (tiles * N + mlpwgrad::WAVES - 1) / mlpwgrad::WAVES : tiles * N * splits) + head_blocks * N;
         const dim3 grid((wgs + mlpwgrad::XCDS - 1) / mlpwgrad::XCDS * mlpwgrad::XCDS);
-        if (tn == 64)
+        if (thin && B <= 16)
+            hipLaunchKernelGGL(mlpthin::wgrad_kernel<4>, grid, dim3(mlpwgrad::THREADS), 0, s, q, h, head_chunks, head_blocks);
+        else if (thin && B <= 32)
+            hipLaunchKernelGGL(mlpthin::wgrad_kernel<8>, grid, dim3(mlpwgrad::THREADS), 0, s, q, h, head_chunks, head_blocks);
+        else if (thin)
+            hipLaunchKernelGGL(mlpthin::wgrad_kernel<16>, grid, dim3(mlpwgrad::THREADS), 0, s, q, h, head_chunks, head_blocks);
+        else if (tn == 64)
             hipLaunchKernelGGL(mlpwgrad::kernel<4>, grid, dim3(mlpwgrad::THREADS), 0, s, q, h, head_chunks, head_blocks);
         else
             hipLaunchKernelGGL(mlpwgrad::kernel<2>, grid, dim3(mlpwgrad::THREADS), 0, s, q, h, head_chunks, head_blocks);
@@ -419,6 +428,27 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
             DBW_HIP(hipGetLastError());
             continue;
         }
+        // short batches: operands straight from global memory into matrix-instruction fragments (mlp_thin.h)
+        if (a.grad_path == DBW_GRAD_AUTO && B <= mlpthin::MAX_B && dims[l - 1] % 4 == 0 && dims[l] % 4 == 0 &&
+            A.ld % 4 == 0 && A.stride % 4 == 0 && fc32::aligned16(A.p) && fc32::aligned16(params) && c->ld % 4 == 0 &&
+            w_off[l] % 4 == 0 && fc32::aligned16(act) && wstride % 4 == 0 && a_off[l] % 4 == 0) {
+            mlpthin::FwdArgs f{};
+            f.B = B; f.K = dims[l - 1]; f.N = dims[l]; f.workers = N; f.relu = l < L ? 1 : 0;
+            f.a = A.p; f.a_ld = A.ld; f.a_stride = A.stride;
+            f.params = params; f.p_stride = c->ld; f.w_off = w_off[l]; f.b_off = b_off[l];
+            f.out = act + a_off[l]; f.out_stride = wstride;
+            const int wgs = (dims[l] + 16 * mlpthin::FWD_CB - 1) / (16 * mlpthin::FWD_CB) * N;
+            const dim3 grid((wgs + mlpthin::XCDS - 1) / mlpthin::XCDS * mlpthin::XCDS), block(mlpthin::FWD_THREADS);
+            dbw_timer tm(c, "mlp_thin_forward", s);
+            switch ((B + 15) / 16) {
+            case 1: hipLaunchKernelGGL(mlpthin::forward_kernel<1>, grid, block, 0, s, f); break;
+            case 2: hipLaunchKernelGGL(mlpthin::forward_kernel<2>, grid, block, 0, s, f); break;
+            case 3: hipLaunchKernelGGL(mlpthin::forward_kernel<3>, grid, block, 0, s, f); break;
+            default: hipLaunchKernelGGL(mlpthin::forward_kernel<4>, grid, block, 0, s, f); break;
+            }
+            DBW_HIP(hipGetLastError());
+            continue;
+        }
         const int splits = forward_splits(B, dims[l], dims[l - 1], N);
         if (splits > 1) {
             float *part = act + 2 * per;
@@ -448,7 +478,7 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
     // against 21 us for the GEMM kernel, whose wavefronts share the tile instead).  The batch-32 streaming kernels
     // keep their layers.
     const int Lw = head.use ? L - 1 : L;
-    bool grouped = !chain.use && a.grad_path == DBW_GRAD_AUTO && Lw >= 1 && B >= 256 && a.in_ld % 4 == 0 && a.in_stride % 4 == 0 &&
+    bool grouped = !chain.use && a.grad_path == DBW_GRAD_AUTO && Lw >= 1 && (B >= 256 || B <= mlpthin::MAX_B) && a.in_ld % 4 == 0 && a.in_stride % 4 == 0 &&
                    fc32::aligned16(a.in) && fc32::aligned16(grads) && c->ld % 4 == 0 && a.param_off % 4 == 0 &&
                    fc32::aligned16(act) && wstride % 4 == 0;
     for (int l = 0; l <= Lw && grouped; ++l) grouped = dims[l] % 4 == 0;

@@ -20,7 +20,8 @@ def _mlp(cfg, dims):
     dgrad = [2 * B * dims[l] * dims[l + 1] for l in range(1, last)]
     table = {"fc_head_kernel": _head(B, n, dims[-2], dims[-1], L > 1)}
     if fwd:
-        table.update({"mlp_forward_gemm": n * sum(fwd) / len(fwd), "mlp_wgrad_gemm": n * sum(fwd) / len(fwd)})
+        table.update({"mlp_forward_gemm": n * sum(fwd) / len(fwd), "mlp_wgrad_gemm": n * sum(fwd) / len(fwd),
+                      "mlp_thin_forward": n * sum(fwd) / len(fwd)})
     if dgrad:
         table["mlp_dgrad_gemm"] = n * sum(dgrad) / len(dgrad)
     # the same products when the whole chain of layers runs in one launch and the weight gradients in another

@@ -146,6 +146,28 @@ def test_grouped_weight_gradients_match_oracle(B, orc, dims, batch, n, loss_kind
     check_gradients(B, orc, dims, batch, n, loss_kind, grad_path=B.GRAD_LAYERS, expect={"mlp_wgrad_gemm"})
 
 
+# Batches of at most 64 samples with widths that divide by 4: forward products and weight gradients straight from
+# global memory into matrix-instruction fragments.  One, two, three and four blocks of 16 samples; batches that
+# end inside a group of four samples; input widths with a partial chunk of 16 (100, 20) and below one chunk (12);
+# output widths with partial tiles of 32 columns and of 64 rows; 20 classes (no fused head: the logits go through
+# the same forward kernel without ReLU, and every bias gradient comes from the weight-gradient kernel).
+THIN_SHAPES = [
+    ([784, 200, 10], 64, 32, "xent"),
+    ([100, 72, 36, 68, 3], 50, 4, "xent"),
+    ([20, 12, 8], 3, 2, "mse"),
+    ([256, 128, 10], 17, 5, "mse"),
+    ([64, 40, 20], 33, 3, "xent"),
+    ([48, 24, 16], 48, 3, "xent"),
+]
+
+
+@pytest.mark.parametrize("dims,batch,n,loss_kind", THIN_SHAPES,
+                         ids=[f"{'-'.join(map(str, s[0]))}-B{s[1]}-N{s[2]}-{s[3]}" for s in THIN_SHAPES])
+def test_short_batch_kernels_match_oracle(B, orc, dims, batch, n, loss_kind):
+    check_gradients(B, orc, dims, batch, n, loss_kind, expect={"mlp_thin_forward", "mlp_wgrad_kernel"})
+    check_gradients(B, orc, dims, batch, n, loss_kind, grad_path=B.GRAD_LAYERS, expect={"mlp_forward_gemm", "mlp_wgrad_gemm"})
+
+
 def test_chain_falls_back_when_the_batch_is_not_16_byte_aligned(B, orc):
     """The chain kernel fetches the batch with 128-bit loads.  A batch that starts 4 bytes into an allocation takes
     the layered path under DBW_GRAD_AUTO (same gradients), and is refused under DBW_GRAD_CHAIN."""
