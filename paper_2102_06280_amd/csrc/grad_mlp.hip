@@ -294,8 +294,9 @@ int launch_grouped_wgrad(dbw_ctx *c, const dbw_fc_args &a, const WgradPlan &wp, 
     const int head_blocks = head_chunks > 1 ? (int)((fchead::partial_floats(h.H, h.C, h.bprev_off >= 0) + 255) / 256) : 0;
     {
         dbw_timer tm(c, "mlp_wgrad_kernel", s);
-        const int wgs = (thin ? (tiles * N + mlpwgrad::WAVES - 1) / mlpwgrad::WAVES : tiles * N * splits) + head_blocks * N;
-        const dim3 grid((wgs + mlpwgrad::XCDS - 1) / mlpwgrad::XCDS * mlpwgrad::XCDS);
+        auto whole_xcds = [](int n) { return (n + mlpwgrad::XCDS - 1) / mlpwgrad::XCDS * mlpwgrad::XCDS; };
+        const int tile_wgs = thin ? (tiles * N + mlpwgrad::WAVES - 1) / mlpwgrad::WAVES : tiles * N * splits;
+        const dim3 grid(whole_xcds(head_blocks * N) + whole_xcds(tile_wgs));
         if (thin && B <= 16)
             hipLaunchKernelGGL(mlpthin::wgrad_kernel<4>, grid, dim3(mlpwgrad::THREADS), 0, s, q, h, head_chunks, head_blocks);
         else if (thin && B <= 32)
@@ -484,6 +485,14 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
     for (int l = 0; l <= Lw && grouped; ++l) grouped = dims[l] % 4 == 0;
     for (int l = 1; l <= Lw && grouped; ++l)
         grouped = !batch32_layer(B, dims[l - 1], dims[l], c->ld, w_off[l], params, grads);
+    // A short batch is one chunk of the head per worker, so that its sums over the batch are final.  When the grouped
+    // launch follows, which adds per-chunk sums on the side, smaller chunks cost nothing and put the head on more CUs
+    // (784-200-10, 64 samples, 32 workers: 16.1 -> 10.9 us with four chunks of 16).
+    if (grouped && head.use && B <= 64)
+        while (head.S > 16 && (int64_t)head.chunks * N < 256) {
+            head.S /= 2;
+            head.chunks = (B + head.S - 1) / head.S;
+        }
     int64_t split_floats = 0;                            // the split partials of the layers, which the head's own follow
     for (int q = 1; q <= L; ++q) split_floats = std::max<int64_t>(split_floats, (int64_t)MAX_SPLITS * B * dims[q]);
     fchead::Args h{};

@@ -170,9 +170,9 @@ __global__ __launch_bounds__(FWD_THREADS) void forward_kernel(FwdArgs g)
 }
 
 // Weight (and bias) gradients for batches of at most 4 GROUPS <= 64 samples: mlpwgrad::Args with splits = 1,
-// 64 x 32 tiles, one tile per wavefront.  grid = ceil(tiles x workers / 4) + head_blocks x workers workgroups of
-// four wavefronts, rounded up to a multiple of XCDS; the workgroups behind the tiles add the head's per-chunk sums
-// as in mlp_wgrad.h.
+// 64 x 32 tiles, one tile per wavefront.  grid = head_blocks x workers + ceil(tiles x workers / 4) workgroups of
+// four wavefronts, each part rounded up to a multiple of XCDS; the workgroups in front of the tiles add the head's
+// per-chunk sums as in mlp_wgrad.h.
 template <int GROUPS>
 __global__ __launch_bounds__(mlpwgrad::THREADS) void wgrad_kernel(mlpwgrad::Args g, fchead::Args h, int chunks, int head_blocks)
 {
@@ -181,13 +181,15 @@ __global__ __launch_bounds__(mlpwgrad::THREADS) void wgrad_kernel(mlpwgrad::Args
     const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, lq = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int tiles = pick(g.tile_begin, g.layers + 1);
-    const int per = gridDim.x / XCDS, id = (blockIdx.x % XCDS) * per + blockIdx.x / XCDS;
     const int wave_tiles = tiles * g.workers, tile_wgs = (wave_tiles + WAVES - 1) / WAVES;
-    if (id >= tile_wgs) {                                       // the whole workgroup
-        const int hid = id - tile_wgs;
+    const int head_grid = gridDim.x - (tile_wgs + XCDS - 1) / XCDS * XCDS;
+    if ((int)blockIdx.x < head_grid) {                          // the whole workgroup
+        const int hid = blockIdx.x;
         if (hid < head_blocks * g.workers) fchead::reduce_body(h, chunks, hid % head_blocks, hid / head_blocks);
         return;
     }
+    const int b = blockIdx.x - head_grid, per = (gridDim.x - head_grid) / XCDS, id = (b % XCDS) * per + b / XCDS;
+    if (id >= tile_wgs) return;
     const int wt = id * WAVES + wave;
     if (wt >= wave_tiles) return;                               // no barrier below
     const int bx = wt % tiles, w = wt / tiles;

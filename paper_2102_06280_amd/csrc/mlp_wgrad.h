@@ -54,11 +54,13 @@ struct Args {
     int splits, kper;                        // samples per split, a multiple of 4
 };
 
-// grid = (tiles of all layers x workers x splits) + (head_blocks x workers), rounded up to a multiple of XCDS.
-// Workgroup ids are renumbered so that the ids one XCD receives are consecutive tiles: the tiles that read the same
-// samples of the same worker and layer then share that XCD's L2 instead of fetching them into all eight.
+// grid = (head_blocks x workers) + (tiles of all layers x workers x splits), each rounded up to a multiple of XCDS.
+// The tile workgroups are renumbered so that the ids one XCD receives are consecutive tiles: the tiles that read
+// the same samples of the same worker and layer then share that XCD's L2 instead of fetching them into all eight
+// (the head's workgroups stay out of that numbering: as its last ids they would be two whole XCDs' share, and
+// the tiles would run on the other six).
 // CBK = column blocks of a tile: 64 x 64 tiles (4) or 64 x 32 (2, twice as many workgroups, for launches that
-// would otherwise have to split the batch to fill the chip).  The workgroups behind the tiles add the per-chunk
+// would otherwise have to split the batch to fill the chip).  The workgroups in front of the tiles add the per-chunk
 // sums of the head (fc_head.h), which the chain kernel left before this launch: head_blocks of them per worker.
 template <int CBK>
 __global__ __launch_bounds__(THREADS, 2) void kernel(Args g, fchead::Args h, int chunks, int head_blocks)
@@ -70,13 +72,15 @@ __global__ __launch_bounds__(THREADS, 2) void kernel(Args g, fchead::Args h, int
     const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, lq = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);       // on the scalar unit: the loops below branch on it
     const int tiles = pick(g.tile_begin, g.layers + 1);
-    const int per = gridDim.x / XCDS, id = (blockIdx.x % XCDS) * per + blockIdx.x / XCDS;
     const int tile_wgs = tiles * g.workers * g.splits;
-    if (id >= tile_wgs) {                                       // the whole workgroup, before any barrier
-        const int hid = id - tile_wgs;
+    const int head_grid = gridDim.x - (tile_wgs + XCDS - 1) / XCDS * XCDS;
+    if ((int)blockIdx.x < head_grid) {                          // the whole workgroup, before any barrier
+        const int hid = blockIdx.x;
         if (hid < head_blocks * g.workers) fchead::reduce_body(h, chunks, hid % head_blocks, hid / head_blocks);
         return;
     }
+    const int b = blockIdx.x - head_grid, per = (gridDim.x - head_grid) / XCDS, id = (b % XCDS) * per + b / XCDS;
+    if (id >= tile_wgs) return;
     const int bx = id % tiles, w = (id / tiles) % g.workers, split = id / (tiles * g.workers);
     int l = 1;
     while (l < g.layers && bx >= pick(g.tile_begin, l + 1)) ++l;
