@@ -121,7 +121,9 @@ enum {
 /* How the gradient of a fully connected model is launched.  The results agree to rounding (the
  * products are summed in different orders). */
 enum {
-    DBW_GRAD_AUTO = 0,   /* the library picks (per-layer launches may share one weight-gradient launch) */
+    DBW_GRAD_AUTO = 0,   /* the library picks: the chain where it applies, else per-layer launches, which
+                            may share one weight-gradient launch and take the kernels for batches of at
+                            most 64 samples */
     DBW_GRAD_LAYERS = 1, /* one batched GEMM launch per layer and pass */
     DBW_GRAD_CHAIN = 2   /* forward pass, loss and data gradients of all layers in one launch, a
                             workgroup per block of samples with the activations in LDS; for
