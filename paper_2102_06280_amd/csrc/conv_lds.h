@@ -58,11 +58,30 @@ struct Cfg {
     static constexpr size_t lds_bytes = sizeof(float) * (IMG + 2 * COUT * LDA) + sizeof(int) * KGS * 16;
 };
 
+// The value of the horizontally adjacent lane (lane ^ 1) as one data-parallel move (quad permutation 1, 0, 3, 2)
+// instead of a round trip through the LDS crossbar.
+__device__ __forceinline__ float neighbour_lane(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));
+}
+
+// The bias values of the output channels a lane's accumulator registers stand for (channel 16 mt + 4 (lane / 16) + v),
+// fetched once, ahead of the multiplies.  Loaded inside the epilogue instead, each of them made the wave wait for the
+// load and for every store issued before it (one counter covers both), eight times per sample.
+template <int MT>
+__device__ __forceinline__ void load_bias(float (&bv)[MT][4], const float *bias, int lane)
+{
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) bv[mt][v] = bias ? bias[16 * mt + 4 * (lane >> 4) + v] : 0.f;
+}
+
 // ReLU + 2 x 2 max pooling of one sample's accumulators, written as the pooled map ob [COUT][H/2][W/2]
 // and the window codes cb of the same shape (see conv_forward_kernel).  A wave's fragments cover
 // whole pairs of image rows, so a window is two accumulators of one lane and of its neighbour.
 template <int MT, int NT, int H, int W>
-__device__ __forceinline__ void relu_pool_store(const f32x4 (&acc)[MT][NT], const float *bias, float *ob, uint8_t *cb,
+__device__ __forceinline__ void relu_pool_store(const f32x4 (&acc)[MT][NT], const float (&bv)[MT][4], float *ob, uint8_t *cb,
                                                 int wave, int lane)
 {
     constexpr int FR = W / 16;                       // fragments per image row
@@ -73,18 +92,20 @@ __device__ __forceinline__ void relu_pool_store(const f32x4 (&acc)[MT][NT], cons
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const int co = 16 * mt + 4 * (lane >> 4) + v;
-            const float bv = bias ? bias[co] : 0.f;
 #pragma unroll
             for (int nf = 0; nf < NT; ++nf) {
                 if ((nf / FR) % 2) continue;         // lower row of a pair: handled with the upper one
                 const int p = (wave * NT + nf) * 16 + (lane & 15);
                 const int y = p / W, x = p % W;
-                const float a = acc[mt][nf][v] + bv, c = acc[mt][nf + FR][v] + bv;
-                const float a1 = __shfl_xor(a, 1), c1 = __shfl_xor(c, 1);
-                if ((lane & 1) == 0) {               // even x: window (y, x) (y, x+1) (y+1, x) (y+1, x+1)
-                    const float m = fmaxf(fmaxf(a, a1), fmaxf(c, c1));
-                    int arg = 4;
-                    if (m > 0.f) arg = (a == m) ? 0 : (a1 == m) ? 1 : (c == m) ? 2 : 3;
+                const float a = acc[mt][nf][v] + bv[mt][v], c = acc[mt][nf + FR][v] + bv[mt][v];
+                const float a1 = neighbour_lane(a), c1 = neighbour_lane(c);
+                // window (y, x) (y, x+1) (y+1, x) (y+1, x+1): the first element that attains the maximum, as selects
+                const float m = fmaxf(fmaxf(a, a1), fmaxf(c, c1));
+                int arg = c == m ? 2 : 3;
+                arg = a1 == m ? 1 : arg;
+                arg = a == m ? 0 : arg;
+                arg = m > 0.f ? arg : 4;
+                if ((lane & 1) == 0) {               // even x
                     const int o = co * PP + (y / 2) * (W / 2) + x / 2;
                     ob[o] = fmaxf(m, 0.f);
                     cb[o] = (uint8_t)arg;
@@ -138,6 +159,8 @@ __global__ __launch_bounds__(64 * WAVES) void conv_forward_kernel(
 #pragma unroll
         for (int nf = 0; nf < NT; ++nf) acc[mt][nf] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+    float bv[MT][4];
+    load_bias<MT>(bv, bias ? bias + w * bias_stride : nullptr, lane);
     const float *inb = in + w * in_stride + (int64_t)b * Cin * (EXPAND ? C::PIX / 4 : C::PIX);
     const uint8_t *icb = EXPAND ? in_code + w * in_code_stride + (int64_t)b * Cin * (C::PIX / 4) : nullptr;
     const float *ww = wgt + w * w_stride;
@@ -210,8 +233,7 @@ __global__ __launch_bounds__(64 * WAVES) void conv_forward_kernel(
 
     if (POOL) {
         constexpr int PP = (H / 2) * (W / 2);
-        relu_pool_store<MT, NT, H, W>(acc, bias ? bias + w * bias_stride : nullptr,
-                                      out + w * out_stride + (int64_t)b * C::COUT * PP,
+        relu_pool_store<MT, NT, H, W>(acc, bv, out + w * out_stride + (int64_t)b * C::COUT * PP,
                                       code + w * code_stride + (int64_t)b * C::COUT * PP, wave, lane);
         return;
     }
@@ -221,11 +243,10 @@ __global__ __launch_bounds__(64 * WAVES) void conv_forward_kernel(
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const int co = 16 * mt + 4 * (lane >> 4) + v;
-            const float bv = bias ? bias[w * bias_stride + co] : 0.f;
 #pragma unroll
             for (int nf = 0; nf < NT; ++nf) {
                 const int p = (wave * NT + nf) * 16 + (lane & 15);
-                ob[co * C::PIX + p] = acc[mt][nf][v] + bv;
+                ob[co * C::PIX + p] = acc[mt][nf][v] + bv[mt][v];
             }
         }
 }
@@ -276,6 +297,8 @@ __global__ __launch_bounds__(64 * WAVES) void conv_forward_pool_multi_kernel(
         }
     }
 
+    float bv[MT][4];
+    load_bias<MT>(bv, bias ? bias + w * bias_stride : nullptr, lane);
     float4 iv[PER];
     auto request_image = [&](int b) {
         const float *inb = in + w * in_stride + (int64_t)b * Cin * C::PIX;
@@ -333,8 +356,7 @@ __global__ __launch_bounds__(64 * WAVES) void conv_forward_pool_multi_kernel(
                         acc[mt][nf] = __builtin_amdgcn_mfma_f32_16x16x4f32(fa[mt][j], fb[nf][j], acc[mt][nf], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);         // keeps the LDS reads of later groups from piling up in registers
         }
-        relu_pool_store<MT, NT, H, W>(acc, bias ? bias + w * bias_stride : nullptr,
-                                      out + w * out_stride + (int64_t)b * C::COUT * PP,
+        relu_pool_store<MT, NT, H, W>(acc, bv, out + w * out_stride + (int64_t)b * C::COUT * PP,
                                       code + w * code_stride + (int64_t)b * C::COUT * PP, wave, lane);
         if (!more) break;
         __syncthreads();                               // every wave has read this sample's image
