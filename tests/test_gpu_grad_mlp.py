@@ -210,6 +210,43 @@ def test_chain_falls_back_when_the_batch_is_not_16_byte_aligned(B, orc):
         B.dbw_destroy(h)
 
 
+def test_short_batch_kernels_fall_back_when_the_batch_is_not_16_byte_aligned(B, orc):
+    """The short-batch kernels fetch the batch with 128-bit loads.  A batch that starts 4 bytes into an allocation
+    takes the GEMM kernels for the first layer instead (forward and weight gradient), with the same gradients."""
+    dims, batch, n = [784, 200, 10], 64, 8
+    desc = {"kind": "mlp", "dims": dims, "loss": "xent"}
+    d = inputs.param_count(desc)
+    ld = inputs.pad_ld(d)
+    rowptr, colidx = inputs.graph_ring(n)
+    g = np.random.default_rng(411)
+    params = dev(inputs.init_params(desc, n, ld, g))
+    x = g.standard_normal((n, batch, dims[0])).astype(np.float32)
+    y = dev(g.integers(0, 10, (n, batch)).astype(np.int32))
+    store = torch.zeros(x.size + 1, dtype=torch.float32, device="cuda")
+    store[1:] = torch.from_numpy(x.ravel()).cuda()
+    shifted = store[1:].view(n, batch, dims[0])
+    assert shifted.data_ptr() % 16 == 4
+    out = {}
+    for name, bx in (("aligned", dev(x)), ("shifted", shifted)):
+        h = B.dbw_create(rowptr, colidx, n, d, ld=ld, model=B.make_model(B.MODEL_MLP, batch, dims, B.LOSS_XENT))
+        try:
+            grads = torch.zeros((n, ld), device="cuda")
+            loss = torch.zeros(n, device="cuda")
+            B.dbw_set_timing(h, True)
+            B.dbw_grad(h, params, bx, y, grads, loss)
+            out[name] = (grads.cpu().numpy(), loss.cpu().numpy(), set(B.dbw_get_timing(h)))
+        finally:
+            B.dbw_destroy(h)
+    assert {"mlp_thin_forward", "mlp_wgrad_kernel"} <= out["aligned"][2]
+    assert not ({"mlp_thin_forward", "mlp_wgrad_kernel"} & out["shifted"][2])
+    assert {"mlp_forward_gemm", "mlp_wgrad_gemm"} <= out["shifted"][2]
+    scale = np.abs(out["aligned"][0]).max()
+    # two summation orders, and a ReLU unit within rounding of zero may fall either way: a loose bound, the strict
+    # comparison with the oracle is test_short_batch_kernels_match_oracle
+    assert np.abs(out["aligned"][0] - out["shifted"][0]).max() <= 1e-4 * scale
+    assert np.allclose(out["aligned"][1], out["shifted"][1], rtol=2e-6)
+
+
 def test_chain_is_picked_for_the_2nn_and_refused_where_it_cannot_run(B):
     rowptr, colidx = inputs.graph_ring(10)
 
