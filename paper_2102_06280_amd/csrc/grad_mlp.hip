@@ -473,15 +473,15 @@ int dbw_fc_forward_backward(dbw_ctx *c, const dbw_fc_args &a, hipStream_t s)
         dbw_timer tm(c, "mlp_forward_gemm", s);
         DBW_HIP(bgemm::launch<64>(A, Bm, E, B, dims[l], dims[l - 1], N, s));
     }
-    // Weight gradients of the layers the GEMM kernels would take: all of them in one launch (mlp_wgrad.h) when the
-    // library may choose, every operand allows 128-bit accesses and the batch is long enough for that kernel's four
-    // wavefronts per tile, which share the samples (measured on 784-200-10 with 64 samples on 32 workers: 26 us
-    // against 21 us for the GEMM kernel, whose wavefronts share the tile instead).  The batch-32 streaming kernels
-    // keep their layers.
+    // Weight gradients of the layers the GEMM kernels would take: all of them in one launch when the library may
+    // choose and every operand allows 128-bit accesses.  Batches of 256 and more: mlp_wgrad.h, four wavefronts per
+    // tile, which share the samples.  Batches of at most 64: mlp_thin.h, a tile per wavefront.  In between the GEMM
+    // kernel, whose wavefronts share the tile, stays (784-200-10 with 64 samples on 32 workers: the four-wavefront
+    // kernel 26 us, the GEMM kernel 21 us, a tile per wavefront 18 us).  The batch-32 streaming kernels keep their layers.
     const int Lw = head.use ? L - 1 : L;
-    bool grouped = !chain.use && a.grad_path == DBW_GRAD_AUTO && Lw >= 1 && (B >= 256 || B <= mlpthin::MAX_B) && a.in_ld % 4 == 0 && a.in_stride % 4 == 0 &&
-                   fc32::aligned16(a.in) && fc32::aligned16(grads) && c->ld % 4 == 0 && a.param_off % 4 == 0 &&
-                   fc32::aligned16(act) && wstride % 4 == 0;
+    bool grouped = !chain.use && a.grad_path == DBW_GRAD_AUTO && Lw >= 1 && (B >= 256 || B <= mlpthin::MAX_B) &&
+                   a.in_ld % 4 == 0 && a.in_stride % 4 == 0 && fc32::aligned16(a.in) && fc32::aligned16(grads) &&
+                   c->ld % 4 == 0 && a.param_off % 4 == 0 && fc32::aligned16(act) && wstride % 4 == 0;
     for (int l = 0; l <= Lw && grouped; ++l) grouped = dims[l] % 4 == 0;
     for (int l = 1; l <= Lw && grouped; ++l)
         grouped = !batch32_layer(B, dims[l - 1], dims[l], c->ld, w_off[l], params, grads);
