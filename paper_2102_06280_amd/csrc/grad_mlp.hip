@@ -258,18 +258,18 @@ int launch_grouped_wgrad(dbw_ctx *c, const dbw_fc_args &a, const WgradPlan &wp, 
     q.B = B; q.layers = wp.layers; q.workers = N;
     // 64 x 64 tiles when they alone give every CU two workgroups, else 64 x 32; if that still leaves CUs idle, the
     // batch is split as well (partial tiles to scratch, one more launch to add them)
-    auto count_tiles = [&](int tn, int *begin) {
+    auto count_tiles = [&](int tm, int tn, int *begin) {
         int t = 0;
         for (int l = 1; l <= wp.layers; ++l) {
             if (begin) begin[l] = t;
-            t += ((dims[l] + 63) / 64) * ((dims[l - 1] + tn - 1) / tn);
+            t += ((dims[l] + tm - 1) / tm) * ((dims[l - 1] + tn - 1) / tn);
         }
         if (begin) begin[wp.layers + 1] = t;
         return t;
     };
-    const bool thin = B <= mlpthin::MAX_B;        // one wavefront per 64 x 32 tile, no split (mlp_thin.h)
-    const int tn = !thin && (int64_t)count_tiles(64, nullptr) * N >= 512 ? 64 : 32;
-    const int tiles = count_tiles(tn, q.tile_begin);
+    const bool thin = B <= mlpthin::MAX_B;        // one wavefront per 32 x 64 tile, no split (mlp_thin.h)
+    const int tn = !thin && (int64_t)count_tiles(64, 64, nullptr) * N >= 512 ? 64 : 32;
+    const int tiles = thin ? count_tiles(mlpthin::WG_TM, mlpthin::WG_TN, q.tile_begin) : count_tiles(64, tn, q.tile_begin);
     for (int l = 1; l <= wp.layers; ++l) {
         q.n_rows[l] = dims[l];
         q.n_cols[l] = dims[l - 1];

@@ -16,7 +16,7 @@
 //
 // wgrad: both operands are contiguous along their output index; the layout trick of mlp_wgrad.h
 // (a lane's four consecutive outputs go to four different tiles) applies, but with at most 16 groups
-// of four samples a tile is too little work to share: every wavefront owns a 64 x 32 tile, fetches
+// of four samples a tile is too little work to share: every wavefront owns a 32 x 64 tile, fetches
 // all its samples at once, multiplies and stores, with no LDS and no barrier.
 #pragma once
 
@@ -169,15 +169,18 @@ __global__ __launch_bounds__(FWD_THREADS) void forward_kernel(FwdArgs g)
     }
 }
 
-// Weight (and bias) gradients for batches of at most 4 GROUPS <= 64 samples: mlpwgrad::Args with splits = 1,
-// 64 x 32 tiles, one tile per wavefront.  grid = head_blocks x workers + ceil(tiles x workers / 4) workgroups of
-// four wavefronts, each part rounded up to a multiple of XCDS; the workgroups in front of the tiles add the head's
+// Weight (and bias) gradients for batches of at most 4 GROUPS <= 64 samples: mlpwgrad::Args with splits = 1 and
+// tiles of 32 rows x 64 columns, one tile per wavefront (a lane loads two consecutive outputs of dz and four of a:
+// narrow layers lose less to padding on the row side than with mlp_wgrad.h's 64 x 32, and a lane's four columns
+// leave as one 128-bit store).  grid = head_blocks x workers + ceil(tiles x workers / 4) workgroups of four
+// wavefronts, each part rounded up to a multiple of XCDS; the workgroups in front of the tiles add the head's
 // per-chunk sums as in mlp_wgrad.h.
+constexpr int WG_TM = 32, WG_TN = 64;
 template <int GROUPS>
 __global__ __launch_bounds__(mlpwgrad::THREADS) void wgrad_kernel(mlpwgrad::Args g, fchead::Args h, int chunks, int head_blocks)
 {
-    constexpr int CBK = 2, TN = 16 * CBK, WAVES = mlpwgrad::WAVES;
-    typedef mlpwgrad::Vec<CBK> vec;
+    constexpr int TM = WG_TM, TN = WG_TN, WAVES = mlpwgrad::WAVES;
+    typedef mlpwgrad::Vec<2> vec2;
     const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, lq = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int tiles = pick(g.tile_begin, g.layers + 1);
@@ -196,63 +199,67 @@ __global__ __launch_bounds__(mlpwgrad::THREADS) void wgrad_kernel(mlpwgrad::Args
     int l = 1;
     while (l < g.layers && bx >= pick(g.tile_begin, l + 1)) ++l;
     const int N = pick(g.n_cols, l), H = pick(g.n_rows, l), ntn = (N + TN - 1) / TN;
-    const int t = bx - pick(g.tile_begin, l), m0 = 64 * (t / ntn), n0 = TN * (t % ntn);
+    const int t = bx - pick(g.tile_begin, l), m0 = TM * (t / ntn), n0 = TN * (t % ntn);
     const bool bias = pick(g.want_db, l) && n0 == 0;
-    const bool rows_ok = m0 + 4 * l16 < H, cols_ok = n0 + CBK * l16 < N;
-    const float *__restrict__ dz = g.dz + w * g.dz_stride + pick(g.dz_off, l) + (rows_ok ? m0 + 4 * l16 : 0);
-    const float *__restrict__ av = pick(g.a, l) + w * pick(g.a_stride, l) + (cols_ok ? n0 + CBK * l16 : 0);
+    // a row pair or column group beyond the matrix (H and N divide by 4): any valid one instead, never stored
+    const bool rows_ok = m0 + 2 * l16 < H, cols_ok = n0 + 4 * l16 < N;
+    const float *__restrict__ dz = g.dz + w * g.dz_stride + pick(g.dz_off, l) + (rows_ok ? m0 + 2 * l16 : 0);
+    const float *__restrict__ av = pick(g.a, l) + w * pick(g.a_stride, l) + (cols_ok ? n0 + 4 * l16 : 0);
     const int64_t a_ld = pick(g.a_ld, l);
 
     // group u = samples 4 u .. 4 u + 3, lane group lq takes sample 4 u + lq; a sample beyond the batch: a valid
     // row, zeroed (every load unconditional: loads under a condition each cost a register move per element)
-    f32x4 x[GROUPS];
-    vec y[GROUPS];
+    vec2 x[GROUPS];
+    f32x4 y[GROUPS];
 #pragma unroll
     for (int u = 0; u < GROUPS; ++u) {
         const int sm = 4 * u + lq, sl = sm < g.B ? sm : 0;
-        x[u] = *(const f32x4 *)(dz + (int64_t)sl * H);
-        y[u] = *(const vec *)(av + (int64_t)sl * a_ld);
+        x[u] = *(const vec2 *)(dz + (int64_t)sl * H);
+        y[u] = *(const f32x4 *)(av + (int64_t)sl * a_ld);
     }
-    f32x4 acc[4][CBK];
+    __builtin_amdgcn_sched_barrier(0);     // every load in flight before the first multiply (left alone, the compiler
+                                           // saves registers by fetching a few groups at a time: 18.1 against 17.6 us)
+    // row block i, column block j: tile row 2 m + i, tile column 4 n + j for the instruction's indices m, n
+    f32x4 acc[2][4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < CBK; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    f32x4 dsum = {0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float dsum[2] = {0.f, 0.f};
 #pragma unroll
     for (int u = 0; u < GROUPS; ++u) {
-        f32x4 xv = x[u];
-        vec yv = y[u];
+        vec2 xv = x[u];
+        f32x4 yv = y[u];
         if (4 * u + lq >= g.B) {
-            xv = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int j = 0; j < CBK; ++j) yv.v[j] = 0.f;
+            xv.v[0] = xv.v[1] = 0.f;
+            yv = f32x4{0.f, 0.f, 0.f, 0.f};
         }
-        dsum += xv;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 2; ++i) {
+            dsum[i] += xv.v[i];
 #pragma unroll
-            for (int j = 0; j < CBK; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(xv[i], yv.v[j], acc[i][j], 0, 0, 0);
+            for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(xv.v[i], yv[j], acc[i][j], 0, 0, 0);
+        }
     }
-    // register r of row block i, lane (l16, lq): output row 4 (4 lq + r) + i, columns CBK l16 .. CBK l16 + CBK - 1
+    // register r of (i, j), lane (l16, lq): tile row 2 (4 lq + r) + i, tile column 4 l16 + j
     float *__restrict__ out = g.grads + w * g.g_stride + pick(g.w_off, l);
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const int row = 4 * (4 * lq + r) + i;
-            vec v;
-#pragma unroll
-            for (int j = 0; j < CBK; ++j) v.v[j] = acc[i][j][r];
-            if (cols_ok && m0 + row < H) *(vec *)(out + (int64_t)(m0 + row) * N + n0 + CBK * l16) = v;
+            const int row = 2 * (4 * lq + r) + i;
+            const f32x4 v = {acc[i][0][r], acc[i][1][r], acc[i][2][r], acc[i][3][r]};
+            if (cols_ok && m0 + row < H) *(f32x4 *)(out + (int64_t)(m0 + row) * N + n0 + 4 * l16) = v;
         }
     if (bias) {
+        vec2 v;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            dsum[e] += __shfl_xor(dsum[e], 16, 64);
-            dsum[e] += __shfl_xor(dsum[e], 32, 64);
+        for (int i = 0; i < 2; ++i) {
+            dsum[i] += __shfl_xor(dsum[i], 16, 64);
+            dsum[i] += __shfl_xor(dsum[i], 32, 64);
+            v.v[i] = dsum[i];
         }
-        if (lq == 0 && rows_ok) *(f32x4 *)(out + (int64_t)H * N + m0 + 4 * l16) = dsum;
+        if (lq == 0 && rows_ok) *(vec2 *)(out + (int64_t)H * N + m0 + 2 * l16) = v;
     }
 }
 
